@@ -1,0 +1,195 @@
+"""Oracle: the per-frame pipeline of Algorithm 1 with a compacted mixed-precision cache.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+Algorithm 1: for every frame, (t > 1) compute R_frame by optical flow against
+the previous frame; if R_frame > theta_R the cache entry of t is a pointer to
+the previous entry and nothing else happens; otherwise compute the saliency
+map, pool it per patch, assign Q(s_i) and store (K_i, V_i) at that precision.
+Just-In-Time Dequantization: entries are expanded again when read.
+
+Storage reading (the paper describes none): three pools indexed
+[layer][K|V][head][slot][...], slots handed out in token order per tier; a
+frame-table row (frame_id, src, stored, base16, base8, base4, n16, n8, n4, np)
+per frame; a pointer frame carries the `src` of the last stored frame.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, Optional
+
+import numpy as np
+
+from . import flow as oflow
+from . import quant as oq
+from . import saliency as osal
+
+
+@dataclasses.dataclass
+class OracleConfig:
+    src_h: int
+    src_w: int
+    grid: int = 24
+    flow_levels: int = 3
+    flow_iters: int = 3
+    tau_t: float = 0.5
+    theta_r: float = 0.90
+    canny_lo: int = 50
+    canny_hi: int = 100
+    tier_mode: int = 0
+    tau_high: float = 0.30
+    tau_med: float = 0.15
+    tau_low: float = 0.03
+    k_fp16: int = 0
+    k_int8: int = 0
+    k_int4: int = 0
+    n_layers: int = 1
+    n_heads: int = 32
+    head_dim: int = 128
+    cap_fp16: int = 0
+    cap_int8: int = 0
+    cap_int4: int = 0
+    max_frames: int = 0
+
+
+@dataclasses.dataclass
+class FrameRow:
+    frame_id: int
+    src: int
+    stored: int
+    base16: int = 0
+    base8: int = 0
+    base4: int = 0
+    n16: int = 0
+    n8: int = 0
+    n4: int = 0
+    npr: int = 0
+
+    def as_tuple(self):
+        return (self.frame_id, self.src, self.stored, self.base16, self.base8, self.base4,
+                self.n16, self.n8, self.n4, self.npr)
+
+
+class SaliCacheOracle:
+    def __init__(self, cfg: OracleConfig):
+        self.cfg = cfg
+        nl, nh, d = cfg.n_layers, cfg.n_heads, cfg.head_dim
+        g = d // oq.GROUP
+        self.pool16 = np.zeros((nl, 2, nh, cfg.cap_fp16, d), dtype=np.float16)
+        self.codes8 = np.zeros((nl, 2, nh, cfg.cap_int8, d), dtype=np.int8)
+        self.scale8 = np.zeros((nl, 2, nh, cfg.cap_int8, g), dtype=np.float32)
+        self.codes4 = np.zeros((nl, 2, nh, cfg.cap_int4, d // 2), dtype=np.uint8)
+        self.scale4 = np.zeros((nl, 2, nh, cfg.cap_int4, g), dtype=np.float32)
+        self.zero4 = np.zeros((nl, 2, nh, cfg.cap_int4, g), dtype=np.float16)
+        self.cursor = [0, 0, 0]
+        self.last_src = -1
+        self.rows: Dict[int, FrameRow] = {}
+        self.tier: Dict[int, np.ndarray] = {}
+        self.slot: Dict[int, np.ndarray] = {}
+        self.prev_gray: Optional[np.ndarray] = None
+        self.overflow = False
+        self.nonfinite = False
+        self.last_gate = None
+        self.last_dp = None
+        self.last_scores = None
+
+    # ---- the stand-alone calls ------------------------------------------------
+    def flow_score(self, prev_rgb, cur_rgb):
+        c = self.cfg
+        d = oflow.flow(prev_rgb, cur_rgb, c.flow_levels, c.flow_iters)
+        dp = oflow.patch_motion(d, c.grid)
+        return d, dp, oflow.gate(dp, c.tau_t, c.theta_r)
+
+    def saliency_pool(self, rgb):
+        c = self.cfg
+        return osal.saliency_pool(rgb, c.grid, c.canny_lo, c.canny_hi)
+
+    def assign_tiers(self, scores):
+        c = self.cfg
+        if c.tier_mode == 0:
+            return oq.tiers_threshold(scores, c.tau_high, c.tau_med, c.tau_low)
+        return oq.tiers_topk(scores, c.k_fp16, c.k_int8, c.k_int4)
+
+    def kv_compress(self, kv_fp16, scores, frame_id):
+        """kv_fp16: [n_l, 2, n_h, N, D].  Stores the frame; returns its table row."""
+        tier = self.assign_tiers(scores)
+        slot, cnt = oq.slots(tier)
+        c = self.cfg
+        if oq.has_nonfinite(kv_fp16[:, :, :, tier != oq.T_PRUNE, :]):
+            self.nonfinite = True
+        if (self.cursor[0] + cnt[0] > c.cap_fp16 or self.cursor[1] + cnt[1] > c.cap_int8
+                or self.cursor[2] + cnt[2] > c.cap_int4):
+            self.overflow = True
+            row = FrameRow(frame_id, -1, 0)
+            self.rows[frame_id] = row
+            return row
+        b16, b8, b4 = self.cursor
+        row = FrameRow(frame_id, frame_id, 1, b16, b8, b4, int(cnt[0]), int(cnt[1]), int(cnt[2]), int(cnt[3]))
+        i16 = np.nonzero(tier == oq.T_FP16)[0]
+        i8 = np.nonzero(tier == oq.T_INT8)[0]
+        i4 = np.nonzero(tier == oq.T_INT4)[0]
+        if i16.size:
+            self.pool16[:, :, :, b16 + slot[i16], :] = kv_fp16[:, :, :, i16, :]
+        if i8.size:
+            q, s = oq.quant_int8(kv_fp16[:, :, :, i8, :])
+            self.codes8[:, :, :, b8 + slot[i8], :] = q
+            self.scale8[:, :, :, b8 + slot[i8], :] = s
+        if i4.size:
+            q, s, z = oq.quant_int4(kv_fp16[:, :, :, i4, :])
+            self.codes4[:, :, :, b4 + slot[i4], :] = oq.pack_nibbles(q)
+            self.scale4[:, :, :, b4 + slot[i4], :] = s
+            self.zero4[:, :, :, b4 + slot[i4], :] = z
+        self.cursor = [b16 + int(cnt[0]), b8 + int(cnt[1]), b4 + int(cnt[2])]
+        self.last_src = frame_id
+        self.rows[frame_id] = row
+        self.tier[frame_id] = tier
+        self.slot[frame_id] = slot
+        return row
+
+    def kv_decompress(self, frame_id):
+        """-> (kv fp16 [n_l, 2, n_h, N, D], valid uint8 [N]); a pointer frame reads its source."""
+        row = self.rows[frame_id]
+        if row.src < 0:
+            raise KeyError("frame holds no data")
+        src = self.rows[row.src]
+        tier, slot = self.tier[row.src], self.slot[row.src]
+        c = self.cfg
+        n = tier.size
+        out = np.zeros((c.n_layers, 2, c.n_heads, n, c.head_dim), dtype=np.float16)
+        i16 = np.nonzero(tier == oq.T_FP16)[0]
+        i8 = np.nonzero(tier == oq.T_INT8)[0]
+        i4 = np.nonzero(tier == oq.T_INT4)[0]
+        if i16.size:
+            out[:, :, :, i16, :] = self.pool16[:, :, :, src.base16 + slot[i16], :]
+        if i8.size:
+            out[:, :, :, i8, :] = oq.dequant_int8(self.codes8[:, :, :, src.base8 + slot[i8], :],
+                                                  self.scale8[:, :, :, src.base8 + slot[i8], :])
+        if i4.size:
+            out[:, :, :, i4, :] = oq.dequant_int4(
+                oq.unpack_nibbles(self.codes4[:, :, :, src.base4 + slot[i4], :]),
+                self.scale4[:, :, :, src.base4 + slot[i4], :],
+                self.zero4[:, :, :, src.base4 + slot[i4], :])
+        valid = (tier != oq.T_PRUNE).astype(np.uint8)
+        return out, valid
+
+    # ---- Algorithm 1, one loop body -------------------------------------------
+    def step(self, rgb, kv_fp16, frame_id):
+        c = self.cfg
+        gray = oflow.gray_float(rgb)
+        redundant = False
+        self.last_gate = None
+        self.last_dp = None
+        if self.prev_gray is not None:
+            d = oflow.flow_from_gray(self.prev_gray, gray, c.flow_levels, c.flow_iters)
+            dp = oflow.patch_motion(d, c.grid)
+            self.last_dp = dp
+            self.last_gate = oflow.gate(dp, c.tau_t, c.theta_r)
+            redundant = self.last_gate[2]
+        self.prev_gray = gray
+        if redundant:
+            row = FrameRow(frame_id, self.last_src, 0)
+            self.rows[frame_id] = row
+            return row
+        scores, _ = self.saliency_pool(rgb)
+        self.last_scores = scores
+        return self.kv_compress(kv_fp16, scores, frame_id)
