@@ -1,0 +1,206 @@
+/*
+ * sali.h - C ABI of the Sali-Cache pre-attention filter for AMD MI355X (gfx950).
+ *
+ * The library implements the per-frame work the method does before any attention
+ * (Methodology; Algorithm 1):
+ *   - temporal filter: dense optical flow between consecutive frames, per-patch motion
+ *     (Eq. 5), frame redundancy score (Eq. 6) and the reuse rule R_frame > theta_R;
+ *   - spatial filter: Canny + LAB colour-variance saliency map pooled per patch (Eq. 7)
+ *     and the four storage tiers FP16 / INT8 / INT4 / Prune (Eq. 8);
+ *   - storing each new frame's K/V rows at the precision of their tier (Algorithm 1,
+ *     "Store (K_i, V_i) with precision Q(s_i)"; Implementation Details: symmetric min-max
+ *     INT8, asymmetric INT4) in compacted pools, and expanding them again on read
+ *     (Just-In-Time Dequantization).
+ *
+ * Conventions
+ *   - Every pointer named d_* is DEVICE memory owned by the caller.  The library never
+ *     allocates or frees device memory; it launches kernels on the HIP stream passed as
+ *     `void* stream` (a hipStream_t, NULL = the default stream) and returns at once.
+ *     Buffers must stay alive and unmodified until the stream has passed that point.
+ *   - Pointers named h_* are HOST memory.
+ *   - Calls return SALI_OK (0) or a negative SALI_ERR_* for argument errors found on the
+ *     host; nothing is launched in that case.  Conditions only the device can see (pool
+ *     overflow, non-finite input) set sticky bits in a device status word read by
+ *     sali_get_status.
+ *   - Calls on one context must be issued from one host thread at a time and on one
+ *     stream (or on streams the caller orders); the context keeps the previous frame's
+ *     polynomial expansion and the pool cursors between calls.
+ *   - Token i of a frame is patch (row r, column c) of the grid x grid partition,
+ *     i = grid * r + c; patch r covers source rows [floor(r*H/grid), floor((r+1)*H/grid)).
+ */
+#ifndef SALI_H
+#define SALI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SALI_OK             0
+#define SALI_ERR_NULL      -1   /* a required pointer is NULL                                */
+#define SALI_ERR_SHAPE     -2   /* frame id / count / size outside the configured range      */
+#define SALI_ERR_ALIGN     -3   /* K/V or workspace pointer not 16-byte (256 for workspaces) aligned */
+#define SALI_ERR_CONFIG    -4   /* inconsistent sali_config                                  */
+#define SALI_ERR_STATE     -5   /* call not valid in the context's current state             */
+#define SALI_ERR_HIP       -6   /* the HIP runtime reported an error on launch / copy        */
+
+/* sticky device status bits (sali_get_status) */
+#define SALI_FAULT_OVERFLOW    0x1u   /* a pool had no room: that frame was recorded as not stored */
+#define SALI_FAULT_NONFINITE   0x2u   /* an inf/NaN K/V value was met while storing                */
+#define SALI_FAULT_NAN_SCORE   0x4u   /* a NaN saliency score: that frame was recorded as not stored */
+#define SALI_FAULT_NO_DATA     0x8u   /* sali_kv_decompress of a frame that holds no data          */
+
+/* tier codes (Eq. 8) */
+#define SALI_TIER_FP16  0
+#define SALI_TIER_INT8  1
+#define SALI_TIER_INT4  2
+#define SALI_TIER_PRUNE 3
+
+#define SALI_TOKENS_MAX 576     /* grid * grid; grid is 24 (576 visual tokens per frame)     */
+
+typedef struct sali_ctx sali_ctx;   /* opaque host object; owns no device memory */
+
+typedef struct sali_config {
+    int32_t src_h, src_w;            /* source frame size in pixels, each >= grid                      */
+    int32_t grid;                    /* patches per side; must be 24                                   */
+    int32_t flow_levels;             /* pyramid levels (scale 0.5), 1..6; the paper uses 3             */
+    int32_t flow_iters;              /* displacement updates per level, 1..8 (3)                       */
+    float   tau_t;                   /* Eq. 5/6: patch i is static iff Delta P_i < tau_t (pixels)      */
+    float   theta_r;                 /* frame is redundant iff R_frame > theta_r                       */
+    int32_t canny_lo, canny_hi;      /* Sobel-magnitude thresholds, 1 <= lo <= hi <= 1442              */
+    int32_t tier_mode;               /* 0: thresholds of Eq. 8; 1: top-k counts                        */
+    float   tau_high, tau_med, tau_low;      /* mode 0, tau_low <= tau_med <= tau_high                 */
+    int32_t k_fp16, k_int8, k_int4;  /* mode 1: tokens per tier by descending score; rest pruned       */
+    int32_t n_layers, n_heads;       /* K/V shape [n_layers][2][n_heads][576][head_dim]                */
+    int32_t head_dim;                /* must be 128                                                    */
+    int32_t group;                   /* quantisation group along head_dim; must be 32                  */
+    int64_t cap_fp16, cap_int8, cap_int4;    /* pool capacities in tokens (rows per layer/K|V/head)    */
+    int32_t max_frames;              /* frame ids are 0 .. max_frames-1                                */
+    int32_t reserved;
+} sali_config;
+
+/* Result of the temporal filter for one frame pair (Eq. 6 and the reuse rule). */
+typedef struct sali_gate {
+    int32_t n_static;                /* #{i : Delta P_i < tau_t}                                       */
+    float   r_frame;                 /* n_static / 576                                                 */
+    int32_t redundant;               /* r_frame > theta_r                                              */
+    int32_t reserved;
+} sali_gate;
+
+/* One frame-table row (Algorithm 1: C[t] is either stored data or a pointer). */
+typedef struct sali_frame_row {
+    int32_t frame_id;
+    int32_t src;                     /* frame whose pool rows hold this frame's K/V; -1 = none         */
+    int32_t stored;                  /* 1: this frame wrote pool rows; 0: pointer or failed            */
+    int32_t base16, base8, base4;    /* first pool row of this frame in each pool                      */
+    int32_t n16, n8, n4, n_pruned;   /* tokens per tier; sum = 576 when stored                         */
+    int32_t reserved[2];
+} sali_frame_row;
+
+/* Byte offsets of the six arrays inside the caller's pool buffer, each
+ * [n_layers][2][n_heads][cap][row]:  fp16 rows (head_dim halves), int8 codes (head_dim
+ * bytes), int8 scales (head_dim/32 fp32), int4 codes (head_dim/2 bytes, element 2j in the
+ * low nibble of byte j), int4 scales (fp32), int4 zero-points (fp16). */
+typedef struct sali_pool_layout {
+    uint64_t off_fp16, off_codes8, off_scale8, off_codes4, off_scale4, off_zero4;
+    uint64_t total_bytes;
+} sali_pool_layout;
+
+/* Sizes of the three device buffers sali_create needs for `cfg`.  Host only. */
+int sali_workspace_bytes(const sali_config* cfg, size_t* scratch_bytes, size_t* pool_bytes,
+                         size_t* table_bytes);
+
+/* Where each pool array lies inside the pool buffer.  Host only. */
+int sali_pool_offsets(const sali_config* cfg, sali_pool_layout* out);
+
+/* Build a context over three caller-owned device buffers (256-byte aligned, at least the
+ * sizes sali_workspace_bytes reports).  Synchronous: clears the tables and uploads the
+ * colour look-up tables with blocking copies on the current device.  The pools are not
+ * cleared.  On error *out is NULL. */
+int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_tables,
+                sali_ctx** out);
+
+/* Frees the host object only; pending work on the caller's stream is the caller's to wait for. */
+void sali_destroy(sali_ctx* ctx);
+
+/* Forget all frames: cursors, frame table, status word and the cached previous frame.
+ * Asynchronous on `stream`. */
+int sali_reset(sali_ctx* ctx, void* stream);
+
+/* Change the temporal thresholds (Eq. 5/6; Discussion: thresholds may need tuning per
+ * video domain).  Applies to calls issued afterwards. */
+int sali_set_gate_thresholds(sali_ctx* ctx, float tau_t, float theta_r);
+
+/* Temporal filter on an explicit frame pair (Temporal Filtering via Optical Flow; Eq. 5,
+ * Eq. 6): dense flow from d_prev_rgb to d_cur_rgb (uint8 [H][W][3]), then
+ *   d_patch_motion576[i] = sqrt(mean over patch i of u^2 + v^2)        (fp32, 576 values)
+ *   *d_gate_out          = {n_static, r_frame, redundant}               (sali_gate, device)
+ * d_flow_uv_or_null, if given, receives the flow as fp32 [2][H][W] (u plane, then v plane);
+ * flow (u, v) at (x, y) means the content at (x, y) of prev appears at (x+u, y+v) in cur.
+ * Does not touch the frame history used by sali_step. */
+int sali_flow_score(sali_ctx* ctx, const uint8_t* d_prev_rgb, const uint8_t* d_cur_rgb,
+                    float* d_flow_uv_or_null, float* d_patch_motion576, sali_gate* d_gate_out,
+                    void* stream);
+
+/* Spatial filter (Spatial Filtering via Saliency-Guided Quantization; Eq. 7): saliency map
+ * of d_rgb (uint8 [H][W][3]) pooled per patch.
+ *   d_scores576[i]     = floor(q_i * 2^15 / |P_i|) / 65536, q_i = sum over patch i of (E + C)
+ *   d_salmap_or_null   = E + C in {0, 1, 2} per pixel, uint8 [H][W]  (the map S is half of it) */
+int sali_saliency_pool(sali_ctx* ctx, const uint8_t* d_rgb, uint8_t* d_salmap_or_null,
+                       float* d_scores576, void* stream);
+
+/* Tier assignment (Eq. 8, or top-k counts in mode 1), compaction and storage of one frame
+ * (Algorithm 1, "Store (K_i, V_i) with precision Q(s_i)").
+ *   d_kv_fp16   : fp16 [n_layers][2][n_heads][576][head_dim], 16-byte aligned; index 0 of
+ *                 the second axis is K, 1 is V
+ *   d_scores576 : fp32 saliency per token, from sali_saliency_pool or any other source
+ *   frame_id    : row of the frame table to fill, 0 <= frame_id < max_frames
+ * Pool rows are appended at the cursors; if any pool lacks room the frame is recorded as
+ * not stored and SALI_FAULT_OVERFLOW is set. */
+int sali_kv_compress(sali_ctx* ctx, const void* d_kv_fp16, const float* d_scores576,
+                     int32_t frame_id, void* stream);
+
+/* Dequantise-on-read (Just-In-Time Dequantization): rebuild frame `frame_id` (or the frame
+ * its pointer refers to) as dense fp16 [n_layers][2][n_heads][576][head_dim] in token order.
+ * FP16-tier rows are bit-identical to what was stored, pruned rows are zeros.
+ * d_valid576_or_null, if given, receives 1 for kept tokens and 0 for pruned ones. */
+int sali_kv_decompress(sali_ctx* ctx, int32_t frame_id, void* d_kv_fp16_out,
+                       uint8_t* d_valid576_or_null, void* stream);
+
+/* One loop body of Algorithm 1 for frame `frame_id` with image d_rgb_t and K/V d_kv_t:
+ * flow against the frame of the previous sali_step call -> gate; a redundant frame becomes
+ * a pointer row and nothing else happens; otherwise saliency -> tiers -> storage as in
+ * sali_kv_compress.  The first call after create/reset has no previous frame and always
+ * stores.  No host synchronisation: the gate lives in device memory and later kernels
+ * test it. */
+int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id,
+              void* stream);
+
+/* Copy `count` frame-table rows starting at `first` to host memory.  Waits for `stream`. */
+int sali_read_frame_table(sali_ctx* ctx, sali_frame_row* h_rows, int32_t first, int32_t count,
+                          void* stream);
+
+/* Copy the tier (uint8[576]) and slot (uint16[576]) tables of a stored frame to host memory.
+ * Waits for `stream`. */
+int sali_read_frame_tiers(sali_ctx* ctx, int32_t frame_id, uint8_t* h_tier576, uint16_t* h_slot576,
+                          void* stream);
+
+/* Results the last sali_step left in device memory, copied to host: per-patch motion
+ * (fp32[576]), the gate, and the saliency scores (fp32[576]); any pointer may be NULL.
+ * Motion and gate are zeros if the step had no previous frame; scores are stale if the
+ * frame was redundant.  Waits for `stream`. */
+int sali_read_last_step(sali_ctx* ctx, float* h_patch_motion576, sali_gate* h_gate,
+                        float* h_scores576, void* stream);
+
+/* Read and keep the sticky device status word.  Waits for `stream`. */
+int sali_get_status(sali_ctx* ctx, uint32_t* h_flags, void* stream);
+
+/* Static text for a return code. */
+const char* sali_error_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SALI_H */

@@ -1,0 +1,65 @@
+"""Builds libsali.so (the HIP kernels + C ABI) in-tree with hipcc for gfx950.
+
+Usage: python -m paper_2602_14236_amd.build   (or call build()).
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+OUT = os.path.join(HERE, "libsali.so")
+
+COMMON = [
+    "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+    # packed fp32 instructions are kept out of the generated code on this target
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+]
+
+# per-file extra flags: the quantiser must not fuse multiply-adds (codes are defined by
+# single fp32 operations); the flow kernels may.
+SOURCES = {
+    "api.hip": [],
+    "kv_kernels.hip": ["-ffp-contract=off"],
+    "saliency_kernels.hip": [],
+    "flow_kernels.hip": ["-ffp-contract=fast"],
+}
+
+
+def build(verbose: bool = True) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    bdir = os.path.join(HERE, "_build")
+    os.makedirs(bdir, exist_ok=True)
+    objs = []
+    procs = []
+    for src, extra in SOURCES.items():
+        obj = os.path.join(bdir, src.replace(".hip", ".o"))
+        cmd = [hipcc, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    failed = False
+    for src, p in procs:
+        out, _ = p.communicate()
+        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and "warning generated" not in l)
+        if out.strip() and verbose:
+            print(out)
+        if p.returncode != 0:
+            print(f"hipcc failed on {src}", file=sys.stderr)
+            failed = True
+    if failed:
+        raise RuntimeError("libsali build failed")
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return OUT
+
+
+if __name__ == "__main__":
+    build()

@@ -1,0 +1,552 @@
+// C ABI of libsali: context management, argument checks and the per-call kernel chains.
+// Every step of the method runs in the kernels of kv_kernels.hip, saliency_kernels.hip and
+// flow_kernels.hip; this file only validates, lays out the caller's buffers and enqueues.
+
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "sali_internal.h"
+
+namespace sali {
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct ScratchLayout {
+    size_t y8, pyr, expA[4], expB[4], flow[2], cls, var, parent, msum, dp, scores, gate, total;
+};
+
+struct TableLayout {
+    size_t lin, fl, cursors, rows, tier, slot, order, total;
+};
+
+int check_config(const sali_config* c) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    if (c->grid != kGrid || c->head_dim != kHeadDim || c->group != kGroup) return SALI_ERR_CONFIG;
+    if (c->src_h < kGrid || c->src_w < kGrid || c->src_h > 16384 || c->src_w > 16384) return SALI_ERR_CONFIG;
+    if (c->flow_levels < 1 || c->flow_levels > kMaxLevels || c->flow_iters < 1 || c->flow_iters > kMaxIters)
+        return SALI_ERR_CONFIG;
+    if (!(c->tau_t >= 0.0f) || !(c->theta_r >= 0.0f)) return SALI_ERR_CONFIG;
+    if (c->canny_lo < 1 || c->canny_hi < c->canny_lo || c->canny_hi > 1442) return SALI_ERR_CONFIG;
+    if (c->tier_mode != 0 && c->tier_mode != 1) return SALI_ERR_CONFIG;
+    if (c->tier_mode == 0) {
+        if (!(c->tau_low <= c->tau_med) || !(c->tau_med <= c->tau_high)) return SALI_ERR_CONFIG;
+    } else {
+        if (c->k_fp16 < 0 || c->k_int8 < 0 || c->k_int4 < 0 ||
+            (long long)c->k_fp16 + c->k_int8 + c->k_int4 > kTokens)
+            return SALI_ERR_CONFIG;
+    }
+    if (c->n_layers < 1 || c->n_heads < 1 || (long long)c->n_layers * 2 * c->n_heads > 65535) return SALI_ERR_CONFIG;
+    if (c->cap_fp16 < 0 || c->cap_int8 < 0 || c->cap_int4 < 0) return SALI_ERR_CONFIG;
+    if (c->cap_fp16 > 0x7FFFFFFFll || c->cap_int8 > 0x7FFFFFFFll || c->cap_int4 > 0x7FFFFFFFll) return SALI_ERR_CONFIG;
+    if (c->max_frames < 1 || c->max_frames > (1 << 24)) return SALI_ERR_CONFIG;
+    // the smallest pyramid level must still be an image
+    int h = c->src_h, w = c->src_w;
+    for (int l = 1; l < c->flow_levels; ++l) {
+        h = (h + 1) / 2;
+        w = (w + 1) / 2;
+    }
+    if (h < 2 || w < 2) return SALI_ERR_CONFIG;
+    return SALI_OK;
+}
+
+LevelGeom make_geom(const sali_config& c) {
+    LevelGeom g = {};
+    g.levels = c.flow_levels;
+    int h = c.src_h, w = c.src_w;
+    int64_t off = 0;
+    int tiles = 0;
+    for (int l = 0; l < g.levels; ++l) {
+        g.h[l] = h;
+        g.w[l] = w;
+        g.off[l] = off;
+        g.tiles_x[l] = (w + 31) / 32;
+        g.tile_start[l] = tiles;
+        tiles += g.tiles_x[l] * ((h + 31) / 32);
+        off += (int64_t)h * w;
+        off = (off + 63) / 64 * 64;
+        h = (h + 1) / 2;
+        w = (w + 1) / 2;
+    }
+    g.tile_start[g.levels] = tiles;
+    return g;
+}
+
+int64_t total_px(const LevelGeom& g) {
+    return g.off[g.levels - 1] + (int64_t)g.h[g.levels - 1] * g.w[g.levels - 1];
+}
+
+FlowWeights make_weights() {
+    FlowWeights fw = {};
+    double pg[2 * kPolyN + 1], sum = 0;
+    for (int k = -kPolyN; k <= kPolyN; ++k) {
+        pg[k + kPolyN] = exp(-(double)(k * k) / (2.0 * (double)kPolySigma * (double)kPolySigma));
+        sum += pg[k + kPolyN];
+    }
+    double m2 = 0, m4 = 0;
+    for (int k = -kPolyN; k <= kPolyN; ++k) {
+        pg[k + kPolyN] /= sum;
+        m2 += pg[k + kPolyN] * k * k;
+        m4 += pg[k + kPolyN] * k * k * k * k;
+        fw.poly_g[k + kPolyN] = (float)pg[k + kPolyN];
+    }
+    fw.m2 = (float)m2;
+    fw.inv_m2 = (float)(1.0 / m2);
+    fw.inv_den = (float)(1.0 / (m4 - m2 * m2));
+    fw.inv_2m2sq = (float)(1.0 / (2.0 * m2 * m2));
+    double wg[2 * kWinR + 1];
+    sum = 0;
+    for (int k = -kWinR; k <= kWinR; ++k) {
+        wg[k + kWinR] = exp(-(double)(k * k) / (2.0 * (double)kWinSigma * (double)kWinSigma));
+        sum += wg[k + kWinR];
+    }
+    for (int k = 0; k <= 2 * kWinR; ++k) fw.win_g[k] = (float)(wg[k] / sum);
+    return fw;
+}
+
+ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
+    ScratchLayout s = {};
+    const size_t hw = (size_t)c.src_h * c.src_w;
+    const size_t px = (size_t)total_px(g);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    s.y8 = take(hw);
+    s.pyr = take(px * sizeof(float));
+    for (int i = 0; i < 4; ++i) {
+        s.expA[i] = take(px * sizeof(float4));
+        s.expB[i] = take(px * sizeof(float2));
+    }
+    s.flow[0] = take(hw * sizeof(float2));
+    s.flow[1] = take(hw * sizeof(float2));
+    s.cls = take(hw);
+    s.var = take(hw * sizeof(uint32_t));
+    s.parent = take(hw * sizeof(uint32_t));
+    s.msum = take(2 * sizeof(unsigned long long));
+    s.dp = take(kTokens * sizeof(float));
+    s.scores = take(kTokens * sizeof(float));
+    s.gate = take(sizeof(sali_gate));
+    s.total = o;
+    return s;
+}
+
+TableLayout table_layout(const sali_config& c) {
+    TableLayout t = {};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    t.lin = take(256 * sizeof(uint16_t));
+    t.fl = take(4096 * sizeof(uint16_t));
+    t.cursors = take(sizeof(Cursors));
+    t.rows = take((size_t)c.max_frames * sizeof(sali_frame_row));
+    t.tier = take((size_t)c.max_frames * kTokens);
+    t.slot = take((size_t)c.max_frames * kTokens * sizeof(uint16_t));
+    t.order = take((size_t)c.max_frames * kTokens * sizeof(uint16_t));
+    t.total = o;
+    return t;
+}
+
+sali_pool_layout pool_layout(const sali_config& c) {
+    sali_pool_layout p = {};
+    const size_t planes = (size_t)c.n_layers * 2 * c.n_heads;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    p.off_fp16 = take(planes * (size_t)c.cap_fp16 * kHeadDim * 2);
+    p.off_codes8 = take(planes * (size_t)c.cap_int8 * kHeadDim);
+    p.off_scale8 = take(planes * (size_t)c.cap_int8 * kGroupsPerRow * 4);
+    p.off_codes4 = take(planes * (size_t)c.cap_int4 * (kHeadDim / 2));
+    p.off_scale4 = take(planes * (size_t)c.cap_int4 * kGroupsPerRow * 4);
+    p.off_zero4 = take(planes * (size_t)c.cap_int4 * kGroupsPerRow * 2);
+    p.total_bytes = o > 0 ? o : kAlign;
+    return p;
+}
+
+__global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, unsigned long long* msum,
+                        float* dp, float* scores, sali_gate* gate) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < max_frames) {
+        sali_frame_row r = {};
+        r.frame_id = -1;
+        r.src = -1;
+        rows[i] = r;
+    }
+    if (i < kTokens) {
+        dp[i] = 0.0f;
+        scores[i] = 0.0f;
+    }
+    if (i == 0) {
+        Cursors c = {};
+        c.last_src = -1;
+        *cur = c;
+        msum[0] = 0ull;
+        msum[1] = 0ull;
+        sali_gate g = {0, 0.0f, 0, 0};
+        *gate = g;
+    }
+}
+
+}  // namespace
+
+}  // namespace sali
+
+using namespace sali;
+
+struct sali_ctx {
+    sali_config cfg;
+    LevelGeom geom;
+    FlowWeights fw;
+    ScratchLayout sl;
+    TableLayout tl;
+    uint8_t* scratch;
+    uint8_t* tables;
+    Pools pools;
+    int n_planes;
+    bool prev_valid;     // the expansion of the previous sali_step frame is cached in slot `step_slot ^ 1`
+    int step_slot;       // expansion slot the NEXT sali_step frame writes (0 or 1)
+    unsigned sal_seq;    // parity selects the frame-sum accumulator
+
+    template <typename T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
+    template <typename T> T* tb(size_t off) const { return reinterpret_cast<T*>(tables + off); }
+    Cursors* cursors() const { return tb<Cursors>(tl.cursors); }
+    sali_frame_row* rows() const { return tb<sali_frame_row>(tl.rows); }
+    uint8_t* tier(int f) const { return tb<uint8_t>(tl.tier) + (size_t)f * kTokens; }
+    uint16_t* slot(int f) const { return tb<uint16_t>(tl.slot) + (size_t)f * kTokens; }
+    uint16_t* order(int f) const { return tb<uint16_t>(tl.order) + (size_t)f * kTokens; }
+};
+
+namespace {
+
+#define SALI_TRY(expr)                         \
+    do {                                       \
+        if ((expr) != hipSuccess) return SALI_ERR_HIP; \
+    } while (0)
+
+// gray (+ saliency pre-pass), pyramid and polynomial expansion of one frame into slot `slot`
+int enqueue_frame_analysis(sali_ctx* c, const uint8_t* d_rgb, int slot, bool with_saliency, hipStream_t s) {
+    const sali_config& cfg = c->cfg;
+    unsigned long long* msum = c->sc<unsigned long long>(c->sl.msum);
+    unsigned long long* acc = nullptr;
+    unsigned long long* clr = nullptr;
+    if (with_saliency) {
+        acc = msum + (c->sal_seq & 1u);
+        clr = msum + ((c->sal_seq + 1u) & 1u);
+    }
+    SALI_TRY(launch_prep(d_rgb, cfg.src_h, cfg.src_w, with_saliency, c->sc<uint8_t>(c->sl.y8),
+                         c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.var), c->sc<uint32_t>(c->sl.parent), acc,
+                         clr, c->tb<uint16_t>(c->tl.lin), c->tb<uint16_t>(c->tl.fl), cfg.canny_lo * cfg.canny_lo,
+                         cfg.canny_hi * cfg.canny_hi, s));
+    if (slot < 0) return SALI_OK;
+    float* pyr = c->sc<float>(c->sl.pyr);
+    const LevelGeom& g = c->geom;
+    for (int l = 1; l < g.levels; ++l) {
+        SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(c->sl.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
+                                 g.h[l - 1], g.w[l - 1], pyr + g.off[l], g.h[l], g.w[l], s));
+    }
+    SALI_TRY(launch_polyexp(c->sc<uint8_t>(c->sl.y8), pyr, g, c->fw, c->sc<float4>(c->sl.expA[slot]),
+                            c->sc<float2>(c->sl.expB[slot]), s));
+    return SALI_OK;
+}
+
+// coarse-to-fine displacement estimation between expansion slots; result in *result_buf
+int enqueue_flow(sali_ctx* c, int slot_prev, int slot_cur, const float2** result_buf, hipStream_t s) {
+    const LevelGeom& g = c->geom;
+    float2* buf[2] = {c->sc<float2>(c->sl.flow[0]), c->sc<float2>(c->sl.flow[1])};
+    const float4* A1 = c->sc<float4>(c->sl.expA[slot_prev]);
+    const float2* b1 = c->sc<float2>(c->sl.expB[slot_prev]);
+    const float4* A2 = c->sc<float4>(c->sl.expA[slot_cur]);
+    const float2* b2 = c->sc<float2>(c->sl.expB[slot_cur]);
+    int cur = 0;            // buffer holding the latest estimate
+    bool have = false;
+    for (int l = g.levels - 1; l >= 0; --l) {
+        for (int it = 0; it < c->cfg.flow_iters; ++it) {
+            int mode;
+            int ch = 0, cw = 0;
+            if (it > 0) mode = 2;
+            else if (!have) mode = 0;
+            else { mode = 1; ch = g.h[l + 1]; cw = g.w[l + 1]; }
+            SALI_TRY(launch_flow_iter(A1 + g.off[l], b1 + g.off[l], A2 + g.off[l], b2 + g.off[l], buf[cur],
+                                      buf[cur ^ 1], g.h[l], g.w[l], ch, cw, mode, c->fw, s));
+            cur ^= 1;
+            have = true;
+        }
+    }
+    *result_buf = buf[cur];
+    return SALI_OK;
+}
+
+int enqueue_saliency_tail(sali_ctx* c, const sali_gate* gate, float* d_scores, uint8_t* d_salmap, hipStream_t s) {
+    const sali_config& cfg = c->cfg;
+    unsigned long long* msum = c->sc<unsigned long long>(c->sl.msum) + (c->sal_seq & 1u);
+    SALI_TRY(launch_union(c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.parent), cfg.src_h, cfg.src_w, gate, s));
+    SALI_TRY(launch_pool(c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.parent), c->sc<uint32_t>(c->sl.var), msum,
+                         cfg.src_h, cfg.src_w, gate, d_scores, d_salmap, s));
+    c->sal_seq += 1u;
+    return SALI_OK;
+}
+
+TierParams tier_params(const sali_config& cfg) {
+    TierParams tp;
+    tp.mode = cfg.tier_mode;
+    tp.tau_high = cfg.tau_high;
+    tp.tau_med = cfg.tau_med;
+    tp.tau_low = cfg.tau_low;
+    tp.k16 = cfg.k_fp16;
+    tp.k8 = cfg.k_int8;
+    tp.k4 = cfg.k_int4;
+    return tp;
+}
+
+int enqueue_store(sali_ctx* c, const void* d_kv, const float* d_scores, const sali_gate* gate, int frame_id,
+                  hipStream_t s) {
+    SALI_TRY(launch_tier(d_scores, gate, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
+                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, s));
+    SALI_TRY(launch_pack(d_kv, c->rows() + frame_id, c->order(frame_id), c->pools, c->cursors(), c->n_planes, s));
+    return SALI_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+void fill_luts(uint16_t* lin, uint16_t* fl) {
+    // sRGB decoding to 12-bit linear light, and the CIE L*a*b* companding function on a
+    // 12-bit argument scaled by 2^15
+    for (int v = 0; v < 256; ++v) {
+        const double c = v / 255.0;
+        const double l = c <= 0.04045 ? c / 12.92 : pow((c + 0.055) / 1.055, 2.4);
+        lin[v] = (uint16_t)floor(4095.0 * l + 0.5);
+    }
+    const double d = 6.0 / 29.0;
+    for (int t = 0; t < 4096; ++t) {
+        const double u = t / 4095.0;
+        const double f = u > d * d * d ? cbrt(u) : u / (3.0 * d * d) + 4.0 / 29.0;
+        fl[t] = (uint16_t)floor(32768.0 * f + 0.5);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int sali_workspace_bytes(const sali_config* cfg, size_t* scratch_bytes, size_t* pool_bytes, size_t* table_bytes) {
+    const int rc = check_config(cfg);
+    if (rc != SALI_OK) return rc;
+    if (scratch_bytes == nullptr || pool_bytes == nullptr || table_bytes == nullptr) return SALI_ERR_NULL;
+    const LevelGeom g = make_geom(*cfg);
+    *scratch_bytes = scratch_layout(*cfg, g).total;
+    *pool_bytes = (size_t)pool_layout(*cfg).total_bytes;
+    *table_bytes = table_layout(*cfg).total;
+    return SALI_OK;
+}
+
+int sali_pool_offsets(const sali_config* cfg, sali_pool_layout* out) {
+    const int rc = check_config(cfg);
+    if (rc != SALI_OK) return rc;
+    if (out == nullptr) return SALI_ERR_NULL;
+    *out = pool_layout(*cfg);
+    return SALI_OK;
+}
+
+int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_tables, sali_ctx** out) {
+    if (out == nullptr) return SALI_ERR_NULL;
+    *out = nullptr;
+    const int rc = check_config(cfg);
+    if (rc != SALI_OK) return rc;
+    if (d_scratch == nullptr || d_pools == nullptr || d_tables == nullptr) return SALI_ERR_NULL;
+    if (!aligned256(d_scratch) || !aligned256(d_pools) || !aligned256(d_tables)) return SALI_ERR_ALIGN;
+    sali_ctx* c = new (std::nothrow) sali_ctx();
+    if (c == nullptr) return SALI_ERR_STATE;
+    c->cfg = *cfg;
+    c->geom = make_geom(*cfg);
+    c->fw = make_weights();
+    c->sl = scratch_layout(*cfg, c->geom);
+    c->tl = table_layout(*cfg);
+    c->scratch = static_cast<uint8_t*>(d_scratch);
+    c->tables = static_cast<uint8_t*>(d_tables);
+    const sali_pool_layout pl = pool_layout(*cfg);
+    uint8_t* pb = static_cast<uint8_t*>(d_pools);
+    c->pools.p16 = reinterpret_cast<uint16_t*>(pb + pl.off_fp16);
+    c->pools.c8 = reinterpret_cast<int8_t*>(pb + pl.off_codes8);
+    c->pools.s8 = reinterpret_cast<float*>(pb + pl.off_scale8);
+    c->pools.c4 = pb + pl.off_codes4;
+    c->pools.s4 = reinterpret_cast<float*>(pb + pl.off_scale4);
+    c->pools.z4 = reinterpret_cast<uint16_t*>(pb + pl.off_zero4);
+    c->pools.cap16 = (int32_t)cfg->cap_fp16;
+    c->pools.cap8 = (int32_t)cfg->cap_int8;
+    c->pools.cap4 = (int32_t)cfg->cap_int4;
+    c->n_planes = cfg->n_layers * 2 * cfg->n_heads;
+    c->prev_valid = false;
+    c->step_slot = 0;
+    c->sal_seq = 0;
+
+    uint16_t lin[256];
+    static uint16_t fl[4096];
+    fill_luts(lin, fl);
+    if (hipMemcpy(c->tables + c->tl.lin, lin, sizeof(lin), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(c->tables + c->tl.fl, fl, sizeof(fl), hipMemcpyHostToDevice) != hipSuccess) {
+        delete c;
+        return SALI_ERR_HIP;
+    }
+    if (sali_reset(c, nullptr) != SALI_OK || hipStreamSynchronize(nullptr) != hipSuccess) {
+        delete c;
+        return SALI_ERR_HIP;
+    }
+    *out = c;
+    return SALI_OK;
+}
+
+void sali_destroy(sali_ctx* ctx) { delete ctx; }
+
+int sali_reset(sali_ctx* c, void* stream) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int n = c->cfg.max_frames > kTokens ? c->cfg.max_frames : kTokens;
+    hipLaunchKernelGGL(k_reset, dim3((n + 255) / 256), dim3(256), 0, s, c->cursors(), c->rows(), c->cfg.max_frames,
+                       c->sc<unsigned long long>(c->sl.msum), c->sc<float>(c->sl.dp), c->sc<float>(c->sl.scores),
+                       c->sc<sali_gate>(c->sl.gate));
+    SALI_TRY(hipGetLastError());
+    c->prev_valid = false;
+    c->step_slot = 0;
+    c->sal_seq = 0;
+    return SALI_OK;
+}
+
+int sali_set_gate_thresholds(sali_ctx* c, float tau_t, float theta_r) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    if (!(tau_t >= 0.0f) || !(theta_r >= 0.0f)) return SALI_ERR_CONFIG;
+    c->cfg.tau_t = tau_t;
+    c->cfg.theta_r = theta_r;
+    return SALI_OK;
+}
+
+int sali_flow_score(sali_ctx* c, const uint8_t* d_prev_rgb, const uint8_t* d_cur_rgb, float* d_flow_uv_or_null,
+                    float* d_patch_motion576, sali_gate* d_gate_out, void* stream) {
+    if (c == nullptr || d_prev_rgb == nullptr || d_cur_rgb == nullptr || d_patch_motion576 == nullptr ||
+        d_gate_out == nullptr)
+        return SALI_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = enqueue_frame_analysis(c, d_prev_rgb, 2, false, s);
+    if (rc != SALI_OK) return rc;
+    rc = enqueue_frame_analysis(c, d_cur_rgb, 3, false, s);
+    if (rc != SALI_OK) return rc;
+    const float2* flow = nullptr;
+    rc = enqueue_flow(c, 2, 3, &flow, s);
+    if (rc != SALI_OK) return rc;
+    SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, d_patch_motion576,
+                               d_gate_out, c->cursors(), d_flow_uv_or_null, s));
+    return SALI_OK;
+}
+
+int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_null, float* d_scores576,
+                       void* stream) {
+    if (c == nullptr || d_rgb == nullptr || d_scores576 == nullptr) return SALI_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = enqueue_frame_analysis(c, d_rgb, -1, true, s);
+    if (rc != SALI_OK) return rc;
+    return enqueue_saliency_tail(c, nullptr, d_scores576, d_salmap_or_null, s);
+}
+
+int sali_kv_compress(sali_ctx* c, const void* d_kv_fp16, const float* d_scores576, int32_t frame_id, void* stream) {
+    if (c == nullptr || d_kv_fp16 == nullptr || d_scores576 == nullptr) return SALI_ERR_NULL;
+    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
+    if (!aligned16(d_kv_fp16)) return SALI_ERR_ALIGN;
+    return enqueue_store(c, d_kv_fp16, d_scores576, nullptr, frame_id, static_cast<hipStream_t>(stream));
+}
+
+int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8_t* d_valid576_or_null,
+                       void* stream) {
+    if (c == nullptr || d_kv_fp16_out == nullptr) return SALI_ERR_NULL;
+    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
+    if (!aligned16(d_kv_fp16_out)) return SALI_ERR_ALIGN;
+    SALI_TRY(launch_unpack(c->rows(), frame_id, c->tb<uint16_t>(c->tl.order), c->pools, d_kv_fp16_out,
+                           d_valid576_or_null, c->cursors(), c->n_planes, static_cast<hipStream_t>(stream)));
+    return SALI_OK;
+}
+
+int sali_step(sali_ctx* c, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id, void* stream) {
+    if (c == nullptr || d_rgb_t == nullptr || d_kv_t == nullptr) return SALI_ERR_NULL;
+    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
+    if (!aligned16(d_kv_t)) return SALI_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int slot = c->step_slot;
+    int rc = enqueue_frame_analysis(c, d_rgb_t, slot, true, s);
+    if (rc != SALI_OK) return rc;
+    float* dp = c->sc<float>(c->sl.dp);
+    float* scores = c->sc<float>(c->sl.scores);
+    sali_gate* gate = c->sc<sali_gate>(c->sl.gate);
+    if (c->prev_valid) {
+        const float2* flow = nullptr;
+        rc = enqueue_flow(c, slot ^ 1, slot, &flow, s);
+        if (rc != SALI_OK) return rc;
+        SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, dp, gate,
+                                   c->cursors(), nullptr, s));
+    } else {
+        SALI_TRY(launch_clear_gate(dp, gate, s));      // first frame: never redundant (Algorithm 1, t > 1)
+    }
+    rc = enqueue_saliency_tail(c, gate, scores, nullptr, s);
+    if (rc != SALI_OK) return rc;
+    rc = enqueue_store(c, d_kv_t, scores, gate, frame_id, s);
+    if (rc != SALI_OK) return rc;
+    c->prev_valid = true;
+    c->step_slot = slot ^ 1;
+    return SALI_OK;
+}
+
+int sali_read_frame_table(sali_ctx* c, sali_frame_row* h_rows, int32_t first, int32_t count, void* stream) {
+    if (c == nullptr || h_rows == nullptr) return SALI_ERR_NULL;
+    if (first < 0 || count < 0 || (long long)first + count > c->cfg.max_frames) return SALI_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (count > 0)
+        SALI_TRY(hipMemcpyAsync(h_rows, c->rows() + first, (size_t)count * sizeof(sali_frame_row),
+                                hipMemcpyDeviceToHost, s));
+    SALI_TRY(hipStreamSynchronize(s));
+    return SALI_OK;
+}
+
+int sali_read_frame_tiers(sali_ctx* c, int32_t frame_id, uint8_t* h_tier576, uint16_t* h_slot576, void* stream) {
+    if (c == nullptr || h_tier576 == nullptr || h_slot576 == nullptr) return SALI_ERR_NULL;
+    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SALI_TRY(hipMemcpyAsync(h_tier576, c->tier(frame_id), kTokens, hipMemcpyDeviceToHost, s));
+    SALI_TRY(hipMemcpyAsync(h_slot576, c->slot(frame_id), kTokens * sizeof(uint16_t), hipMemcpyDeviceToHost, s));
+    SALI_TRY(hipStreamSynchronize(s));
+    return SALI_OK;
+}
+
+int sali_read_last_step(sali_ctx* c, float* h_patch_motion576, sali_gate* h_gate, float* h_scores576, void* stream) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (h_patch_motion576 != nullptr)
+        SALI_TRY(hipMemcpyAsync(h_patch_motion576, c->sc<float>(c->sl.dp), kTokens * sizeof(float),
+                                hipMemcpyDeviceToHost, s));
+    if (h_gate != nullptr)
+        SALI_TRY(hipMemcpyAsync(h_gate, c->sc<sali_gate>(c->sl.gate), sizeof(sali_gate), hipMemcpyDeviceToHost, s));
+    if (h_scores576 != nullptr)
+        SALI_TRY(hipMemcpyAsync(h_scores576, c->sc<float>(c->sl.scores), kTokens * sizeof(float),
+                                hipMemcpyDeviceToHost, s));
+    SALI_TRY(hipStreamSynchronize(s));
+    return SALI_OK;
+}
+
+int sali_get_status(sali_ctx* c, uint32_t* h_flags, void* stream) {
+    if (c == nullptr || h_flags == nullptr) return SALI_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SALI_TRY(hipMemcpyAsync(h_flags, &c->cursors()->status, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    SALI_TRY(hipStreamSynchronize(s));
+    return SALI_OK;
+}
+
+const char* sali_error_string(int code) {
+    switch (code) {
+        case SALI_OK: return "ok";
+        case SALI_ERR_NULL: return "null pointer";
+        case SALI_ERR_SHAPE: return "index or size out of range";
+        case SALI_ERR_ALIGN: return "misaligned pointer";
+        case SALI_ERR_CONFIG: return "invalid configuration";
+        case SALI_ERR_STATE: return "invalid state";
+        case SALI_ERR_HIP: return "HIP runtime error";
+        default: return "unknown";
+    }
+}
+
+}  // extern "C"

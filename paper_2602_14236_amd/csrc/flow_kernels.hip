@@ -1,0 +1,344 @@
+// Dense polynomial-expansion optical flow, per-patch motion and the redundancy gate for gfx950.
+//
+// Temporal Filtering via Optical Flow (Eq. 5, Eq. 6, reuse rule R_frame > theta_R) and
+// Implementation Details (Farneback's algorithm, pyramid scale 0.5).  Plain fp32 VALU work on
+// small images: no dense contraction here, so no MFMA; the design goal is few launches and no
+// spilled intermediates.
+//
+//   k_pyr_down   5x5 binomial [1 4 6 4 1]/16, stride 2 (level 0 is gray / 255)
+//   k_polyexp    all pyramid levels in one launch; 32x32 tile + 3-pixel halo in LDS, separable
+//                moments, closed-form solution of the 6-unknown weighted least-squares fit
+//   k_flow_iter  one displacement update: per cell of a 32x32 tile + 5-pixel halo, sample the new
+//                frame's expansion bilinearly at x + prior, build A^T A (3 values) and A^T db
+//                (2 values) in LDS, separable 11x11 Gaussian aggregation in LDS, 2x2 ridge solve.
+//                The coarse-to-fine transfer (2 * bilinear of the coarser flow) is folded into
+//                the first update of a level, so G/h fields never touch HBM.
+//   k_patch_gate per patch RMS flow magnitude (Eq. 5); the last block to finish counts static
+//                patches and writes the gate (Eq. 6).
+//
+// All stencils replicate the border.
+
+#include "sali_internal.h"
+
+namespace sali {
+
+namespace {
+
+constexpr int kT = 32;                       // tile side
+constexpr int kPR = kT + 2 * kPolyN;         // 38
+constexpr int kFR = kT + 2 * kWinR;          // 42
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+__device__ __forceinline__ float clampf(float v, float lo, float hi) { return fminf(fmaxf(v, lo), hi); }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pyr_down(const uint8_t* __restrict__ y8, const float* __restrict__ src,
+                                                  int sh, int sw, float* __restrict__ dst, int dh, int dw) {
+    const int x = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (x >= dw || y >= dh) return;
+    const float k[5] = {1.0f / 16, 4.0f / 16, 6.0f / 16, 4.0f / 16, 1.0f / 16};
+    float acc = 0.0f;
+#pragma unroll
+    for (int a = -2; a <= 2; ++a) {
+        const int yy = clampi(2 * y + a, 0, sh - 1);
+        float row = 0.0f;
+#pragma unroll
+        for (int b = -2; b <= 2; ++b) {
+            const int xx = clampi(2 * x + b, 0, sw - 1);
+            const float v = y8 != nullptr ? (float)y8[(size_t)yy * sw + xx] / 255.0f : src[(size_t)yy * sw + xx];
+            row += k[b + 2] * v;
+        }
+        acc += k[a + 2] * row;
+    }
+    dst[(size_t)y * dw + x] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Polynomial expansion f(x + d) ~ c + b.d + d^T A d over the 7x7 Gaussian-weighted window.
+// With separable symmetric weights (sum 1, second moment m2, fourth moment m4) the normal
+// equations decouple:  b = (sx, sy) / m2,  A_xx = (sxx - m2 s0) / (m4 - m2^2),  A_yy likewise,
+// A_xy = sxy / (2 m2^2), where s* are the weighted correlations of f with 1, x, y, x^2, y^2, xy.
+__global__ __launch_bounds__(256) void k_polyexp(const uint8_t* __restrict__ y8, const float* __restrict__ pyr,
+                                                 LevelGeom g, FlowWeights fw, float4* __restrict__ A_out,
+                                                 float2* __restrict__ b_out) {
+    __shared__ float s_f[kPR][kPR + 1];
+    __shared__ float s_v[3][kT][kPR + 1];
+
+    int lvl = 0;
+    while (lvl + 1 < g.levels && (int)blockIdx.x >= g.tile_start[lvl + 1]) ++lvl;
+    const int t = blockIdx.x - g.tile_start[lvl];
+    const int h = g.h[lvl], w = g.w[lvl];
+    const int x0 = (t % g.tiles_x[lvl]) * kT, y0 = (t / g.tiles_x[lvl]) * kT;
+    const float* src = pyr + g.off[lvl];
+    const int tid = threadIdx.x;
+
+    for (int p = tid; p < kPR * kPR; p += 256) {
+        const int ry = p / kPR, rx = p % kPR;
+        const int gy = clampi(y0 - kPolyN + ry, 0, h - 1), gx = clampi(x0 - kPolyN + rx, 0, w - 1);
+        const size_t gi = (size_t)gy * w + gx;
+        s_f[ry][rx] = (lvl == 0) ? (float)y8[gi] / 255.0f : src[gi];
+    }
+    __syncthreads();
+
+    // Out-of-image cells of the region hold the value at the clamped coordinate, which is exactly
+    // what a replicate-border stencil centred on an in-image pixel reads.  Vertical moments:
+    for (int p = tid; p < kT * kPR; p += 256) {
+        const int ty = p / kPR, rx = p % kPR;
+        float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f;
+#pragma unroll
+        for (int k = -kPolyN; k <= kPolyN; ++k) {
+            const float f = s_f[ty + kPolyN + k][rx] * fw.poly_g[k + kPolyN];
+            v0 += f;
+            v1 += f * (float)k;
+            v2 += f * (float)(k * k);
+        }
+        s_v[0][ty][rx] = v0;
+        s_v[1][ty][rx] = v1;
+        s_v[2][ty][rx] = v2;
+    }
+    __syncthreads();
+
+    for (int p = tid; p < kT * kT; p += 256) {
+        const int ty = p / kT, tx = p % kT;
+        const int gy = y0 + ty, gx = x0 + tx;
+        if (gy >= h || gx >= w) continue;
+        float s0 = 0, sx = 0, sxx = 0, sy = 0, sxy = 0, syy = 0;
+#pragma unroll
+        for (int k = -kPolyN; k <= kPolyN; ++k) {
+            const float gk = fw.poly_g[k + kPolyN];
+            const float a0 = s_v[0][ty][tx + kPolyN + k] * gk;
+            const float a1 = s_v[1][ty][tx + kPolyN + k] * gk;
+            const float a2 = s_v[2][ty][tx + kPolyN + k] * gk;
+            s0 += a0;
+            sx += a0 * (float)k;
+            sxx += a0 * (float)(k * k);
+            sy += a1;
+            sxy += a1 * (float)k;
+            syy += a2;
+        }
+        const size_t gi = g.off[lvl] + (size_t)gy * w + gx;
+        const float axx = (sxx - fw.m2 * s0) * fw.inv_den;
+        const float ayy = (syy - fw.m2 * s0) * fw.inv_den;
+        const float axy = sxy * fw.inv_2m2sq;
+        A_out[gi] = make_float4(axx, axy, ayy, 0.0f);
+        b_out[gi] = make_float2(sx * fw.inv_m2, sy * fw.inv_m2);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+// bilinear sample of a float2 field at real (y, x), coordinates clamped to the image
+__device__ __forceinline__ float2 bilerp2(const float2* __restrict__ f, int h, int w, float y, float x) {
+    y = clampf(y, 0.0f, (float)(h - 1));
+    x = clampf(x, 0.0f, (float)(w - 1));
+    const float fy0 = floorf(y), fx0 = floorf(x);
+    const int y0 = (int)fy0, x0 = (int)fx0;
+    const int y1 = min(y0 + 1, h - 1), x1 = min(x0 + 1, w - 1);
+    const float wy = y - fy0, wx = x - fx0;
+    const float2 a = f[(size_t)y0 * w + x0], b = f[(size_t)y0 * w + x1];
+    const float2 c = f[(size_t)y1 * w + x0], d = f[(size_t)y1 * w + x1];
+    const float tx = a.x * (1.0f - wx) + b.x * wx, ty = a.y * (1.0f - wx) + b.y * wx;
+    const float bx = c.x * (1.0f - wx) + d.x * wx, by = c.y * (1.0f - wx) + d.y * wx;
+    return make_float2(tx * (1.0f - wy) + bx * wy, ty * (1.0f - wy) + by * wy);
+}
+
+// prior displacement of a pixel: 0 (coarsest level), 2 * bilinear(coarser flow; y/2, x/2) for
+// the first update of a finer level, or the previous update's result
+__device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int mode, int gy, int gx, int w, int ch,
+                                           int cw) {
+    if (mode == 0) return make_float2(0.0f, 0.0f);
+    if (mode == 1) {
+        const float2 c = bilerp2(d_in, ch, cw, 0.5f * (float)gy, 0.5f * (float)gx);
+        return make_float2(2.0f * c.x, 2.0f * c.y);
+    }
+    return d_in[(size_t)gy * w + gx];
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1, const float2* __restrict__ b1,
+                                                   const float4* __restrict__ A2, const float2* __restrict__ b2,
+                                                   const float2* __restrict__ d_in, float2* __restrict__ d_out,
+                                                   int h, int w, int ch, int cw, int prior_mode, FlowWeights fw) {
+    __shared__ float s_in[5][kFR][kFR + 1];
+    __shared__ float s_row[5][kFR][kT];
+
+    const int tid = threadIdx.x;
+    const int x0 = blockIdx.x * kT, y0 = blockIdx.y * kT;
+
+    // per-cell A^T A and A^T db at the clamped coordinate of the cell
+    for (int p = tid; p < kFR * kFR; p += 256) {
+        const int ry = p / kFR, rx = p % kFR;
+        const int gy = clampi(y0 - kWinR + ry, 0, h - 1), gx = clampi(x0 - kWinR + rx, 0, w - 1);
+        const size_t gi = (size_t)gy * w + gx;
+        const float2 dp = prior_at(d_in, prior_mode, gy, gx, w, ch, cw);
+        // sample the new frame's expansion at x + prior
+        const float sy = clampf((float)gy + dp.y, 0.0f, (float)(h - 1));
+        const float sx = clampf((float)gx + dp.x, 0.0f, (float)(w - 1));
+        const float fy0 = floorf(sy), fx0 = floorf(sx);
+        const int iy0 = (int)fy0, ix0 = (int)fx0;
+        const int iy1 = min(iy0 + 1, h - 1), ix1 = min(ix0 + 1, w - 1);
+        const float wy = sy - fy0, wx = sx - fx0;
+        const size_t i00 = (size_t)iy0 * w + ix0, i01 = (size_t)iy0 * w + ix1;
+        const size_t i10 = (size_t)iy1 * w + ix0, i11 = (size_t)iy1 * w + ix1;
+        const float4 a00 = A2[i00], a01 = A2[i01], a10 = A2[i10], a11 = A2[i11];
+        const float2 c00 = b2[i00], c01 = b2[i01], c10 = b2[i10], c11 = b2[i11];
+        const float w00 = (1.0f - wx) * (1.0f - wy), w01 = wx * (1.0f - wy), w10 = (1.0f - wx) * wy, w11 = wx * wy;
+        const float a2xx = a00.x * w00 + a01.x * w01 + a10.x * w10 + a11.x * w11;
+        const float a2xy = a00.y * w00 + a01.y * w01 + a10.y * w10 + a11.y * w11;
+        const float a2yy = a00.z * w00 + a01.z * w01 + a10.z * w10 + a11.z * w11;
+        const float b2x = c00.x * w00 + c01.x * w01 + c10.x * w10 + c11.x * w11;
+        const float b2y = c00.y * w00 + c01.y * w01 + c10.y * w10 + c11.y * w11;
+        const float4 a1 = A1[gi];
+        const float2 bb1 = b1[gi];
+        const float axx = 0.5f * (a1.x + a2xx), axy = 0.5f * (a1.y + a2xy), ayy = 0.5f * (a1.z + a2yy);
+        const float dbx = -0.5f * (b2x - bb1.x) + axx * dp.x + axy * dp.y;
+        const float dby = -0.5f * (b2y - bb1.y) + axy * dp.x + ayy * dp.y;
+        s_in[0][ry][rx] = axx * axx + axy * axy;
+        s_in[1][ry][rx] = axy * (axx + ayy);
+        s_in[2][ry][rx] = axy * axy + ayy * ayy;
+        s_in[3][ry][rx] = axx * dbx + axy * dby;
+        s_in[4][ry][rx] = axy * dbx + ayy * dby;
+    }
+    __syncthreads();
+
+    // row pass of the separable Gaussian window
+    for (int p = tid; p < kFR * kT; p += 256) {
+        const int ry = p / kT, tx = p % kT;
+        float acc[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k <= 2 * kWinR; ++k) {
+            const float wk = fw.win_g[k];
+#pragma unroll
+            for (int c = 0; c < 5; ++c) acc[c] += wk * s_in[c][ry][tx + k];
+        }
+#pragma unroll
+        for (int c = 0; c < 5; ++c) s_row[c][ry][tx] = acc[c];
+    }
+    __syncthreads();
+
+    // column pass + ridge solve
+    for (int p = tid; p < kT * kT; p += 256) {
+        const int ty = p / kT, tx = p % kT;
+        const int gy = y0 + ty, gx = x0 + tx;
+        if (gy >= h || gx >= w) continue;
+        float acc[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k <= 2 * kWinR; ++k) {
+            const float wk = fw.win_g[k];
+#pragma unroll
+            for (int c = 0; c < 5; ++c) acc[c] += wk * s_row[c][ty + k][tx];
+        }
+        const float2 dp = prior_at(d_in, prior_mode, gy, gx, w, ch, cw);
+        const float lam = kLamAbs + kLamRel * 0.5f * (acc[0] + acc[2]);
+        const float m11 = acc[0] + lam, m22 = acc[2] + lam, m12 = acc[1];
+        const float r1 = acc[3] + lam * dp.x, r2 = acc[4] + lam * dp.y;
+        const float det = m11 * m22 - m12 * m12;
+        d_out[(size_t)gy * w + gx] = make_float2((m22 * r1 - m12 * r2) / det, (m11 * r2 - m12 * r1) / det);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 5 / Eq. 6.  One block per patch; the last block to arrive evaluates the gate.
+__global__ __launch_bounds__(256) void k_patch_gate(const float2* __restrict__ flow, int h, int w, float tau_t,
+                                                    float theta_r, float* dp_out, sali_gate* gate, Cursors* cur,
+                                                    float* __restrict__ flow_uv) {
+    __shared__ float s_part[4];
+    __shared__ int s_cnt[4];
+    __shared__ int s_last;
+    const int pr = blockIdx.x / kGrid, pc = blockIdx.x % kGrid;
+    const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
+    const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
+    const int pw = xb - xa, area = pw * (yb - ya);
+    float acc = 0.0f;
+    for (int p = threadIdx.x; p < area; p += 256) {
+        const int y = ya + p / pw, x = xa + p % pw;
+        const float2 d = flow[(size_t)y * w + x];
+        acc += d.x * d.x + d.y * d.y;
+        if (flow_uv != nullptr) {
+            flow_uv[(size_t)y * w + x] = d.x;
+            flow_uv[(size_t)h * w + (size_t)y * w + x] = d.y;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float total = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+        __hip_atomic_store(dp_out + blockIdx.x, sqrtf(total / (float)area), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        const uint32_t prev = atomicAdd(&cur->patch_done, 1u);
+        s_last = (prev == (uint32_t)(kTokens - 1)) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    int n = 0;
+    for (int i = threadIdx.x; i < kTokens; i += 256) {
+        const float v = __hip_atomic_load(dp_out + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        n += (v < tau_t) ? 1 : 0;
+    }
+    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        const float r = (float)n_static / (float)kTokens;
+        sali_gate gt;
+        gt.n_static = n_static;
+        gt.r_frame = r;
+        gt.redundant = (r > theta_r) ? 1 : 0;
+        gt.reserved = 0;
+        *gate = gt;
+        cur->patch_done = 0u;       // ready for the next launch
+    }
+}
+
+__global__ void k_clear_gate(float* dp, sali_gate* gate) {
+    for (int i = threadIdx.x; i < kTokens; i += blockDim.x) dp[i] = 0.0f;
+    if (threadIdx.x == 0) {
+        sali_gate gt = {0, 0.0f, 0, 0};
+        *gate = gt;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
+                           int dh, int dw, hipStream_t s) {
+    dim3 grid((dw + 63) / 64, (dh + 3) / 4);
+    hipLaunchKernelGGL(k_pyr_down, grid, dim3(256), 0, s, d_y8_or_null, d_src_or_null, sh, sw, d_dst, dh, dw);
+    return hipGetLastError();
+}
+
+hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
+                          float2* d_b, hipStream_t s) {
+    hipLaunchKernelGGL(k_polyexp, dim3(g.tile_start[g.levels]), dim3(256), 0, s, d_y8, d_pyr, g, fw, d_A, d_b);
+    return hipGetLastError();
+}
+
+hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2, const float2* b2,
+                            const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
+                            FlowWeights fw, hipStream_t s) {
+    dim3 grid((w + kT - 1) / kT, (h + kT - 1) / kT);
+    hipLaunchKernelGGL(k_flow_iter, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw, prior_mode, fw);
+    return hipGetLastError();
+}
+
+hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
+                             sali_gate* d_gate, Cursors* d_cur, float* d_flow_uv_or_null, hipStream_t s) {
+    hipLaunchKernelGGL(k_patch_gate, dim3(kTokens), dim3(256), 0, s, d_flow, h, w, tau_t, theta_r, d_dp, d_gate,
+                       d_cur, d_flow_uv_or_null);
+    return hipGetLastError();
+}
+
+hipError_t launch_clear_gate(float* d_dp, sali_gate* d_gate, hipStream_t s) {
+    hipLaunchKernelGGL(k_clear_gate, dim3(1), dim3(256), 0, s, d_dp, d_gate);
+    return hipGetLastError();
+}
+
+}  // namespace sali

@@ -1,0 +1,108 @@
+// Internal declarations shared by the host API and the kernel files of libsali.
+// gfx950 only; wave size 64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sali.h"
+
+namespace sali {
+
+constexpr int kGrid = 24;
+constexpr int kTokens = kGrid * kGrid;      // 576 visual tokens per frame
+constexpr int kHeadDim = 128;
+constexpr int kGroup = 32;                  // quantisation group along head_dim
+constexpr int kGroupsPerRow = kHeadDim / kGroup;
+constexpr int kMaxLevels = 6;
+constexpr int kMaxIters = 8;
+
+// flow constants (polynomial expansion 7x7 sigma 1.5; aggregation window 11x11 sigma 2.5;
+// prior-centred ridge term lambda = kLamAbs + kLamRel * trace(G) / 2)
+constexpr int kPolyN = 3;
+constexpr float kPolySigma = 1.5f;
+constexpr int kWinR = 5;
+constexpr float kWinSigma = 2.5f;
+constexpr float kLamAbs = 1e-4f;
+constexpr float kLamRel = 1e-2f;
+
+constexpr uint32_t kVMin = 10000u;          // floor of the colour-variance mask
+
+// Device-resident bookkeeping (lives in the caller's table buffer).
+struct Cursors {
+    int32_t c16, c8, c4;        // next free row of each pool
+    int32_t last_src;           // frame id of the last stored frame, -1 = none
+    uint32_t status;            // sticky SALI_FAULT_* bits
+    uint32_t patch_done;        // arrival counter of the patch-motion kernel (self-resetting)
+    uint32_t pad[2];
+};
+
+struct Pools {
+    uint16_t* p16;              // fp16 bit patterns
+    int8_t* c8;
+    float* s8;
+    uint8_t* c4;
+    float* s4;
+    uint16_t* z4;
+    int32_t cap16, cap8, cap4;
+};
+
+struct TierParams {
+    int32_t mode;
+    float tau_high, tau_med, tau_low;
+    int32_t k16, k8, k4;
+};
+
+struct LevelGeom {
+    int32_t h[kMaxLevels];
+    int32_t w[kMaxLevels];
+    int64_t off[kMaxLevels];    // pixel offset of the level inside a concatenated per-level array
+    int32_t tiles_x[kMaxLevels];
+    int32_t tile_start[kMaxLevels + 1];   // first block index of each level in a fused launch
+    int32_t levels;
+};
+
+struct FlowWeights {
+    float poly_g[2 * kPolyN + 1];    // normalised Gaussian of the expansion
+    float win_g[2 * kWinR + 1];      // normalised Gaussian of the aggregation window
+    float inv_m2;                    // 1 / m2
+    float inv_den;                   // 1 / (m4 - m2^2)
+    float inv_2m2sq;                 // 1 / (2 m2^2)
+    float m2;
+};
+
+// ---- launchers (each returns hipGetLastError()) ---------------------------------------------
+// kv_kernels.hip
+hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,
+                       sali_frame_row* d_rows, uint8_t* d_tier, uint16_t* d_slot, uint16_t* d_order,
+                       Cursors* d_cur, Pools pools, hipStream_t s);
+hipError_t launch_pack(const void* d_kv, const sali_frame_row* d_row, const uint16_t* d_order, Pools pools,
+                       Cursors* d_cur, int n_planes, hipStream_t s);
+hipError_t launch_unpack(const sali_frame_row* d_rows, int frame_id, const uint16_t* d_order_base, Pools pools,
+                         void* d_out, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes, hipStream_t s);
+
+// saliency_kernels.hip
+hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
+                       uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
+                       unsigned long long* d_msum_clear, const uint16_t* d_lin, const uint16_t* d_fl,
+                       int lo2, int hi2, hipStream_t s);
+hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, const sali_gate* d_gate_or_null,
+                        hipStream_t s);
+hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
+                       const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
+                       float* d_scores, uint8_t* d_salmap_or_null, hipStream_t s);
+
+// flow_kernels.hip
+hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
+                           int dh, int dw, hipStream_t s);
+hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
+                          float2* d_b, hipStream_t s);
+hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2, const float2* b2,
+                            const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
+                            FlowWeights fw, hipStream_t s);
+hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
+                             sali_gate* d_gate, Cursors* d_cur, float* d_flow_uv_or_null, hipStream_t s);
+hipError_t launch_clear_gate(float* d_dp, sali_gate* d_gate, hipStream_t s);
+
+}  // namespace sali

@@ -1,0 +1,303 @@
+// Saliency map (Canny edges + LAB colour variance) and patch pooling for gfx950.
+//
+// Spatial Filtering via Saliency-Guided Quantization (saliency map S, Eq. 7) and
+// Implementation Details (Canny edge detection combined with adaptive thresholding on the
+// local colour variance in LAB).  Everything here is integer arithmetic, so scores are exact.
+//
+//   k_prep   one pass over the RGB frame, 32x32 tiles with a 4-pixel halo staged in LDS:
+//            gray -> 5x5 binomial blur -> Sobel -> squared magnitude -> non-maximum suppression
+//            -> weak/strong class, and RGB -> 8-bit LAB -> 5x5 variance sum V, plus the frame
+//            sum of V (one 64-bit atomic per block).  Also emits the gray image for the flow.
+//   k_union  8-connected hysteresis as a lock-free union-find over weak/strong pixels.  A
+//            pixel's key is its index with bit 31 set for weak pixels; links always point to
+//            the smaller key, so the root of a component is a strong pixel iff it has one.
+//   k_pool   per patch: E = edge pixel whose root is strong, C = V above the frame mean and
+//            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.
+//
+// All stencils replicate the border; non-maximum suppression treats out-of-image neighbours
+// as magnitude 0.
+
+#include "sali_internal.h"
+
+namespace sali {
+
+namespace {
+
+constexpr int kTile = 32;
+constexpr int kHalo = 4;
+constexpr int kReg = kTile + 2 * kHalo;        // 40: gray region
+constexpr int kRegB = kTile + 4;               // 36: blur / LAB region (halo 2)
+constexpr int kRegM = kTile + 2;               // 34: gradient-magnitude region (halo 1)
+constexpr uint32_t kWeakBit = 0x80000000u;
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+}  // namespace
+
+__global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, int h, int w, int with_saliency,
+                                              uint8_t* __restrict__ y8_out, uint8_t* __restrict__ cls_out,
+                                              uint32_t* __restrict__ var_out, uint32_t* __restrict__ parent_out,
+                                              unsigned long long* msum_acc, unsigned long long* msum_clear,
+                                              const uint16_t* __restrict__ lut_lin,
+                                              const uint16_t* __restrict__ lut_fl, int lo2, int hi2) {
+    __shared__ uint8_t s_y[kReg][kReg];
+    __shared__ uint8_t s_b[kRegB][kRegB];
+    __shared__ int s_m2[kRegM][kRegM];
+    __shared__ uint8_t s_lab[3][kRegB][kRegB];
+    __shared__ unsigned long long s_sum[4];
+
+    const int tid = threadIdx.x;
+    const int x0 = blockIdx.x * kTile, y0 = blockIdx.y * kTile;
+
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0 && msum_clear != nullptr) *msum_clear = 0ull;
+
+    // stage 1: gray (halo 4) and LAB (halo 2) at clamped image coordinates
+    for (int p = tid; p < kReg * kReg; p += 256) {
+        const int ry = p / kReg, rx = p % kReg;
+        const int gy = clampi(y0 - kHalo + ry, 0, h - 1), gx = clampi(x0 - kHalo + rx, 0, w - 1);
+        const uint8_t* px = rgb + ((size_t)gy * w + gx) * 3;
+        const int r = px[0], g = px[1], b = px[2];
+        s_y[ry][rx] = (uint8_t)((77 * r + 150 * g + 29 * b + 128) >> 8);
+        if (with_saliency && ry >= 2 && ry < kReg - 2 && rx >= 2 && rx < kReg - 2) {
+            const int lr = lut_lin[r], lg = lut_lin[g], lb = lut_lin[b];
+            const int tx = (1777 * lr + 1541 * lg + 778 * lb + 2048) >> 12;
+            const int ty = (871 * lr + 2929 * lg + 296 * lb + 2048) >> 12;
+            const int tz = (73 * lr + 448 * lg + 3575 * lb + 2048) >> 12;
+            const int fx = lut_fl[tx], fy = lut_fl[ty], fz = lut_fl[tz];
+            const int L = clampi(((116 * fy - 524288) * 255 + 1638400) / 3276800, 0, 255);
+            const int A = clampi((500 * (fx - fy) + 4194304 + 16384) >> 15, 0, 255);
+            const int B = clampi((200 * (fy - fz) + 4194304 + 16384) >> 15, 0, 255);
+            s_lab[0][ry - 2][rx - 2] = (uint8_t)L;
+            s_lab[1][ry - 2][rx - 2] = (uint8_t)A;
+            s_lab[2][ry - 2][rx - 2] = (uint8_t)B;
+        }
+    }
+    __syncthreads();
+
+    // gray image for the flow pyramid
+    for (int p = tid; p < kTile * kTile; p += 256) {
+        const int ty = p / kTile, tx = p % kTile;
+        const int gy = y0 + ty, gx = x0 + tx;
+        if (gy < h && gx < w) y8_out[(size_t)gy * w + gx] = s_y[ty + kHalo][tx + kHalo];
+    }
+    if (!with_saliency) return;
+
+    // Region arrays are indexed by (image coordinate - region origin).  A stage evaluates its
+    // stencil at the CLAMPED image coordinate c of each region cell and reads its input at
+    // clamp(c + offset); both stay inside the previous stage's region.
+    const int oy_y = y0 - kHalo, ox_y = x0 - kHalo;      // origin of s_y
+    const int oy_b = y0 - 2, ox_b = x0 - 2;              // origin of s_b / s_lab
+    const int oy_m = y0 - 1, ox_m = x0 - 1;              // origin of s_m2
+
+    // stage 2: 5x5 binomial blur, (sum + 128) >> 8
+    for (int p = tid; p < kRegB * kRegB; p += 256) {
+        const int ry = p / kRegB, rx = p % kRegB;
+        const int cy = clampi(oy_b + ry, 0, h - 1), cx = clampi(ox_b + rx, 0, w - 1);
+        const int kw[5] = {1, 4, 6, 4, 1};
+        int acc = 0;
+#pragma unroll
+        for (int a = -2; a <= 2; ++a) {
+            const int yy = clampi(cy + a, 0, h - 1) - oy_y;
+            int rowacc = 0;
+#pragma unroll
+            for (int b = -2; b <= 2; ++b) {
+                const int xx = clampi(cx + b, 0, w - 1) - ox_y;
+                rowacc += kw[b + 2] * s_y[yy][xx];
+            }
+            acc += kw[a + 2] * rowacc;
+        }
+        s_b[ry][rx] = (uint8_t)((acc + 128) >> 8);
+    }
+    __syncthreads();
+
+    // stage 3: Sobel squared magnitude on the 34x34 region; cells outside the image hold 0
+    // (that is what non-maximum suppression wants to see there)
+    for (int p = tid; p < kRegM * kRegM; p += 256) {
+        const int ry = p / kRegM, rx = p % kRegM;
+        const int gy = oy_m + ry, gx = ox_m + rx;
+        int m2 = 0;
+        if (gy >= 0 && gy < h && gx >= 0 && gx < w) {
+            const int ym = clampi(gy - 1, 0, h - 1) - oy_b, yc = gy - oy_b, yp = clampi(gy + 1, 0, h - 1) - oy_b;
+            const int xm = clampi(gx - 1, 0, w - 1) - ox_b, xc = gx - ox_b, xp = clampi(gx + 1, 0, w - 1) - ox_b;
+            const int sgx = (s_b[ym][xp] + 2 * s_b[yc][xp] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[yc][xm] + s_b[yp][xm]);
+            const int sgy = (s_b[yp][xm] + 2 * s_b[yp][xc] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[ym][xc] + s_b[ym][xp]);
+            m2 = sgx * sgx + sgy * sgy;
+        }
+        s_m2[ry][rx] = m2;
+    }
+    __syncthreads();
+
+    // stage 4: per output pixel - non-maximum suppression + class, colour variance
+    unsigned long long local_sum = 0ull;
+    for (int p = tid; p < kTile * kTile; p += 256) {
+        const int ty = p / kTile, tx = p % kTile;
+        const int gy = y0 + ty, gx = x0 + tx;
+        if (gy >= h || gx >= w) continue;
+        // gradient at the pixel (recomputed; cheaper than keeping two more LDS planes)
+        const int ym = clampi(gy - 1, 0, h - 1) - oy_b, yc = gy - oy_b, yp = clampi(gy + 1, 0, h - 1) - oy_b;
+        const int xm = clampi(gx - 1, 0, w - 1) - ox_b, xc = gx - ox_b, xp = clampi(gx + 1, 0, w - 1) - ox_b;
+        const int sgx = (s_b[ym][xp] + 2 * s_b[yc][xp] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[yc][xm] + s_b[yp][xm]);
+        const int sgy = (s_b[yp][xm] + 2 * s_b[yp][xc] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[ym][xc] + s_b[ym][xp]);
+        const int m2 = sgx * sgx + sgy * sgy;
+        const int ax = abs(sgx), ay = abs(sgy);
+        const int s2 = (ax + ay) * (ax + ay);
+        int dy1, dx1;                     // first-listed neighbour; the second is its mirror
+        if (s2 < 2 * sgx * sgx) { dy1 = 0; dx1 = -1; }
+        else if (s2 < 2 * sgy * sgy) { dy1 = -1; dx1 = 0; }
+        else if (sgx * sgy > 0) { dy1 = -1; dx1 = -1; }
+        else { dy1 = -1; dx1 = 1; }
+        const int my = ty + 1, mx = tx + 1;
+        const int n1 = s_m2[my + dy1][mx + dx1];
+        const int n2 = s_m2[my - dy1][mx - dx1];
+        int cls = 0;
+        if (m2 > n1 && m2 >= n2) cls = m2 >= hi2 ? 2 : (m2 >= lo2 ? 1 : 0);
+        const size_t gi = (size_t)gy * w + gx;
+        cls_out[gi] = (uint8_t)cls;
+        parent_out[gi] = (uint32_t)gi | (cls == 1 ? kWeakBit : 0u);
+
+        // 5x5 colour variance: 25 * sum v^2 - (sum v)^2 per channel
+        uint32_t v = 0;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            int s1 = 0, sq = 0;
+#pragma unroll
+            for (int a = -2; a <= 2; ++a) {
+                const int yy = clampi(gy + a, 0, h - 1) - oy_b;
+#pragma unroll
+                for (int b = -2; b <= 2; ++b) {
+                    const int xx = clampi(gx + b, 0, w - 1) - ox_b;
+                    const int val = s_lab[c][yy][xx];
+                    s1 += val;
+                    sq += val * val;
+                }
+            }
+            v += (uint32_t)(25 * sq - s1 * s1);
+        }
+        var_out[gi] = v;
+        local_sum += v;
+    }
+    // block sum -> one atomic
+    for (int off = 32; off > 0; off >>= 1) local_sum += __shfl_down(local_sum, off);
+    if ((tid & 63) == 0) s_sum[tid >> 6] = local_sum;
+    __syncthreads();
+    if (tid == 0) atomicAdd(msum_acc, s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
+}
+
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+__device__ __forceinline__ uint32_t load_parent(const uint32_t* parent, uint32_t idx) {
+    return __hip_atomic_load(parent + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint32_t find_root(const uint32_t* parent, uint32_t key) {
+    // keys strictly decrease along links, so this terminates
+    uint32_t k = key;
+    for (;;) {
+        const uint32_t p = load_parent(parent, k & ~kWeakBit);
+        if (p == k) return k;
+        k = p;
+    }
+}
+
+__device__ void unite(uint32_t* parent, uint32_t ka, uint32_t kb) {
+    for (;;) {
+        ka = find_root(parent, ka);
+        kb = find_root(parent, kb);
+        if (ka == kb) return;
+        if (ka < kb) { const uint32_t t = ka; ka = kb; kb = t; }      // ka is the larger key
+        const uint32_t old = atomicMin(parent + (ka & ~kWeakBit), kb);
+        if (old == ka) return;      // ka was a root and now points at kb
+        ka = old;                   // somebody linked ka first: continue from where it pointed
+    }
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, uint32_t* parent, int h, int w,
+                                               const sali_gate* gate) {
+    if (gate != nullptr && gate->redundant != 0) return;
+    const int x = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (x >= w || y >= h) return;
+    const size_t gi = (size_t)y * w + x;
+    const int c = cls[gi];
+    if (c == 0) return;
+    const uint32_t me = (uint32_t)gi | (c == 1 ? kWeakBit : 0u);
+    // forward half of the 8-neighbourhood: E, SW, S, SE
+    const int ny[4] = {0, 1, 1, 1};
+    const int nx[4] = {1, -1, 0, 1};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int yy = y + ny[k], xx = x + nx[k];
+        if (yy >= h || xx < 0 || xx >= w) continue;
+        const size_t gj = (size_t)yy * w + xx;
+        const int cj = cls[gj];
+        if (cj == 0) continue;
+        unite(parent, me, (uint32_t)gj | (cj == 1 ? kWeakBit : 0u));
+    }
+}
+
+// one block per patch
+__global__ __launch_bounds__(256) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
+                                              const uint32_t* __restrict__ var, const unsigned long long* msum,
+                                              int h, int w, const sali_gate* gate, float* __restrict__ scores,
+                                              uint8_t* __restrict__ salmap) {
+    if (gate != nullptr && gate->redundant != 0) return;
+    __shared__ uint32_t s_q[4];
+    const int pr = blockIdx.x / kGrid, pc = blockIdx.x % kGrid;
+    const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
+    const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
+    const int pw = xb - xa, area = pw * (yb - ya);
+    const unsigned long long m = *msum;
+    const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
+    uint32_t q = 0;
+    for (int p = threadIdx.x; p < area; p += 256) {
+        const int y = ya + p / pw, x = xa + p % pw;
+        const size_t gi = (size_t)y * w + x;
+        const int c = cls[gi];
+        uint32_t e = 0;
+        if (c == 2) e = 1;
+        else if (c == 1) e = (find_root(parent, (uint32_t)gi | kWeakBit) & kWeakBit) ? 0u : 1u;
+        const uint32_t v = var[gi];
+        const uint32_t cm = ((unsigned long long)v * hw > m && v >= kVMin) ? 1u : 0u;
+        q += e + cm;
+        if (salmap != nullptr) salmap[gi] = (uint8_t)(e + cm);
+    }
+    for (int off = 32; off > 0; off >>= 1) q += __shfl_down(q, off);
+    if ((threadIdx.x & 63) == 0) s_q[threadIdx.x >> 6] = q;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t total = s_q[0] + s_q[1] + s_q[2] + s_q[3];
+        const uint32_t s_fix = (uint32_t)(((unsigned long long)total << 15) / (unsigned long long)area);
+        scores[blockIdx.x] = (float)s_fix * (1.0f / 65536.0f);     // exact: s_fix <= 2^16
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
+                       uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
+                       unsigned long long* d_msum_clear, const uint16_t* d_lin, const uint16_t* d_fl,
+                       int lo2, int hi2, hipStream_t s) {
+    dim3 grid((w + kTile - 1) / kTile, (h + kTile - 1) / kTile);
+    hipLaunchKernelGGL(k_prep, grid, dim3(256), 0, s, d_rgb, h, w, with_saliency ? 1 : 0, d_y8, d_cls, d_var,
+                       d_parent, d_msum_acc, d_msum_clear, d_lin, d_fl, lo2, hi2);
+    return hipGetLastError();
+}
+
+hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, const sali_gate* d_gate_or_null,
+                        hipStream_t s) {
+    dim3 grid((w + 63) / 64, (h + 3) / 4);
+    hipLaunchKernelGGL(k_union, grid, dim3(256), 0, s, d_cls, d_parent, h, w, d_gate_or_null);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
+                       const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
+                       float* d_scores, uint8_t* d_salmap_or_null, hipStream_t s) {
+    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(256), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
+                       d_gate_or_null, d_scores, d_salmap_or_null);
+    return hipGetLastError();
+}
+
+}  // namespace sali

@@ -251,7 +251,7 @@ def _plan_frames(wl: Workload, n: int):
                     src = plan[src][1]
                 plan.append(("split", (src, _split_scene(wl), _SPLIT_SHIFT, _SPLIT_X)))
             elif t == split_at - 1:
-                plan.append(("scene", (_split_scene(wl), np.zeros((0, 2)), False)))
+                plan.append(("scene", (_split_scene(wl), np.zeros((1, 2)), False)))
             else:
                 plan.append(("scene", (scene, off.copy(), True)))
         return plan

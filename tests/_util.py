@@ -1,0 +1,72 @@
+"""Shared helpers of the GPU parity tests: one parameter dict -> library config and oracle config."""
+import numpy as np
+
+from oracle.cache import OracleConfig
+
+FLOW_RTOL = 1e-3
+FLOW_ATOL = 1e-4
+
+
+def params(src_h=336, src_w=336, **kw):
+    p = dict(src_h=src_h, src_w=src_w, flow_levels=3, flow_iters=3, tau_t=0.5, theta_r=0.90, canny_lo=50,
+             canny_hi=100, tier_mode=0, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0,
+             n_layers=1, n_heads=2, cap_fp16=1200, cap_int8=1200, cap_int4=1200, max_frames=8)
+    p.update(kw)
+    return p
+
+
+def lib_config(p):
+    from paper_2602_14236_amd import binding
+    return binding.make_config(p["src_h"], p["src_w"], **{k: v for k, v in p.items() if k not in ("src_h", "src_w")})
+
+
+def oracle_config(p):
+    return OracleConfig(grid=24, head_dim=128, **p)
+
+
+def workload_params(wl, frames=None, n_layers=None, n_heads=None, **kw):
+    """Parameters of a benchmark workload (paper_2602_14236_amd.synth.Workload), optionally cut down."""
+    frames = wl.frames if frames is None else frames
+    nl = wl.n_layers if n_layers is None else n_layers
+    nh = wl.n_heads if n_heads is None else n_heads
+    if wl.tier_mode == 1:
+        caps = dict(cap_fp16=wl.k_fp16 * frames, cap_int8=wl.k_int8 * frames, cap_int4=wl.k_int4 * frames)
+    else:
+        caps = dict(cap_fp16=576 * frames, cap_int8=576 * frames, cap_int4=576 * frames)
+    p = params(wl.height, wl.width, flow_levels=wl.flow_levels, tier_mode=wl.tier_mode, k_fp16=wl.k_fp16,
+               k_int8=wl.k_int8, k_int4=wl.k_int4, n_layers=nl, n_heads=nh, max_frames=frames, **caps)
+    p.update(kw)
+    return p
+
+
+def close(a, b, rtol=FLOW_RTOL, atol=FLOW_ATOL):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return np.abs(a - b) <= atol + rtol * np.abs(b)
+
+
+def pool_arrays(ctx):
+    """Pool contents as numpy arrays shaped like the oracle's [n_l, 2, n_h, cap, row]."""
+    c = ctx.cfg
+    v = ctx.pool_views()
+    shp = (c.n_layers, 2, c.n_heads)
+    out = {}
+    for k, t in v.items():
+        a = t.cpu().numpy()
+        out[k] = a.reshape(shp + a.shape[1:])
+    return out
+
+
+def assert_same(got, exp, name):
+    """Bit-exact comparison that reports a short summary instead of dumping the arrays."""
+    got = np.asarray(got)
+    exp = np.asarray(exp)
+    assert got.shape == exp.shape, f"{name}: shape {got.shape} != {exp.shape}"
+    if got.dtype.kind == "f":
+        got = got.view({2: np.uint16, 4: np.uint32, 8: np.uint64}[got.dtype.itemsize])
+        exp = exp.view(got.dtype)
+    bad = np.argwhere(got != exp)
+    if bad.size:
+        first = [tuple(int(v) for v in b) for b in bad[:4]]
+        vals = [(got[b], exp[b]) for b in first]
+        raise AssertionError(f"{name}: {len(bad)} of {got.size} differ; first at {first}: (got, expected) = {vals}")

@@ -1,0 +1,205 @@
+"""GPU parity: tiering, compaction, K/V pack and dequantise-on-read against the oracle, through the C ABI.
+Integer codes, scales, zero-points, tiers, slots, rows and dequantised fp16 values must be bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import quant as oq
+from oracle.cache import SaliCacheOracle
+
+from _util import assert_same, lib_config, oracle_config, params, pool_arrays
+
+pytestmark = pytest.mark.gpu
+
+
+def _kv(seed, nl, nh, heavy=False):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.randn((nl, 2, nh, 576, 128), generator=g, device="cuda")
+    if heavy:
+        x = x * torch.exp(2.0 * torch.randn((nl, 2, nh, 1, 128), generator=g, device="cuda"))
+    return x.clamp_(-65504, 65504).to(torch.float16)
+
+
+def _scores(seed, mode):
+    rng = np.random.default_rng(seed)
+    if mode == "coarse":          # many exact ties, every tier populated
+        return (rng.integers(0, 40, 576) / 64.0).astype(np.float32)
+    if mode == "fine":
+        return rng.uniform(0, 1, 576).astype(np.float32)
+    if mode == "zeros":
+        return np.zeros(576, dtype=np.float32)
+    raise ValueError(mode)
+
+
+def _compare_state(ctx, orc, frames):
+    rows = ctx.read_frame_table(0, len(frames))
+    for f in frames:
+        assert rows[f].as_tuple() == orc.rows[f].as_tuple(), f"row {f}"
+        if orc.rows[f].stored:
+            tier, slot = ctx.read_frame_tiers(f)
+            assert_same(tier, orc.tier[f], f"tier {f}")
+            assert_same(slot.astype(np.int32), orc.slot[f], f"slot {f}")
+    pa = pool_arrays(ctx)
+    c16, c8, c4 = orc.cursor
+    assert_same(pa["fp16"][..., :c16, :], orc.pool16[..., :c16, :], "fp16 pool")
+    assert_same(pa["codes8"][..., :c8, :], orc.codes8[..., :c8, :], "int8 codes")
+    assert_same(pa["scale8"][..., :c8, :], orc.scale8[..., :c8, :], "int8 scales")
+    assert_same(pa["codes4"][..., :c4, :], orc.codes4[..., :c4, :], "int4 codes")
+    assert_same(pa["scale4"][..., :c4, :], orc.scale4[..., :c4, :], "int4 scales")
+    assert_same(pa["zero4"][..., :c4, :], orc.zero4[..., :c4, :], "int4 zero-points")
+
+
+def _compare_decompress(ctx, orc, f):
+    c = ctx.cfg
+    out = torch.full((c.n_layers, 2, c.n_heads, 576, 128), 7.0, dtype=torch.float16, device="cuda")
+    valid = torch.full((576,), 9, dtype=torch.uint8, device="cuda")
+    ctx.kv_decompress(f, out, valid)
+    torch.cuda.synchronize()
+    exp, exp_valid = orc.kv_decompress(f)
+    got = out.cpu().numpy()
+    tier = orc.tier[orc.rows[f].src]
+    for t, name in enumerate(("fp16", "int8", "int4", "pruned")):
+        assert_same(got[:, :, :, tier == t], exp[:, :, :, tier == t], f"decompress frame {f} {name} rows")
+    assert_same(valid.cpu().numpy(), exp_valid, "valid mask")
+
+
+@pytest.mark.parametrize("mode,scores,nl,nh", [
+    (0, "coarse", 1, 2), (0, "fine", 2, 3), (1, "coarse", 1, 2), (1, "fine", 1, 5), (0, "zeros", 1, 1),
+])
+def test_compress_then_decompress_three_frames(mode, scores, nl, nh):
+    from paper_2602_14236_amd import binding
+    p = params(tier_mode=mode, k_fp16=173, k_int8=150, k_int4=200, n_layers=nl, n_heads=nh,
+               cap_fp16=1728, cap_int8=1728, cap_int4=1728)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    for f in range(3):
+        print(f"case mode={mode} scores={scores} nl={nl} nh={nh} frame={f}", flush=True)
+        kv = _kv(100 + f, nl, nh, heavy=(f == 2))
+        sc = _scores(7 * f + 1, scores)
+        ctx.kv_compress(kv, torch.from_numpy(sc).cuda(), f)
+        orc.kv_compress(kv.cpu().numpy(), sc, f)
+    torch.cuda.synchronize()
+    assert ctx.get_status() == 0
+    _compare_state(ctx, orc, range(3))
+    for f in range(3):
+        _compare_decompress(ctx, orc, f)
+    ctx.close()
+
+
+@pytest.mark.parametrize("ks", [(576, 0, 0), (0, 576, 0), (0, 0, 576), (0, 0, 0), (1, 1, 1), (63, 65, 129)])
+def test_topk_extreme_counts(ks):
+    from paper_2602_14236_amd import binding
+    p = params(tier_mode=1, k_fp16=ks[0], k_int8=ks[1], k_int4=ks[2], n_layers=1, n_heads=2,
+               cap_fp16=600, cap_int8=600, cap_int4=600)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    kv = _kv(5, 1, 2)
+    sc = _scores(3, "coarse")
+    ctx.kv_compress(kv, torch.from_numpy(sc).cuda(), 0)
+    orc.kv_compress(kv.cpu().numpy(), sc, 0)
+    _compare_state(ctx, orc, [0])
+    _compare_decompress(ctx, orc, 0)
+    ctx.close()
+
+
+def test_special_values_zero_constant_subnormal_groups():
+    from paper_2602_14236_amd import binding
+    p = params(tier_mode=1, k_fp16=100, k_int8=200, k_int4=200, n_layers=1, n_heads=1,
+               cap_fp16=600, cap_int8=600, cap_int4=600)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    kv = _kv(9, 1, 1)
+    kv[0, 0, 0, 0:100, 0:32] = 0.0                 # all-zero groups
+    kv[0, 0, 0, 100:200, 32:64] = 2.5              # constant groups
+    kv[0, 1, 0, 200:300, :] = 6e-8                 # fp16 subnormals
+    kv[0, 1, 0, 300:400, 0:32] = -65504.0          # largest magnitude
+    kv[0, 1, 0, 400:500, 64:96] = torch.tensor([0.5, 1.5, 2.5, 127.0] * 8, dtype=torch.float16)   # exact halves
+    sc = _scores(11, "fine")
+    ctx.kv_compress(kv, torch.from_numpy(sc).cuda(), 0)
+    orc.kv_compress(kv.cpu().numpy(), sc, 0)
+    assert ctx.get_status() == 0
+    _compare_state(ctx, orc, [0])
+    _compare_decompress(ctx, orc, 0)
+    ctx.close()
+
+
+def test_pool_overflow_and_faults_are_reported_not_fatal():
+    from paper_2602_14236_amd import binding
+    p = params(tier_mode=1, k_fp16=100, k_int8=100, k_int4=100, n_layers=1, n_heads=1,
+               cap_fp16=150, cap_int8=150, cap_int4=150, max_frames=4)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    kv = _kv(1, 1, 1)
+    sc = _scores(2, "fine")
+    d_sc = torch.from_numpy(sc).cuda()
+    ctx.kv_compress(kv, d_sc, 0)
+    ctx.kv_compress(kv, d_sc, 1)                   # no room: recorded as not stored, cursors unchanged
+    orc.kv_compress(kv.cpu().numpy(), sc, 0)
+    orc.kv_compress(kv.cpu().numpy(), sc, 1)
+    assert ctx.get_status() == binding.FAULT_OVERFLOW
+    _compare_state(ctx, orc, [0, 1])
+    # decompress of a frame without data: zeros, valid = 0, status bit
+    out = torch.ones((1, 2, 1, 576, 128), dtype=torch.float16, device="cuda")
+    valid = torch.ones(576, dtype=torch.uint8, device="cuda")
+    ctx.kv_decompress(1, out, valid)
+    ctx.kv_decompress(3, out, valid)               # never written
+    torch.cuda.synchronize()
+    assert not out.any() and not valid.any()
+    assert ctx.get_status() & binding.FAULT_NO_DATA
+    # NaN score
+    ctx.reset()
+    bad = d_sc.clone()
+    bad[17] = float("nan")
+    ctx.kv_compress(kv, bad, 0)
+    assert ctx.get_status() == binding.FAULT_NAN_SCORE
+    assert ctx.read_frame_table(0, 1)[0].as_tuple()[:3] == (0, -1, 0)
+    # non-finite K/V value in a kept row
+    ctx.reset()
+    kv2 = kv.clone()
+    kv2[0, 1, 0, :, 5] = float("inf")
+    ctx.kv_compress(kv2, d_sc, 0)
+    assert ctx.get_status() & binding.FAULT_NONFINITE
+    ctx.close()
+
+
+def test_argument_errors_are_synchronous():
+    from paper_2602_14236_amd import binding
+    p = params(max_frames=2)
+    ctx = binding.SaliContext(lib_config(p))
+    kv = _kv(1, 1, 2)
+    sc = torch.zeros(576, device="cuda")
+    with pytest.raises(binding.SaliError) as e:
+        ctx.kv_compress(kv, sc, 2)
+    assert e.value.code == -2
+    with pytest.raises(binding.SaliError) as e:
+        ctx.kv_compress(None, sc, 0)
+    assert e.value.code == -1
+    flat = torch.zeros(kv.numel() + 8, dtype=torch.float16, device="cuda")
+    with pytest.raises(binding.SaliError) as e:
+        ctx.kv_compress(flat[1:], sc, 0)           # 2-byte offset: not 16-byte aligned
+    assert e.value.code == -3
+    with pytest.raises(binding.SaliError) as e:
+        ctx.kv_decompress(-1, kv)
+    assert e.value.code == -2
+    bad = lib_config(params(k_fp16=500, k_int8=100, tier_mode=1))
+    with pytest.raises(binding.SaliError) as e:
+        binding.workspace_bytes(bad)
+    assert e.value.code == -4
+    assert ctx.get_status() == 0
+    ctx.close()
+
+
+def test_two_runs_are_byte_identical():
+    from paper_2602_14236_amd import binding
+    p = params(n_layers=2, n_heads=4, cap_fp16=1200, cap_int8=1200, cap_int4=1200)
+    outs = []
+    for _ in range(2):
+        ctx = binding.SaliContext(lib_config(p))
+        ctx.pools.zero_()
+        for f in range(2):
+            ctx.kv_compress(_kv(50 + f, 2, 4), torch.from_numpy(_scores(f, "coarse")).cuda(), f)
+        torch.cuda.synchronize()
+        outs.append((ctx.pools.cpu().numpy().copy(), ctx.tables.cpu().numpy().copy()))
+        ctx.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
