@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the Sali-Cache pre-attention filter on one MI355X.
+
+One step = one frame through the whole hot path: sali_step (gray + pyramid + polynomial
+expansion + flow + per-patch motion + gate; saliency + pooling; tiers + compaction; K/V pack)
+followed by sali_kv_decompress of that frame (dequantise-on-read).  Inputs (all frames and all
+K/V tensors of the workload) are resident in HBM before the timed region starts.
+
+Prints one JSON line: frames/s, the HBM roofline of the dominant kernel (k_pack, timed with HIP
+events around every launch inside the timed region) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12
+TIER_W = (2.0, 1.0 + 4.0 / 32.0, 0.5 + 4.0 / 32.0 + 2.0 / 32.0)      # bytes written per element: fp16, int8, int4
+
+
+def algorithmic_bytes(wl, row):
+    """Bytes the method must move for one frame (none for a pointer frame beyond the image work)."""
+    e = wl.elems_per_token
+    image = 5 * wl.height * wl.width + 7 * 1024
+    if not row.stored:
+        return image, 0, 0
+    kept = (row.n16, row.n8, row.n4)
+    pack = sum(n * e * (2.0 + w) for n, w in zip(kept, TIER_W))
+    unpack = sum(n * e * w for n, w in zip(kept, TIER_W)) + 576 * e * 2.0
+    return image, pack, unpack
+
+
+def cpu_baseline(wl, video, max_frames=16, budget_s=12.0):
+    """The oracle, as it stands, on the host cores of this machine: the leading frames of the workload
+    at its full K/V shape through step + dequantise-on-read, as many as fit in about `budget_s`
+    seconds (at least 2, at most `max_frames`).  Single thread."""
+    from threadpoolctl import threadpool_limits
+    from oracle.cache import OracleConfig, SaliCacheOracle
+    from paper_2602_14236_amd import synth
+
+    frames = max_frames
+    cap = lambda k: max(1, (k if wl.tier_mode == 1 else 576) * frames)
+    oc = OracleConfig(src_h=wl.height, src_w=wl.width, flow_levels=wl.flow_levels, tier_mode=wl.tier_mode,
+                      k_fp16=wl.k_fp16, k_int8=wl.k_int8, k_int4=wl.k_int4, n_layers=wl.n_layers, n_heads=wl.n_heads,
+                      cap_fp16=cap(wl.k_fp16), cap_int8=cap(wl.k_int8), cap_int4=cap(wl.k_int4), max_frames=frames)
+    scale = synth.kv_channel_scale(wl)
+    total = 0.0
+    done = 0
+    with threadpool_limits(limits=1):
+        orc = SaliCacheOracle(oc)
+        for t in range(frames):
+            if done >= 2 and total >= budget_s:
+                break
+            rgb = video.frame(t)
+            kv = synth.kv_frame(wl, t, scale=scale).numpy()
+            a = time.perf_counter()
+            orc.step(rgb, kv, t)
+            orc.kv_decompress(t)
+            total += time.perf_counter() - a
+            done += 1
+            del kv
+    frames = done
+    return {"value": frames / total, "unit": "frames/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {frames} frames of {wl.name} at the full K/V shape, step + dequantise-on-read, "
+                      f"{total:.1f} s of CPU work, one thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (BASELINE configs); 2 is the metric's")
+    ap.add_argument("--layers", type=int, default=None, help="cut the K/V down to this many layers (not a valid bench)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU (the method has no cross-GPU step); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_14236_amd import binding, synth
+
+    wl = synth.WORKLOADS[args.config]
+    n_layers = wl.n_layers if args.layers is None else args.layers
+    steps, warmup = args.steps, args.warmup
+    n_src = min(wl.frames, max(steps, warmup))          # distinct input frames kept resident
+    if args.config == 4:
+        n_src = min(n_src, 8)                           # 13B-shaped K/V: 472 MB per frame; cycle a ring > the 256 MB cache
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cap = lambda k: max(1, (k if wl.tier_mode == 1 else 576) * steps)
+    cfg = binding.make_config(wl.height, wl.width, flow_levels=wl.flow_levels, tier_mode=wl.tier_mode,
+                              k_fp16=wl.k_fp16, k_int8=wl.k_int8, k_int4=wl.k_int4, n_layers=n_layers,
+                              n_heads=wl.n_heads, cap_fp16=cap(wl.k_fp16), cap_int8=cap(wl.k_int8),
+                              cap_int4=cap(wl.k_int4), max_frames=max(steps, warmup))
+    ctx = binding.SaliContext(cfg, dev)
+
+    # resident inputs
+    video = synth.video(args.config, n_src)
+    scale = synth.kv_channel_scale(wl, n_layers)
+    rgbs = [torch.from_numpy(video.frame(t)).to(dev) for t in range(n_src)]
+    kvs = [synth.kv_frame(wl, t, device=dev, n_layers=n_layers, scale=scale) for t in range(n_src)]
+    out = torch.empty((n_layers, 2, wl.n_heads, 576, 128), dtype=torch.float16, device=dev)
+    torch.cuda.synchronize()
+
+    def make_events(n):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:            # a first record creates the HIP handles
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        return evs
+
+    def run(n, with_unpack, pack_events=None, unpack_events=None):
+        for t in range(n):
+            if pack_events is not None:
+                ctx.set_profile_events(0, *pack_events[t])
+            ctx.step(rgbs[t % n_src], kvs[t % n_src], t)
+            if with_unpack:
+                if unpack_events is not None:
+                    ctx.set_profile_events(1, *unpack_events[t])
+                ctx.kv_decompress(t, out)
+
+    # warm-up, then forget it
+    run(warmup, True)
+    torch.cuda.synchronize()
+    ctx.reset()
+
+    pack_ev, unpack_ev = make_events(steps), make_events(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps, True, pack_ev, unpack_ev)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    rows = ctx.read_frame_table(0, steps)
+    status = ctx.get_status()
+    pack_ms = [a.elapsed_time(b) for a, b in pack_ev]
+    unpack_ms = [a.elapsed_time(b) for a, b in unpack_ev]
+
+    # the same frames through sali_step alone (no dequantise-on-read), for reference
+    ctx.reset()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    run(steps, False)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    elapsed_step_only = t3 - t2
+
+    wl_eff = wl if n_layers == wl.n_layers else type(wl)(**{**wl.__dict__, "n_layers": n_layers})
+    img_b = pack_b = unpack_b = 0.0
+    for r in rows:
+        i, p, u = algorithmic_bytes(wl_eff, r)
+        img_b += i
+        pack_b += p
+        # dequantise-on-read of a pointer frame reads its source frame
+        if not r.stored and r.src >= 0:
+            u = algorithmic_bytes(wl_eff, rows[r.src])[2]
+        unpack_b += u
+    n_stored = sum(1 for r in rows if r.stored)
+    pack_s = sum(pack_ms) / 1e3
+    unpack_s = sum(unpack_ms) / 1e3
+    pack_gbps = pack_b / pack_s / 1e9 if pack_s > 0 else 0.0
+    unpack_gbps = unpack_b / unpack_s / 1e9 if unpack_s > 0 else 0.0
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_k_pack.json")
+    if os.path.exists(tpath) and args.layers is None:
+        tj = json.load(open(tpath))
+        if tj.get("workload") == wl.name:
+            traffic = tj.get("hbm_bytes_per_launch")
+
+    result = {
+        "metric": "frames/s through sali_step + KV compress GB/s (% of HBM peak), 1 MI355X",
+        "value": steps / elapsed,
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": elapsed / steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "frames": steps, "source": f"{wl.width}x{wl.height}",
+                   "kv_shape": [n_layers, 2, wl.n_heads, 576, 128], "tier_mode": wl.tier_mode,
+                   "k": [wl.k_fp16, wl.k_int8, wl.k_int4], "step": "sali_step + sali_kv_decompress",
+                   "stored_frames": n_stored, "status_word": status},
+        "roofline": {"bound": "hbm", "kernel": "k_pack", "achieved": pack_gbps, "peak": HBM_PEAK / 1e9,
+                     "unit": "GB/s", "frac": pack_gbps / (HBM_PEAK / 1e9), "traffic": traffic,
+                     "avg_launch_us": pack_s / steps * 1e6, "algorithmic_bytes_per_launch": pack_b / steps},
+        "kv_compress_gbps": pack_gbps,
+        "kv_compress_pct_of_hbm_peak": 100.0 * pack_gbps / (HBM_PEAK / 1e9),
+        "kv_decompress_gbps": unpack_gbps,
+        "kv_decompress_avg_launch_us": unpack_s / steps * 1e6,
+        "step_hbm_frac": (img_b + pack_b + unpack_b) / elapsed / HBM_PEAK,
+        "sali_step_only_fps": steps / elapsed_step_only,
+        "sali_step_only_hbm_frac": (img_b + pack_b) / elapsed_step_only / HBM_PEAK,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl_eff, synth.video(args.config, 16))
+    ctx.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -194,6 +194,15 @@ int sali_read_frame_tiers(sali_ctx* ctx, int32_t frame_id, uint8_t* h_tier576, u
 int sali_read_last_step(sali_ctx* ctx, float* h_patch_motion576, sali_gate* h_gate,
                         float* h_scores576, void* stream);
 
+/* Measurement hook.  Arms one pair of caller-created HIP events (hipEvent_t, passed as void*):
+ * the next launch of the chosen kernel records `start` just before and `stop` just after it on
+ * the call's stream, then the pair is disarmed.  which: SALI_PROF_PACK = the storage kernel of
+ * sali_step / sali_kv_compress, SALI_PROF_UNPACK = the kernel of sali_kv_decompress.  NULL
+ * events disarm.  The caller reads the elapsed time after synchronising. */
+#define SALI_PROF_PACK   0
+#define SALI_PROF_UNPACK 1
+int sali_set_profile_events(sali_ctx* ctx, int which, void* start_event, void* stop_event);
+
 /* Read and keep the sticky device status word.  Waits for `stream`. */
 int sali_get_status(sali_ctx* ctx, uint32_t* h_flags, void* stream);
 

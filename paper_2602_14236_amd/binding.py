@@ -81,6 +81,7 @@ EXPORTS = {
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
     "sali_read_frame_tiers": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_read_last_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sali_set_profile_events": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
     "sali_get_status": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p]),
     "sali_error_string": (C.c_char_p, [C.c_int]),
 }
@@ -224,6 +225,13 @@ class SaliContext:
         _check(self.lib.sali_read_last_step(self.handle, dp.ctypes.data_as(C.c_void_p), C.byref(g),
                                             sc.ctypes.data_as(C.c_void_p), _stream()), "sali_read_last_step")
         return dp, g, sc
+
+    def set_profile_events(self, which: int, start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]):
+        """Arm a pair of torch events (created with enable_timing=True and already recorded once, so that
+        their HIP handles exist) around the next pack (0) / unpack (1) kernel."""
+        a = None if start is None else C.c_void_p(start.cuda_event)
+        b = None if stop is None else C.c_void_p(stop.cuda_event)
+        _check(self.lib.sali_set_profile_events(self.handle, which, a, b), "sali_set_profile_events")
 
     def get_status(self) -> int:
         f = C.c_uint32()

@@ -205,6 +205,7 @@ struct sali_ctx {
     bool prev_valid;     // the expansion of the previous sali_step frame is cached in slot `step_slot ^ 1`
     int step_slot;       // expansion slot the NEXT sali_step frame writes (0 or 1)
     unsigned sal_seq;    // parity selects the frame-sum accumulator
+    hipEvent_t prof[2][2];   // [SALI_PROF_*][start, stop], armed for one launch
 
     template <typename T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
     template <typename T> T* tb(size_t off) const { return reinterpret_cast<T*>(tables + off); }
@@ -301,7 +302,11 @@ int enqueue_store(sali_ctx* c, const void* d_kv, const float* d_scores, const sa
                   hipStream_t s) {
     SALI_TRY(launch_tier(d_scores, gate, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
                          c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, s));
+    hipEvent_t* ev = c->prof[SALI_PROF_PACK];
+    if (ev[0] != nullptr) SALI_TRY(hipEventRecord(ev[0], s));
     SALI_TRY(launch_pack(d_kv, c->rows() + frame_id, c->order(frame_id), c->pools, c->cursors(), c->n_planes, s));
+    if (ev[1] != nullptr) SALI_TRY(hipEventRecord(ev[1], s));
+    ev[0] = ev[1] = nullptr;
     return SALI_OK;
 }
 
@@ -378,6 +383,7 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->prev_valid = false;
     c->step_slot = 0;
     c->sal_seq = 0;
+    c->prof[0][0] = c->prof[0][1] = c->prof[1][0] = c->prof[1][1] = nullptr;
 
     uint16_t lin[256];
     static uint16_t fl[4096];
@@ -458,8 +464,13 @@ int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8
     if (c == nullptr || d_kv_fp16_out == nullptr) return SALI_ERR_NULL;
     if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
     if (!aligned16(d_kv_fp16_out)) return SALI_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t* ev = c->prof[SALI_PROF_UNPACK];
+    if (ev[0] != nullptr) SALI_TRY(hipEventRecord(ev[0], s));
     SALI_TRY(launch_unpack(c->rows(), frame_id, c->tb<uint16_t>(c->tl.order), c->pools, d_kv_fp16_out,
-                           d_valid576_or_null, c->cursors(), c->n_planes, static_cast<hipStream_t>(stream)));
+                           d_valid576_or_null, c->cursors(), c->n_planes, s));
+    if (ev[1] != nullptr) SALI_TRY(hipEventRecord(ev[1], s));
+    ev[0] = ev[1] = nullptr;
     return SALI_OK;
 }
 
@@ -525,6 +536,14 @@ int sali_read_last_step(sali_ctx* c, float* h_patch_motion576, sali_gate* h_gate
         SALI_TRY(hipMemcpyAsync(h_scores576, c->sc<float>(c->sl.scores), kTokens * sizeof(float),
                                 hipMemcpyDeviceToHost, s));
     SALI_TRY(hipStreamSynchronize(s));
+    return SALI_OK;
+}
+
+int sali_set_profile_events(sali_ctx* c, int which, void* start_event, void* stop_event) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    if (which != SALI_PROF_PACK && which != SALI_PROF_UNPACK) return SALI_ERR_SHAPE;
+    c->prof[which][0] = static_cast<hipEvent_t>(start_event);
+    c->prof[which][1] = static_cast<hipEvent_t>(stop_event);
     return SALI_OK;
 }
 

@@ -285,10 +285,12 @@ def video(config: int, n_frames: Optional[int] = None) -> Video:
 # --------------------------------------------------------------------------
 # K/V tensors
 # --------------------------------------------------------------------------
-def kv_channel_scale(wl: Workload, n_layers: Optional[int] = None):
-    """Per-channel lognormal(0, 0.5) scale, fixed per workload: torch fp32 [n_l, 2, n_h, 1, D] (CPU)."""
+def kv_channel_scale(wl: Workload, n_layers: Optional[int] = None, n_heads: Optional[int] = None):
+    """Per-channel lognormal(0, 0.5) scale, fixed per workload: torch fp32 [n_l, 2, n_h, 1, D] (CPU).
+    n_layers / n_heads cut the tensor down to its leading layers / heads."""
     import torch
     nl = wl.n_layers if n_layers is None else n_layers
+    nh = wl.n_heads if n_heads is None else n_heads
     g = torch.Generator(device="cpu")
     g.manual_seed(wl.seed * 1000 + 17)
     c = torch.exp(0.5 * torch.randn((nl, 2, wl.n_heads, 1, wl.head_dim), generator=g, dtype=torch.float32))
@@ -299,10 +301,11 @@ def kv_channel_scale(wl: Workload, n_layers: Optional[int] = None):
         for h in range(wl.n_heads):
             dims = torch.randperm(wl.head_dim, generator=gi)[:4]
             c[:, :, h, 0, dims] *= 20.0
-    return c
+    return c[:, :, :nh].contiguous()
 
 
-def kv_frame(wl: Workload, t: int, device="cpu", n_layers: Optional[int] = None, scale=None):
+def kv_frame(wl: Workload, t: int, device="cpu", n_layers: Optional[int] = None, n_heads: Optional[int] = None,
+             scale=None):
     """K/V of frame t: fp16 [n_l, 2, n_h, 576, D], drawn on `device` from a (seed, t) generator.
 
     The draw depends on the device's RNG, so a caller that needs the same bytes on host and
@@ -310,12 +313,13 @@ def kv_frame(wl: Workload, t: int, device="cpu", n_layers: Optional[int] = None,
     """
     import torch
     nl = wl.n_layers if n_layers is None else n_layers
+    nh = wl.n_heads if n_heads is None else n_heads
     dev = torch.device(device)
     g = torch.Generator(device=dev)
     g.manual_seed(wl.seed * 100003 + t)
-    shape = (nl, 2, wl.n_heads, TOKENS, wl.head_dim)
+    shape = (nl, 2, nh, TOKENS, wl.head_dim)
     if scale is None:
-        scale = kv_channel_scale(wl, nl)
+        scale = kv_channel_scale(wl, nl, nh)
     scale = scale.to(dev)
     out = torch.empty(shape, dtype=torch.float16, device=dev)
     for l in range(nl):                                   # layer at a time keeps the fp32 temporaries small

@@ -1,0 +1,132 @@
+"""GPU parity of the chained per-frame path (Algorithm 1) against the oracle, through the C ABI.
+Rows, tiers, slots, pool contents and dequantised frames are bit-exact; Delta P within the flow
+tolerance; gate decisions equal wherever the oracle's margin to tau_t exceeds that tolerance (the
+minimum margin met is printed)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.cache import SaliCacheOracle
+from paper_2602_14236_amd import synth
+
+from _util import FLOW_ATOL, FLOW_RTOL, assert_same, close, lib_config, oracle_config, pool_arrays, workload_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_sequence(p, wl, frames, video):
+    from paper_2602_14236_amd import binding
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    min_margin = np.inf
+    nl, nh = p["n_layers"], p["n_heads"]
+    kv_scale = synth.kv_channel_scale(wl, nl, nh)
+    for t in frames:
+        print(f"{wl.name} frame {t} ({video.kind(t)})", flush=True)
+        rgb = video.frame(t)
+        kv = synth.kv_frame(wl, t, device="cuda", n_layers=nl, n_heads=nh, scale=kv_scale)
+        ctx.step(torch.from_numpy(rgb).cuda(), kv, t)
+        dp, gate, scores = ctx.read_last_step()
+        row = orc.step(rgb, kv.cpu().numpy(), t)
+        if orc.last_gate is not None:
+            n, r, red, margin = orc.last_gate
+            tau = p["tau_t"]
+            fragile = int(np.count_nonzero(np.abs(orc.last_dp - tau) <= FLOW_ATOL + FLOW_RTOL * tau))
+            min_margin = min(min_margin, margin)
+            assert close(dp, orc.last_dp).all(), f"frame {t}: Delta P out of tolerance"
+            assert abs(gate.n_static - n) <= fragile
+            assert fragile == 0, "seeded input sits on the threshold: pick another seed"
+            assert (gate.n_static, gate.r_frame, gate.redundant) == (n, float(r), int(red)), f"gate of frame {t}"
+        if row.stored:
+            assert_same(scores, orc.last_scores, f"scores of frame {t}")
+    torch.cuda.synchronize()
+    print(f"{wl.name}: minimum gate margin {min_margin:.3e}", flush=True)
+    return ctx, orc
+
+
+def _compare_all(ctx, orc, frames):
+    rows = ctx.read_frame_table(0, ctx.cfg.max_frames)
+    for f in frames:
+        assert rows[f].as_tuple() == orc.rows[f].as_tuple(), f"row {f}: {rows[f].as_tuple()} vs {orc.rows[f].as_tuple()}"
+        if orc.rows[f].stored:
+            tier, slot = ctx.read_frame_tiers(f)
+            assert_same(tier, orc.tier[f], f"tier {f}")
+            assert_same(slot.astype(np.int32), orc.slot[f], f"slot {f}")
+    pa = pool_arrays(ctx)
+    c16, c8, c4 = orc.cursor
+    assert_same(pa["fp16"][..., :c16, :], orc.pool16[..., :c16, :], "fp16 pool")
+    assert_same(pa["codes8"][..., :c8, :], orc.codes8[..., :c8, :], "int8 codes")
+    assert_same(pa["scale8"][..., :c8, :], orc.scale8[..., :c8, :], "int8 scales")
+    assert_same(pa["codes4"][..., :c4, :], orc.codes4[..., :c4, :], "int4 codes")
+    assert_same(pa["scale4"][..., :c4, :], orc.scale4[..., :c4, :], "int4 scales")
+    assert_same(pa["zero4"][..., :c4, :], orc.zero4[..., :c4, :], "int4 zero-points")
+    c = ctx.cfg
+    out = torch.empty((c.n_layers, 2, c.n_heads, 576, 128), dtype=torch.float16, device="cuda")
+    valid = torch.empty(576, dtype=torch.uint8, device="cuda")
+    for f in frames:
+        if orc.rows[f].src < 0:
+            continue
+        ctx.kv_decompress(f, out, valid)
+        torch.cuda.synchronize()
+        exp, exp_valid = orc.kv_decompress(f)
+        assert_same(out.cpu().numpy(), exp, f"decompressed frame {f}")
+        assert_same(valid.cpu().numpy(), exp_valid, f"valid mask {f}")
+    assert ctx.get_status() == 0
+
+
+def test_config1_whole():
+    """8 frames 336x336, 1 layer x 32 heads, threshold tiers; frame 3 (0-based) is a byte copy of frame 2."""
+    wl = synth.WORKLOADS[1]
+    p = workload_params(wl)
+    v = synth.video(1)
+    ctx, orc = _run_sequence(p, wl, range(8), v)
+    assert [orc.rows[t].stored for t in range(8)] == [1, 1, 1, 0, 1, 1, 1, 1]
+    assert orc.rows[3].src == 2
+    _compare_all(ctx, orc, range(8))
+    ctx.close()
+
+
+def test_config3_prefix_near_static_runs():
+    """640x360 source, paper-mix top-k tiers; a prefix long enough to hold moving and near-static frames."""
+    wl = synth.WORKLOADS[3]
+    v = synth.video(3, 100)
+    frames = list(range(76, 88))             # crosses from a moving run into a near-static run
+    p = workload_params(wl, frames=100, n_layers=1, n_heads=4,
+                        cap_fp16=249 * 12, cap_int8=56 * 12, cap_int4=168 * 12)
+    ctx, orc = _run_sequence(p, wl, frames, v)
+    flags = [orc.rows[t].stored for t in frames]
+    assert 0 in flags[1:] and 1 in flags[1:]
+    _compare_all(ctx, orc, frames)
+    ctx.close()
+
+
+def test_config5_adversarial_prefix():
+    """Scene cuts, duplicate runs, uniform-noise frames; Student-t K/V with outlier channels."""
+    wl = synth.WORKLOADS[5]
+    v = synth.video(5, 32)
+    frames = list(range(0, 24))              # cut at 16, duplicates 5..8, noise at 21, 22
+    p = workload_params(wl, frames=32, n_layers=1, n_heads=2)
+    ctx, orc = _run_sequence(p, wl, frames, v)
+    assert [orc.rows[t].stored for t in (5, 6, 7, 8)] == [0, 0, 0, 0]
+    assert orc.rows[16].stored == 1 and orc.rows[21].stored == 1
+    _compare_all(ctx, orc, frames)
+    ctx.close()
+
+
+def test_reset_forgets_history():
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[1]
+    p = workload_params(wl, n_heads=1)
+    v = synth.video(1)
+    ctx = binding.SaliContext(lib_config(p))
+    rgb = torch.from_numpy(v.frame(0)).cuda()
+    kv = synth.kv_frame(wl, 0, device="cuda", n_heads=1)
+    ctx.step(rgb, kv, 0)
+    ctx.step(rgb, kv, 1)                     # identical frame: pointer
+    rows = ctx.read_frame_table(0, 2)
+    assert (rows[0].stored, rows[1].stored, rows[1].src) == (1, 0, 0)
+    ctx.reset()
+    ctx.step(rgb, kv, 0)                     # first frame again: stored, cursors restart at 0
+    rows = ctx.read_frame_table(0, 2)
+    assert rows[0].stored == 1 and rows[0].base16 == 0 and rows[1].src == -1
+    ctx.close()
