@@ -178,6 +178,31 @@ int sali_kv_decompress(sali_ctx* ctx, int32_t frame_id, void* d_kv_fp16_out,
 int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id,
               void* stream);
 
+/* The two halves of sali_step, for callers that overlap them.  The decision of Algorithm 1
+ * needs only the image, and a redundant frame needs no K/V at all, so the image side of frame
+ * t+1 can run while the K/V of frame t is still being stored.
+ *
+ * sali_analyze: temporal filter against the previously analysed frame, and for a non-redundant
+ * frame saliency, tiers and compaction indices; fills the frame-table row of `frame_id`
+ * (pointer row if redundant).  Asynchronous on `stream`.  All image-side calls on one context
+ * (sali_analyze, sali_step, sali_flow_score, sali_saliency_pool) share scratch memory and
+ * must be ordered with respect to each other by the caller (same stream, or events).
+ *
+ * sali_store: packs `d_kv_fp16` into the pools according to the row that sali_analyze wrote.
+ * Makes `stream` wait (on the device) for that frame's analysis if it ran on another stream.
+ * SALI_ERR_STATE if `frame_id` is not among the last 8 analysed frames.
+ *
+ * sali_step(ctx, rgb, kv, id, s) == sali_analyze(ctx, rgb, id, s); sali_store(ctx, kv, id, s). */
+int sali_analyze(sali_ctx* ctx, const uint8_t* d_rgb, int32_t frame_id, void* stream);
+int sali_store(sali_ctx* ctx, const void* d_kv_fp16, int32_t frame_id, void* stream);
+
+/* One loop body of Algorithm 1 with a one-frame look-ahead on two caller-owned streams:
+ * analyses frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
+ * `image_stream` and stores the K/V of the already analysed frame `frame_id` (d_kv, may be NULL
+ * at the start) on `kv_stream`.  Results are identical to calling sali_step frame by frame. */
+int sali_step_pipelined(sali_ctx* ctx, const uint8_t* d_rgb_next_or_null, int32_t next_frame_id,
+                        const void* d_kv_or_null, int32_t frame_id, void* image_stream, void* kv_stream);
+
 /* Copy `count` frame-table rows starting at `first` to host memory.  Waits for `stream`. */
 int sali_read_frame_table(sali_ctx* ctx, sali_frame_row* h_rows, int32_t first, int32_t count,
                           void* stream);

@@ -78,6 +78,10 @@ EXPORTS = {
     "sali_kv_compress": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sali_kv_decompress": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sali_analyze": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sali_store": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sali_step_pipelined": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_void_p]),
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
     "sali_read_frame_tiers": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_read_last_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -204,6 +208,19 @@ class SaliContext:
 
     def step(self, rgb, kv, frame_id: int):
         _check(self.lib.sali_step(self.handle, _ptr(rgb), _ptr(kv), frame_id, _stream()), "sali_step")
+
+    def analyze(self, rgb, frame_id: int, stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_analyze(self.handle, _ptr(rgb), frame_id, s), "sali_analyze")
+
+    def store(self, kv, frame_id: int, stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_store(self.handle, _ptr(kv), frame_id, s), "sali_store")
+
+    def step_pipelined(self, rgb_next, next_frame_id: int, kv, frame_id: int, image_stream: torch.cuda.Stream,
+                       kv_stream: torch.cuda.Stream):
+        _check(self.lib.sali_step_pipelined(self.handle, _ptr(rgb_next), next_frame_id, _ptr(kv), frame_id,
+                                            image_stream.cuda_stream, kv_stream.cuda_stream), "sali_step_pipelined")
 
     def read_frame_table(self, first=0, count=None):
         count = self.cfg.max_frames - first if count is None else count

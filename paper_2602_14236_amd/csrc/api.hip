@@ -192,6 +192,8 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, unsi
 
 using namespace sali;
 
+constexpr int kEventRing = 8;
+
 struct sali_ctx {
     sali_config cfg;
     LevelGeom geom;
@@ -206,6 +208,9 @@ struct sali_ctx {
     int step_slot;       // expansion slot the NEXT sali_step frame writes (0 or 1)
     unsigned sal_seq;    // parity selects the frame-sum accumulator
     hipEvent_t prof[2][2];   // [SALI_PROF_*][start, stop], armed for one launch
+    hipEvent_t analysis_done[kEventRing];    // recorded when the analysis of frame id % ring is enqueued
+    int analysed_frame[kEventRing];          // which frame that was (-1 = none)
+    hipStream_t analysed_stream[kEventRing];
 
     template <typename T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
     template <typename T> T* tb(size_t off) const { return reinterpret_cast<T*>(tables + off); }
@@ -276,12 +281,15 @@ int enqueue_flow(sali_ctx* c, int slot_prev, int slot_cur, const float2** result
     return SALI_OK;
 }
 
-int enqueue_saliency_tail(sali_ctx* c, const sali_gate* gate, float* d_scores, uint8_t* d_salmap, hipStream_t s) {
+// cross-tile hysteresis + pooling; with `tier` the pooling kernel also assigns tiers and writes
+// the frame-table row of `tier->frame_id`
+int enqueue_saliency_tail(sali_ctx* c, const sali_gate* gate, float* d_scores, uint8_t* d_salmap,
+                          const TierLaunch* tier, hipStream_t s) {
     const sali_config& cfg = c->cfg;
     unsigned long long* msum = c->sc<unsigned long long>(c->sl.msum) + (c->sal_seq & 1u);
     SALI_TRY(launch_union(c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.parent), cfg.src_h, cfg.src_w, gate, s));
     SALI_TRY(launch_pool(c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.parent), c->sc<uint32_t>(c->sl.var), msum,
-                         cfg.src_h, cfg.src_w, gate, d_scores, d_salmap, s));
+                         cfg.src_h, cfg.src_w, gate, d_scores, d_salmap, tier, s));
     c->sal_seq += 1u;
     return SALI_OK;
 }
@@ -298,10 +306,23 @@ TierParams tier_params(const sali_config& cfg) {
     return tp;
 }
 
-int enqueue_store(sali_ctx* c, const void* d_kv, const float* d_scores, const sali_gate* gate, int frame_id,
-                  hipStream_t s) {
-    SALI_TRY(launch_tier(d_scores, gate, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
-                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, s));
+TierLaunch tier_launch(sali_ctx* c, int frame_id) {
+    TierLaunch t;
+    t.tp = tier_params(c->cfg);
+    t.frame_id = frame_id;
+    t.rows = c->rows();
+    t.tier = c->tier(frame_id);
+    t.slot = c->slot(frame_id);
+    t.order = c->order(frame_id);
+    t.cur = c->cursors();
+    t.cap16 = c->pools.cap16;
+    t.cap8 = c->pools.cap8;
+    t.cap4 = c->pools.cap4;
+    return t;
+}
+
+// the storage kernel of frame `frame_id`; its frame-table row and order list must be in place
+int enqueue_pack(sali_ctx* c, const void* d_kv, int frame_id, hipStream_t s) {
     hipEvent_t* ev = c->prof[SALI_PROF_PACK];
     if (ev[0] != nullptr) SALI_TRY(hipEventRecord(ev[0], s));
     SALI_TRY(launch_pack(d_kv, c->rows() + frame_id, c->order(frame_id), c->pools, c->cursors(), c->n_planes, s));
@@ -384,24 +405,41 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->step_slot = 0;
     c->sal_seq = 0;
     c->prof[0][0] = c->prof[0][1] = c->prof[1][0] = c->prof[1][1] = nullptr;
+    for (int i = 0; i < kEventRing; ++i) {
+        c->analysis_done[i] = nullptr;
+        c->analysed_frame[i] = -1;
+        c->analysed_stream[i] = nullptr;
+    }
+    for (int i = 0; i < kEventRing; ++i) {
+        if (hipEventCreateWithFlags(&c->analysis_done[i], hipEventDisableTiming) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(c->analysis_done[j]);
+            delete c;
+            return SALI_ERR_HIP;
+        }
+    }
 
     uint16_t lin[256];
     static uint16_t fl[4096];
     fill_luts(lin, fl);
     if (hipMemcpy(c->tables + c->tl.lin, lin, sizeof(lin), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(c->tables + c->tl.fl, fl, sizeof(fl), hipMemcpyHostToDevice) != hipSuccess) {
-        delete c;
+        sali_destroy(c);
         return SALI_ERR_HIP;
     }
     if (sali_reset(c, nullptr) != SALI_OK || hipStreamSynchronize(nullptr) != hipSuccess) {
-        delete c;
+        sali_destroy(c);
         return SALI_ERR_HIP;
     }
     *out = c;
     return SALI_OK;
 }
 
-void sali_destroy(sali_ctx* ctx) { delete ctx; }
+void sali_destroy(sali_ctx* ctx) {
+    if (ctx == nullptr) return;
+    for (int i = 0; i < kEventRing; ++i)
+        if (ctx->analysis_done[i] != nullptr) (void)hipEventDestroy(ctx->analysis_done[i]);
+    delete ctx;
+}
 
 int sali_reset(sali_ctx* c, void* stream) {
     if (c == nullptr) return SALI_ERR_NULL;
@@ -414,6 +452,7 @@ int sali_reset(sali_ctx* c, void* stream) {
     c->prev_valid = false;
     c->step_slot = 0;
     c->sal_seq = 0;
+    for (int i = 0; i < kEventRing; ++i) c->analysed_frame[i] = -1;
     return SALI_OK;
 }
 
@@ -449,14 +488,17 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc = enqueue_frame_analysis(c, d_rgb, -1, true, s);
     if (rc != SALI_OK) return rc;
-    return enqueue_saliency_tail(c, nullptr, d_scores576, d_salmap_or_null, s);
+    return enqueue_saliency_tail(c, nullptr, d_scores576, d_salmap_or_null, nullptr, s);
 }
 
 int sali_kv_compress(sali_ctx* c, const void* d_kv_fp16, const float* d_scores576, int32_t frame_id, void* stream) {
     if (c == nullptr || d_kv_fp16 == nullptr || d_scores576 == nullptr) return SALI_ERR_NULL;
     if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
     if (!aligned16(d_kv_fp16)) return SALI_ERR_ALIGN;
-    return enqueue_store(c, d_kv_fp16, d_scores576, nullptr, frame_id, static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SALI_TRY(launch_tier(d_scores576, nullptr, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
+                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, s));
+    return enqueue_pack(c, d_kv_fp16, frame_id, s);
 }
 
 int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8_t* d_valid576_or_null,
@@ -474,13 +516,12 @@ int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8
     return SALI_OK;
 }
 
-int sali_step(sali_ctx* c, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id, void* stream) {
-    if (c == nullptr || d_rgb_t == nullptr || d_kv_t == nullptr) return SALI_ERR_NULL;
+int sali_analyze(sali_ctx* c, const uint8_t* d_rgb, int32_t frame_id, void* stream) {
+    if (c == nullptr || d_rgb == nullptr) return SALI_ERR_NULL;
     if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
-    if (!aligned16(d_kv_t)) return SALI_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int slot = c->step_slot;
-    int rc = enqueue_frame_analysis(c, d_rgb_t, slot, true, s);
+    int rc = enqueue_frame_analysis(c, d_rgb, slot, true, s);
     if (rc != SALI_OK) return rc;
     float* dp = c->sc<float>(c->sl.dp);
     float* scores = c->sc<float>(c->sl.scores);
@@ -494,12 +535,46 @@ int sali_step(sali_ctx* c, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t f
     } else {
         SALI_TRY(launch_clear_gate(dp, gate, s));      // first frame: never redundant (Algorithm 1, t > 1)
     }
-    rc = enqueue_saliency_tail(c, gate, scores, nullptr, s);
+    const TierLaunch tl = tier_launch(c, frame_id);
+    rc = enqueue_saliency_tail(c, gate, scores, nullptr, &tl, s);
     if (rc != SALI_OK) return rc;
-    rc = enqueue_store(c, d_kv_t, scores, gate, frame_id, s);
-    if (rc != SALI_OK) return rc;
+    const int e = frame_id % kEventRing;
+    SALI_TRY(hipEventRecord(c->analysis_done[e], s));
+    c->analysed_frame[e] = frame_id;
+    c->analysed_stream[e] = s;
     c->prev_valid = true;
     c->step_slot = slot ^ 1;
+    return SALI_OK;
+}
+
+int sali_store(sali_ctx* c, const void* d_kv, int32_t frame_id, void* stream) {
+    if (c == nullptr || d_kv == nullptr) return SALI_ERR_NULL;
+    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
+    if (!aligned16(d_kv)) return SALI_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int e = frame_id % kEventRing;
+    if (c->analysed_frame[e] != frame_id) return SALI_ERR_STATE;      // not analysed (or too long ago)
+    if (c->analysed_stream[e] != s) SALI_TRY(hipStreamWaitEvent(s, c->analysis_done[e], 0));
+    return enqueue_pack(c, d_kv, frame_id, s);
+}
+
+int sali_step(sali_ctx* c, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id, void* stream) {
+    if (c == nullptr || d_rgb_t == nullptr || d_kv_t == nullptr) return SALI_ERR_NULL;
+    if (!aligned16(d_kv_t)) return SALI_ERR_ALIGN;
+    const int rc = sali_analyze(c, d_rgb_t, frame_id, stream);
+    if (rc != SALI_OK) return rc;
+    return sali_store(c, d_kv_t, frame_id, stream);
+}
+
+int sali_step_pipelined(sali_ctx* c, const uint8_t* d_rgb_next_or_null, int32_t next_frame_id,
+                        const void* d_kv_or_null, int32_t frame_id, void* image_stream, void* kv_stream) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    if (d_kv_or_null != nullptr && !aligned16(d_kv_or_null)) return SALI_ERR_ALIGN;
+    if (d_rgb_next_or_null != nullptr) {
+        const int rc = sali_analyze(c, d_rgb_next_or_null, next_frame_id, image_stream);
+        if (rc != SALI_OK) return rc;
+    }
+    if (d_kv_or_null != nullptr) return sali_store(c, d_kv_or_null, frame_id, kv_stream);
     return SALI_OK;
 }
 

@@ -24,9 +24,8 @@ namespace sali {
 
 namespace {
 
-constexpr int kT = 32;                       // tile side
+constexpr int kT = 32;                       // tile side of the expansion kernel
 constexpr int kPR = kT + 2 * kPolyN;         // 38
-constexpr int kFR = kT + 2 * kWinR;          // 42
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 __device__ __forceinline__ float clampf(float v, float lo, float hi) { return fminf(fmaxf(v, lo), hi); }
@@ -160,22 +159,29 @@ __device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int 
 
 }  // namespace
 
+// T = tile side: 32 for large levels, 16 for small ones (more blocks and fewer cells per thread:
+// the small levels are latency-bound, not throughput-bound).
+template <int T>
 __global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1, const float2* __restrict__ b1,
                                                    const float4* __restrict__ A2, const float2* __restrict__ b2,
                                                    const float2* __restrict__ d_in, float2* __restrict__ d_out,
                                                    int h, int w, int ch, int cw, int prior_mode, FlowWeights fw) {
-    __shared__ float s_in[5][kFR][kFR + 1];
-    __shared__ float s_row[5][kFR][kT];
+    constexpr int R = T + 2 * kWinR;
+    __shared__ float s_in[5][R][R + 1];
+    __shared__ float s_row[5][R][T];
 
     const int tid = threadIdx.x;
-    const int x0 = blockIdx.x * kT, y0 = blockIdx.y * kT;
+    const int x0 = blockIdx.x * T, y0 = blockIdx.y * T;
 
     // per-cell A^T A and A^T db at the clamped coordinate of the cell
-    for (int p = tid; p < kFR * kFR; p += 256) {
-        const int ry = p / kFR, rx = p % kFR;
+#pragma unroll 2
+    for (int p = tid; p < R * R; p += 256) {
+        const int ry = p / R, rx = p % R;
         const int gy = clampi(y0 - kWinR + ry, 0, h - 1), gx = clampi(x0 - kWinR + rx, 0, w - 1);
         const size_t gi = (size_t)gy * w + gx;
         const float2 dp = prior_at(d_in, prior_mode, gy, gx, w, ch, cw);
+        const float4 a1 = A1[gi];
+        const float2 bb1 = b1[gi];
         // sample the new frame's expansion at x + prior
         const float sy = clampf((float)gy + dp.y, 0.0f, (float)(h - 1));
         const float sx = clampf((float)gx + dp.x, 0.0f, (float)(w - 1));
@@ -193,8 +199,6 @@ __global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1
         const float a2yy = a00.z * w00 + a01.z * w01 + a10.z * w10 + a11.z * w11;
         const float b2x = c00.x * w00 + c01.x * w01 + c10.x * w10 + c11.x * w11;
         const float b2y = c00.y * w00 + c01.y * w01 + c10.y * w10 + c11.y * w11;
-        const float4 a1 = A1[gi];
-        const float2 bb1 = b1[gi];
         const float axx = 0.5f * (a1.x + a2xx), axy = 0.5f * (a1.y + a2xy), ayy = 0.5f * (a1.z + a2yy);
         const float dbx = -0.5f * (b2x - bb1.x) + axx * dp.x + axy * dp.y;
         const float dby = -0.5f * (b2y - bb1.y) + axy * dp.x + ayy * dp.y;
@@ -207,8 +211,8 @@ __global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1
     __syncthreads();
 
     // row pass of the separable Gaussian window
-    for (int p = tid; p < kFR * kT; p += 256) {
-        const int ry = p / kT, tx = p % kT;
+    for (int p = tid; p < R * T; p += 256) {
+        const int ry = p / T, tx = p % T;
         float acc[5] = {0, 0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k <= 2 * kWinR; ++k) {
@@ -222,8 +226,8 @@ __global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1
     __syncthreads();
 
     // column pass + ridge solve
-    for (int p = tid; p < kT * kT; p += 256) {
-        const int ty = p / kT, tx = p % kT;
+    for (int p = tid; p < T * T; p += 256) {
+        const int ty = p / T, tx = p % T;
         const int gy = y0 + ty, gx = x0 + tx;
         if (gy >= h || gx >= w) continue;
         float acc[5] = {0, 0, 0, 0, 0};
@@ -243,51 +247,54 @@ __global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 5 / Eq. 6.  One block per patch; the last block to arrive evaluates the gate.
-__global__ __launch_bounds__(256) void k_patch_gate(const float2* __restrict__ flow, int h, int w, float tau_t,
-                                                    float theta_r, float* dp_out, sali_gate* gate, Cursors* cur,
-                                                    float* __restrict__ flow_uv) {
-    __shared__ float s_part[4];
-    __shared__ int s_cnt[4];
+// Eq. 5 / Eq. 6.  One block per patch row, one wave per patch (16 waves take the 24 patches of
+// the row in two rounds); the last block to finish evaluates the gate.
+__global__ __launch_bounds__(1024) void k_patch_gate(const float2* __restrict__ flow, int h, int w, float tau_t,
+                                                     float theta_r, float* dp_out, sali_gate* gate, Cursors* cur,
+                                                     float* __restrict__ flow_uv) {
+    __shared__ int s_cnt[16];
     __shared__ int s_last;
-    const int pr = blockIdx.x / kGrid, pc = blockIdx.x % kGrid;
+    const int pr = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
-    const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
-    const int pw = xb - xa, area = pw * (yb - ya);
-    float acc = 0.0f;
-    for (int p = threadIdx.x; p < area; p += 256) {
-        const int y = ya + p / pw, x = xa + p % pw;
-        const float2 d = flow[(size_t)y * w + x];
-        acc += d.x * d.x + d.y * d.y;
-        if (flow_uv != nullptr) {
-            flow_uv[(size_t)y * w + x] = d.x;
-            flow_uv[(size_t)h * w + (size_t)y * w + x] = d.y;
+    for (int pc = wave; pc < kGrid; pc += 16) {
+        const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
+        const int pw = xb - xa, area = pw * (yb - ya);
+        float acc = 0.0f;
+        for (int p = lane; p < area; p += 64) {
+            const int y = ya + p / pw, x = xa + p % pw;
+            const float2 d = flow[(size_t)y * w + x];
+            acc += d.x * d.x + d.y * d.y;
+            if (flow_uv != nullptr) {
+                flow_uv[(size_t)y * w + x] = d.x;
+                flow_uv[(size_t)h * w + (size_t)y * w + x] = d.y;
+            }
         }
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+        if (lane == 0)
+            __hip_atomic_store(dp_out + pr * kGrid + pc, sqrtf(acc / (float)area), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     }
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
-    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const float total = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
-        __hip_atomic_store(dp_out + blockIdx.x, sqrtf(total / (float)area), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
         __threadfence();
         const uint32_t prev = atomicAdd(&cur->patch_done, 1u);
-        s_last = (prev == (uint32_t)(kTokens - 1)) ? 1 : 0;
+        s_last = (prev == (uint32_t)(kGrid - 1)) ? 1 : 0;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();
     int n = 0;
-    for (int i = threadIdx.x; i < kTokens; i += 256) {
-        const float v = __hip_atomic_load(dp_out + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        n += (v < tau_t) ? 1 : 0;
+    if (threadIdx.x < kTokens) {
+        const float v = __hip_atomic_load(dp_out + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        n = (v < tau_t) ? 1 : 0;
     }
     for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
-    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = n;
+    if (lane == 0) s_cnt[wave] = n;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        int n_static = 0;
+        for (int k = 0; k < 16; ++k) n_static += s_cnt[k];
         const float r = (float)n_static / (float)kTokens;
         sali_gate gt;
         gt.n_static = n_static;
@@ -324,14 +331,22 @@ hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, 
 hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2, const float2* b2,
                             const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
                             FlowWeights fw, hipStream_t s) {
-    dim3 grid((w + kT - 1) / kT, (h + kT - 1) / kT);
-    hipLaunchKernelGGL(k_flow_iter, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw, prior_mode, fw);
+    // small levels: 16x16 tiles so that the level spreads over many compute units
+    if ((long long)((w + 31) / 32) * ((h + 31) / 32) < 2048) {
+        dim3 grid((w + 15) / 16, (h + 15) / 16);
+        hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw,
+                           prior_mode, fw);
+    } else {
+        dim3 grid((w + 31) / 32, (h + 31) / 32);
+        hipLaunchKernelGGL(k_flow_iter<32>, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw,
+                           prior_mode, fw);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
                              sali_gate* d_gate, Cursors* d_cur, float* d_flow_uv_or_null, hipStream_t s) {
-    hipLaunchKernelGGL(k_patch_gate, dim3(kTokens), dim3(256), 0, s, d_flow, h, w, tau_t, theta_r, d_dp, d_gate,
+    hipLaunchKernelGGL(k_patch_gate, dim3(kGrid), dim3(1024), 0, s, d_flow, h, w, tau_t, theta_r, d_dp, d_gate,
                        d_cur, d_flow_uv_or_null);
     return hipGetLastError();
 }

@@ -15,6 +15,7 @@
 // a tier), so pool writes are contiguous runs and pruned tokens are never read.
 
 #include "sali_internal.h"
+#include "tier_body.h"
 
 namespace sali {
 
@@ -67,122 +68,9 @@ __global__ __launch_bounds__(kTokens) void k_tier(const float* __restrict__ scor
                                                   uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
                                                   uint16_t* __restrict__ order_out, Cursors* cur, int cap16,
                                                   int cap8, int cap4) {
-    __shared__ float s_score[kTokens];
-    __shared__ int s_wave_cnt[kTokens / 64][4];
-    __shared__ int s_nan;
-    const int i = threadIdx.x;
-    const int wave = i >> 6, lane = i & 63;
-
-    if (gate != nullptr && gate->redundant != 0) {
-        // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame.
-        if (i == 0) {
-            sali_frame_row r = {};
-            r.frame_id = frame_id;
-            r.src = cur->last_src;
-            r.stored = 0;
-            rows[frame_id] = r;
-        }
-        return;
-    }
-
-    const float s = scores[i];
-    s_score[i] = s;
-    if (i == 0) s_nan = 0;
-    __syncthreads();
-    if (s != s) s_nan = 1;
-    __syncthreads();
-    if (s_nan) {
-        if (i == 0) {
-            atomicOr(&cur->status, SALI_FAULT_NAN_SCORE);
-            sali_frame_row r = {};
-            r.frame_id = frame_id;
-            r.src = -1;
-            rows[frame_id] = r;
-        }
-        return;
-    }
-
-    int tier;
-    if (tp.mode == 0) {
-        // Eq. 8, inequalities as printed
-        tier = SALI_TIER_PRUNE;
-        if (s > tp.tau_low) tier = SALI_TIER_INT4;
-        if (s > tp.tau_med) tier = SALI_TIER_INT8;
-        if (s > tp.tau_high) tier = SALI_TIER_FP16;
-    } else {
-        // rank by (score descending, token index ascending)
-        int rank = 0;
-        for (int j = 0; j < kTokens; ++j) {
-            const float sj = s_score[j];
-            rank += (sj > s || (sj == s && j < i)) ? 1 : 0;
-        }
-        tier = SALI_TIER_PRUNE;
-        if (rank < tp.k16 + tp.k8 + tp.k4) tier = SALI_TIER_INT4;
-        if (rank < tp.k16 + tp.k8) tier = SALI_TIER_INT8;
-        if (rank < tp.k16) tier = SALI_TIER_FP16;
-    }
-
-    // slot = number of earlier tokens in the same tier (ballot inside the wave + wave prefix)
-    const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int in_wave = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const unsigned long long m = __ballot(tier == k);
-        if (tier == k) in_wave = __popcll(m & lt_mask);
-        if (lane == 0) s_wave_cnt[wave][k] = __popcll(m);
-    }
-    __syncthreads();
-    int before = 0;
-    int cnt[4] = {0, 0, 0, 0};
-    for (int w = 0; w < kTokens / 64; ++w) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int c = s_wave_cnt[w][k];
-            cnt[k] += c;
-            if (w < wave && k == tier) before += c;
-        }
-    }
-    const int slot = before + in_wave;
-
-    // capacity check (uniform: every thread reads the same cursors)
-    const int c16 = cur->c16, c8 = cur->c8, c4 = cur->c4;
-    const bool overflow = (long long)c16 + cnt[0] > cap16 || (long long)c8 + cnt[1] > cap8 ||
-                          (long long)c4 + cnt[2] > cap4;
-    __syncthreads();    // all cursor reads precede the update below
-    if (overflow) {
-        if (i == 0) {
-            atomicOr(&cur->status, SALI_FAULT_OVERFLOW);
-            sali_frame_row r = {};
-            r.frame_id = frame_id;
-            r.src = -1;
-            rows[frame_id] = r;
-        }
-        return;
-    }
-
-    tier_out[i] = (uint8_t)tier;
-    slot_out[i] = (uint16_t)slot;
-    const int tier_base = (tier > 0 ? cnt[0] : 0) + (tier > 1 ? cnt[1] : 0) + (tier > 2 ? cnt[2] : 0);
-    order_out[tier_base + slot] = (uint16_t)i;
-
-    if (i == 0) {
-        sali_frame_row r = {};
-        r.frame_id = frame_id;
-        r.src = frame_id;
-        r.stored = 1;
-        r.base16 = c16;
-        r.base8 = c8;
-        r.base4 = c4;
-        r.n16 = cnt[0];
-        r.n8 = cnt[1];
-        r.n4 = cnt[2];
-        r.n_pruned = cnt[3];
-        rows[frame_id] = r;
-        cur->c16 = c16 + cnt[0];
-        cur->c8 = c8 + cnt[1];
-        cur->c4 = c4 + cnt[2];
-        cur->last_src = frame_id;
-    }
+    __shared__ TierShared sh;
+    const bool redundant = gate != nullptr && gate->redundant != 0;
+    tier_body(sh, scores, redundant, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
 }
 
 // ---------------------------------------------------------------------------------------------

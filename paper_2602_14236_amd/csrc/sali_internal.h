@@ -35,7 +35,8 @@ struct Cursors {
     int32_t last_src;           // frame id of the last stored frame, -1 = none
     uint32_t status;            // sticky SALI_FAULT_* bits
     uint32_t patch_done;        // arrival counter of the patch-motion kernel (self-resetting)
-    uint32_t pad[2];
+    uint32_t pool_done;         // arrival counter of the pooling kernel (self-resetting)
+    uint32_t pad;
 };
 
 struct Pools {
@@ -52,6 +53,18 @@ struct TierParams {
     int32_t mode;
     float tau_high, tau_med, tau_low;
     int32_t k16, k8, k4;
+};
+
+// everything the tier / compaction step needs when it is fused into another kernel
+struct TierLaunch {
+    TierParams tp;
+    int32_t frame_id;
+    sali_frame_row* rows;
+    uint8_t* tier;
+    uint16_t* slot;
+    uint16_t* order;
+    Cursors* cur;
+    int32_t cap16, cap8, cap4;
 };
 
 struct LevelGeom {
@@ -91,7 +104,7 @@ hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, 
                         hipStream_t s);
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
                        const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
-                       float* d_scores, uint8_t* d_salmap_or_null, hipStream_t s);
+                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null, hipStream_t s);
 
 // flow_kernels.hip
 hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,

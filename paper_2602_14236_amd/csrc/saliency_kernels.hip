@@ -8,16 +8,21 @@
 //            gray -> 5x5 binomial blur -> Sobel -> squared magnitude -> non-maximum suppression
 //            -> weak/strong class, and RGB -> 8-bit LAB -> 5x5 variance sum V, plus the frame
 //            sum of V (one 64-bit atomic per block).  Also emits the gray image for the flow.
-//   k_union  8-connected hysteresis as a lock-free union-find over weak/strong pixels.  A
+//            8-connected hysteresis is a lock-free union-find over weak/strong pixels.  A
 //            pixel's key is its index with bit 31 set for weak pixels; links always point to
 //            the smaller key, so the root of a component is a strong pixel iff it has one.
+//            k_prep joins the pixels of its own tile in LDS and writes each pixel's link to
+//            its tile-local root.
+//   k_union  joins components across tile borders with global atomics (border pixels only).
 //   k_pool   per patch: E = edge pixel whose root is strong, C = V above the frame mean and
-//            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.
+//            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.  In the
+//            chained step the last block to finish also assigns tiers and compaction indices.
 //
 // All stencils replicate the border; non-maximum suppression treats out-of-image neighbours
 // as magnitude 0.
 
 #include "sali_internal.h"
+#include "tier_body.h"
 
 namespace sali {
 
@@ -32,6 +37,45 @@ constexpr uint32_t kWeakBit = 0x80000000u;
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// union-find on a parent array (LDS or global); key = index | weak bit; links go to smaller keys
+template <int kScope>
+__device__ __forceinline__ uint32_t uf_load(const uint32_t* parent, uint32_t idx) {
+    return __hip_atomic_load(parent + idx, __ATOMIC_RELAXED, kScope);
+}
+
+template <int kScope>
+__device__ __forceinline__ uint32_t uf_find(const uint32_t* parent, uint32_t key) {
+    uint32_t k = key;               // keys strictly decrease along links, so this terminates
+    for (;;) {
+        const uint32_t p = uf_load<kScope>(parent, k & ~kWeakBit);
+        if (p == k) return k;
+        k = p;
+    }
+}
+
+// for kernels that run after all links are final: ordinary cached loads
+__device__ __forceinline__ uint32_t uf_find_settled(const uint32_t* __restrict__ parent, uint32_t key) {
+    uint32_t k = key;
+    for (;;) {
+        const uint32_t p = parent[k & ~kWeakBit];
+        if (p == k) return k;
+        k = p;
+    }
+}
+
+template <int kScope>
+__device__ __forceinline__ void uf_unite(uint32_t* parent, uint32_t ka, uint32_t kb) {
+    for (;;) {
+        ka = uf_find<kScope>(parent, ka);
+        kb = uf_find<kScope>(parent, kb);
+        if (ka == kb) return;
+        if (ka < kb) { const uint32_t t = ka; ka = kb; kb = t; }      // ka is the larger key
+        const uint32_t old = atomicMin(parent + (ka & ~kWeakBit), kb);
+        if (old == ka) return;      // ka was a root and now points at kb
+        ka = old;                   // somebody linked ka first: continue from where it pointed
+    }
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, int h, int w, int with_saliency,
@@ -45,6 +89,8 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
     __shared__ int s_m2[kRegM][kRegM];
     __shared__ uint8_t s_lab[3][kRegB][kRegB];
     __shared__ unsigned long long s_sum[4];
+    __shared__ uint32_t s_par[kTile * kTile];     // tile-local union-find, key = local index | weak bit
+    __shared__ uint8_t s_cls[kTile][kTile];
 
     const int tid = threadIdx.x;
     const int x0 = blockIdx.x * kTile, y0 = blockIdx.y * kTile;
@@ -153,7 +199,8 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
         if (m2 > n1 && m2 >= n2) cls = m2 >= hi2 ? 2 : (m2 >= lo2 ? 1 : 0);
         const size_t gi = (size_t)gy * w + gx;
         cls_out[gi] = (uint8_t)cls;
-        parent_out[gi] = (uint32_t)gi | (cls == 1 ? kWeakBit : 0u);
+        s_cls[ty][tx] = (uint8_t)cls;
+        s_par[p] = (uint32_t)p | (cls == 1 ? kWeakBit : 0u);
 
         // 5x5 colour variance: 25 * sum v^2 - (sum v)^2 per channel
         uint32_t v = 0;
@@ -181,70 +228,105 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
     if ((tid & 63) == 0) s_sum[tid >> 6] = local_sum;
     __syncthreads();
     if (tid == 0) atomicAdd(msum_acc, s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
+
+    // hysteresis, tile-local part.  First every pixel of a horizontal run of weak/strong pixels
+    // links to the run's smallest key (no atomics, at most one row of LDS reads) ...
+    const int th = min(kTile, h - y0), tw = min(kTile, w - x0);
+    for (int p = tid; p < kTile * kTile; p += 256) {
+        const int ty = p / kTile, tx = p % kTile;
+        if (ty >= th || tx >= tw) continue;
+        const int c = s_cls[ty][tx];
+        if (c == 0) continue;
+        uint32_t best = (uint32_t)p | (c == 1 ? kWeakBit : 0u);
+        for (int xx = tx - 1; xx >= 0; --xx) {
+            const int cj = s_cls[ty][xx];
+            if (cj == 0) break;
+            best = min(best, (uint32_t)(ty * kTile + xx) | (cj == 1 ? kWeakBit : 0u));
+        }
+        for (int xx = tx + 1; xx < tw; ++xx) {
+            const int cj = s_cls[ty][xx];
+            if (cj == 0) break;
+            best = min(best, (uint32_t)(ty * kTile + xx) | (cj == 1 ? kWeakBit : 0u));
+        }
+        s_par[p] = best;
+    }
+    __syncthreads();
+    // ... then runs of adjacent rows are joined through their heads (S, SW, SE neighbours; a
+    // neighbour whose left neighbour touches this pixel too belongs to an already joined run)
+    for (int p = tid; p < kTile * kTile; p += 256) {
+        const int ty = p / kTile, tx = p % kTile;
+        if (ty + 1 >= th || tx >= tw) continue;
+        if (s_cls[ty][tx] == 0) continue;
+#pragma unroll
+        for (int dx = -1; dx <= 1; ++dx) {
+            const int xx = tx + dx;
+            if (xx < 0 || xx >= tw) continue;
+            if (s_cls[ty + 1][xx] == 0) continue;
+            if (dx > -1 && xx - 1 >= 0 && s_cls[ty + 1][xx - 1] != 0) continue;
+            uf_unite<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, uf_load<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, p),
+                                                   uf_load<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, (ty + 1) * kTile + xx));
+        }
+    }
+    __syncthreads();
+    // each pixel's global link: the global key of its tile-local root (itself if it is the root or
+    // not an edge candidate).  Tile-local row-major order agrees with image row-major order.
+    for (int p = tid; p < kTile * kTile; p += 256) {
+        const int ty = p / kTile, tx = p % kTile;
+        if (ty >= th || tx >= tw) continue;
+        const int c = s_cls[ty][tx];
+        uint32_t root = (uint32_t)p | (c == 1 ? kWeakBit : 0u);
+        if (c != 0) root = uf_find<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, root);
+        const uint32_t rl = root & ~kWeakBit;
+        const size_t rg = (size_t)(y0 + (int)(rl / kTile)) * w + (x0 + (int)(rl % kTile));
+        parent_out[(size_t)(y0 + ty) * w + (x0 + tx)] = (uint32_t)rg | (root & kWeakBit);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
-namespace {
-
-__device__ __forceinline__ uint32_t load_parent(const uint32_t* parent, uint32_t idx) {
-    return __hip_atomic_load(parent + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ uint32_t find_root(const uint32_t* parent, uint32_t key) {
-    // keys strictly decrease along links, so this terminates
-    uint32_t k = key;
-    for (;;) {
-        const uint32_t p = load_parent(parent, k & ~kWeakBit);
-        if (p == k) return k;
-        k = p;
-    }
-}
-
-__device__ void unite(uint32_t* parent, uint32_t ka, uint32_t kb) {
-    for (;;) {
-        ka = find_root(parent, ka);
-        kb = find_root(parent, kb);
-        if (ka == kb) return;
-        if (ka < kb) { const uint32_t t = ka; ka = kb; kb = t; }      // ka is the larger key
-        const uint32_t old = atomicMin(parent + (ka & ~kWeakBit), kb);
-        if (old == ka) return;      // ka was a root and now points at kb
-        ka = old;                   // somebody linked ka first: continue from where it pointed
-    }
-}
-
-}  // namespace
-
+// hysteresis, cross-tile part: only pairs of neighbours that lie in different k_prep tiles
 __global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, uint32_t* parent, int h, int w,
                                                const sali_gate* gate) {
     if (gate != nullptr && gate->redundant != 0) return;
     const int x = blockIdx.x * 64 + (threadIdx.x & 63);
     const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (x >= w || y >= h) return;
+    const int lx = x % kTile, ly = y % kTile;
+    if (lx != 0 && lx != kTile - 1 && ly != kTile - 1) return;      // all forward neighbours in the same tile
     const size_t gi = (size_t)y * w + x;
     const int c = cls[gi];
     if (c == 0) return;
     const uint32_t me = (uint32_t)gi | (c == 1 ? kWeakBit : 0u);
-    // forward half of the 8-neighbourhood: E, SW, S, SE
     const int ny[4] = {0, 1, 1, 1};
     const int nx[4] = {1, -1, 0, 1};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int yy = y + ny[k], xx = x + nx[k];
         if (yy >= h || xx < 0 || xx >= w) continue;
+        if (yy / kTile == y / kTile && xx / kTile == x / kTile) continue;     // joined in LDS already
         const size_t gj = (size_t)yy * w + xx;
         const int cj = cls[gj];
         if (cj == 0) continue;
-        unite(parent, me, (uint32_t)gj | (cj == 1 ? kWeakBit : 0u));
+        uf_unite<__HIP_MEMORY_SCOPE_AGENT>(parent, me, (uint32_t)gj | (cj == 1 ? kWeakBit : 0u));
     }
 }
 
-// one block per patch
-__global__ __launch_bounds__(256) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
-                                              const uint32_t* __restrict__ var, const unsigned long long* msum,
-                                              int h, int w, const sali_gate* gate, float* __restrict__ scores,
-                                              uint8_t* __restrict__ salmap) {
-    if (gate != nullptr && gate->redundant != 0) return;
-    __shared__ uint32_t s_q[4];
+// One block of 576 threads per patch.  With do_tier the last block to finish runs the tier /
+// compaction step on the 576 scores (and block 0 writes the pointer row of a redundant frame).
+__global__ __launch_bounds__(kTokens) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
+                                                  const uint32_t* __restrict__ var, const unsigned long long* msum,
+                                                  int h, int w, const sali_gate* gate, float* scores,
+                                                  uint8_t* __restrict__ salmap, int do_tier, TierParams tp,
+                                                  int frame_id, sali_frame_row* rows, uint8_t* tier_out,
+                                                  uint16_t* slot_out, uint16_t* order_out, Cursors* cur, int cap16,
+                                                  int cap8, int cap4) {
+    __shared__ TierShared sh;
+    __shared__ uint32_t s_q[kTokens / 64];
+    __shared__ int s_last;
+    if (gate != nullptr && gate->redundant != 0) {
+        if (do_tier && blockIdx.x == 0)
+            tier_body(sh, scores, true, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
+        return;
+    }
     const int pr = blockIdx.x / kGrid, pc = blockIdx.x % kGrid;
     const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
     const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
@@ -252,13 +334,13 @@ __global__ __launch_bounds__(256) void k_pool(const uint8_t* __restrict__ cls, c
     const unsigned long long m = *msum;
     const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
     uint32_t q = 0;
-    for (int p = threadIdx.x; p < area; p += 256) {
+    for (int p = threadIdx.x; p < area; p += kTokens) {
         const int y = ya + p / pw, x = xa + p % pw;
         const size_t gi = (size_t)y * w + x;
         const int c = cls[gi];
         uint32_t e = 0;
         if (c == 2) e = 1;
-        else if (c == 1) e = (find_root(parent, (uint32_t)gi | kWeakBit) & kWeakBit) ? 0u : 1u;
+        else if (c == 1) e = (uf_find_settled(parent, (uint32_t)gi | kWeakBit) & kWeakBit) ? 0u : 1u;
         const uint32_t v = var[gi];
         const uint32_t cm = ((unsigned long long)v * hw > m && v >= kVMin) ? 1u : 0u;
         q += e + cm;
@@ -268,10 +350,23 @@ __global__ __launch_bounds__(256) void k_pool(const uint8_t* __restrict__ cls, c
     if ((threadIdx.x & 63) == 0) s_q[threadIdx.x >> 6] = q;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t total = s_q[0] + s_q[1] + s_q[2] + s_q[3];
+        uint32_t total = 0;
+        for (int k = 0; k < kTokens / 64; ++k) total += s_q[k];
         const uint32_t s_fix = (uint32_t)(((unsigned long long)total << 15) / (unsigned long long)area);
-        scores[blockIdx.x] = (float)s_fix * (1.0f / 65536.0f);     // exact: s_fix <= 2^16
+        const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
+        __hip_atomic_store(scores + blockIdx.x, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int last = 0;
+        if (do_tier) {
+            __threadfence();
+            last = (atomicAdd(&cur->pool_done, 1u) == (uint32_t)(kTokens - 1)) ? 1 : 0;
+        }
+        s_last = last;
     }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    if (threadIdx.x == 0) cur->pool_done = 0u;      // ready for the next launch
+    tier_body(sh, scores, false, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -294,9 +389,12 @@ hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, 
 
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
                        const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
-                       float* d_scores, uint8_t* d_salmap_or_null, hipStream_t s) {
-    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(256), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
-                       d_gate_or_null, d_scores, d_salmap_or_null);
+                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null, hipStream_t s) {
+    TierLaunch t = {};
+    if (tier_or_null != nullptr) t = *tier_or_null;
+    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(kTokens), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
+                       d_gate_or_null, d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, t.tp, t.frame_id,
+                       t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4);
     return hipGetLastError();
 }
 

@@ -130,3 +130,36 @@ def test_reset_forgets_history():
     rows = ctx.read_frame_table(0, 2)
     assert rows[0].stored == 1 and rows[0].base16 == 0 and rows[1].src == -1
     ctx.close()
+
+
+def test_pipelined_step_matches_oracle_and_serial_path():
+    """sali_step_pipelined (analysis of frame t+1 on one stream while frame t is stored on another)
+    must leave exactly the state the frame-by-frame path leaves."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[1]
+    p = workload_params(wl, n_heads=4)
+    v = synth.video(1)
+    n = 8
+    scale = synth.kv_channel_scale(wl, 1, 4)
+    rgbs = [torch.from_numpy(v.frame(t)).cuda() for t in range(n)]
+    kvs = [synth.kv_frame(wl, t, device="cuda", n_layers=1, n_heads=4, scale=scale) for t in range(n)]
+    orc = SaliCacheOracle(oracle_config(p))
+    for t in range(n):
+        orc.step(v.frame(t), kvs[t].cpu().numpy(), t)
+    ctx = binding.SaliContext(lib_config(p))
+    s_img, s_kv = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    print("pipelined: prologue", flush=True)
+    ctx.step_pipelined(rgbs[0], 0, None, -1, s_img, s_kv)
+    for t in range(n):
+        print("pipelined: frame", t, flush=True)
+        nxt = rgbs[t + 1] if t + 1 < n else None
+        ctx.step_pipelined(nxt, t + 1, kvs[t], t, s_img, s_kv)
+    torch.cuda.synchronize()
+    _compare_all(ctx, orc, range(n))
+    # storing a frame that was never analysed is a synchronous error
+    ctx.reset()
+    with pytest.raises(binding.SaliError) as e:
+        ctx.store(kvs[0], 3, s_kv)
+    assert e.value.code == -5
+    ctx.close()
