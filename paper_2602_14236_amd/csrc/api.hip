@@ -20,7 +20,7 @@ struct ScratchLayout {
 };
 
 struct TableLayout {
-    size_t lin, fl, cursors, rows, tier, slot, order, total;
+    size_t lut, cursors, rows, tier, slot, order, total;      // lut = lin[256] followed by fl[4096]
 };
 
 int check_config(const sali_config* c) {
@@ -136,8 +136,7 @@ TableLayout table_layout(const sali_config& c) {
     TableLayout t = {};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    t.lin = take(256 * sizeof(uint16_t));
-    t.fl = take(4096 * sizeof(uint16_t));
+    t.lut = take((256 + 4096) * sizeof(uint16_t));
     t.cursors = take(sizeof(Cursors));
     t.rows = take((size_t)c.max_frames * sizeof(sali_frame_row));
     t.tier = take((size_t)c.max_frames * kTokens);
@@ -240,8 +239,7 @@ int enqueue_frame_analysis(sali_ctx* c, const uint8_t* d_rgb, int slot, bool wit
     }
     SALI_TRY(launch_prep(d_rgb, cfg.src_h, cfg.src_w, with_saliency, c->sc<uint8_t>(c->sl.y8),
                          c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.var), c->sc<uint32_t>(c->sl.parent), acc,
-                         clr, c->tb<uint16_t>(c->tl.lin), c->tb<uint16_t>(c->tl.fl), cfg.canny_lo * cfg.canny_lo,
-                         cfg.canny_hi * cfg.canny_hi, s));
+                         clr, c->tb<uint16_t>(c->tl.lut), cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
     if (slot < 0) return SALI_OK;
     float* pyr = c->sc<float>(c->sl.pyr);
     const LevelGeom& g = c->geom;
@@ -418,11 +416,9 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
         }
     }
 
-    uint16_t lin[256];
-    static uint16_t fl[4096];
-    fill_luts(lin, fl);
-    if (hipMemcpy(c->tables + c->tl.lin, lin, sizeof(lin), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(c->tables + c->tl.fl, fl, sizeof(fl), hipMemcpyHostToDevice) != hipSuccess) {
+    uint16_t lut[256 + 4096];
+    fill_luts(lut, lut + 256);
+    if (hipMemcpy(c->tables + c->tl.lut, lut, sizeof(lut), hipMemcpyHostToDevice) != hipSuccess) {
         sali_destroy(c);
         return SALI_ERR_HIP;
     }

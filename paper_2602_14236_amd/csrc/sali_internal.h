@@ -98,8 +98,7 @@ hipError_t launch_unpack(const sali_frame_row* d_rows, int frame_id, const uint1
 // saliency_kernels.hip
 hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
                        uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
-                       unsigned long long* d_msum_clear, const uint16_t* d_lin, const uint16_t* d_fl,
-                       int lo2, int hi2, hipStream_t s);
+                       unsigned long long* d_msum_clear, const uint16_t* d_lut, int lo2, int hi2, hipStream_t s);
 hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, const sali_gate* d_gate_or_null,
                         hipStream_t s);
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,

@@ -4,15 +4,16 @@
 // Implementation Details (Canny edge detection combined with adaptive thresholding on the
 // local colour variance in LAB).  Everything here is integer arithmetic, so scores are exact.
 //
-//   k_prep   one pass over the RGB frame, 32x32 tiles with a 4-pixel halo staged in LDS:
+//   k_prep   one pass over the RGB frame, 32x32 tiles with a 4-pixel halo staged in LDS, 1024
+//            threads per tile (one output pixel each; colour tables held in LDS):
 //            gray -> 5x5 binomial blur -> Sobel -> squared magnitude -> non-maximum suppression
 //            -> weak/strong class, and RGB -> 8-bit LAB -> 5x5 variance sum V, plus the frame
 //            sum of V (one 64-bit atomic per block).  Also emits the gray image for the flow.
 //            8-connected hysteresis is a lock-free union-find over weak/strong pixels.  A
 //            pixel's key is its index with bit 31 set for weak pixels; links always point to
 //            the smaller key, so the root of a component is a strong pixel iff it has one.
-//            k_prep joins the pixels of its own tile in LDS and writes each pixel's link to
-//            its tile-local root.
+//            k_prep labels the components of its own tile in LDS (label equivalence, no
+//            global traffic) and writes each pixel's link to its tile-local root.
 //   k_union  joins components across tile borders with global atomics (border pixels only).
 //   k_pool   per patch: E = edge pixel whose root is strong, C = V above the frame mean and
 //            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.  In the
@@ -78,55 +79,81 @@ __device__ __forceinline__ void uf_unite(uint32_t* parent, uint32_t ka, uint32_t
 
 }  // namespace
 
-__global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, int h, int w, int with_saliency,
-                                              uint8_t* __restrict__ y8_out, uint8_t* __restrict__ cls_out,
-                                              uint32_t* __restrict__ var_out, uint32_t* __restrict__ parent_out,
-                                              unsigned long long* msum_acc, unsigned long long* msum_clear,
-                                              const uint16_t* __restrict__ lut_lin,
-                                              const uint16_t* __restrict__ lut_fl, int lo2, int hi2) {
+// gray only (the stand-alone flow call needs no saliency)
+__global__ __launch_bounds__(256) void k_gray(const uint8_t* __restrict__ rgb, int n, uint8_t* __restrict__ y8_out) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint8_t* px = rgb + (size_t)i * 3;
+    y8_out[i] = (uint8_t)((77 * px[0] + 150 * px[1] + 29 * px[2] + 128) >> 8);
+}
+
+// 1024 threads per 32x32 tile: one output pixel per thread, at most two region cells per thread
+// in the halo stages.  The tile is latency-bound, so the point is many waves and few steps.
+constexpr int kPrepThreads = 1024;
+
+__global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict__ rgb, int h, int w,
+                                                       uint8_t* __restrict__ y8_out, uint8_t* __restrict__ cls_out,
+                                                       uint32_t* __restrict__ var_out,
+                                                       uint32_t* __restrict__ parent_out,
+                                                       unsigned long long* msum_acc, unsigned long long* msum_clear,
+                                                       const uint32_t* __restrict__ lut_words, int lo2, int hi2) {
+    __shared__ uint32_t s_lut[(256 + 4096) / 2];          // lin[256] then fl[4096], 16-bit entries
     __shared__ uint8_t s_y[kReg][kReg];
     __shared__ uint8_t s_b[kRegB][kRegB];
     __shared__ int s_m2[kRegM][kRegM];
     __shared__ uint8_t s_lab[3][kRegB][kRegB];
-    __shared__ unsigned long long s_sum[4];
-    __shared__ uint32_t s_par[kTile * kTile];     // tile-local union-find, key = local index | weak bit
+    __shared__ unsigned long long s_sum[kPrepThreads / 64];
+    __shared__ uint32_t s_lbl[kTile * kTile];             // tile-local union-find links, key = local index | weak bit
     __shared__ uint8_t s_cls[kTile][kTile];
 
     const int tid = threadIdx.x;
     const int x0 = blockIdx.x * kTile, y0 = blockIdx.y * kTile;
+    const uint16_t* s_lin = reinterpret_cast<const uint16_t*>(s_lut);
+    const uint16_t* s_fl = s_lin + 256;
 
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0 && msum_clear != nullptr) *msum_clear = 0ull;
 
-    // stage 1: gray (halo 4) and LAB (halo 2) at clamped image coordinates
-    for (int p = tid; p < kReg * kReg; p += 256) {
-        const int ry = p / kReg, rx = p % kReg;
-        const int gy = clampi(y0 - kHalo + ry, 0, h - 1), gx = clampi(x0 - kHalo + rx, 0, w - 1);
-        const uint8_t* px = rgb + ((size_t)gy * w + gx) * 3;
-        const int r = px[0], g = px[1], b = px[2];
-        s_y[ry][rx] = (uint8_t)((77 * r + 150 * g + 29 * b + 128) >> 8);
-        if (with_saliency && ry >= 2 && ry < kReg - 2 && rx >= 2 && rx < kReg - 2) {
-            const int lr = lut_lin[r], lg = lut_lin[g], lb = lut_lin[b];
-            const int tx = (1777 * lr + 1541 * lg + 778 * lb + 2048) >> 12;
-            const int ty = (871 * lr + 2929 * lg + 296 * lb + 2048) >> 12;
-            const int tz = (73 * lr + 448 * lg + 3575 * lb + 2048) >> 12;
-            const int fx = lut_fl[tx], fy = lut_fl[ty], fz = lut_fl[tz];
-            const int L = clampi(((116 * fy - 524288) * 255 + 1638400) / 3276800, 0, 255);
-            const int A = clampi((500 * (fx - fy) + 4194304 + 16384) >> 15, 0, 255);
-            const int B = clampi((200 * (fy - fz) + 4194304 + 16384) >> 15, 0, 255);
-            s_lab[0][ry - 2][rx - 2] = (uint8_t)L;
-            s_lab[1][ry - 2][rx - 2] = (uint8_t)A;
-            s_lab[2][ry - 2][rx - 2] = (uint8_t)B;
+    // stage 1a: colour tables -> LDS; RGB of the 40x40 region (clamped coordinates) -> gray
+    for (int i = tid; i < (256 + 4096) / 2; i += kPrepThreads) s_lut[i] = lut_words[i];
+    int cr[2], cg[2], cb[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int p = tid + k * kPrepThreads;
+        cr[k] = cg[k] = cb[k] = 0;
+        if (p < kReg * kReg) {
+            const int ry = p / kReg, rx = p % kReg;
+            const int gy = clampi(y0 - kHalo + ry, 0, h - 1), gx = clampi(x0 - kHalo + rx, 0, w - 1);
+            const uint8_t* px = rgb + ((size_t)gy * w + gx) * 3;
+            cr[k] = px[0];
+            cg[k] = px[1];
+            cb[k] = px[2];
+            s_y[ry][rx] = (uint8_t)((77 * cr[k] + 150 * cg[k] + 29 * cb[k] + 128) >> 8);
         }
     }
     __syncthreads();
 
-    // gray image for the flow pyramid
-    for (int p = tid; p < kTile * kTile; p += 256) {
-        const int ty = p / kTile, tx = p % kTile;
-        const int gy = y0 + ty, gx = x0 + tx;
-        if (gy < h && gx < w) y8_out[(size_t)gy * w + gx] = s_y[ty + kHalo][tx + kHalo];
+    // stage 1b: 8-bit LAB of the 36x36 region through the LDS tables
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int p = tid + k * kPrepThreads;
+        if (p >= kReg * kReg) continue;
+        const int ry = p / kReg, rx = p % kReg;
+        if (ry < 2 || ry >= kReg - 2 || rx < 2 || rx >= kReg - 2) continue;
+        const int lr = s_lin[cr[k]], lg = s_lin[cg[k]], lb = s_lin[cb[k]];
+        const int tx = (1777 * lr + 1541 * lg + 778 * lb + 2048) >> 12;
+        const int ty = (871 * lr + 2929 * lg + 296 * lb + 2048) >> 12;
+        const int tz = (73 * lr + 448 * lg + 3575 * lb + 2048) >> 12;
+        const int fx = s_fl[tx], fy = s_fl[ty], fz = s_fl[tz];
+        s_lab[0][ry - 2][rx - 2] = (uint8_t)clampi(((116 * fy - 524288) * 255 + 1638400) / 3276800, 0, 255);
+        s_lab[1][ry - 2][rx - 2] = (uint8_t)clampi((500 * (fx - fy) + 4194304 + 16384) >> 15, 0, 255);
+        s_lab[2][ry - 2][rx - 2] = (uint8_t)clampi((200 * (fy - fz) + 4194304 + 16384) >> 15, 0, 255);
     }
-    if (!with_saliency) return;
+
+    // this thread's output pixel
+    const int ty = tid / kTile, tx = tid % kTile;
+    const int gy = y0 + ty, gx = x0 + tx;
+    const bool inside = gy < h && gx < w;
+    if (inside) y8_out[(size_t)gy * w + gx] = s_y[ty + kHalo][tx + kHalo];     // gray image for the flow pyramid
 
     // Region arrays are indexed by (image coordinate - region origin).  A stage evaluates its
     // stencil at the CLAMPED image coordinate c of each region cell and reads its input at
@@ -136,7 +163,7 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
     const int oy_m = y0 - 1, ox_m = x0 - 1;              // origin of s_m2
 
     // stage 2: 5x5 binomial blur, (sum + 128) >> 8
-    for (int p = tid; p < kRegB * kRegB; p += 256) {
+    for (int p = tid; p < kRegB * kRegB; p += kPrepThreads) {
         const int ry = p / kRegB, rx = p % kRegB;
         const int cy = clampi(oy_b + ry, 0, h - 1), cx = clampi(ox_b + rx, 0, w - 1);
         const int kw[5] = {1, 4, 6, 4, 1};
@@ -158,13 +185,13 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
 
     // stage 3: Sobel squared magnitude on the 34x34 region; cells outside the image hold 0
     // (that is what non-maximum suppression wants to see there)
-    for (int p = tid; p < kRegM * kRegM; p += 256) {
+    for (int p = tid; p < kRegM * kRegM; p += kPrepThreads) {
         const int ry = p / kRegM, rx = p % kRegM;
-        const int gy = oy_m + ry, gx = ox_m + rx;
+        const int my = oy_m + ry, mx = ox_m + rx;
         int m2 = 0;
-        if (gy >= 0 && gy < h && gx >= 0 && gx < w) {
-            const int ym = clampi(gy - 1, 0, h - 1) - oy_b, yc = gy - oy_b, yp = clampi(gy + 1, 0, h - 1) - oy_b;
-            const int xm = clampi(gx - 1, 0, w - 1) - ox_b, xc = gx - ox_b, xp = clampi(gx + 1, 0, w - 1) - ox_b;
+        if (my >= 0 && my < h && mx >= 0 && mx < w) {
+            const int ym = clampi(my - 1, 0, h - 1) - oy_b, yc = my - oy_b, yp = clampi(my + 1, 0, h - 1) - oy_b;
+            const int xm = clampi(mx - 1, 0, w - 1) - ox_b, xc = mx - ox_b, xp = clampi(mx + 1, 0, w - 1) - ox_b;
             const int sgx = (s_b[ym][xp] + 2 * s_b[yc][xp] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[yc][xm] + s_b[yp][xm]);
             const int sgy = (s_b[yp][xm] + 2 * s_b[yp][xc] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[ym][xc] + s_b[ym][xp]);
             m2 = sgx * sgx + sgy * sgy;
@@ -173,12 +200,10 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
     }
     __syncthreads();
 
-    // stage 4: per output pixel - non-maximum suppression + class, colour variance
+    // stage 4: non-maximum suppression + class, colour variance (one pixel per thread)
+    int cls = 0;
     unsigned long long local_sum = 0ull;
-    for (int p = tid; p < kTile * kTile; p += 256) {
-        const int ty = p / kTile, tx = p % kTile;
-        const int gy = y0 + ty, gx = x0 + tx;
-        if (gy >= h || gx >= w) continue;
+    if (inside) {
         // gradient at the pixel (recomputed; cheaper than keeping two more LDS planes)
         const int ym = clampi(gy - 1, 0, h - 1) - oy_b, yc = gy - oy_b, yp = clampi(gy + 1, 0, h - 1) - oy_b;
         const int xm = clampi(gx - 1, 0, w - 1) - ox_b, xc = gx - ox_b, xp = clampi(gx + 1, 0, w - 1) - ox_b;
@@ -192,15 +217,9 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
         else if (s2 < 2 * sgy * sgy) { dy1 = -1; dx1 = 0; }
         else if (sgx * sgy > 0) { dy1 = -1; dx1 = -1; }
         else { dy1 = -1; dx1 = 1; }
-        const int my = ty + 1, mx = tx + 1;
-        const int n1 = s_m2[my + dy1][mx + dx1];
-        const int n2 = s_m2[my - dy1][mx - dx1];
-        int cls = 0;
+        const int n1 = s_m2[ty + 1 + dy1][tx + 1 + dx1];
+        const int n2 = s_m2[ty + 1 - dy1][tx + 1 - dx1];
         if (m2 > n1 && m2 >= n2) cls = m2 >= hi2 ? 2 : (m2 >= lo2 ? 1 : 0);
-        const size_t gi = (size_t)gy * w + gx;
-        cls_out[gi] = (uint8_t)cls;
-        s_cls[ty][tx] = (uint8_t)cls;
-        s_par[p] = (uint32_t)p | (cls == 1 ? kWeakBit : 0u);
 
         // 5x5 colour variance: 25 * sum v^2 - (sum v)^2 per channel
         uint32_t v = 0;
@@ -220,65 +239,71 @@ __global__ __launch_bounds__(256) void k_prep(const uint8_t* __restrict__ rgb, i
             }
             v += (uint32_t)(25 * sq - s1 * s1);
         }
+        const size_t gi = (size_t)gy * w + gx;
+        cls_out[gi] = (uint8_t)cls;
         var_out[gi] = v;
-        local_sum += v;
+        local_sum = v;
     }
-    // block sum -> one atomic
+    s_cls[ty][tx] = (uint8_t)cls;
+    // block sum of V -> one atomic
     for (int off = 32; off > 0; off >>= 1) local_sum += __shfl_down(local_sum, off);
     if ((tid & 63) == 0) s_sum[tid >> 6] = local_sum;
     __syncthreads();
-    if (tid == 0) atomicAdd(msum_acc, s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
-
-    // hysteresis, tile-local part.  First every pixel of a horizontal run of weak/strong pixels
-    // links to the run's smallest key (no atomics, at most one row of LDS reads) ...
-    const int th = min(kTile, h - y0), tw = min(kTile, w - x0);
-    for (int p = tid; p < kTile * kTile; p += 256) {
-        const int ty = p / kTile, tx = p % kTile;
-        if (ty >= th || tx >= tw) continue;
-        const int c = s_cls[ty][tx];
-        if (c == 0) continue;
-        uint32_t best = (uint32_t)p | (c == 1 ? kWeakBit : 0u);
-        for (int xx = tx - 1; xx >= 0; --xx) {
-            const int cj = s_cls[ty][xx];
-            if (cj == 0) break;
-            best = min(best, (uint32_t)(ty * kTile + xx) | (cj == 1 ? kWeakBit : 0u));
-        }
-        for (int xx = tx + 1; xx < tw; ++xx) {
-            const int cj = s_cls[ty][xx];
-            if (cj == 0) break;
-            best = min(best, (uint32_t)(ty * kTile + xx) | (cj == 1 ? kWeakBit : 0u));
-        }
-        s_par[p] = best;
+    if (tid == 0) {
+        unsigned long long t = 0ull;
+        for (int k = 0; k < kPrepThreads / 64; ++k) t += s_sum[k];
+        atomicAdd(msum_acc, t);
     }
+
+    // hysteresis, tile-local part: union-find in LDS over horizontal runs.
+    // A wave holds two tile rows (lanes 0-31 and 32-63), so the run a pixel lies in and the run's
+    // smallest key (its leftmost strong pixel, else its leftmost pixel) follow from two ballots.
+    const uint32_t my_key = (uint32_t)tid | (cls == 1 ? kWeakBit : 0u);
+    const unsigned long long cand64 = __ballot(cls != 0);
+    const unsigned long long strong64 = __ballot(cls == 2);
+    const uint32_t row_c = (uint32_t)((tid & 32) ? (cand64 >> 32) : cand64);
+    const uint32_t row_s = (uint32_t)((tid & 32) ? (strong64 >> 32) : strong64);
+    uint32_t head_key = my_key;
+    bool left_is_cand = false;
+    if (cls != 0) {
+        const uint32_t zeros = ~row_c;
+        const uint32_t below = zeros & ((1u << tx) - 1u);
+        const uint32_t above = (tx == 31) ? 0u : (zeros & ~((2u << tx) - 1u));
+        const int start = below == 0u ? 0 : 32 - __builtin_clz(below);
+        const int end = above == 0u ? 31 : __builtin_ctz(above) - 1;
+        const uint32_t run = (end == 31 ? 0xFFFFFFFFu : ((2u << end) - 1u)) & ~((1u << start) - 1u);
+        const uint32_t strong_in_run = row_s & run;
+        head_key = strong_in_run != 0u ? (uint32_t)(ty * kTile + __builtin_ctz(strong_in_run))
+                                       : ((uint32_t)(ty * kTile + start) | kWeakBit);
+        left_is_cand = tx > 0 && ((row_c >> (tx - 1)) & 1u) != 0u;
+    }
+    s_lbl[tid] = head_key;
     __syncthreads();
-    // ... then runs of adjacent rows are joined through their heads (S, SW, SE neighbours; a
-    // neighbour whose left neighbour touches this pixel too belongs to an already joined run)
-    for (int p = tid; p < kTile * kTile; p += 256) {
-        const int ty = p / kTile, tx = p % kTile;
-        if (ty + 1 >= th || tx >= tw) continue;
-        if (s_cls[ty][tx] == 0) continue;
+    // join runs of adjacent rows through their heads (S, SW, SE neighbours)
+    if (cls != 0 && ty + 1 < kTile) {
 #pragma unroll
         for (int dx = -1; dx <= 1; ++dx) {
             const int xx = tx + dx;
-            if (xx < 0 || xx >= tw) continue;
+            if (xx < 0 || xx >= kTile) continue;
             if (s_cls[ty + 1][xx] == 0) continue;
-            if (dx > -1 && xx - 1 >= 0 && s_cls[ty + 1][xx - 1] != 0) continue;
-            uf_unite<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, uf_load<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, p),
-                                                   uf_load<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, (ty + 1) * kTile + xx));
+            // The contact of the two runs is made once, by the leftmost pixel pair that touches:
+            if (dx <= 0 && left_is_cand) continue;                       // the left neighbour touches (ty+1, xx) too
+            if (dx >= 0 && xx >= 1 && s_cls[ty + 1][xx - 1] != 0) continue;  // this pixel touches (ty+1, xx-1) too
+            uf_unite<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, head_key,
+                                                   uf_load<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, (ty + 1) * kTile + xx));
         }
     }
     __syncthreads();
-    // each pixel's global link: the global key of its tile-local root (itself if it is the root or
-    // not an edge candidate).  Tile-local row-major order agrees with image row-major order.
-    for (int p = tid; p < kTile * kTile; p += 256) {
-        const int ty = p / kTile, tx = p % kTile;
-        if (ty >= th || tx >= tw) continue;
-        const int c = s_cls[ty][tx];
-        uint32_t root = (uint32_t)p | (c == 1 ? kWeakBit : 0u);
-        if (c != 0) root = uf_find<__HIP_MEMORY_SCOPE_WORKGROUP>(s_par, root);
+    if (cls != 0) s_lbl[tid] = uf_find<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, head_key);
+    __syncthreads();
+    // each pixel's global link: the global key of its component's smallest key in this tile
+    // (itself for pixels that are no edge candidates).  Tile-local row-major order agrees with
+    // image row-major order, so "smallest" means the same in both.
+    if (inside) {
+        const uint32_t root = (cls != 0) ? s_lbl[tid] : my_key;
         const uint32_t rl = root & ~kWeakBit;
         const size_t rg = (size_t)(y0 + (int)(rl / kTile)) * w + (x0 + (int)(rl % kTile));
-        parent_out[(size_t)(y0 + ty) * w + (x0 + tx)] = (uint32_t)rg | (root & kWeakBit);
+        parent_out[(size_t)gy * w + gx] = (uint32_t)rg | (root & kWeakBit);
     }
 }
 
@@ -372,11 +397,15 @@ __global__ __launch_bounds__(kTokens) void k_pool(const uint8_t* __restrict__ cl
 // ---------------------------------------------------------------------------------------------
 hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
                        uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
-                       unsigned long long* d_msum_clear, const uint16_t* d_lin, const uint16_t* d_fl,
-                       int lo2, int hi2, hipStream_t s) {
+                       unsigned long long* d_msum_clear, const uint16_t* d_lut, int lo2, int hi2, hipStream_t s) {
+    if (!with_saliency) {
+        const int n = h * w;
+        hipLaunchKernelGGL(k_gray, dim3((n + 255) / 256), dim3(256), 0, s, d_rgb, n, d_y8);
+        return hipGetLastError();
+    }
     dim3 grid((w + kTile - 1) / kTile, (h + kTile - 1) / kTile);
-    hipLaunchKernelGGL(k_prep, grid, dim3(256), 0, s, d_rgb, h, w, with_saliency ? 1 : 0, d_y8, d_cls, d_var,
-                       d_parent, d_msum_acc, d_msum_clear, d_lin, d_fl, lo2, hi2);
+    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, d_rgb, h, w, d_y8, d_cls, d_var, d_parent, d_msum_acc,
+                       d_msum_clear, reinterpret_cast<const uint32_t*>(d_lut), lo2, hi2);
     return hipGetLastError();
 }
 
