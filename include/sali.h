@@ -59,6 +59,7 @@ extern "C" {
 #define SALI_TIER_PRUNE 3
 
 #define SALI_TOKENS_MAX 576     /* grid * grid; grid is 24 (576 visual tokens per frame)     */
+#define SALI_ANALYSIS_LANES 3   /* frames whose image-side analysis may be in flight at once */
 
 typedef struct sali_ctx sali_ctx;   /* opaque host object; owns no device memory */
 
@@ -179,14 +180,18 @@ int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t
               void* stream);
 
 /* The two halves of sali_step, for callers that overlap them.  The decision of Algorithm 1
- * needs only the image, and a redundant frame needs no K/V at all, so the image side of frame
- * t+1 can run while the K/V of frame t is still being stored.
+ * needs only the image, and a redundant frame needs no K/V at all, so the image side of later
+ * frames can run while the K/V of frame t is still being stored.
  *
  * sali_analyze: temporal filter against the previously analysed frame, and for a non-redundant
  * frame saliency, tiers and compaction indices; fills the frame-table row of `frame_id`
- * (pointer row if redundant).  Asynchronous on `stream`.  All image-side calls on one context
- * (sali_analyze, sali_step, sali_flow_score, sali_saliency_pool) share scratch memory and
- * must be ordered with respect to each other by the caller (same stream, or events).
+ * (pointer row if redundant).  Asynchronous on `stream`.  Frames must be analysed in video
+ * order.  Consecutive calls may use different streams: the context keeps SALI_ANALYSIS_LANES
+ * copies of its image scratch, so that many analyses can be in flight, and orders what must
+ * be ordered (a frame's flow after its predecessor's expansion, tier assignment in frame
+ * order, reuse of a scratch copy after its previous user) with device-side event waits.
+ * sali_flow_score and sali_saliency_pool share one of the scratch copies: do not run them
+ * while analyses are in flight on other streams.
  *
  * sali_store: packs `d_kv_fp16` into the pools according to the row that sali_analyze wrote.
  * Makes `stream` wait (on the device) for that frame's analysis if it ran on another stream.
@@ -196,10 +201,12 @@ int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t
 int sali_analyze(sali_ctx* ctx, const uint8_t* d_rgb, int32_t frame_id, void* stream);
 int sali_store(sali_ctx* ctx, const void* d_kv_fp16, int32_t frame_id, void* stream);
 
-/* One loop body of Algorithm 1 with a one-frame look-ahead on two caller-owned streams:
- * analyses frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
+/* One loop body of Algorithm 1 with look-ahead on caller-owned streams: analyses a later
+ * frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
  * `image_stream` and stores the K/V of the already analysed frame `frame_id` (d_kv, may be NULL
- * at the start) on `kv_stream`.  Results are identical to calling sali_step frame by frame. */
+ * while the look-ahead fills) on `kv_stream`.  With a look-ahead of k frames the caller cycles
+ * through k image streams (k <= SALI_ANALYSIS_LANES is useful).  Results are identical to
+ * calling sali_step frame by frame. */
 int sali_step_pipelined(sali_ctx* ctx, const uint8_t* d_rgb_next_or_null, int32_t next_frame_id,
                         const void* d_kv_or_null, int32_t frame_id, void* image_stream, void* kv_stream);
 

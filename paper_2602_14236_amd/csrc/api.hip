@@ -15,12 +15,31 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+// Image-side scratch exists in kLanes copies so that the analyses of consecutive frames can be in
+// flight at once on different streams; polynomial expansions live in a ring one longer than that
+// (a frame's flow reads its predecessor's expansion), plus two slots for the stand-alone flow call.
+constexpr int kLanes = SALI_ANALYSIS_LANES;
+constexpr int kStepSlots = kLanes + 1;
+constexpr int kExpSlots = kStepSlots + 2;
+constexpr int kRing = 8;              // bookkeeping of the most recent analyses
+
+struct LaneLayout {
+    size_t y8, pyr, flow[2], cls, var, parent, msum, dp, scores, gate, counters;
+};
+
 struct ScratchLayout {
-    size_t y8, pyr, expA[4], expB[4], flow[2], cls, var, parent, msum, dp, scores, gate, total;
+    LaneLayout lane[kLanes];
+    size_t expA[kExpSlots], expB[kExpSlots];
+    size_t total;
 };
 
 struct TableLayout {
     size_t lut, cursors, rows, tier, slot, order, total;      // lut = lin[256] followed by fl[4096]
+};
+
+struct LaneCounters {
+    uint32_t patch_done;      // arrival counter of the patch-motion kernel (self-resetting)
+    uint32_t pool_done;       // arrival counter of the pooling kernel (self-resetting)
 };
 
 int check_config(const sali_config* c) {
@@ -113,21 +132,25 @@ ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
     const size_t px = (size_t)total_px(g);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    s.y8 = take(hw);
-    s.pyr = take(px * sizeof(float));
-    for (int i = 0; i < 4; ++i) {
+    for (int l = 0; l < kLanes; ++l) {
+        LaneLayout& L = s.lane[l];
+        L.y8 = take(hw);
+        L.pyr = take(px * sizeof(float));
+        L.flow[0] = take(hw * sizeof(float2));
+        L.flow[1] = take(hw * sizeof(float2));
+        L.cls = take(hw);
+        L.var = take(hw * sizeof(uint32_t));
+        L.parent = take(hw * sizeof(uint32_t));
+        L.msum = take(2 * sizeof(unsigned long long));
+        L.dp = take(kTokens * sizeof(float));
+        L.scores = take(kTokens * sizeof(float));
+        L.gate = take(sizeof(sali_gate));
+        L.counters = take(sizeof(LaneCounters));
+    }
+    for (int i = 0; i < kExpSlots; ++i) {
         s.expA[i] = take(px * sizeof(float4));
         s.expB[i] = take(px * sizeof(float2));
     }
-    s.flow[0] = take(hw * sizeof(float2));
-    s.flow[1] = take(hw * sizeof(float2));
-    s.cls = take(hw);
-    s.var = take(hw * sizeof(uint32_t));
-    s.parent = take(hw * sizeof(uint32_t));
-    s.msum = take(2 * sizeof(unsigned long long));
-    s.dp = take(kTokens * sizeof(float));
-    s.scores = take(kTokens * sizeof(float));
-    s.gate = take(sizeof(sali_gate));
     s.total = o;
     return s;
 }
@@ -161,8 +184,19 @@ sali_pool_layout pool_layout(const sali_config& c) {
     return p;
 }
 
-__global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, unsigned long long* msum,
-                        float* dp, float* scores, sali_gate* gate) {
+struct LanePtrs {
+    unsigned long long* msum;
+    float* dp;
+    float* scores;
+    sali_gate* gate;
+    LaneCounters* counters;
+};
+
+struct LanePtrArray {
+    LanePtrs lane[kLanes];
+};
+
+__global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, LanePtrArray lanes) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < max_frames) {
         sali_frame_row r = {};
@@ -170,18 +204,24 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, unsi
         r.src = -1;
         rows[i] = r;
     }
-    if (i < kTokens) {
-        dp[i] = 0.0f;
-        scores[i] = 0.0f;
+    for (int l = 0; l < kLanes; ++l) {
+        if (i < kTokens) {
+            lanes.lane[l].dp[i] = 0.0f;
+            lanes.lane[l].scores[i] = 0.0f;
+        }
+        if (i == 0) {
+            lanes.lane[l].msum[0] = 0ull;
+            lanes.lane[l].msum[1] = 0ull;
+            sali_gate g = {0, 0.0f, 0, 0};
+            *lanes.lane[l].gate = g;
+            LaneCounters z = {0u, 0u};
+            *lanes.lane[l].counters = z;
+        }
     }
     if (i == 0) {
         Cursors c = {};
         c.last_src = -1;
         *cur = c;
-        msum[0] = 0ull;
-        msum[1] = 0ull;
-        sali_gate g = {0, 0.0f, 0, 0};
-        *gate = g;
     }
 }
 
@@ -191,7 +231,13 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, unsi
 
 using namespace sali;
 
-constexpr int kEventRing = 8;
+// one entry of the ring of recent analyses
+struct AnalysisRecord {
+    int frame_id;             // -1 = empty
+    hipStream_t stream;
+    hipEvent_t exp_ready;     // the frame's polynomial expansion is complete
+    hipEvent_t done;          // the frame's row / tier tables are complete
+};
 
 struct sali_ctx {
     sali_config cfg;
@@ -203,13 +249,10 @@ struct sali_ctx {
     uint8_t* tables;
     Pools pools;
     int n_planes;
-    bool prev_valid;     // the expansion of the previous sali_step frame is cached in slot `step_slot ^ 1`
-    int step_slot;       // expansion slot the NEXT sali_step frame writes (0 or 1)
-    unsigned sal_seq;    // parity selects the frame-sum accumulator
-    hipEvent_t prof[2][2];   // [SALI_PROF_*][start, stop], armed for one launch
-    hipEvent_t analysis_done[kEventRing];    // recorded when the analysis of frame id % ring is enqueued
-    int analysed_frame[kEventRing];          // which frame that was (-1 = none)
-    hipStream_t analysed_stream[kEventRing];
+    unsigned n_analysed;      // analyses since create / reset; analysis n uses lane n % kLanes
+    unsigned lane_uses[kLanes];   // saliency passes run in each lane; the parity selects the frame-sum accumulator
+    AnalysisRecord ring[kRing];
+    hipEvent_t prof[2][2];    // [SALI_PROF_*][start, stop], armed for one launch
 
     template <typename T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
     template <typename T> T* tb(size_t off) const { return reinterpret_cast<T*>(tables + off); }
@@ -218,6 +261,16 @@ struct sali_ctx {
     uint8_t* tier(int f) const { return tb<uint8_t>(tl.tier) + (size_t)f * kTokens; }
     uint16_t* slot(int f) const { return tb<uint16_t>(tl.slot) + (size_t)f * kTokens; }
     uint16_t* order(int f) const { return tb<uint16_t>(tl.order) + (size_t)f * kTokens; }
+    LanePtrs lane_ptrs(int l) const {
+        const LaneLayout& L = sl.lane[l];
+        LanePtrs p;
+        p.msum = sc<unsigned long long>(L.msum);
+        p.dp = sc<float>(L.dp);
+        p.scores = sc<float>(L.scores);
+        p.gate = sc<sali_gate>(L.gate);
+        p.counters = sc<LaneCounters>(L.counters);
+        return p;
+    }
 };
 
 namespace {
@@ -227,35 +280,40 @@ namespace {
         if ((expr) != hipSuccess) return SALI_ERR_HIP; \
     } while (0)
 
-// gray (+ saliency pre-pass), pyramid and polynomial expansion of one frame into slot `slot`
-int enqueue_frame_analysis(sali_ctx* c, const uint8_t* d_rgb, int slot, bool with_saliency, hipStream_t s) {
+// gray (+ saliency pre-pass) of one frame in lane `lane`; msum_parity selects the accumulator of
+// the colour-variance frame sum (the other one is cleared for the lane's next use)
+int enqueue_prep(sali_ctx* c, const uint8_t* d_rgb, int lane, bool with_saliency, unsigned msum_parity,
+                 hipStream_t s) {
     const sali_config& cfg = c->cfg;
-    unsigned long long* msum = c->sc<unsigned long long>(c->sl.msum);
-    unsigned long long* acc = nullptr;
-    unsigned long long* clr = nullptr;
-    if (with_saliency) {
-        acc = msum + (c->sal_seq & 1u);
-        clr = msum + ((c->sal_seq + 1u) & 1u);
-    }
-    SALI_TRY(launch_prep(d_rgb, cfg.src_h, cfg.src_w, with_saliency, c->sc<uint8_t>(c->sl.y8),
-                         c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.var), c->sc<uint32_t>(c->sl.parent), acc,
-                         clr, c->tb<uint16_t>(c->tl.lut), cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
-    if (slot < 0) return SALI_OK;
-    float* pyr = c->sc<float>(c->sl.pyr);
+    const LaneLayout& L = c->sl.lane[lane];
+    unsigned long long* msum = c->sc<unsigned long long>(L.msum);
+    unsigned long long* acc = with_saliency ? msum + (msum_parity & 1u) : nullptr;
+    unsigned long long* clr = with_saliency ? msum + ((msum_parity + 1u) & 1u) : nullptr;
+    SALI_TRY(launch_prep(d_rgb, cfg.src_h, cfg.src_w, with_saliency, c->sc<uint8_t>(L.y8), c->sc<uint8_t>(L.cls),
+                         c->sc<uint32_t>(L.var), c->sc<uint32_t>(L.parent), acc, clr, c->tb<uint16_t>(c->tl.lut),
+                         cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
+    return SALI_OK;
+}
+
+// pyramid and polynomial expansion of the lane's gray image into expansion slot `slot`
+int enqueue_expansion(sali_ctx* c, int lane, int slot, hipStream_t s) {
+    const LaneLayout& L = c->sl.lane[lane];
+    float* pyr = c->sc<float>(L.pyr);
     const LevelGeom& g = c->geom;
     for (int l = 1; l < g.levels; ++l) {
-        SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(c->sl.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
+        SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(L.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
                                  g.h[l - 1], g.w[l - 1], pyr + g.off[l], g.h[l], g.w[l], s));
     }
-    SALI_TRY(launch_polyexp(c->sc<uint8_t>(c->sl.y8), pyr, g, c->fw, c->sc<float4>(c->sl.expA[slot]),
+    SALI_TRY(launch_polyexp(c->sc<uint8_t>(L.y8), pyr, g, c->fw, c->sc<float4>(c->sl.expA[slot]),
                             c->sc<float2>(c->sl.expB[slot]), s));
     return SALI_OK;
 }
 
 // coarse-to-fine displacement estimation between expansion slots; result in *result_buf
-int enqueue_flow(sali_ctx* c, int slot_prev, int slot_cur, const float2** result_buf, hipStream_t s) {
+int enqueue_flow(sali_ctx* c, int lane, int slot_prev, int slot_cur, const float2** result_buf, hipStream_t s) {
     const LevelGeom& g = c->geom;
-    float2* buf[2] = {c->sc<float2>(c->sl.flow[0]), c->sc<float2>(c->sl.flow[1])};
+    const LaneLayout& L = c->sl.lane[lane];
+    float2* buf[2] = {c->sc<float2>(L.flow[0]), c->sc<float2>(L.flow[1])};
     const float4* A1 = c->sc<float4>(c->sl.expA[slot_prev]);
     const float2* b1 = c->sc<float2>(c->sl.expB[slot_prev]);
     const float4* A2 = c->sc<float4>(c->sl.expA[slot_cur]);
@@ -279,16 +337,19 @@ int enqueue_flow(sali_ctx* c, int slot_prev, int slot_cur, const float2** result
     return SALI_OK;
 }
 
-// cross-tile hysteresis + pooling; with `tier` the pooling kernel also assigns tiers and writes
-// the frame-table row of `tier->frame_id`
-int enqueue_saliency_tail(sali_ctx* c, const sali_gate* gate, float* d_scores, uint8_t* d_salmap,
-                          const TierLaunch* tier, hipStream_t s) {
-    const sali_config& cfg = c->cfg;
-    unsigned long long* msum = c->sc<unsigned long long>(c->sl.msum) + (c->sal_seq & 1u);
-    SALI_TRY(launch_union(c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.parent), cfg.src_h, cfg.src_w, gate, s));
-    SALI_TRY(launch_pool(c->sc<uint8_t>(c->sl.cls), c->sc<uint32_t>(c->sl.parent), c->sc<uint32_t>(c->sl.var), msum,
-                         cfg.src_h, cfg.src_w, gate, d_scores, d_salmap, tier, s));
-    c->sal_seq += 1u;
+int enqueue_union(sali_ctx* c, int lane, const sali_gate* gate, hipStream_t s) {
+    const LaneLayout& L = c->sl.lane[lane];
+    SALI_TRY(launch_union(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), c->cfg.src_h, c->cfg.src_w, gate, s));
+    return SALI_OK;
+}
+
+// pooling; with `tier` the pooling kernel also assigns tiers and writes the frame-table row
+int enqueue_pool(sali_ctx* c, int lane, unsigned msum_parity, const sali_gate* gate, float* d_scores,
+                 uint8_t* d_salmap, const TierLaunch* tier, hipStream_t s) {
+    const LaneLayout& L = c->sl.lane[lane];
+    SALI_TRY(launch_pool(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), c->sc<uint32_t>(L.var),
+                         c->sc<unsigned long long>(L.msum) + (msum_parity & 1u), c->cfg.src_h, c->cfg.src_w, gate,
+                         d_scores, d_salmap, tier, &c->sc<LaneCounters>(L.counters)->pool_done, s));
     return SALI_OK;
 }
 
@@ -329,6 +390,12 @@ int enqueue_pack(sali_ctx* c, const void* d_kv, int frame_id, hipStream_t s) {
     return SALI_OK;
 }
 
+// make stream `s` wait for `ev` unless the event was recorded on `s` itself
+int wait_unless_same(hipStream_t s, hipStream_t recorded_on, hipEvent_t ev) {
+    if (recorded_on != s) SALI_TRY(hipStreamWaitEvent(s, ev, 0));
+    return SALI_OK;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
@@ -345,6 +412,14 @@ void fill_luts(uint16_t* lin, uint16_t* fl) {
         const double u = t / 4095.0;
         const double f = u > d * d * d ? cbrt(u) : u / (3.0 * d * d) + 4.0 / 29.0;
         fl[t] = (uint16_t)floor(32768.0 * f + 0.5);
+    }
+}
+
+void destroy_events(sali_ctx* c) {
+    for (int i = 0; i < kRing; ++i) {
+        if (c->ring[i].exp_ready != nullptr) (void)hipEventDestroy(c->ring[i].exp_ready);
+        if (c->ring[i].done != nullptr) (void)hipEventDestroy(c->ring[i].done);
+        c->ring[i].exp_ready = c->ring[i].done = nullptr;
     }
 }
 
@@ -399,18 +474,18 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->pools.cap8 = (int32_t)cfg->cap_int8;
     c->pools.cap4 = (int32_t)cfg->cap_int4;
     c->n_planes = cfg->n_layers * 2 * cfg->n_heads;
-    c->prev_valid = false;
-    c->step_slot = 0;
-    c->sal_seq = 0;
+    c->n_analysed = 0;
+    for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
     c->prof[0][0] = c->prof[0][1] = c->prof[1][0] = c->prof[1][1] = nullptr;
-    for (int i = 0; i < kEventRing; ++i) {
-        c->analysis_done[i] = nullptr;
-        c->analysed_frame[i] = -1;
-        c->analysed_stream[i] = nullptr;
+    for (int i = 0; i < kRing; ++i) {
+        c->ring[i].frame_id = -1;
+        c->ring[i].stream = nullptr;
+        c->ring[i].exp_ready = c->ring[i].done = nullptr;
     }
-    for (int i = 0; i < kEventRing; ++i) {
-        if (hipEventCreateWithFlags(&c->analysis_done[i], hipEventDisableTiming) != hipSuccess) {
-            for (int j = 0; j < i; ++j) (void)hipEventDestroy(c->analysis_done[j]);
+    for (int i = 0; i < kRing; ++i) {
+        if (hipEventCreateWithFlags(&c->ring[i].exp_ready, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&c->ring[i].done, hipEventDisableTiming) != hipSuccess) {
+            destroy_events(c);
             delete c;
             return SALI_ERR_HIP;
         }
@@ -418,11 +493,8 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
 
     uint16_t lut[256 + 4096];
     fill_luts(lut, lut + 256);
-    if (hipMemcpy(c->tables + c->tl.lut, lut, sizeof(lut), hipMemcpyHostToDevice) != hipSuccess) {
-        sali_destroy(c);
-        return SALI_ERR_HIP;
-    }
-    if (sali_reset(c, nullptr) != SALI_OK || hipStreamSynchronize(nullptr) != hipSuccess) {
+    if (hipMemcpy(c->tables + c->tl.lut, lut, sizeof(lut), hipMemcpyHostToDevice) != hipSuccess ||
+        sali_reset(c, nullptr) != SALI_OK || hipStreamSynchronize(nullptr) != hipSuccess) {
         sali_destroy(c);
         return SALI_ERR_HIP;
     }
@@ -432,8 +504,7 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
 
 void sali_destroy(sali_ctx* ctx) {
     if (ctx == nullptr) return;
-    for (int i = 0; i < kEventRing; ++i)
-        if (ctx->analysis_done[i] != nullptr) (void)hipEventDestroy(ctx->analysis_done[i]);
+    destroy_events(ctx);
     delete ctx;
 }
 
@@ -441,14 +512,14 @@ int sali_reset(sali_ctx* c, void* stream) {
     if (c == nullptr) return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int n = c->cfg.max_frames > kTokens ? c->cfg.max_frames : kTokens;
+    LanePtrArray lanes;
+    for (int l = 0; l < kLanes; ++l) lanes.lane[l] = c->lane_ptrs(l);
     hipLaunchKernelGGL(k_reset, dim3((n + 255) / 256), dim3(256), 0, s, c->cursors(), c->rows(), c->cfg.max_frames,
-                       c->sc<unsigned long long>(c->sl.msum), c->sc<float>(c->sl.dp), c->sc<float>(c->sl.scores),
-                       c->sc<sali_gate>(c->sl.gate));
+                       lanes);
     SALI_TRY(hipGetLastError());
-    c->prev_valid = false;
-    c->step_slot = 0;
-    c->sal_seq = 0;
-    for (int i = 0; i < kEventRing; ++i) c->analysed_frame[i] = -1;
+    c->n_analysed = 0;
+    for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
+    for (int i = 0; i < kRing; ++i) c->ring[i].frame_id = -1;
     return SALI_OK;
 }
 
@@ -466,15 +537,17 @@ int sali_flow_score(sali_ctx* c, const uint8_t* d_prev_rgb, const uint8_t* d_cur
         d_gate_out == nullptr)
         return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc = enqueue_frame_analysis(c, d_prev_rgb, 2, false, s);
-    if (rc != SALI_OK) return rc;
-    rc = enqueue_frame_analysis(c, d_cur_rgb, 3, false, s);
+    const int lane = 0, slot_a = kStepSlots, slot_b = kStepSlots + 1;
+    int rc = enqueue_prep(c, d_prev_rgb, lane, false, 0, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, lane, slot_a, s);
+    if (rc == SALI_OK) rc = enqueue_prep(c, d_cur_rgb, lane, false, 0, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, lane, slot_b, s);
     if (rc != SALI_OK) return rc;
     const float2* flow = nullptr;
-    rc = enqueue_flow(c, 2, 3, &flow, s);
+    rc = enqueue_flow(c, lane, slot_a, slot_b, &flow, s);
     if (rc != SALI_OK) return rc;
     SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, d_patch_motion576,
-                               d_gate_out, c->cursors(), d_flow_uv_or_null, s));
+                               d_gate_out, &c->lane_ptrs(lane).counters->patch_done, d_flow_uv_or_null, s));
     return SALI_OK;
 }
 
@@ -482,9 +555,12 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
                        void* stream) {
     if (c == nullptr || d_rgb == nullptr || d_scores576 == nullptr) return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc = enqueue_frame_analysis(c, d_rgb, -1, true, s);
-    if (rc != SALI_OK) return rc;
-    return enqueue_saliency_tail(c, nullptr, d_scores576, d_salmap_or_null, nullptr, s);
+    const int lane = 0;
+    const unsigned parity = c->lane_uses[lane]++ & 1u;
+    int rc = enqueue_prep(c, d_rgb, lane, true, parity, s);
+    if (rc == SALI_OK) rc = enqueue_union(c, lane, nullptr, s);
+    if (rc == SALI_OK) rc = enqueue_pool(c, lane, parity, nullptr, d_scores576, d_salmap_or_null, nullptr, s);
+    return rc;
 }
 
 int sali_kv_compress(sali_ctx* c, const void* d_kv_fp16, const float* d_scores576, int32_t frame_id, void* stream) {
@@ -516,30 +592,52 @@ int sali_analyze(sali_ctx* c, const uint8_t* d_rgb, int32_t frame_id, void* stre
     if (c == nullptr || d_rgb == nullptr) return SALI_ERR_NULL;
     if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int slot = c->step_slot;
-    int rc = enqueue_frame_analysis(c, d_rgb, slot, true, s);
-    if (rc != SALI_OK) return rc;
-    float* dp = c->sc<float>(c->sl.dp);
-    float* scores = c->sc<float>(c->sl.scores);
-    sali_gate* gate = c->sc<sali_gate>(c->sl.gate);
-    if (c->prev_valid) {
-        const float2* flow = nullptr;
-        rc = enqueue_flow(c, slot ^ 1, slot, &flow, s);
+    const unsigned n = c->n_analysed;
+    const int lane = (int)(n % kLanes);
+    const int slot = (int)(n % kStepSlots);
+    const unsigned parity = c->lane_uses[lane]++ & 1u;      // alternates per saliency pass in the lane
+    AnalysisRecord& rec = c->ring[n % kRing];
+    const AnalysisRecord* prev = n >= 1 ? &c->ring[(n - 1) % kRing] : nullptr;
+    int rc;
+    // the lane's scratch and the expansion slot were last used by analysis n - kLanes (and read by
+    // the flow of its successor, which finished before it in tier order)
+    if (n >= (unsigned)kLanes) {
+        const AnalysisRecord& old = c->ring[(n - kLanes) % kRing];
+        rc = wait_unless_same(s, old.stream, old.done);
         if (rc != SALI_OK) return rc;
-        SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, dp, gate,
-                                   c->cursors(), nullptr, s));
+    }
+    rc = enqueue_prep(c, d_rgb, lane, true, parity, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, lane, slot, s);
+    if (rc != SALI_OK) return rc;
+    SALI_TRY(hipEventRecord(rec.exp_ready, s));
+    const LanePtrs lp = c->lane_ptrs(lane);
+    if (prev != nullptr) {
+        rc = wait_unless_same(s, prev->stream, prev->exp_ready);
+        if (rc != SALI_OK) return rc;
+        const float2* flow = nullptr;
+        rc = enqueue_flow(c, lane, (int)((n - 1) % kStepSlots), slot, &flow, s);
+        if (rc != SALI_OK) return rc;
+        SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, lp.dp, lp.gate,
+                                   &lp.counters->patch_done, nullptr, s));
     } else {
-        SALI_TRY(launch_clear_gate(dp, gate, s));      // first frame: never redundant (Algorithm 1, t > 1)
+        SALI_TRY(launch_clear_gate(lp.dp, lp.gate, s));      // first frame: never redundant (Algorithm 1, t > 1)
+    }
+    rc = enqueue_union(c, lane, lp.gate, s);
+    if (rc != SALI_OK) return rc;
+    // tiers are handed out in frame order: the cursors must have seen the previous frame
+    if (prev != nullptr) {
+        rc = wait_unless_same(s, prev->stream, prev->done);
+        if (rc != SALI_OK) return rc;
     }
     const TierLaunch tl = tier_launch(c, frame_id);
-    rc = enqueue_saliency_tail(c, gate, scores, nullptr, &tl, s);
+    rc = enqueue_pool(c, lane, parity, lp.gate, lp.scores, nullptr, &tl, s);
     if (rc != SALI_OK) return rc;
-    const int e = frame_id % kEventRing;
-    SALI_TRY(hipEventRecord(c->analysis_done[e], s));
-    c->analysed_frame[e] = frame_id;
-    c->analysed_stream[e] = s;
-    c->prev_valid = true;
-    c->step_slot = slot ^ 1;
+    SALI_TRY(hipEventRecord(rec.done, s));
+    for (int i = 0; i < kRing; ++i)
+        if (c->ring[i].frame_id == frame_id) c->ring[i].frame_id = -1;      // an older analysis under the same id
+    rec.frame_id = frame_id;
+    rec.stream = s;
+    c->n_analysed = n + 1;
     return SALI_OK;
 }
 
@@ -548,9 +646,12 @@ int sali_store(sali_ctx* c, const void* d_kv, int32_t frame_id, void* stream) {
     if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
     if (!aligned16(d_kv)) return SALI_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int e = frame_id % kEventRing;
-    if (c->analysed_frame[e] != frame_id) return SALI_ERR_STATE;      // not analysed (or too long ago)
-    if (c->analysed_stream[e] != s) SALI_TRY(hipStreamWaitEvent(s, c->analysis_done[e], 0));
+    const AnalysisRecord* rec = nullptr;
+    for (int i = 0; i < kRing; ++i)
+        if (c->ring[i].frame_id == frame_id) rec = &c->ring[i];
+    if (rec == nullptr) return SALI_ERR_STATE;      // not analysed (or too long ago)
+    const int rc = wait_unless_same(s, rec->stream, rec->done);
+    if (rc != SALI_OK) return rc;
     return enqueue_pack(c, d_kv, frame_id, s);
 }
 
@@ -598,14 +699,12 @@ int sali_read_frame_tiers(sali_ctx* c, int32_t frame_id, uint8_t* h_tier576, uin
 int sali_read_last_step(sali_ctx* c, float* h_patch_motion576, sali_gate* h_gate, float* h_scores576, void* stream) {
     if (c == nullptr) return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const LanePtrs lp = c->lane_ptrs(c->n_analysed == 0 ? 0 : (int)((c->n_analysed - 1) % kLanes));
     if (h_patch_motion576 != nullptr)
-        SALI_TRY(hipMemcpyAsync(h_patch_motion576, c->sc<float>(c->sl.dp), kTokens * sizeof(float),
-                                hipMemcpyDeviceToHost, s));
-    if (h_gate != nullptr)
-        SALI_TRY(hipMemcpyAsync(h_gate, c->sc<sali_gate>(c->sl.gate), sizeof(sali_gate), hipMemcpyDeviceToHost, s));
+        SALI_TRY(hipMemcpyAsync(h_patch_motion576, lp.dp, kTokens * sizeof(float), hipMemcpyDeviceToHost, s));
+    if (h_gate != nullptr) SALI_TRY(hipMemcpyAsync(h_gate, lp.gate, sizeof(sali_gate), hipMemcpyDeviceToHost, s));
     if (h_scores576 != nullptr)
-        SALI_TRY(hipMemcpyAsync(h_scores576, c->sc<float>(c->sl.scores), kTokens * sizeof(float),
-                                hipMemcpyDeviceToHost, s));
+        SALI_TRY(hipMemcpyAsync(h_scores576, lp.scores, kTokens * sizeof(float), hipMemcpyDeviceToHost, s));
     SALI_TRY(hipStreamSynchronize(s));
     return SALI_OK;
 }

@@ -247,54 +247,53 @@ __global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 5 / Eq. 6.  One block per patch row, one wave per patch (16 waves take the 24 patches of
-// the row in two rounds); the last block to finish evaluates the gate.
-__global__ __launch_bounds__(1024) void k_patch_gate(const float2* __restrict__ flow, int h, int w, float tau_t,
-                                                     float theta_r, float* dp_out, sali_gate* gate, Cursors* cur,
-                                                     float* __restrict__ flow_uv) {
-    __shared__ int s_cnt[16];
+// Eq. 5 / Eq. 6.  One wave per patch, four patches per block of 256 threads (small blocks find
+// room next to other streams' kernels); the last block to finish evaluates the gate.
+constexpr int kGateBlocks = kTokens / 4;
+
+__global__ __launch_bounds__(256) void k_patch_gate(const float2* __restrict__ flow, int h, int w, float tau_t,
+                                                    float theta_r, float* dp_out, sali_gate* gate,
+                                                    uint32_t* done_counter, float* __restrict__ flow_uv) {
+    __shared__ int s_cnt[4];
     __shared__ int s_last;
-    const int pr = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int token = blockIdx.x * 4 + wave;
+    const int pr = token / kGrid, pc = token % kGrid;
     const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
-    for (int pc = wave; pc < kGrid; pc += 16) {
-        const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
-        const int pw = xb - xa, area = pw * (yb - ya);
-        float acc = 0.0f;
-        for (int p = lane; p < area; p += 64) {
-            const int y = ya + p / pw, x = xa + p % pw;
-            const float2 d = flow[(size_t)y * w + x];
-            acc += d.x * d.x + d.y * d.y;
-            if (flow_uv != nullptr) {
-                flow_uv[(size_t)y * w + x] = d.x;
-                flow_uv[(size_t)h * w + (size_t)y * w + x] = d.y;
-            }
+    const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
+    const int pw = xb - xa, area = pw * (yb - ya);
+    float acc = 0.0f;
+    for (int p = lane; p < area; p += 64) {
+        const int y = ya + p / pw, x = xa + p % pw;
+        const float2 d = flow[(size_t)y * w + x];
+        acc += d.x * d.x + d.y * d.y;
+        if (flow_uv != nullptr) {
+            flow_uv[(size_t)y * w + x] = d.x;
+            flow_uv[(size_t)h * w + (size_t)y * w + x] = d.y;
         }
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
-        if (lane == 0)
-            __hip_atomic_store(dp_out + pr * kGrid + pc, sqrtf(acc / (float)area), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
     }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+    if (lane == 0)
+        __hip_atomic_store(dp_out + token, sqrtf(acc / (float)area), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (threadIdx.x == 0) {
         __threadfence();
-        const uint32_t prev = atomicAdd(&cur->patch_done, 1u);
-        s_last = (prev == (uint32_t)(kGrid - 1)) ? 1 : 0;
+        const uint32_t prev = atomicAdd(done_counter, 1u);
+        s_last = (prev == (uint32_t)(kGateBlocks - 1)) ? 1 : 0;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();
     int n = 0;
-    if (threadIdx.x < kTokens) {
-        const float v = __hip_atomic_load(dp_out + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        n = (v < tau_t) ? 1 : 0;
+    for (int i = threadIdx.x; i < kTokens; i += 256) {
+        const float v = __hip_atomic_load(dp_out + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        n += (v < tau_t) ? 1 : 0;
     }
     for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
     if (lane == 0) s_cnt[wave] = n;
     __syncthreads();
     if (threadIdx.x == 0) {
-        int n_static = 0;
-        for (int k = 0; k < 16; ++k) n_static += s_cnt[k];
+        const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
         const float r = (float)n_static / (float)kTokens;
         sali_gate gt;
         gt.n_static = n_static;
@@ -302,7 +301,7 @@ __global__ __launch_bounds__(1024) void k_patch_gate(const float2* __restrict__ 
         gt.redundant = (r > theta_r) ? 1 : 0;
         gt.reserved = 0;
         *gate = gt;
-        cur->patch_done = 0u;       // ready for the next launch
+        *done_counter = 0u;         // ready for the next launch
     }
 }
 
@@ -345,9 +344,9 @@ hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2
 }
 
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
-                             sali_gate* d_gate, Cursors* d_cur, float* d_flow_uv_or_null, hipStream_t s) {
-    hipLaunchKernelGGL(k_patch_gate, dim3(kGrid), dim3(1024), 0, s, d_flow, h, w, tau_t, theta_r, d_dp, d_gate,
-                       d_cur, d_flow_uv_or_null);
+                             sali_gate* d_gate, uint32_t* d_done_counter, float* d_flow_uv_or_null, hipStream_t s) {
+    hipLaunchKernelGGL(k_patch_gate, dim3(kGateBlocks), dim3(256), 0, s, d_flow, h, w, tau_t, theta_r, d_dp, d_gate,
+                       d_done_counter, d_flow_uv_or_null);
     return hipGetLastError();
 }
 

@@ -61,9 +61,9 @@ __device__ __forceinline__ float quad_min(float v) {
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
-// Tier + rank + compaction indices: one block of 576 threads, one thread per token.
+// Tier + rank + compaction indices: one block of 256 threads (see tier_body.h).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kTokens) void k_tier(const float* __restrict__ scores, const sali_gate* gate,
+__global__ __launch_bounds__(kTierThreads) void k_tier(const float* __restrict__ scores, const sali_gate* gate,
                                                   TierParams tp, int frame_id, sali_frame_row* rows,
                                                   uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
                                                   uint16_t* __restrict__ order_out, Cursors* cur, int cap16,
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
 hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,
                        sali_frame_row* d_rows, uint8_t* d_tier, uint16_t* d_slot, uint16_t* d_order,
                        Cursors* d_cur, Pools pools, hipStream_t s) {
-    hipLaunchKernelGGL(k_tier, dim3(1), dim3(kTokens), 0, s, d_scores, d_gate_or_null, tp, frame_id, d_rows,
+    hipLaunchKernelGGL(k_tier, dim3(1), dim3(kTierThreads), 0, s, d_scores, d_gate_or_null, tp, frame_id, d_rows,
                        d_tier, d_slot, d_order, d_cur, pools.cap16, pools.cap8, pools.cap4);
     return hipGetLastError();
 }

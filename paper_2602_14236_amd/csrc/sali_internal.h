@@ -34,9 +34,7 @@ struct Cursors {
     int32_t c16, c8, c4;        // next free row of each pool
     int32_t last_src;           // frame id of the last stored frame, -1 = none
     uint32_t status;            // sticky SALI_FAULT_* bits
-    uint32_t patch_done;        // arrival counter of the patch-motion kernel (self-resetting)
-    uint32_t pool_done;         // arrival counter of the pooling kernel (self-resetting)
-    uint32_t pad;
+    uint32_t pad[3];
 };
 
 struct Pools {
@@ -103,7 +101,8 @@ hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, 
                         hipStream_t s);
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
                        const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
-                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null, hipStream_t s);
+                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null,
+                       uint32_t* d_done_counter, hipStream_t s);
 
 // flow_kernels.hip
 hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
@@ -114,7 +113,7 @@ hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2
                             const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
                             FlowWeights fw, hipStream_t s);
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
-                             sali_gate* d_gate, Cursors* d_cur, float* d_flow_uv_or_null, hipStream_t s);
+                             sali_gate* d_gate, uint32_t* d_done_counter, float* d_flow_uv_or_null, hipStream_t s);
 hipError_t launch_clear_gate(float* d_dp, sali_gate* d_gate, hipStream_t s);
 
 }  // namespace sali

@@ -4,8 +4,8 @@
 // Implementation Details (Canny edge detection combined with adaptive thresholding on the
 // local colour variance in LAB).  Everything here is integer arithmetic, so scores are exact.
 //
-//   k_prep   one pass over the RGB frame, 32x32 tiles with a 4-pixel halo staged in LDS, 1024
-//            threads per tile (one output pixel each; colour tables held in LDS):
+//   k_prep   one pass over the RGB frame, 32x32 tiles with a 4-pixel halo staged in LDS (colour
+//            tables held in LDS too):
 //            gray -> 5x5 binomial blur -> Sobel -> squared magnitude -> non-maximum suppression
 //            -> weak/strong class, and RGB -> 8-bit LAB -> 5x5 variance sum V, plus the frame
 //            sum of V (one 64-bit atomic per block).  Also emits the gray image for the flow.
@@ -87,9 +87,12 @@ __global__ __launch_bounds__(256) void k_gray(const uint8_t* __restrict__ rgb, i
     y8_out[i] = (uint8_t)((77 * px[0] + 150 * px[1] + 29 * px[2] + 128) >> 8);
 }
 
-// 1024 threads per 32x32 tile: one output pixel per thread, at most two region cells per thread
-// in the halo stages.  The tile is latency-bound, so the point is many waves and few steps.
-constexpr int kPrepThreads = 1024;
+// 256 threads per 32x32 tile, four output pixels per thread (pixel p = tid + 256 q sits in tile
+// row p / 32, so a wave always holds two complete tile rows).  Workgroups are kept this small so
+// that they find room on compute units that a bandwidth kernel of another stream keeps busy.
+constexpr int kPrepThreads = 256;
+constexpr int kPrepPx = kTile * kTile / kPrepThreads;                          // 4
+constexpr int kPrepCells = (kReg * kReg + kPrepThreads - 1) / kPrepThreads;   // 7
 
 __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict__ rgb, int h, int w,
                                                        uint8_t* __restrict__ y8_out, uint8_t* __restrict__ cls_out,
@@ -115,31 +118,30 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict
 
     // stage 1a: colour tables -> LDS; RGB of the 40x40 region (clamped coordinates) -> gray
     for (int i = tid; i < (256 + 4096) / 2; i += kPrepThreads) s_lut[i] = lut_words[i];
-    int cr[2], cg[2], cb[2];
+    uint32_t crgb[kPrepCells];
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < kPrepCells; ++k) {
         const int p = tid + k * kPrepThreads;
-        cr[k] = cg[k] = cb[k] = 0;
+        crgb[k] = 0u;
         if (p < kReg * kReg) {
             const int ry = p / kReg, rx = p % kReg;
             const int gy = clampi(y0 - kHalo + ry, 0, h - 1), gx = clampi(x0 - kHalo + rx, 0, w - 1);
             const uint8_t* px = rgb + ((size_t)gy * w + gx) * 3;
-            cr[k] = px[0];
-            cg[k] = px[1];
-            cb[k] = px[2];
-            s_y[ry][rx] = (uint8_t)((77 * cr[k] + 150 * cg[k] + 29 * cb[k] + 128) >> 8);
+            const uint32_t r = px[0], g = px[1], b = px[2];
+            crgb[k] = r | (g << 8) | (b << 16);
+            s_y[ry][rx] = (uint8_t)((77 * r + 150 * g + 29 * b + 128) >> 8);
         }
     }
     __syncthreads();
 
     // stage 1b: 8-bit LAB of the 36x36 region through the LDS tables
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < kPrepCells; ++k) {
         const int p = tid + k * kPrepThreads;
         if (p >= kReg * kReg) continue;
         const int ry = p / kReg, rx = p % kReg;
         if (ry < 2 || ry >= kReg - 2 || rx < 2 || rx >= kReg - 2) continue;
-        const int lr = s_lin[cr[k]], lg = s_lin[cg[k]], lb = s_lin[cb[k]];
+        const int lr = s_lin[crgb[k] & 0xFF], lg = s_lin[(crgb[k] >> 8) & 0xFF], lb = s_lin[(crgb[k] >> 16) & 0xFF];
         const int tx = (1777 * lr + 1541 * lg + 778 * lb + 2048) >> 12;
         const int ty = (871 * lr + 2929 * lg + 296 * lb + 2048) >> 12;
         const int tz = (73 * lr + 448 * lg + 3575 * lb + 2048) >> 12;
@@ -149,11 +151,14 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict
         s_lab[2][ry - 2][rx - 2] = (uint8_t)clampi((200 * (fy - fz) + 4194304 + 16384) >> 15, 0, 255);
     }
 
-    // this thread's output pixel
-    const int ty = tid / kTile, tx = tid % kTile;
-    const int gy = y0 + ty, gx = x0 + tx;
-    const bool inside = gy < h && gx < w;
-    if (inside) y8_out[(size_t)gy * w + gx] = s_y[ty + kHalo][tx + kHalo];     // gray image for the flow pyramid
+    // gray image for the flow pyramid
+    const int tx = tid % kTile;
+    const int gx = x0 + tx;
+#pragma unroll
+    for (int q = 0; q < kPrepPx; ++q) {
+        const int ty = (tid + q * kPrepThreads) / kTile;
+        if (y0 + ty < h && gx < w) y8_out[(size_t)(y0 + ty) * w + gx] = s_y[ty + kHalo][tx + kHalo];
+    }
 
     // Region arrays are indexed by (image coordinate - region origin).  A stage evaluates its
     // stencil at the CLAMPED image coordinate c of each region cell and reads its input at
@@ -200,51 +205,57 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict
     }
     __syncthreads();
 
-    // stage 4: non-maximum suppression + class, colour variance (one pixel per thread)
-    int cls = 0;
+    // stage 4: non-maximum suppression + class, colour variance
+    int cls[kPrepPx];
     unsigned long long local_sum = 0ull;
-    if (inside) {
-        // gradient at the pixel (recomputed; cheaper than keeping two more LDS planes)
-        const int ym = clampi(gy - 1, 0, h - 1) - oy_b, yc = gy - oy_b, yp = clampi(gy + 1, 0, h - 1) - oy_b;
-        const int xm = clampi(gx - 1, 0, w - 1) - ox_b, xc = gx - ox_b, xp = clampi(gx + 1, 0, w - 1) - ox_b;
-        const int sgx = (s_b[ym][xp] + 2 * s_b[yc][xp] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[yc][xm] + s_b[yp][xm]);
-        const int sgy = (s_b[yp][xm] + 2 * s_b[yp][xc] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[ym][xc] + s_b[ym][xp]);
-        const int m2 = sgx * sgx + sgy * sgy;
-        const int ax = abs(sgx), ay = abs(sgy);
-        const int s2 = (ax + ay) * (ax + ay);
-        int dy1, dx1;                     // first-listed neighbour; the second is its mirror
-        if (s2 < 2 * sgx * sgx) { dy1 = 0; dx1 = -1; }
-        else if (s2 < 2 * sgy * sgy) { dy1 = -1; dx1 = 0; }
-        else if (sgx * sgy > 0) { dy1 = -1; dx1 = -1; }
-        else { dy1 = -1; dx1 = 1; }
-        const int n1 = s_m2[ty + 1 + dy1][tx + 1 + dx1];
-        const int n2 = s_m2[ty + 1 - dy1][tx + 1 - dx1];
-        if (m2 > n1 && m2 >= n2) cls = m2 >= hi2 ? 2 : (m2 >= lo2 ? 1 : 0);
+#pragma unroll
+    for (int q = 0; q < kPrepPx; ++q) {
+        const int ty = (tid + q * kPrepThreads) / kTile;
+        const int gy = y0 + ty;
+        cls[q] = 0;
+        if (gy < h && gx < w) {
+            // gradient at the pixel (recomputed; cheaper than keeping two more LDS planes)
+            const int ym = clampi(gy - 1, 0, h - 1) - oy_b, yc = gy - oy_b, yp = clampi(gy + 1, 0, h - 1) - oy_b;
+            const int xm = clampi(gx - 1, 0, w - 1) - ox_b, xc = gx - ox_b, xp = clampi(gx + 1, 0, w - 1) - ox_b;
+            const int sgx = (s_b[ym][xp] + 2 * s_b[yc][xp] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[yc][xm] + s_b[yp][xm]);
+            const int sgy = (s_b[yp][xm] + 2 * s_b[yp][xc] + s_b[yp][xp]) - (s_b[ym][xm] + 2 * s_b[ym][xc] + s_b[ym][xp]);
+            const int m2 = sgx * sgx + sgy * sgy;
+            const int ax = abs(sgx), ay = abs(sgy);
+            const int s2 = (ax + ay) * (ax + ay);
+            int dy1, dx1;                     // first-listed neighbour; the second is its mirror
+            if (s2 < 2 * sgx * sgx) { dy1 = 0; dx1 = -1; }
+            else if (s2 < 2 * sgy * sgy) { dy1 = -1; dx1 = 0; }
+            else if (sgx * sgy > 0) { dy1 = -1; dx1 = -1; }
+            else { dy1 = -1; dx1 = 1; }
+            const int n1 = s_m2[ty + 1 + dy1][tx + 1 + dx1];
+            const int n2 = s_m2[ty + 1 - dy1][tx + 1 - dx1];
+            if (m2 > n1 && m2 >= n2) cls[q] = m2 >= hi2 ? 2 : (m2 >= lo2 ? 1 : 0);
 
-        // 5x5 colour variance: 25 * sum v^2 - (sum v)^2 per channel
-        uint32_t v = 0;
+            // 5x5 colour variance: 25 * sum v^2 - (sum v)^2 per channel
+            uint32_t v = 0;
 #pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            int s1 = 0, sq = 0;
+            for (int c = 0; c < 3; ++c) {
+                int s1 = 0, sq = 0;
 #pragma unroll
-            for (int a = -2; a <= 2; ++a) {
-                const int yy = clampi(gy + a, 0, h - 1) - oy_b;
+                for (int a = -2; a <= 2; ++a) {
+                    const int yy = clampi(gy + a, 0, h - 1) - oy_b;
 #pragma unroll
-                for (int b = -2; b <= 2; ++b) {
-                    const int xx = clampi(gx + b, 0, w - 1) - ox_b;
-                    const int val = s_lab[c][yy][xx];
-                    s1 += val;
-                    sq += val * val;
+                    for (int b = -2; b <= 2; ++b) {
+                        const int xx = clampi(gx + b, 0, w - 1) - ox_b;
+                        const int val = s_lab[c][yy][xx];
+                        s1 += val;
+                        sq += val * val;
+                    }
                 }
+                v += (uint32_t)(25 * sq - s1 * s1);
             }
-            v += (uint32_t)(25 * sq - s1 * s1);
+            const size_t gi = (size_t)gy * w + gx;
+            cls_out[gi] = (uint8_t)cls[q];
+            var_out[gi] = v;
+            local_sum += v;
         }
-        const size_t gi = (size_t)gy * w + gx;
-        cls_out[gi] = (uint8_t)cls;
-        var_out[gi] = v;
-        local_sum = v;
+        s_cls[ty][tx] = (uint8_t)cls[q];
     }
-    s_cls[ty][tx] = (uint8_t)cls;
     // block sum of V -> one atomic
     for (int off = 32; off > 0; off >>= 1) local_sum += __shfl_down(local_sum, off);
     if ((tid & 63) == 0) s_sum[tid >> 6] = local_sum;
@@ -258,52 +269,64 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict
     // hysteresis, tile-local part: union-find in LDS over horizontal runs.
     // A wave holds two tile rows (lanes 0-31 and 32-63), so the run a pixel lies in and the run's
     // smallest key (its leftmost strong pixel, else its leftmost pixel) follow from two ballots.
-    const uint32_t my_key = (uint32_t)tid | (cls == 1 ? kWeakBit : 0u);
-    const unsigned long long cand64 = __ballot(cls != 0);
-    const unsigned long long strong64 = __ballot(cls == 2);
-    const uint32_t row_c = (uint32_t)((tid & 32) ? (cand64 >> 32) : cand64);
-    const uint32_t row_s = (uint32_t)((tid & 32) ? (strong64 >> 32) : strong64);
-    uint32_t head_key = my_key;
-    bool left_is_cand = false;
-    if (cls != 0) {
-        const uint32_t zeros = ~row_c;
-        const uint32_t below = zeros & ((1u << tx) - 1u);
-        const uint32_t above = (tx == 31) ? 0u : (zeros & ~((2u << tx) - 1u));
-        const int start = below == 0u ? 0 : 32 - __builtin_clz(below);
-        const int end = above == 0u ? 31 : __builtin_ctz(above) - 1;
-        const uint32_t run = (end == 31 ? 0xFFFFFFFFu : ((2u << end) - 1u)) & ~((1u << start) - 1u);
-        const uint32_t strong_in_run = row_s & run;
-        head_key = strong_in_run != 0u ? (uint32_t)(ty * kTile + __builtin_ctz(strong_in_run))
-                                       : ((uint32_t)(ty * kTile + start) | kWeakBit);
-        left_is_cand = tx > 0 && ((row_c >> (tx - 1)) & 1u) != 0u;
+    uint32_t head_key[kPrepPx];
+    bool left_is_cand[kPrepPx];
+#pragma unroll
+    for (int q = 0; q < kPrepPx; ++q) {
+        const int p = tid + q * kPrepThreads;
+        const int ty = p / kTile;
+        const unsigned long long cand64 = __ballot(cls[q] != 0);
+        const unsigned long long strong64 = __ballot(cls[q] == 2);
+        const uint32_t row_c = (uint32_t)((tid & 32) ? (cand64 >> 32) : cand64);
+        const uint32_t row_s = (uint32_t)((tid & 32) ? (strong64 >> 32) : strong64);
+        head_key[q] = (uint32_t)p | (cls[q] == 1 ? kWeakBit : 0u);
+        left_is_cand[q] = false;
+        if (cls[q] != 0) {
+            const uint32_t zeros = ~row_c;
+            const uint32_t below = zeros & ((1u << tx) - 1u);
+            const uint32_t above = (tx == 31) ? 0u : (zeros & ~((2u << tx) - 1u));
+            const int start = below == 0u ? 0 : 32 - __builtin_clz(below);
+            const int end = above == 0u ? 31 : __builtin_ctz(above) - 1;
+            const uint32_t run = (end == 31 ? 0xFFFFFFFFu : ((2u << end) - 1u)) & ~((1u << start) - 1u);
+            const uint32_t strong_in_run = row_s & run;
+            head_key[q] = strong_in_run != 0u ? (uint32_t)(ty * kTile + __builtin_ctz(strong_in_run))
+                                              : ((uint32_t)(ty * kTile + start) | kWeakBit);
+            left_is_cand[q] = tx > 0 && ((row_c >> (tx - 1)) & 1u) != 0u;
+        }
+        s_lbl[p] = head_key[q];
     }
-    s_lbl[tid] = head_key;
     __syncthreads();
     // join runs of adjacent rows through their heads (S, SW, SE neighbours)
-    if (cls != 0 && ty + 1 < kTile) {
+#pragma unroll
+    for (int q = 0; q < kPrepPx; ++q) {
+        const int ty = (tid + q * kPrepThreads) / kTile;
+        if (cls[q] == 0 || ty + 1 >= kTile) continue;
 #pragma unroll
         for (int dx = -1; dx <= 1; ++dx) {
             const int xx = tx + dx;
             if (xx < 0 || xx >= kTile) continue;
             if (s_cls[ty + 1][xx] == 0) continue;
             // The contact of the two runs is made once, by the leftmost pixel pair that touches:
-            if (dx <= 0 && left_is_cand) continue;                       // the left neighbour touches (ty+1, xx) too
+            if (dx <= 0 && left_is_cand[q]) continue;                        // the left neighbour touches (ty+1, xx) too
             if (dx >= 0 && xx >= 1 && s_cls[ty + 1][xx - 1] != 0) continue;  // this pixel touches (ty+1, xx-1) too
-            uf_unite<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, head_key,
+            uf_unite<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, head_key[q],
                                                    uf_load<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, (ty + 1) * kTile + xx));
         }
     }
     __syncthreads();
-    if (cls != 0) s_lbl[tid] = uf_find<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, head_key);
-    __syncthreads();
     // each pixel's global link: the global key of its component's smallest key in this tile
     // (itself for pixels that are no edge candidates).  Tile-local row-major order agrees with
     // image row-major order, so "smallest" means the same in both.
-    if (inside) {
-        const uint32_t root = (cls != 0) ? s_lbl[tid] : my_key;
+#pragma unroll
+    for (int q = 0; q < kPrepPx; ++q) {
+        const int p = tid + q * kPrepThreads;
+        const int ty = p / kTile;
+        if (y0 + ty >= h || gx >= w) continue;
+        const uint32_t root = (cls[q] != 0) ? uf_find<__HIP_MEMORY_SCOPE_WORKGROUP>(s_lbl, head_key[q])
+                                            : ((uint32_t)p);
         const uint32_t rl = root & ~kWeakBit;
         const size_t rg = (size_t)(y0 + (int)(rl / kTile)) * w + (x0 + (int)(rl % kTile));
-        parent_out[(size_t)gy * w + gx] = (uint32_t)rg | (root & kWeakBit);
+        parent_out[(size_t)(y0 + ty) * w + gx] = (uint32_t)rg | (root & kWeakBit);
     }
 }
 
@@ -335,17 +358,17 @@ __global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, 
     }
 }
 
-// One block of 576 threads per patch.  With do_tier the last block to finish runs the tier /
+// One block of 256 threads per patch.  With do_tier the last block to finish runs the tier /
 // compaction step on the 576 scores (and block 0 writes the pointer row of a redundant frame).
-__global__ __launch_bounds__(kTokens) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
+__global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
                                                   const uint32_t* __restrict__ var, const unsigned long long* msum,
                                                   int h, int w, const sali_gate* gate, float* scores,
                                                   uint8_t* __restrict__ salmap, int do_tier, TierParams tp,
                                                   int frame_id, sali_frame_row* rows, uint8_t* tier_out,
                                                   uint16_t* slot_out, uint16_t* order_out, Cursors* cur, int cap16,
-                                                  int cap8, int cap4) {
+                                                  int cap8, int cap4, uint32_t* done_counter) {
     __shared__ TierShared sh;
-    __shared__ uint32_t s_q[kTokens / 64];
+    __shared__ uint32_t s_q[kTierThreads / 64];
     __shared__ int s_last;
     if (gate != nullptr && gate->redundant != 0) {
         if (do_tier && blockIdx.x == 0)
@@ -359,7 +382,7 @@ __global__ __launch_bounds__(kTokens) void k_pool(const uint8_t* __restrict__ cl
     const unsigned long long m = *msum;
     const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
     uint32_t q = 0;
-    for (int p = threadIdx.x; p < area; p += kTokens) {
+    for (int p = threadIdx.x; p < area; p += kTierThreads) {
         const int y = ya + p / pw, x = xa + p % pw;
         const size_t gi = (size_t)y * w + x;
         const int c = cls[gi];
@@ -376,21 +399,21 @@ __global__ __launch_bounds__(kTokens) void k_pool(const uint8_t* __restrict__ cl
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t total = 0;
-        for (int k = 0; k < kTokens / 64; ++k) total += s_q[k];
+        for (int k = 0; k < kTierThreads / 64; ++k) total += s_q[k];
         const uint32_t s_fix = (uint32_t)(((unsigned long long)total << 15) / (unsigned long long)area);
         const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
         __hip_atomic_store(scores + blockIdx.x, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int last = 0;
         if (do_tier) {
             __threadfence();
-            last = (atomicAdd(&cur->pool_done, 1u) == (uint32_t)(kTokens - 1)) ? 1 : 0;
+            last = (atomicAdd(done_counter, 1u) == (uint32_t)(kTokens - 1)) ? 1 : 0;
         }
         s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    if (threadIdx.x == 0) cur->pool_done = 0u;      // ready for the next launch
+    if (threadIdx.x == 0) *done_counter = 0u;       // ready for the next launch
     tier_body(sh, scores, false, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
 }
 
@@ -418,12 +441,13 @@ hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, 
 
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
                        const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
-                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null, hipStream_t s) {
+                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null,
+                       uint32_t* d_done_counter, hipStream_t s) {
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
-    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(kTokens), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
+    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
                        d_gate_or_null, d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, t.tp, t.frame_id,
-                       t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4);
+                       t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4, d_done_counter);
     return hipGetLastError();
 }
 

@@ -1,16 +1,24 @@
 // Tier assignment (Eq. 8 or top-k counts), compaction indices and frame-table row for one frame.
 // Shared by the stand-alone tier kernel and by the last block of the pooling kernel; must be
-// entered by a whole block of exactly 576 threads, one per token.  Only comparisons and integer
-// arithmetic: the result does not depend on floating-point contraction settings.
+// entered by a whole block of exactly kTierThreads threads.  Thread t owns tokens t, t + 256 and
+// (for t < 64) t + 512, so the 64 tokens of "group" g = token / 64 sit in one wave.  Only
+// comparisons and integer arithmetic: the result does not depend on floating-point contraction.
+//
+// Workgroups are kept at 256 threads on purpose: larger ones wait for many free wave slots on
+// one compute unit and starve next to a bandwidth kernel that keeps every unit busy.
 #pragma once
 
 #include "sali_internal.h"
 
 namespace sali {
 
+constexpr int kTierThreads = 256;
+constexpr int kTierSlots = (kTokens + kTierThreads - 1) / kTierThreads;      // tokens per thread (3)
+constexpr int kTierGroups = kTokens / 64;                                    // 9
+
 struct TierShared {
     uint4 key4[kTokens / 4];        // order-preserving integer image of the scores
-    int wave_cnt[kTokens / 64][4];
+    int group_cnt[kTierGroups][4];
     int nan_flag;
 };
 
@@ -18,12 +26,12 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
                                           int frame_id, sali_frame_row* rows, uint8_t* __restrict__ tier_out,
                                           uint16_t* __restrict__ slot_out, uint16_t* __restrict__ order_out,
                                           Cursors* cur, int cap16, int cap8, int cap4) {
-    const int i = threadIdx.x;
-    const int wave = i >> 6, lane = i & 63;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
 
     if (redundant) {
         // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame.
-        if (i == 0) {
+        if (tid == 0) {
             sali_frame_row r = {};
             r.frame_id = frame_id;
             r.src = cur->last_src;
@@ -33,17 +41,29 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
         return;
     }
 
-    const float s = __hip_atomic_load(scores + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // unsigned key with the same order as the float (and -0 == +0, as the float comparison has it)
-    uint32_t bits = (s == 0.0f) ? 0u : __builtin_bit_cast(uint32_t, s);
-    const uint32_t key = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-    reinterpret_cast<uint32_t*>(sh.key4)[i] = key;
-    if (i == 0) sh.nan_flag = 0;
+    if (tid == 0) sh.nan_flag = 0;
+    float s[kTierSlots];
+    uint32_t key[kTierSlots];
+    bool has_nan = false;
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = tid + k * kTierThreads;
+        s[k] = 0.0f;
+        key[k] = 0u;
+        if (i < kTokens) {
+            s[k] = __hip_atomic_load(scores + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            has_nan |= s[k] != s[k];
+            // unsigned key with the same order as the float (and -0 == +0, as the float comparison has it)
+            const uint32_t bits = (s[k] == 0.0f) ? 0u : __builtin_bit_cast(uint32_t, s[k]);
+            key[k] = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+            reinterpret_cast<uint32_t*>(sh.key4)[i] = key[k];
+        }
+    }
     __syncthreads();
-    if (s != s) sh.nan_flag = 1;
+    if (has_nan) sh.nan_flag = 1;
     __syncthreads();
     if (sh.nan_flag) {
-        if (i == 0) {
+        if (tid == 0) {
             atomicOr(&cur->status, SALI_FAULT_NAN_SCORE);
             sali_frame_row r = {};
             r.frame_id = frame_id;
@@ -53,65 +73,82 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
         return;
     }
 
-    int tier;
-    if (tp.mode == 0) {
-        // Eq. 8, inequalities as printed
-        tier = SALI_TIER_PRUNE;
-        if (s > tp.tau_low) tier = SALI_TIER_INT4;
-        if (s > tp.tau_med) tier = SALI_TIER_INT8;
-        if (s > tp.tau_high) tier = SALI_TIER_FP16;
-    } else {
-        // rank by (score descending, token index ascending) = number of tokens j with a larger key,
-        // or an equal key and j < i.  Tokens of earlier waves count with >=, of later waves with >,
-        // so only the 64 tokens of the own wave need the index test.  128-bit broadcast LDS reads.
-        int rank = 0;
-        const int own0 = wave * 16, own1 = own0 + 16;
+    int tier[kTierSlots];
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = tid + k * kTierThreads;
+        tier[k] = SALI_TIER_PRUNE;
+        if (i >= kTokens) continue;
+        if (tp.mode == 0) {
+            // Eq. 8, inequalities as printed
+            if (s[k] > tp.tau_low) tier[k] = SALI_TIER_INT4;
+            if (s[k] > tp.tau_med) tier[k] = SALI_TIER_INT8;
+            if (s[k] > tp.tau_high) tier[k] = SALI_TIER_FP16;
+        } else {
+            // rank by (score descending, token index ascending) = number of tokens j with a larger
+            // key, or an equal key and j < i.  Tokens of earlier groups count with >=, of later
+            // groups with >, so only the 64 tokens of the own group need the index test.  All
+            // lanes of a wave share the group, hence the loop bounds; 128-bit broadcast LDS reads.
+            const uint32_t me = key[k];
+            int rank = 0;
+            const int own0 = (i >> 6) * 16, own1 = own0 + 16;
 #pragma unroll 4
-        for (int j4 = 0; j4 < own0; ++j4) {
-            const uint4 v = sh.key4[j4];
-            rank += (v.x >= key ? 1 : 0) + (v.y >= key ? 1 : 0) + (v.z >= key ? 1 : 0) + (v.w >= key ? 1 : 0);
-        }
+            for (int j4 = 0; j4 < own0; ++j4) {
+                const uint4 v = sh.key4[j4];
+                rank += (v.x >= me ? 1 : 0) + (v.y >= me ? 1 : 0) + (v.z >= me ? 1 : 0) + (v.w >= me ? 1 : 0);
+            }
 #pragma unroll 4
-        for (int j4 = own0; j4 < own1; ++j4) {
-            const uint4 v = sh.key4[j4];
-            const int j = 4 * j4;
-            rank += (v.x > key || (v.x == key && j < i)) ? 1 : 0;
-            rank += (v.y > key || (v.y == key && j + 1 < i)) ? 1 : 0;
-            rank += (v.z > key || (v.z == key && j + 2 < i)) ? 1 : 0;
-            rank += (v.w > key || (v.w == key && j + 3 < i)) ? 1 : 0;
-        }
+            for (int j4 = own0; j4 < own1; ++j4) {
+                const uint4 v = sh.key4[j4];
+                const int j = 4 * j4;
+                rank += (v.x > me || (v.x == me && j < i)) ? 1 : 0;
+                rank += (v.y > me || (v.y == me && j + 1 < i)) ? 1 : 0;
+                rank += (v.z > me || (v.z == me && j + 2 < i)) ? 1 : 0;
+                rank += (v.w > me || (v.w == me && j + 3 < i)) ? 1 : 0;
+            }
 #pragma unroll 4
-        for (int j4 = own1; j4 < kTokens / 4; ++j4) {
-            const uint4 v = sh.key4[j4];
-            rank += (v.x > key ? 1 : 0) + (v.y > key ? 1 : 0) + (v.z > key ? 1 : 0) + (v.w > key ? 1 : 0);
+            for (int j4 = own1; j4 < kTokens / 4; ++j4) {
+                const uint4 v = sh.key4[j4];
+                rank += (v.x > me ? 1 : 0) + (v.y > me ? 1 : 0) + (v.z > me ? 1 : 0) + (v.w > me ? 1 : 0);
+            }
+            if (rank < tp.k16 + tp.k8 + tp.k4) tier[k] = SALI_TIER_INT4;
+            if (rank < tp.k16 + tp.k8) tier[k] = SALI_TIER_INT8;
+            if (rank < tp.k16) tier[k] = SALI_TIER_FP16;
         }
-        tier = SALI_TIER_PRUNE;
-        if (rank < tp.k16 + tp.k8 + tp.k4) tier = SALI_TIER_INT4;
-        if (rank < tp.k16 + tp.k8) tier = SALI_TIER_INT8;
-        if (rank < tp.k16) tier = SALI_TIER_FP16;
     }
 
-    // slot = number of earlier tokens in the same tier (ballot inside the wave + wave prefix)
+    // slot = number of earlier tokens in the same tier: ballot inside the group + prefix over groups
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int in_wave = 0;
+    int in_group[kTierSlots];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const unsigned long long m = __ballot(tier == k);
-        if (tier == k) in_wave = __popcll(m & lt_mask);
-        if (lane == 0) sh.wave_cnt[wave][k] = __popcll(m);
-    }
-    __syncthreads();
-    int before = 0;
-    int cnt[4] = {0, 0, 0, 0};
-    for (int w = 0; w < kTokens / 64; ++w) {
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = tid + k * kTierThreads;
+        const bool valid = i < kTokens;
+        in_group[k] = 0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int c = sh.wave_cnt[w][k];
-            cnt[k] += c;
-            if (w < wave && k == tier) before += c;
+        for (int t = 0; t < 4; ++t) {
+            const unsigned long long m = __ballot(valid && tier[k] == t);
+            if (valid && tier[k] == t) in_group[k] = __popcll(m & lt_mask);
+            if (valid && lane == 0) sh.group_cnt[i >> 6][t] = __popcll(m);
         }
     }
-    const int slot = before + in_wave;
+    __syncthreads();
+    int cnt[4] = {0, 0, 0, 0};
+    int before[kTierSlots];
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) before[k] = 0;
+    for (int g = 0; g < kTierGroups; ++g) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int c = sh.group_cnt[g][t];
+            cnt[t] += c;
+#pragma unroll
+            for (int k = 0; k < kTierSlots; ++k) {
+                const int i = tid + k * kTierThreads;
+                if (g < (i >> 6) && t == tier[k]) before[k] += c;
+            }
+        }
+    }
 
     // capacity check (uniform: every thread reads the same cursors)
     const int c16 = cur->c16, c8 = cur->c8, c4 = cur->c4;
@@ -119,7 +156,7 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
                           (long long)c4 + cnt[2] > cap4;
     __syncthreads();    // all cursor reads precede the update below
     if (overflow) {
-        if (i == 0) {
+        if (tid == 0) {
             atomicOr(&cur->status, SALI_FAULT_OVERFLOW);
             sali_frame_row r = {};
             r.frame_id = frame_id;
@@ -129,12 +166,18 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
         return;
     }
 
-    tier_out[i] = (uint8_t)tier;
-    slot_out[i] = (uint16_t)slot;
-    const int tier_base = (tier > 0 ? cnt[0] : 0) + (tier > 1 ? cnt[1] : 0) + (tier > 2 ? cnt[2] : 0);
-    order_out[tier_base + slot] = (uint16_t)i;
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = tid + k * kTierThreads;
+        if (i >= kTokens) continue;
+        const int slot = before[k] + in_group[k];
+        tier_out[i] = (uint8_t)tier[k];
+        slot_out[i] = (uint16_t)slot;
+        const int tier_base = (tier[k] > 0 ? cnt[0] : 0) + (tier[k] > 1 ? cnt[1] : 0) + (tier[k] > 2 ? cnt[2] : 0);
+        order_out[tier_base + slot] = (uint16_t)i;
+    }
 
-    if (i == 0) {
+    if (tid == 0) {
         sali_frame_row r = {};
         r.frame_id = frame_id;
         r.src = frame_id;
