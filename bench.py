@@ -80,6 +80,10 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (BASELINE configs); 2 is the metric's")
     ap.add_argument("--layers", type=int, default=None, help="cut the K/V down to this many layers (not a valid bench)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the path without the read-back and the one-stream frame-by-frame path")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (the method has no cross-GPU step); use --gpus 1", file=sys.stderr)
@@ -181,9 +185,10 @@ def main():
     unpack_ms = [a.elapsed_time(b) for a, b in unpack_ev]
 
     # reference figures: without the read-back, and the one-stream frame-by-frame path
-    elapsed_step_only = timed(run, steps, False)
-    elapsed_serial = timed(run_serial, steps, True)
-    elapsed_serial_step_only = timed(run_serial, steps, False)
+    if args.extras:
+        elapsed_step_only = timed(run, steps, False)
+        elapsed_serial = timed(run_serial, steps, True)
+        elapsed_serial_step_only = timed(run_serial, steps, False)
 
     wl_eff = wl if n_layers == wl.n_layers else type(wl)(**{**wl.__dict__, "n_layers": n_layers})
     img_b = pack_b = unpack_b = 0.0
@@ -201,12 +206,14 @@ def main():
     pack_gbps = pack_b / pack_s / 1e9 if pack_s > 0 else 0.0
     unpack_gbps = unpack_b / unpack_s / 1e9 if unpack_s > 0 else 0.0
 
+    # HBM bytes per k_pack launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled
+    # by a plain copy of known size); recorded in profiles/ because counters cannot be read in-process
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_k_pack.json")
+    tpath = os.path.join(ROOT, "profiles", f"k_pack_{wl.name}_pmc.txt")
     if os.path.exists(tpath) and args.layers is None:
-        tj = json.load(open(tpath))
-        if tj.get("workload") == wl.name:
-            traffic = tj.get("hbm_bytes_per_launch")
+        for line in open(tpath):
+            if line.startswith("hbm_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
 
     result = {
         "metric": "frames/s through sali_step + KV compress GB/s (% of HBM peak), 1 MI355X",
@@ -234,14 +241,25 @@ def main():
         "kv_decompress_gbps": unpack_gbps,
         "kv_decompress_avg_launch_us": unpack_s / steps * 1e6,
         "step_hbm_frac": (img_b + pack_b + unpack_b) / elapsed / HBM_PEAK,
-        "sali_step_only_fps": steps / elapsed_step_only,
-        "sali_step_only_hbm_frac": (img_b + pack_b) / elapsed_step_only / HBM_PEAK,
         "host_enqueue_us_per_step": host_enqueue[("run", steps, True)] / steps * 1e6,
-        "host_enqueue_us_per_step_sali_step_only": host_enqueue[("run", steps, False)] / steps * 1e6,
-        "one_stream_fps": steps / elapsed_serial,
-        "one_stream_sali_step_only_fps": steps / elapsed_serial_step_only,
-        "one_stream_sali_step_only_hbm_frac": (img_b + pack_b) / elapsed_serial_step_only / HBM_PEAK,
     }
+    if args.extras:
+        result["extras"] = {
+            "sali_step_only_fps": steps / elapsed_step_only,
+            "sali_step_only_hbm_frac": (img_b + pack_b) / elapsed_step_only / HBM_PEAK,
+            "host_enqueue_us_per_step_sali_step_only": host_enqueue[("run", steps, False)] / steps * 1e6,
+            "one_stream_fps": steps / elapsed_serial,
+            "one_stream_sali_step_only_fps": steps / elapsed_serial_step_only,
+            "one_stream_sali_step_only_hbm_frac": (img_b + pack_b) / elapsed_serial_step_only / HBM_PEAK,
+        }
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)              # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes"] = 1 << 30
+        del src, dst
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl_eff, synth.video(args.config, 16))
     ctx.close()
