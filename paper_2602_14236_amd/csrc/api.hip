@@ -292,6 +292,9 @@ int enqueue_prep(sali_ctx* c, const uint8_t* d_rgb, int lane, bool with_saliency
     SALI_TRY(launch_prep(d_rgb, cfg.src_h, cfg.src_w, with_saliency, c->sc<uint8_t>(L.y8), c->sc<uint8_t>(L.cls),
                          c->sc<uint32_t>(L.var), c->sc<uint32_t>(L.parent), acc, clr, c->tb<uint16_t>(c->tl.lut),
                          cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
+    // cross-tile hysteresis (a kernel boundary is the cheapest device-wide ordering there is)
+    if (with_saliency)
+        SALI_TRY(launch_union(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), cfg.src_h, cfg.src_w, s));
     return SALI_OK;
 }
 
@@ -337,19 +340,17 @@ int enqueue_flow(sali_ctx* c, int lane, int slot_prev, int slot_cur, const float
     return SALI_OK;
 }
 
-int enqueue_union(sali_ctx* c, int lane, const sali_gate* gate, hipStream_t s) {
+// pooling of the lane's saliency pre-pass.  With `tier` (the chained step) the kernel also reduces
+// `flow` (NULL for the first frame of a sequence) to per-patch motion, evaluates the gate and writes
+// the frame-table row with tiers and compaction indices.
+int enqueue_pool(sali_ctx* c, int lane, unsigned msum_parity, float* d_scores, uint8_t* d_salmap,
+                 const TierLaunch* tier, const float2* flow, hipStream_t s) {
     const LaneLayout& L = c->sl.lane[lane];
-    SALI_TRY(launch_union(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), c->cfg.src_h, c->cfg.src_w, gate, s));
-    return SALI_OK;
-}
-
-// pooling; with `tier` the pooling kernel also assigns tiers and writes the frame-table row
-int enqueue_pool(sali_ctx* c, int lane, unsigned msum_parity, const sali_gate* gate, float* d_scores,
-                 uint8_t* d_salmap, const TierLaunch* tier, hipStream_t s) {
-    const LaneLayout& L = c->sl.lane[lane];
+    const LanePtrs lp = c->lane_ptrs(lane);
     SALI_TRY(launch_pool(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), c->sc<uint32_t>(L.var),
-                         c->sc<unsigned long long>(L.msum) + (msum_parity & 1u), c->cfg.src_h, c->cfg.src_w, gate,
-                         d_scores, d_salmap, tier, &c->sc<LaneCounters>(L.counters)->pool_done, s));
+                         c->sc<unsigned long long>(L.msum) + (msum_parity & 1u), c->cfg.src_h, c->cfg.src_w, d_scores,
+                         d_salmap, tier, flow, c->cfg.tau_t, c->cfg.theta_r, lp.dp, lp.gate, &lp.counters->pool_done,
+                         s));
     return SALI_OK;
 }
 
@@ -558,8 +559,7 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
     const int lane = 0;
     const unsigned parity = c->lane_uses[lane]++ & 1u;
     int rc = enqueue_prep(c, d_rgb, lane, true, parity, s);
-    if (rc == SALI_OK) rc = enqueue_union(c, lane, nullptr, s);
-    if (rc == SALI_OK) rc = enqueue_pool(c, lane, parity, nullptr, d_scores576, d_salmap_or_null, nullptr, s);
+    if (rc == SALI_OK) rc = enqueue_pool(c, lane, parity, d_scores576, d_salmap_or_null, nullptr, nullptr, s);
     return rc;
 }
 
@@ -611,26 +611,19 @@ int sali_analyze(sali_ctx* c, const uint8_t* d_rgb, int32_t frame_id, void* stre
     if (rc != SALI_OK) return rc;
     SALI_TRY(hipEventRecord(rec.exp_ready, s));
     const LanePtrs lp = c->lane_ptrs(lane);
+    const float2* flow = nullptr;
     if (prev != nullptr) {
         rc = wait_unless_same(s, prev->stream, prev->exp_ready);
         if (rc != SALI_OK) return rc;
-        const float2* flow = nullptr;
         rc = enqueue_flow(c, lane, (int)((n - 1) % kStepSlots), slot, &flow, s);
         if (rc != SALI_OK) return rc;
-        SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, lp.dp, lp.gate,
-                                   &lp.counters->patch_done, nullptr, s));
-    } else {
-        SALI_TRY(launch_clear_gate(lp.dp, lp.gate, s));      // first frame: never redundant (Algorithm 1, t > 1)
-    }
-    rc = enqueue_union(c, lane, lp.gate, s);
-    if (rc != SALI_OK) return rc;
-    // tiers are handed out in frame order: the cursors must have seen the previous frame
-    if (prev != nullptr) {
+        // tiers are handed out in frame order: the cursors must have seen the previous frame
         rc = wait_unless_same(s, prev->stream, prev->done);
         if (rc != SALI_OK) return rc;
     }
+    // per-patch motion, gate, pooling, tiers: one launch (first frame: no flow, never redundant)
     const TierLaunch tl = tier_launch(c, frame_id);
-    rc = enqueue_pool(c, lane, parity, lp.gate, lp.scores, nullptr, &tl, s);
+    rc = enqueue_pool(c, lane, parity, lp.scores, nullptr, &tl, flow, s);
     if (rc != SALI_OK) return rc;
     SALI_TRY(hipEventRecord(rec.done, s));
     for (int i = 0; i < kRing; ++i)

@@ -305,14 +305,6 @@ __global__ __launch_bounds__(256) void k_patch_gate(const float2* __restrict__ f
     }
 }
 
-__global__ void k_clear_gate(float* dp, sali_gate* gate) {
-    for (int i = threadIdx.x; i < kTokens; i += blockDim.x) dp[i] = 0.0f;
-    if (threadIdx.x == 0) {
-        sali_gate gt = {0, 0.0f, 0, 0};
-        *gate = gt;
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
                            int dh, int dw, hipStream_t s) {
@@ -347,11 +339,6 @@ hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, fl
                              sali_gate* d_gate, uint32_t* d_done_counter, float* d_flow_uv_or_null, hipStream_t s) {
     hipLaunchKernelGGL(k_patch_gate, dim3(kGateBlocks), dim3(256), 0, s, d_flow, h, w, tau_t, theta_r, d_dp, d_gate,
                        d_done_counter, d_flow_uv_or_null);
-    return hipGetLastError();
-}
-
-hipError_t launch_clear_gate(float* d_dp, sali_gate* d_gate, hipStream_t s) {
-    hipLaunchKernelGGL(k_clear_gate, dim3(1), dim3(256), 0, s, d_dp, d_gate);
     return hipGetLastError();
 }
 

@@ -97,12 +97,11 @@ hipError_t launch_unpack(const sali_frame_row* d_rows, int frame_id, const uint1
 hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
                        uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
                        unsigned long long* d_msum_clear, const uint16_t* d_lut, int lo2, int hi2, hipStream_t s);
-hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, const sali_gate* d_gate_or_null,
-                        hipStream_t s);
+hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, hipStream_t s);
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
-                       const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
-                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null,
-                       uint32_t* d_done_counter, hipStream_t s);
+                       const unsigned long long* d_msum, int h, int w, float* d_scores, uint8_t* d_salmap_or_null,
+                       const TierLaunch* tier_or_null, const float2* d_flow_or_null, float tau_t, float theta_r,
+                       float* d_dp, sali_gate* d_gate, uint32_t* d_done_counter, hipStream_t s);
 
 // flow_kernels.hip
 hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
@@ -114,6 +113,5 @@ hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2
                             FlowWeights fw, hipStream_t s);
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
                              sali_gate* d_gate, uint32_t* d_done_counter, float* d_flow_uv_or_null, hipStream_t s);
-hipError_t launch_clear_gate(float* d_dp, sali_gate* d_gate, hipStream_t s);
 
 }  // namespace sali

@@ -17,7 +17,8 @@
 //   k_union  joins components across tile borders with global atomics (border pixels only).
 //   k_pool   per patch: E = edge pixel whose root is strong, C = V above the frame mean and
 //            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.  In the
-//            chained step the last block to finish also assigns tiers and compaction indices.
+//            chained step it also reduces the flow field to the patch's motion (Eq. 5), and the
+//            last block to finish evaluates the gate (Eq. 6) and assigns tiers and indices.
 //
 // All stencils replicate the border; non-maximum suppression treats out-of-image neighbours
 // as magnitude 0.
@@ -330,11 +331,8 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict
     }
 }
 
-// ---------------------------------------------------------------------------------------------
 // hysteresis, cross-tile part: only pairs of neighbours that lie in different k_prep tiles
-__global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, uint32_t* parent, int h, int w,
-                                               const sali_gate* gate) {
-    if (gate != nullptr && gate->redundant != 0) return;
+__global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, uint32_t* parent, int h, int w) {
     const int x = blockIdx.x * 64 + (threadIdx.x & 63);
     const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (x >= w || y >= h) return;
@@ -358,23 +356,23 @@ __global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, 
     }
 }
 
-// One block of 256 threads per patch.  With do_tier the last block to finish runs the tier /
-// compaction step on the 576 scores (and block 0 writes the pointer row of a redundant frame).
+// One block of 256 threads per patch: Eq. 7 score of the patch and, in the chained step (do_tier),
+// also its motion (Eq. 5) from the flow field.  The last block to finish (atomic arrival counter,
+// nobody waits) evaluates the gate (Eq. 6) and either writes the pointer row of a redundant
+// frame or assigns tiers and compaction indices.  So one launch replaces three.
 __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
                                                   const uint32_t* __restrict__ var, const unsigned long long* msum,
-                                                  int h, int w, const sali_gate* gate, float* scores,
-                                                  uint8_t* __restrict__ salmap, int do_tier, TierParams tp,
+                                                  int h, int w, float* scores, uint8_t* __restrict__ salmap,
+                                                  int do_tier, const float2* __restrict__ flow, float tau_t,
+                                                  float theta_r, float* dp_out, sali_gate* gate_out, TierParams tp,
                                                   int frame_id, sali_frame_row* rows, uint8_t* tier_out,
                                                   uint16_t* slot_out, uint16_t* order_out, Cursors* cur, int cap16,
                                                   int cap8, int cap4, uint32_t* done_counter) {
     __shared__ TierShared sh;
     __shared__ uint32_t s_q[kTierThreads / 64];
+    __shared__ float s_m[kTierThreads / 64];
+    __shared__ int s_cnt[kTierThreads / 64];
     __shared__ int s_last;
-    if (gate != nullptr && gate->redundant != 0) {
-        if (do_tier && blockIdx.x == 0)
-            tier_body(sh, scores, true, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
-        return;
-    }
     const int pr = blockIdx.x / kGrid, pc = blockIdx.x % kGrid;
     const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
     const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
@@ -382,6 +380,7 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
     const unsigned long long m = *msum;
     const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
     uint32_t q = 0;
+    float mag = 0.0f;
     for (int p = threadIdx.x; p < area; p += kTierThreads) {
         const int y = ya + p / pw, x = xa + p % pw;
         const size_t gi = (size_t)y * w + x;
@@ -393,9 +392,19 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
         const uint32_t cm = ((unsigned long long)v * hw > m && v >= kVMin) ? 1u : 0u;
         q += e + cm;
         if (salmap != nullptr) salmap[gi] = (uint8_t)(e + cm);
+        if (flow != nullptr) {
+            const float2 d = flow[gi];
+            mag += d.x * d.x + d.y * d.y;
+        }
     }
-    for (int off = 32; off > 0; off >>= 1) q += __shfl_down(q, off);
-    if ((threadIdx.x & 63) == 0) s_q[threadIdx.x >> 6] = q;
+    for (int off = 32; off > 0; off >>= 1) {
+        q += __shfl_down(q, off);
+        mag += __shfl_down(mag, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_q[threadIdx.x >> 6] = q;
+        s_m[threadIdx.x >> 6] = mag;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t total = 0;
@@ -405,6 +414,9 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
         __hip_atomic_store(scores + blockIdx.x, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int last = 0;
         if (do_tier) {
+            const float msum4 = (s_m[0] + s_m[1]) + (s_m[2] + s_m[3]);
+            __hip_atomic_store(dp_out + blockIdx.x, flow != nullptr ? sqrtf(msum4 / (float)area) : 0.0f,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __threadfence();
             last = (atomicAdd(done_counter, 1u) == (uint32_t)(kTokens - 1)) ? 1 : 0;
         }
@@ -413,8 +425,31 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    if (threadIdx.x == 0) *done_counter = 0u;       // ready for the next launch
-    tier_body(sh, scores, false, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
+    // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; the first
+    // frame of a sequence (no flow) is never redundant
+    int n = 0;
+    if (flow != nullptr) {
+        for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
+            const float v = __hip_atomic_load(dp_out + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            n += (v < tau_t) ? 1 : 0;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = n;
+    __syncthreads();
+    const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    const float r = (float)n_static / (float)kTokens;
+    const bool redundant = flow != nullptr && r > theta_r;
+    if (threadIdx.x == 0) {
+        sali_gate gt;
+        gt.n_static = n_static;
+        gt.r_frame = flow != nullptr ? r : 0.0f;
+        gt.redundant = redundant ? 1 : 0;
+        gt.reserved = 0;
+        *gate_out = gt;
+        *done_counter = 0u;       // ready for the next launch
+    }
+    tier_body(sh, scores, redundant, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -432,22 +467,22 @@ hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, u
     return hipGetLastError();
 }
 
-hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, const sali_gate* d_gate_or_null,
-                        hipStream_t s) {
+hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, hipStream_t s) {
     dim3 grid((w + 63) / 64, (h + 3) / 4);
-    hipLaunchKernelGGL(k_union, grid, dim3(256), 0, s, d_cls, d_parent, h, w, d_gate_or_null);
+    hipLaunchKernelGGL(k_union, grid, dim3(256), 0, s, d_cls, d_parent, h, w);
     return hipGetLastError();
 }
 
 hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
-                       const unsigned long long* d_msum, int h, int w, const sali_gate* d_gate_or_null,
-                       float* d_scores, uint8_t* d_salmap_or_null, const TierLaunch* tier_or_null,
-                       uint32_t* d_done_counter, hipStream_t s) {
+                       const unsigned long long* d_msum, int h, int w, float* d_scores, uint8_t* d_salmap_or_null,
+                       const TierLaunch* tier_or_null, const float2* d_flow_or_null, float tau_t, float theta_r,
+                       float* d_dp, sali_gate* d_gate, uint32_t* d_done_counter, hipStream_t s) {
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
-    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
-                       d_gate_or_null, d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, t.tp, t.frame_id,
-                       t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4, d_done_counter);
+    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w, d_scores,
+                       d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r, d_dp, d_gate,
+                       t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4,
+                       d_done_counter);
     return hipGetLastError();
 }
 
