@@ -303,6 +303,11 @@ int enqueue_expansion(sali_ctx* c, int lane, int slot, hipStream_t s) {
     const LaneLayout& L = c->sl.lane[lane];
     float* pyr = c->sc<float>(L.pyr);
     const LevelGeom& g = c->geom;
+    if (g.levels <= 3) {
+        SALI_TRY(launch_expand(c->sc<uint8_t>(L.y8), g, c->fw, c->sc<float4>(c->sl.expA[slot]),
+                               c->sc<float2>(c->sl.expB[slot]), s));
+        return SALI_OK;
+    }
     for (int l = 1; l < g.levels; ++l) {
         SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(L.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
                                  g.h[l - 1], g.w[l - 1], pyr + g.off[l], g.h[l], g.w[l], s));

@@ -5,9 +5,11 @@
 // small images: no dense contraction here, so no MFMA; the design goal is few launches and no
 // spilled intermediates.
 //
-//   k_pyr_down   5x5 binomial [1 4 6 4 1]/16, stride 2 (level 0 is gray / 255)
-//   k_polyexp    all pyramid levels in one launch; 32x32 tile + 3-pixel halo in LDS, separable
-//                moments, closed-form solution of the 6-unknown weighted least-squares fit
+//   k_expand     pyramid (5x5 binomial [1 4 6 4 1]/16, stride 2; level 0 is gray / 255) and
+//                polynomial expansion of up to three levels in ONE launch: 16x16 tiles, the pyramid
+//                values a tile needs are rebuilt from the gray image in LDS; separable moments,
+//                closed-form solution of the 6-unknown weighted least-squares fit
+//   k_pyr_down, k_polyexp   the same per level (pyramid in HBM), used for more than three levels
 //   k_flow_iter  one displacement update: per cell of a 32x32 tile + 5-pixel halo, sample the new
 //                frame's expansion bilinearly at x + prior, build A^T A (3 values) and A^T db
 //                (2 values) in LDS, separable 11x11 Gaussian aggregation in LDS, 2x2 ridge solve.
@@ -124,6 +126,132 @@ __global__ __launch_bounds__(256) void k_polyexp(const uint8_t* __restrict__ y8,
         const float axy = sxy * fw.inv_2m2sq;
         A_out[gi] = make_float4(axx, axy, ayy, 0.0f);
         b_out[gi] = make_float2(sx * fw.inv_m2, sy * fw.inv_m2);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pyramid + expansion in one launch for up to three levels: a block owns one 16x16 tile of one
+// level and rebuilds the pyramid values it needs from the gray image in LDS (level 1 from a 47x47
+// gray patch, level 2 from a 47x47 level-1 patch built from a 97x97 gray patch).  This recomputes
+// some pyramid pixels but removes two dependent launches and all pyramid traffic.
+namespace {
+constexpr int kET = 16;                        // tile side
+constexpr int kER = kET + 2 * kPolyN;          // 22: region the expansion stencil reads
+constexpr int kEP = 2 * (kER - 1) + 5;         // 47: region one level below that feeds it
+constexpr int kEQ = 2 * (kEP - 1) + 5;         // 97: region two levels below
+
+// one level of the 5x5 binomial pyramid, LDS to LDS.  dst cell i (i < n_dst) stands for the
+// coordinate clamp(o_dst + i) of the upper level and reads src cells 2 * that + {-2..2} - o_src.
+template <int kSrcStride, int kDstStride>
+__device__ __forceinline__ void pyr_level_lds(const float* src, int o_src_y, int o_src_x, float* dst, int o_dst_y,
+                                              int o_dst_x, int n_dst, int dh, int dw) {
+    const float k[5] = {1.0f / 16, 4.0f / 16, 6.0f / 16, 4.0f / 16, 1.0f / 16};
+    for (int p = threadIdx.x; p < n_dst * n_dst; p += 256) {
+        const int ry = p / n_dst, rx = p % n_dst;
+        const int cy = clampi(o_dst_y + ry, 0, dh - 1), cx = clampi(o_dst_x + rx, 0, dw - 1);
+        const int sy = 2 * cy - o_src_y, sx = 2 * cx - o_src_x;
+        float acc = 0.0f;
+#pragma unroll
+        for (int a = -2; a <= 2; ++a) {
+            float row = 0.0f;
+#pragma unroll
+            for (int b = -2; b <= 2; ++b) row += k[b + 2] * src[(sy + a) * kSrcStride + (sx + b)];
+            acc += k[a + 2] * row;
+        }
+        dst[ry * kDstStride + rx] = acc;
+    }
+}
+}  // namespace
+
+__global__ __launch_bounds__(256) void k_expand(const uint8_t* __restrict__ y8, LevelGeom g, int t1, int t2, int tx0,
+                                                int tx1, int tx2, FlowWeights fw, float4* __restrict__ A_out,
+                                                float2* __restrict__ b_out) {
+    __shared__ float s_q[kEQ * (kEQ + 1)];          // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
+    __shared__ float s_p[kEP * (kEP + 1)];          // level-1 patch of a level-2 block
+    __shared__ float s_f[kER][kER + 1];
+    __shared__ float s_v[3][kET][kER + 1];
+
+    // block -> (level, tile)
+    const int b = blockIdx.x;
+    const int lvl = b < t1 ? 0 : (b < t2 ? 1 : 2);
+    const int t = b - (lvl == 0 ? 0 : (lvl == 1 ? t1 : t2));
+    const int tiles_x = lvl == 0 ? tx0 : (lvl == 1 ? tx1 : tx2);
+    const int h = g.h[lvl], w = g.w[lvl];
+    const int x0 = (t % tiles_x) * kET, y0 = (t / tiles_x) * kET;
+    const int oy = y0 - kPolyN, ox = x0 - kPolyN;   // origin of s_f in this level's coordinates
+    const int tid = threadIdx.x;
+    const int h0 = g.h[0], w0 = g.w[0];
+
+    if (lvl == 0) {
+        for (int p = tid; p < kER * kER; p += 256) {
+            const int ry = p / kER, rx = p % kER;
+            const int gy = clampi(oy + ry, 0, h - 1), gx = clampi(ox + rx, 0, w - 1);
+            s_f[ry][rx] = (float)y8[(size_t)gy * w + gx] / 255.0f;
+        }
+    } else if (lvl == 1) {
+        const int qy = 2 * oy - 2, qx = 2 * ox - 2;              // origin of the gray patch (47 x 47)
+        for (int p = tid; p < kEP * kEP; p += 256) {
+            const int ry = p / kEP, rx = p % kEP;
+            const int gy = clampi(qy + ry, 0, h0 - 1), gx = clampi(qx + rx, 0, w0 - 1);
+            s_q[ry * (kEP + 1) + rx] = (float)y8[(size_t)gy * w0 + gx] / 255.0f;
+        }
+        __syncthreads();
+        pyr_level_lds<kEP + 1, kER + 1>(s_q, qy, qx, &s_f[0][0], oy, ox, kER, h, w);
+    } else {
+        const int h1 = g.h[1], w1 = g.w[1];
+        const int py = 2 * oy - 2, px = 2 * ox - 2;              // origin of the level-1 patch (47 x 47)
+        const int qy = 2 * py - 2, qx = 2 * px - 2;              // origin of the gray patch (97 x 97)
+        for (int p = tid; p < kEQ * kEQ; p += 256) {
+            const int ry = p / kEQ, rx = p % kEQ;
+            const int gy = clampi(qy + ry, 0, h0 - 1), gx = clampi(qx + rx, 0, w0 - 1);
+            s_q[ry * (kEQ + 1) + rx] = (float)y8[(size_t)gy * w0 + gx] / 255.0f;
+        }
+        __syncthreads();
+        pyr_level_lds<kEQ + 1, kEP + 1>(s_q, qy, qx, s_p, py, px, kEP, h1, w1);
+        __syncthreads();
+        pyr_level_lds<kEP + 1, kER + 1>(s_p, py, px, &s_f[0][0], oy, ox, kER, h, w);
+    }
+    __syncthreads();
+
+    // vertical moments, then horizontal moments and the closed-form fit (as in k_polyexp)
+    for (int p = tid; p < kET * kER; p += 256) {
+        const int ty = p / kER, rx = p % kER;
+        float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f;
+#pragma unroll
+        for (int k = -kPolyN; k <= kPolyN; ++k) {
+            const float f = s_f[ty + kPolyN + k][rx] * fw.poly_g[k + kPolyN];
+            v0 += f;
+            v1 += f * (float)k;
+            v2 += f * (float)(k * k);
+        }
+        s_v[0][ty][rx] = v0;
+        s_v[1][ty][rx] = v1;
+        s_v[2][ty][rx] = v2;
+    }
+    __syncthreads();
+    {
+        const int ty = tid / kET, tx = tid % kET;
+        const int gy = y0 + ty, gx = x0 + tx;
+        if (gy < h && gx < w) {
+            float s0 = 0, sx = 0, sxx = 0, sy = 0, sxy = 0, syy = 0;
+#pragma unroll
+            for (int k = -kPolyN; k <= kPolyN; ++k) {
+                const float gk = fw.poly_g[k + kPolyN];
+                const float a0 = s_v[0][ty][tx + kPolyN + k] * gk;
+                const float a1 = s_v[1][ty][tx + kPolyN + k] * gk;
+                const float a2 = s_v[2][ty][tx + kPolyN + k] * gk;
+                s0 += a0;
+                sx += a0 * (float)k;
+                sxx += a0 * (float)(k * k);
+                sy += a1;
+                sxy += a1 * (float)k;
+                syy += a2;
+            }
+            const size_t gi = g.off[lvl] + (size_t)gy * w + gx;
+            A_out[gi] = make_float4((sxx - fw.m2 * s0) * fw.inv_den, sxy * fw.inv_2m2sq, (syy - fw.m2 * s0) * fw.inv_den,
+                                    0.0f);
+            b_out[gi] = make_float2(sx * fw.inv_m2, sy * fw.inv_m2);
+        }
     }
 }
 
@@ -316,6 +444,22 @@ hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_nu
 hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
                           float2* d_b, hipStream_t s) {
     hipLaunchKernelGGL(k_polyexp, dim3(g.tile_start[g.levels]), dim3(256), 0, s, d_y8, d_pyr, g, fw, d_A, d_b);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand(const uint8_t* d_y8, LevelGeom g, FlowWeights fw, float4* d_A, float2* d_b, hipStream_t s) {
+    // up to three levels, 16x16 tiles, one launch
+    int tx[3] = {1, 1, 1}, start[4] = {0, 0, 0, 0};
+    for (int l = 0; l < 3; ++l) {
+        int n = 0;
+        if (l < g.levels) {
+            tx[l] = (g.w[l] + kET - 1) / kET;
+            n = tx[l] * ((g.h[l] + kET - 1) / kET);
+        }
+        start[l + 1] = start[l] + n;
+    }
+    hipLaunchKernelGGL(k_expand, dim3(start[3]), dim3(256), 0, s, d_y8, g, start[1], start[2], tx[0], tx[1], tx[2], fw,
+                       d_A, d_b);
     return hipGetLastError();
 }
 

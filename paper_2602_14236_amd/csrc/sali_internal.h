@@ -108,6 +108,7 @@ hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_nu
                            int dh, int dw, hipStream_t s);
 hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
                           float2* d_b, hipStream_t s);
+hipError_t launch_expand(const uint8_t* d_y8, LevelGeom g, FlowWeights fw, float4* d_A, float2* d_b, hipStream_t s);
 hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2, const float2* b2,
                             const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
                             FlowWeights fw, hipStream_t s);

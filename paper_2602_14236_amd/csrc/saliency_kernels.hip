@@ -356,10 +356,13 @@ __global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, 
     }
 }
 
-// One block of 256 threads per patch: Eq. 7 score of the patch and, in the chained step (do_tier),
-// also its motion (Eq. 5) from the flow field.  The last block to finish (atomic arrival counter,
-// nobody waits) evaluates the gate (Eq. 6) and either writes the pointer row of a redundant
-// frame or assigns tiers and compaction indices.  So one launch replaces three.
+// One wave per patch, four patches per block of 256 threads: Eq. 7 score of the patch and, in the
+// chained step (do_tier), also its motion (Eq. 5) from the flow field.  The last block to finish
+// (atomic arrival counter, nobody waits) evaluates the gate (Eq. 6) and either writes the pointer
+// row of a redundant frame or assigns tiers and compaction indices.  So one launch replaces three,
+// with one device-scope fence per block.
+constexpr int kPoolBlocks = kTokens / 4;
+
 __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
                                                   const uint32_t* __restrict__ var, const unsigned long long* msum,
                                                   int h, int w, float* scores, uint8_t* __restrict__ salmap,
@@ -368,12 +371,13 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
                                                   int frame_id, sali_frame_row* rows, uint8_t* tier_out,
                                                   uint16_t* slot_out, uint16_t* order_out, Cursors* cur, int cap16,
                                                   int cap8, int cap4, uint32_t* done_counter) {
+    static_assert(kTierThreads == 256, "four waves, one patch each");
     __shared__ TierShared sh;
-    __shared__ uint32_t s_q[kTierThreads / 64];
-    __shared__ float s_m[kTierThreads / 64];
     __shared__ int s_cnt[kTierThreads / 64];
     __shared__ int s_last;
-    const int pr = blockIdx.x / kGrid, pc = blockIdx.x % kGrid;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int token = blockIdx.x * 4 + wave;
+    const int pr = token / kGrid, pc = token % kGrid;
     const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
     const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
     const int pw = xb - xa, area = pw * (yb - ya);
@@ -381,7 +385,7 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
     const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
     uint32_t q = 0;
     float mag = 0.0f;
-    for (int p = threadIdx.x; p < area; p += kTierThreads) {
+    for (int p = lane; p < area; p += 64) {
         const int y = ya + p / pw, x = xa + p % pw;
         const size_t gi = (size_t)y * w + x;
         const int c = cls[gi];
@@ -401,24 +405,20 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
         q += __shfl_down(q, off);
         mag += __shfl_down(mag, off);
     }
-    if ((threadIdx.x & 63) == 0) {
-        s_q[threadIdx.x >> 6] = q;
-        s_m[threadIdx.x >> 6] = mag;
+    if (lane == 0) {
+        const uint32_t s_fix = (uint32_t)(((unsigned long long)q << 15) / (unsigned long long)area);
+        const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
+        __hip_atomic_store(scores + token, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (do_tier)
+            __hip_atomic_store(dp_out + token, flow != nullptr ? sqrtf(mag / (float)area) : 0.0f, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t total = 0;
-        for (int k = 0; k < kTierThreads / 64; ++k) total += s_q[k];
-        const uint32_t s_fix = (uint32_t)(((unsigned long long)total << 15) / (unsigned long long)area);
-        const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
-        __hip_atomic_store(scores + blockIdx.x, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int last = 0;
         if (do_tier) {
-            const float msum4 = (s_m[0] + s_m[1]) + (s_m[2] + s_m[3]);
-            __hip_atomic_store(dp_out + blockIdx.x, flow != nullptr ? sqrtf(msum4 / (float)area) : 0.0f,
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __threadfence();
-            last = (atomicAdd(done_counter, 1u) == (uint32_t)(kTokens - 1)) ? 1 : 0;
+            last = (atomicAdd(done_counter, 1u) == (uint32_t)(kPoolBlocks - 1)) ? 1 : 0;
         }
         s_last = last;
     }
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
         }
     }
     for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
-    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = n;
+    if (lane == 0) s_cnt[wave] = n;
     __syncthreads();
     const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
     const float r = (float)n_static / (float)kTokens;
@@ -479,7 +479,7 @@ hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uin
                        float* d_dp, sali_gate* d_gate, uint32_t* d_done_counter, hipStream_t s) {
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
-    hipLaunchKernelGGL(k_pool, dim3(kTokens), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w, d_scores,
+    hipLaunchKernelGGL(k_pool, dim3(kPoolBlocks), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w, d_scores,
                        d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r, d_dp, d_gate,
                        t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4,
                        d_done_counter);
