@@ -467,7 +467,7 @@ hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2
                             const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
                             FlowWeights fw, hipStream_t s) {
     // small levels: 16x16 tiles so that the level spreads over many compute units
-    if ((long long)((w + 31) / 32) * ((h + 31) / 32) < 2048) {
+    if ((long long)((w + 31) / 32) * ((h + 31) / 32) < 1024) {
         dim3 grid((w + 15) / 16, (h + 15) / 16);
         hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw,
                            prior_mode, fw);

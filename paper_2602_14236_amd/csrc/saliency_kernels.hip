@@ -356,13 +356,13 @@ __global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, 
     }
 }
 
-// One wave per patch, four patches per block of 256 threads: Eq. 7 score of the patch and, in the
-// chained step (do_tier), also its motion (Eq. 5) from the flow field.  The last block to finish
+// Eq. 7 score of each patch and, in the chained step (do_tier), also its motion (Eq. 5) from the
+// flow field.  kWaves = 1: one wave per patch, four patches per block of 256 threads (small
+// patches); kWaves = 4: the whole block works on one patch (large frames).  The last block to finish
 // (atomic arrival counter, nobody waits) evaluates the gate (Eq. 6) and either writes the pointer
 // row of a redundant frame or assigns tiers and compaction indices.  So one launch replaces three,
 // with one device-scope fence per block.
-constexpr int kPoolBlocks = kTokens / 4;
-
+template <int kWaves>
 __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
                                                   const uint32_t* __restrict__ var, const unsigned long long* msum,
                                                   int h, int w, float* scores, uint8_t* __restrict__ salmap,
@@ -372,11 +372,14 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
                                                   uint16_t* slot_out, uint16_t* order_out, Cursors* cur, int cap16,
                                                   int cap8, int cap4, uint32_t* done_counter) {
     static_assert(kTierThreads == 256, "four waves, one patch each");
+    static_assert(kWaves == 1 || kWaves == 4, "");
     __shared__ TierShared sh;
     __shared__ int s_cnt[kTierThreads / 64];
+    __shared__ uint32_t s_pq[kTierThreads / 64];
+    __shared__ float s_pm[kTierThreads / 64];
     __shared__ int s_last;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int token = blockIdx.x * 4 + wave;
+    const int token = kWaves == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
     const int pr = token / kGrid, pc = token % kGrid;
     const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
     const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
@@ -385,7 +388,7 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
     const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
     uint32_t q = 0;
     float mag = 0.0f;
-    for (int p = lane; p < area; p += 64) {
+    for (int p = (kWaves == 1 ? lane : (int)threadIdx.x); p < area; p += 64 * kWaves) {
         const int y = ya + p / pw, x = xa + p % pw;
         const size_t gi = (size_t)y * w + x;
         const int c = cls[gi];
@@ -405,7 +408,16 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
         q += __shfl_down(q, off);
         mag += __shfl_down(mag, off);
     }
-    if (lane == 0) {
+    if (kWaves == 4) {
+        if (lane == 0) {
+            s_pq[wave] = q;
+            s_pm[wave] = mag;
+        }
+        __syncthreads();
+        q = s_pq[0] + s_pq[1] + s_pq[2] + s_pq[3];
+        mag = (s_pm[0] + s_pm[1]) + (s_pm[2] + s_pm[3]);
+    }
+    if (lane == 0 && (kWaves == 1 || wave == 0)) {
         const uint32_t s_fix = (uint32_t)(((unsigned long long)q << 15) / (unsigned long long)area);
         const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
         __hip_atomic_store(scores + token, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -418,7 +430,7 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
         int last = 0;
         if (do_tier) {
             __threadfence();
-            last = (atomicAdd(done_counter, 1u) == (uint32_t)(kPoolBlocks - 1)) ? 1 : 0;
+            last = (atomicAdd(done_counter, 1u) == gridDim.x - 1u) ? 1 : 0;
         }
         s_last = last;
     }
@@ -479,10 +491,17 @@ hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uin
                        float* d_dp, sali_gate* d_gate, uint32_t* d_done_counter, hipStream_t s) {
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
-    hipLaunchKernelGGL(k_pool, dim3(kPoolBlocks), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w, d_scores,
-                       d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r, d_dp, d_gate,
-                       t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8, t.cap4,
-                       d_done_counter);
+    // patches of up to 1024 pixels: one wave each (a quarter of the blocks and of the fences)
+    if ((long long)h * w <= 1024ll * kTokens)
+        hipLaunchKernelGGL(k_pool<1>, dim3(kTokens / 4), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
+                           d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r,
+                           d_dp, d_gate, t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8,
+                           t.cap4, d_done_counter);
+    else
+        hipLaunchKernelGGL(k_pool<4>, dim3(kTokens), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
+                           d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r,
+                           d_dp, d_gate, t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8,
+                           t.cap4, d_done_counter);
     return hipGetLastError();
 }
 
