@@ -59,7 +59,8 @@ extern "C" {
 #define SALI_TIER_PRUNE 3
 
 #define SALI_TOKENS_MAX 576     /* grid * grid; grid is 24 (576 visual tokens per frame)     */
-#define SALI_ANALYSIS_LANES 3   /* frames whose image-side analysis may be in flight at once */
+#define SALI_MAX_BATCH 8        /* frames that one sali_analyze_batch call may take               */
+#define SALI_ANALYSIS_LANES 16  /* frames whose image-side analysis may be in flight at once      */
 
 typedef struct sali_ctx sali_ctx;   /* opaque host object; owns no device memory */
 
@@ -195,10 +196,22 @@ int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t
  *
  * sali_store: packs `d_kv_fp16` into the pools according to the row that sali_analyze wrote.
  * Makes `stream` wait (on the device) for that frame's analysis if it ran on another stream.
- * SALI_ERR_STATE if `frame_id` is not among the last 8 analysed frames.
+ * SALI_ERR_STATE if `frame_id` is not among the last 2 * SALI_ANALYSIS_LANES analysed frames.
  *
- * sali_step(ctx, rgb, kv, id, s) == sali_analyze(ctx, rgb, id, s); sali_store(ctx, kv, id, s). */
+ * sali_step(ctx, rgb, kv, id, s) == sali_analyze(ctx, rgb, id, s); sali_store(ctx, kv, id, s).
+ *
+ * sali_analyze_batch: the analysis of `n_frames` (1..SALI_MAX_BATCH) consecutive frames with ids
+ * first_frame_id, first_frame_id + 1, ... in ONE set of kernel launches (the frame is a grid
+ * dimension).  `d_rgb_frames` is a HOST array of n_frames device pointers, read before the call
+ * returns; the images must stay unchanged until the work on `stream` has run.  Results are
+ * identical to n_frames calls of sali_analyze: a frame's flow is taken against the frame before
+ * it (the last frame of the previous call for the first of the batch) and tiers and pool rows
+ * are handed out in frame order.  One 336x336 frame cannot fill 256 compute units and every
+ * kernel boundary disturbs a bandwidth-bound kernel on another stream, so batches are both
+ * faster and quieter.  SALI_ERR_SHAPE if n_frames or the ids are out of range. */
 int sali_analyze(sali_ctx* ctx, const uint8_t* d_rgb, int32_t frame_id, void* stream);
+int sali_analyze_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, int32_t first_frame_id, int32_t n_frames,
+                       void* stream);
 int sali_store(sali_ctx* ctx, const void* d_kv_fp16, int32_t frame_id, void* stream);
 
 /* One loop body of Algorithm 1 with look-ahead on caller-owned streams: analyses a later

@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsali.so
 _lib = None
 
 TOKENS = 576
+MAX_BATCH = 8           # SALI_MAX_BATCH
 TIER_FP16, TIER_INT8, TIER_INT4, TIER_PRUNE = 0, 1, 2, 3
 FAULT_OVERFLOW, FAULT_NONFINITE, FAULT_NAN_SCORE, FAULT_NO_DATA = 1, 2, 4, 8
 
@@ -79,6 +80,7 @@ EXPORTS = {
     "sali_kv_decompress": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sali_analyze": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sali_analyze_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_void_p]),
     "sali_store": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sali_step_pipelined": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p]),
@@ -212,6 +214,12 @@ class SaliContext:
     def analyze(self, rgb, frame_id: int, stream: Optional[torch.cuda.Stream] = None):
         s = _stream() if stream is None else stream.cuda_stream
         _check(self.lib.sali_analyze(self.handle, _ptr(rgb), frame_id, s), "sali_analyze")
+
+    def analyze_batch(self, rgb_frames, first_frame_id: int, stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        ptrs = (C.c_void_p * len(rgb_frames))(*[f.data_ptr() for f in rgb_frames])
+        _check(self.lib.sali_analyze_batch(self.handle, ptrs, first_frame_id, len(rgb_frames), s),
+               "sali_analyze_batch")
 
     def store(self, kv, frame_id: int, stream: Optional[torch.cuda.Stream] = None):
         s = _stream() if stream is None else stream.cuda_stream

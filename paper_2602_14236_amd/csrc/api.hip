@@ -15,13 +15,15 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-// Image-side scratch exists in kLanes copies so that the analyses of consecutive frames can be in
-// flight at once on different streams; polynomial expansions live in a ring one longer than that
-// (a frame's flow reads its predecessor's expansion), plus two slots for the stand-alone flow call.
+// Image-side scratch exists in kLanes copies (one per frame in flight) so that the analyses of
+// many frames can be in flight at once, in one batch or on different streams; polynomial expansions
+// live in a ring one longer than that (a frame's flow reads its predecessor's expansion), plus two
+// slots for the stand-alone flow call.
 constexpr int kLanes = SALI_ANALYSIS_LANES;
 constexpr int kStepSlots = kLanes + 1;
 constexpr int kExpSlots = kStepSlots + 2;
-constexpr int kRing = 8;              // bookkeeping of the most recent analyses
+constexpr int kRing = 2 * kLanes;     // bookkeeping of the most recent analyses
+static_assert(kLanes >= 2 * kMaxBatch, "two batches in flight");
 
 struct LaneLayout {
     size_t y8, pyr, flow[2], cls, var, parent, msum, dp, scores, gate, counters;
@@ -237,6 +239,7 @@ struct AnalysisRecord {
     hipStream_t stream;
     hipEvent_t exp_ready;     // the frame's polynomial expansion is complete
     hipEvent_t done;          // the frame's row / tier tables are complete
+    int batch_last;           // ring entry whose events cover this frame (the last frame of its batch)
 };
 
 struct sali_ctx {
@@ -280,52 +283,86 @@ namespace {
         if ((expr) != hipSuccess) return SALI_ERR_HIP; \
     } while (0)
 
-// gray (+ saliency pre-pass) of one frame in lane `lane`; msum_parity selects the accumulator of
-// the colour-variance frame sum (the other one is cleared for the lane's next use)
-int enqueue_prep(sali_ctx* c, const uint8_t* d_rgb, int lane, bool with_saliency, unsigned msum_parity,
-                 hipStream_t s) {
+// Which scratch copies and expansion slots the frames of one batch use.
+struct BatchPlan {
+    int n;                          // frames, 1..kMaxBatch
+    int lane[kMaxBatch];
+    int slot[kMaxBatch];            // expansion slot of the frame
+    int prev_slot[kMaxBatch];       // expansion slot of its predecessor, -1 = none (first frame of a sequence)
+    unsigned parity[kMaxBatch];     // which frame-sum accumulator of the lane this pass uses
+};
+
+// gray (+ saliency pre-pass) of the batch's frames; the other frame-sum accumulator of each lane is
+// cleared for the lane's next use
+int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool with_saliency, hipStream_t s) {
     const sali_config& cfg = c->cfg;
-    const LaneLayout& L = c->sl.lane[lane];
-    unsigned long long* msum = c->sc<unsigned long long>(L.msum);
-    unsigned long long* acc = with_saliency ? msum + (msum_parity & 1u) : nullptr;
-    unsigned long long* clr = with_saliency ? msum + ((msum_parity + 1u) & 1u) : nullptr;
-    SALI_TRY(launch_prep(d_rgb, cfg.src_h, cfg.src_w, with_saliency, c->sc<uint8_t>(L.y8), c->sc<uint8_t>(L.cls),
-                         c->sc<uint32_t>(L.var), c->sc<uint32_t>(L.parent), acc, clr, c->tb<uint16_t>(c->tl.lut),
+    PrepBatch f = {};
+    for (int i = 0; i < bp.n; ++i) {
+        const LaneLayout& L = c->sl.lane[bp.lane[i]];
+        unsigned long long* msum = c->sc<unsigned long long>(L.msum);
+        f.rgb[i] = d_rgb[i];
+        f.y8[i] = c->sc<uint8_t>(L.y8);
+        f.cls[i] = c->sc<uint8_t>(L.cls);
+        f.var[i] = c->sc<uint32_t>(L.var);
+        f.parent[i] = c->sc<uint32_t>(L.parent);
+        f.msum_acc[i] = with_saliency ? msum + (bp.parity[i] & 1u) : nullptr;
+        f.msum_clear[i] = with_saliency ? msum + ((bp.parity[i] + 1u) & 1u) : nullptr;
+    }
+    SALI_TRY(launch_prep(f, bp.n, cfg.src_h, cfg.src_w, with_saliency, c->tb<uint16_t>(c->tl.lut),
                          cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
     // cross-tile hysteresis (a kernel boundary is the cheapest device-wide ordering there is)
-    if (with_saliency)
-        SALI_TRY(launch_union(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), cfg.src_h, cfg.src_w, s));
+    if (with_saliency) SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
     return SALI_OK;
 }
 
-// pyramid and polynomial expansion of the lane's gray image into expansion slot `slot`
-int enqueue_expansion(sali_ctx* c, int lane, int slot, hipStream_t s) {
-    const LaneLayout& L = c->sl.lane[lane];
-    float* pyr = c->sc<float>(L.pyr);
+// pyramid and polynomial expansion of each frame's gray image into its expansion slot
+int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, hipStream_t s) {
     const LevelGeom& g = c->geom;
     if (g.levels <= 3) {
-        SALI_TRY(launch_expand(c->sc<uint8_t>(L.y8), g, c->fw, c->sc<float4>(c->sl.expA[slot]),
-                               c->sc<float2>(c->sl.expB[slot]), s));
+        ExpandBatch f = {};
+        for (int i = 0; i < bp.n; ++i) {
+            f.y8[i] = c->sc<uint8_t>(c->sl.lane[bp.lane[i]].y8);
+            f.A[i] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
+            f.b[i] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
+        }
+        SALI_TRY(launch_expand(f, bp.n, g, c->fw, s));
         return SALI_OK;
     }
-    for (int l = 1; l < g.levels; ++l) {
-        SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(L.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
-                                 g.h[l - 1], g.w[l - 1], pyr + g.off[l], g.h[l], g.w[l], s));
+    for (int i = 0; i < bp.n; ++i) {
+        const LaneLayout& L = c->sl.lane[bp.lane[i]];
+        float* pyr = c->sc<float>(L.pyr);
+        for (int l = 1; l < g.levels; ++l) {
+            SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(L.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
+                                     g.h[l - 1], g.w[l - 1], pyr + g.off[l], g.h[l], g.w[l], s));
+        }
+        SALI_TRY(launch_polyexp(c->sc<uint8_t>(L.y8), pyr, g, c->fw, c->sc<float4>(c->sl.expA[bp.slot[i]]),
+                                c->sc<float2>(c->sl.expB[bp.slot[i]]), s));
     }
-    SALI_TRY(launch_polyexp(c->sc<uint8_t>(L.y8), pyr, g, c->fw, c->sc<float4>(c->sl.expA[slot]),
-                            c->sc<float2>(c->sl.expB[slot]), s));
     return SALI_OK;
 }
 
-// coarse-to-fine displacement estimation between expansion slots; result in *result_buf
-int enqueue_flow(sali_ctx* c, int lane, int slot_prev, int slot_cur, const float2** result_buf, hipStream_t s) {
+// coarse-to-fine displacement estimation of every frame of the batch that has a predecessor;
+// flow[i] = the frame's result (NULL without predecessor)
+int enqueue_flow(sali_ctx* c, const BatchPlan& bp, const float2** flow, hipStream_t s) {
     const LevelGeom& g = c->geom;
-    const LaneLayout& L = c->sl.lane[lane];
-    float2* buf[2] = {c->sc<float2>(L.flow[0]), c->sc<float2>(L.flow[1])};
-    const float4* A1 = c->sc<float4>(c->sl.expA[slot_prev]);
-    const float2* b1 = c->sc<float2>(c->sl.expB[slot_prev]);
-    const float4* A2 = c->sc<float4>(c->sl.expA[slot_cur]);
-    const float2* b2 = c->sc<float2>(c->sl.expB[slot_cur]);
+    FlowBatch f[2] = {};            // [which of the two flow buffers is read]
+    int idx[kMaxBatch];
+    int m = 0;
+    for (int i = 0; i < bp.n; ++i) {
+        flow[i] = nullptr;
+        if (bp.prev_slot[i] < 0) continue;
+        const LaneLayout& L = c->sl.lane[bp.lane[i]];
+        for (int k = 0; k < 2; ++k) {
+            f[k].A1[m] = c->sc<float4>(c->sl.expA[bp.prev_slot[i]]);
+            f[k].b1[m] = c->sc<float2>(c->sl.expB[bp.prev_slot[i]]);
+            f[k].A2[m] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
+            f[k].b2[m] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
+            f[k].d_in[m] = c->sc<float2>(L.flow[k]);
+            f[k].d_out[m] = c->sc<float2>(L.flow[k ^ 1]);
+        }
+        idx[m++] = i;
+    }
+    if (m == 0) return SALI_OK;
     int cur = 0;            // buffer holding the latest estimate
     bool have = false;
     for (int l = g.levels - 1; l >= 0; --l) {
@@ -335,27 +372,36 @@ int enqueue_flow(sali_ctx* c, int lane, int slot_prev, int slot_cur, const float
             if (it > 0) mode = 2;
             else if (!have) mode = 0;
             else { mode = 1; ch = g.h[l + 1]; cw = g.w[l + 1]; }
-            SALI_TRY(launch_flow_iter(A1 + g.off[l], b1 + g.off[l], A2 + g.off[l], b2 + g.off[l], buf[cur],
-                                      buf[cur ^ 1], g.h[l], g.w[l], ch, cw, mode, c->fw, s));
+            SALI_TRY(launch_flow_iter(f[cur], m, g.off[l], g.h[l], g.w[l], ch, cw, mode, c->fw, s));
             cur ^= 1;
             have = true;
         }
     }
-    *result_buf = buf[cur];
+    for (int k = 0; k < m; ++k) flow[idx[k]] = c->sc<float2>(c->sl.lane[bp.lane[idx[k]]].flow[cur]);
     return SALI_OK;
 }
 
-// pooling of the lane's saliency pre-pass.  With `tier` (the chained step) the kernel also reduces
-// `flow` (NULL for the first frame of a sequence) to per-patch motion, evaluates the gate and writes
-// the frame-table row with tiers and compaction indices.
-int enqueue_pool(sali_ctx* c, int lane, unsigned msum_parity, float* d_scores, uint8_t* d_salmap,
-                 const TierLaunch* tier, const float2* flow, hipStream_t s) {
-    const LaneLayout& L = c->sl.lane[lane];
-    const LanePtrs lp = c->lane_ptrs(lane);
-    SALI_TRY(launch_pool(c->sc<uint8_t>(L.cls), c->sc<uint32_t>(L.parent), c->sc<uint32_t>(L.var),
-                         c->sc<unsigned long long>(L.msum) + (msum_parity & 1u), c->cfg.src_h, c->cfg.src_w, d_scores,
-                         d_salmap, tier, flow, c->cfg.tau_t, c->cfg.theta_r, lp.dp, lp.gate, &lp.counters->pool_done,
-                         s));
+// pooling of the batch's saliency pre-pass.  With `tier` (the chained step) the kernel also reduces
+// each frame's flow (NULL: no predecessor) to per-patch motion, evaluates the gates and writes the
+// frame-table rows with tiers and compaction indices, in frame order.  d_scores_or_null / d_salmap
+// redirect the outputs of a stand-alone single-frame call.
+int enqueue_pool(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, uint8_t* d_salmap,
+                 const TierLaunch* tier, const float2* const* flow, hipStream_t s) {
+    PoolBatch f = {};
+    for (int i = 0; i < bp.n; ++i) {
+        const LaneLayout& L = c->sl.lane[bp.lane[i]];
+        const LanePtrs lp = c->lane_ptrs(bp.lane[i]);
+        f.cls[i] = c->sc<uint8_t>(L.cls);
+        f.parent[i] = c->sc<uint32_t>(L.parent);
+        f.var[i] = c->sc<uint32_t>(L.var);
+        f.msum[i] = lp.msum + (bp.parity[i] & 1u);
+        f.scores[i] = d_scores_or_null != nullptr ? d_scores_or_null : lp.scores;
+        f.flow[i] = flow != nullptr ? flow[i] : nullptr;
+        f.dp[i] = lp.dp;
+        f.gate[i] = lp.gate;
+    }
+    SALI_TRY(launch_pool(f, bp.n, c->cfg.src_h, c->cfg.src_w, d_salmap, tier, c->cfg.tau_t, c->cfg.theta_r,
+                         &c->lane_ptrs(bp.lane[0]).counters->pool_done, s));
     return SALI_OK;
 }
 
@@ -485,6 +531,7 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->prof[0][0] = c->prof[0][1] = c->prof[1][0] = c->prof[1][1] = nullptr;
     for (int i = 0; i < kRing; ++i) {
         c->ring[i].frame_id = -1;
+        c->ring[i].batch_last = i;
         c->ring[i].stream = nullptr;
         c->ring[i].exp_ready = c->ring[i].done = nullptr;
     }
@@ -543,17 +590,22 @@ int sali_flow_score(sali_ctx* c, const uint8_t* d_prev_rgb, const uint8_t* d_cur
         d_gate_out == nullptr)
         return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int lane = 0, slot_a = kStepSlots, slot_b = kStepSlots + 1;
-    int rc = enqueue_prep(c, d_prev_rgb, lane, false, 0, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, lane, slot_a, s);
-    if (rc == SALI_OK) rc = enqueue_prep(c, d_cur_rgb, lane, false, 0, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, lane, slot_b, s);
+    BatchPlan pa = {}, pb = {};
+    pa.n = pb.n = 1;
+    pa.slot[0] = kStepSlots;
+    pa.prev_slot[0] = -1;
+    pb.slot[0] = kStepSlots + 1;
+    pb.prev_slot[0] = kStepSlots;
+    int rc = enqueue_prep(c, &d_prev_rgb, pa, false, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, pa, s);
+    if (rc == SALI_OK) rc = enqueue_prep(c, &d_cur_rgb, pb, false, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, pb, s);
     if (rc != SALI_OK) return rc;
     const float2* flow = nullptr;
-    rc = enqueue_flow(c, lane, slot_a, slot_b, &flow, s);
+    rc = enqueue_flow(c, pb, &flow, s);
     if (rc != SALI_OK) return rc;
     SALI_TRY(launch_patch_gate(flow, c->cfg.src_h, c->cfg.src_w, c->cfg.tau_t, c->cfg.theta_r, d_patch_motion576,
-                               d_gate_out, &c->lane_ptrs(lane).counters->patch_done, d_flow_uv_or_null, s));
+                               d_gate_out, &c->lane_ptrs(0).counters->patch_done, d_flow_uv_or_null, s));
     return SALI_OK;
 }
 
@@ -561,10 +613,11 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
                        void* stream) {
     if (c == nullptr || d_rgb == nullptr || d_scores576 == nullptr) return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int lane = 0;
-    const unsigned parity = c->lane_uses[lane]++ & 1u;
-    int rc = enqueue_prep(c, d_rgb, lane, true, parity, s);
-    if (rc == SALI_OK) rc = enqueue_pool(c, lane, parity, d_scores576, d_salmap_or_null, nullptr, nullptr, s);
+    BatchPlan bp = {};
+    bp.n = 1;
+    bp.parity[0] = c->lane_uses[0]++ & 1u;
+    int rc = enqueue_prep(c, &d_rgb, bp, true, s);
+    if (rc == SALI_OK) rc = enqueue_pool(c, bp, d_scores576, d_salmap_or_null, nullptr, nullptr, s);
     return rc;
 }
 
@@ -593,50 +646,74 @@ int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8
     return SALI_OK;
 }
 
-int sali_analyze(sali_ctx* c, const uint8_t* d_rgb, int32_t frame_id, void* stream) {
-    if (c == nullptr || d_rgb == nullptr) return SALI_ERR_NULL;
-    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
+int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t first_frame_id, int32_t n_frames,
+                       void* stream) {
+    if (c == nullptr || d_rgb_frames == nullptr) return SALI_ERR_NULL;
+    if (n_frames < 1 || n_frames > kMaxBatch) return SALI_ERR_SHAPE;
+    if (first_frame_id < 0 || (long long)first_frame_id + n_frames > c->cfg.max_frames) return SALI_ERR_SHAPE;
+    for (int i = 0; i < n_frames; ++i)
+        if (d_rgb_frames[i] == nullptr) return SALI_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned n = c->n_analysed;
-    const int lane = (int)(n % kLanes);
-    const int slot = (int)(n % kStepSlots);
-    const unsigned parity = c->lane_uses[lane]++ & 1u;      // alternates per saliency pass in the lane
-    AnalysisRecord& rec = c->ring[n % kRing];
-    const AnalysisRecord* prev = n >= 1 ? &c->ring[(n - 1) % kRing] : nullptr;
+    const unsigned n0 = c->n_analysed;                  // analysis number of the batch's first frame
+    const unsigned n_last = n0 + (unsigned)n_frames - 1u;
+    BatchPlan bp = {};
+    bp.n = n_frames;
+    for (int i = 0; i < n_frames; ++i) {
+        const unsigned n = n0 + (unsigned)i;
+        bp.lane[i] = (int)(n % kLanes);
+        bp.slot[i] = (int)(n % kStepSlots);
+        bp.prev_slot[i] = n >= 1 ? (int)((n - 1) % kStepSlots) : -1;
+        bp.parity[i] = c->lane_uses[bp.lane[i]]++ & 1u;      // alternates per saliency pass in the lane
+    }
+    const AnalysisRecord* prev = n0 >= 1 ? &c->ring[c->ring[(n0 - 1) % kRing].batch_last] : nullptr;
     int rc;
-    // the lane's scratch and the expansion slot were last used by analysis n - kLanes (and read by
-    // the flow of its successor, which finished before it in tier order)
-    if (n >= (unsigned)kLanes) {
-        const AnalysisRecord& old = c->ring[(n - kLanes) % kRing];
+    // A lane's scratch and expansion slot were last used by the analysis kLanes before (the slot
+    // was read last by that one's successor's flow, which finished before it in tier order); tier
+    // order also means the latest of them finishing implies that the others have.
+    if (n_last >= (unsigned)kLanes) {
+        const AnalysisRecord& old = c->ring[c->ring[(n_last - kLanes) % kRing].batch_last];
         rc = wait_unless_same(s, old.stream, old.done);
         if (rc != SALI_OK) return rc;
     }
-    rc = enqueue_prep(c, d_rgb, lane, true, parity, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, lane, slot, s);
+    rc = enqueue_prep(c, d_rgb_frames, bp, true, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, bp, s);
     if (rc != SALI_OK) return rc;
+    // the batch's events live in the ring entry of its last frame
+    AnalysisRecord& rec = c->ring[n_last % kRing];
     SALI_TRY(hipEventRecord(rec.exp_ready, s));
-    const LanePtrs lp = c->lane_ptrs(lane);
-    const float2* flow = nullptr;
+    const float2* flow[kMaxBatch];
     if (prev != nullptr) {
         rc = wait_unless_same(s, prev->stream, prev->exp_ready);
         if (rc != SALI_OK) return rc;
-        rc = enqueue_flow(c, lane, (int)((n - 1) % kStepSlots), slot, &flow, s);
-        if (rc != SALI_OK) return rc;
+    }
+    rc = enqueue_flow(c, bp, flow, s);
+    if (rc != SALI_OK) return rc;
+    if (prev != nullptr) {
         // tiers are handed out in frame order: the cursors must have seen the previous frame
         rc = wait_unless_same(s, prev->stream, prev->done);
         if (rc != SALI_OK) return rc;
     }
-    // per-patch motion, gate, pooling, tiers: one launch (first frame: no flow, never redundant)
-    const TierLaunch tl = tier_launch(c, frame_id);
-    rc = enqueue_pool(c, lane, parity, lp.scores, nullptr, &tl, flow, s);
+    // per-patch motion, gate, pooling, tiers: one launch
+    const TierLaunch tl = tier_launch(c, first_frame_id);
+    rc = enqueue_pool(c, bp, nullptr, nullptr, &tl, flow, s);
     if (rc != SALI_OK) return rc;
     SALI_TRY(hipEventRecord(rec.done, s));
     for (int i = 0; i < kRing; ++i)
-        if (c->ring[i].frame_id == frame_id) c->ring[i].frame_id = -1;      // an older analysis under the same id
-    rec.frame_id = frame_id;
-    rec.stream = s;
-    c->n_analysed = n + 1;
+        if (c->ring[i].frame_id >= first_frame_id && c->ring[i].frame_id < first_frame_id + n_frames)
+            c->ring[i].frame_id = -1;      // an older analysis under the same id
+    for (int i = 0; i < n_frames; ++i) {
+        AnalysisRecord& r = c->ring[(n0 + (unsigned)i) % kRing];
+        r.frame_id = first_frame_id + i;
+        r.stream = s;
+        r.batch_last = (int)(n_last % kRing);
+    }
+    c->n_analysed = n_last + 1u;
     return SALI_OK;
+}
+
+int sali_analyze(sali_ctx* c, const uint8_t* d_rgb, int32_t frame_id, void* stream) {
+    if (c == nullptr || d_rgb == nullptr) return SALI_ERR_NULL;
+    return sali_analyze_batch(c, &d_rgb, frame_id, 1, stream);
 }
 
 int sali_store(sali_ctx* c, const void* d_kv, int32_t frame_id, void* stream) {
@@ -648,7 +725,7 @@ int sali_store(sali_ctx* c, const void* d_kv, int32_t frame_id, void* stream) {
     for (int i = 0; i < kRing; ++i)
         if (c->ring[i].frame_id == frame_id) rec = &c->ring[i];
     if (rec == nullptr) return SALI_ERR_STATE;      // not analysed (or too long ago)
-    const int rc = wait_unless_same(s, rec->stream, rec->done);
+    const int rc = wait_unless_same(s, rec->stream, c->ring[rec->batch_last].done);
     if (rc != SALI_OK) return rc;
     return enqueue_pack(c, d_kv, frame_id, s);
 }

@@ -163,9 +163,12 @@ __device__ __forceinline__ void pyr_level_lds(const float* src, int o_src_y, int
 }
 }  // namespace
 
-__global__ __launch_bounds__(256) void k_expand(const uint8_t* __restrict__ y8, LevelGeom g, int t1, int t2, int tx0,
-                                                int tx1, int tx2, FlowWeights fw, float4* __restrict__ A_out,
-                                                float2* __restrict__ b_out) {
+__global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int t1, int t2, int tx0, int tx1, int tx2,
+                                                FlowWeights fw) {
+    // blockIdx.y = frame of the batch
+    const uint8_t* __restrict__ y8 = f.y8[blockIdx.y];
+    float4* __restrict__ A_out = f.A[blockIdx.y];
+    float2* __restrict__ b_out = f.b[blockIdx.y];
     __shared__ float s_q[kEQ * (kEQ + 1)];          // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
     __shared__ float s_p[kEP * (kEP + 1)];          // level-1 patch of a level-2 block
     __shared__ float s_f[kER][kER + 1];
@@ -290,10 +293,15 @@ __device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int 
 // T = tile side: 32 for large levels, 16 for small ones (more blocks and fewer cells per thread:
 // the small levels are latency-bound, not throughput-bound).
 template <int T>
-__global__ __launch_bounds__(256) void k_flow_iter(const float4* __restrict__ A1, const float2* __restrict__ b1,
-                                                   const float4* __restrict__ A2, const float2* __restrict__ b2,
-                                                   const float2* __restrict__ d_in, float2* __restrict__ d_out,
-                                                   int h, int w, int ch, int cw, int prior_mode, FlowWeights fw) {
+__global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_off, int h, int w, int ch, int cw,
+                                                   int prior_mode, FlowWeights fw) {
+    // blockIdx.z = frame of the batch
+    const float4* __restrict__ A1 = f.A1[blockIdx.z] + level_off;
+    const float2* __restrict__ b1 = f.b1[blockIdx.z] + level_off;
+    const float4* __restrict__ A2 = f.A2[blockIdx.z] + level_off;
+    const float2* __restrict__ b2 = f.b2[blockIdx.z] + level_off;
+    const float2* __restrict__ d_in = f.d_in[blockIdx.z];
+    float2* __restrict__ d_out = f.d_out[blockIdx.z];
     constexpr int R = T + 2 * kWinR;
     __shared__ float s_in[5][R][R + 1];
     __shared__ float s_row[5][R][T];
@@ -447,34 +455,32 @@ hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, 
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const uint8_t* d_y8, LevelGeom g, FlowWeights fw, float4* d_A, float2* d_b, hipStream_t s) {
+hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s) {
     // up to three levels, 16x16 tiles, one launch
     int tx[3] = {1, 1, 1}, start[4] = {0, 0, 0, 0};
     for (int l = 0; l < 3; ++l) {
-        int n = 0;
+        int tiles = 0;
         if (l < g.levels) {
             tx[l] = (g.w[l] + kET - 1) / kET;
-            n = tx[l] * ((g.h[l] + kET - 1) / kET);
+            tiles = tx[l] * ((g.h[l] + kET - 1) / kET);
         }
-        start[l + 1] = start[l] + n;
+        start[l + 1] = start[l] + tiles;
     }
-    hipLaunchKernelGGL(k_expand, dim3(start[3]), dim3(256), 0, s, d_y8, g, start[1], start[2], tx[0], tx[1], tx[2], fw,
-                       d_A, d_b);
+    hipLaunchKernelGGL(k_expand, dim3(start[3], n), dim3(256), 0, s, f, g, start[1], start[2], tx[0], tx[1], tx[2], fw);
     return hipGetLastError();
 }
 
-hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2, const float2* b2,
-                            const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
-                            FlowWeights fw, hipStream_t s) {
+hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
+                            int prior_mode, FlowWeights fw, hipStream_t s) {
     // small levels: 16x16 tiles so that the level spreads over many compute units
     if ((long long)((w + 31) / 32) * ((h + 31) / 32) < 1024) {
-        dim3 grid((w + 15) / 16, (h + 15) / 16);
-        hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw,
-                           prior_mode, fw);
+        dim3 grid((w + 15) / 16, (h + 15) / 16, n);
+        hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, f, (long long)level_off, h, w, ch, cw, prior_mode,
+                           fw);
     } else {
-        dim3 grid((w + 31) / 32, (h + 31) / 32);
-        hipLaunchKernelGGL(k_flow_iter<32>, grid, dim3(256), 0, s, A1, b1, A2, b2, d_in, d_out, h, w, ch, cw,
-                           prior_mode, fw);
+        dim3 grid((w + 31) / 32, (h + 31) / 32, n);
+        hipLaunchKernelGGL(k_flow_iter<32>, grid, dim3(256), 0, s, f, (long long)level_off, h, w, ch, cw, prior_mode,
+                           fw);
     }
     return hipGetLastError();
 }

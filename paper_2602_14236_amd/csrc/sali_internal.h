@@ -17,6 +17,7 @@ constexpr int kGroup = 32;                  // quantisation group along head_dim
 constexpr int kGroupsPerRow = kHeadDim / kGroup;
 constexpr int kMaxLevels = 6;
 constexpr int kMaxIters = 8;
+constexpr int kMaxBatch = SALI_MAX_BATCH;   // frames analysed by one set of launches (blockIdx.z / .y)
 
 // flow constants (polynomial expansion 7x7 sigma 1.5; aggregation window 11x11 sigma 2.5;
 // prior-centred ridge term lambda = kLamAbs + kLamRel * trace(G) / 2)
@@ -53,7 +54,8 @@ struct TierParams {
     int32_t k16, k8, k4;
 };
 
-// everything the tier / compaction step needs when it is fused into another kernel
+// everything the tier / compaction step needs when it is fused into another kernel; in a batched
+// launch frame i of the batch has id frame_id + i and its tables follow at i * kTokens
 struct TierLaunch {
     TierParams tp;
     int32_t frame_id;
@@ -72,6 +74,43 @@ struct LevelGeom {
     int32_t tiles_x[kMaxLevels];
     int32_t tile_start[kMaxLevels + 1];   // first block index of each level in a fused launch
     int32_t levels;
+};
+
+// Per-frame operands of the batched image kernels: entry i belongs to frame i of the batch.
+struct PrepBatch {
+    const uint8_t* rgb[kMaxBatch];
+    uint8_t* y8[kMaxBatch];
+    uint8_t* cls[kMaxBatch];
+    uint32_t* var[kMaxBatch];
+    uint32_t* parent[kMaxBatch];
+    unsigned long long* msum_acc[kMaxBatch];      // frame sum of the colour variance, accumulated
+    unsigned long long* msum_clear[kMaxBatch];    // the accumulator of the lane's next use, cleared
+};
+
+struct ExpandBatch {
+    const uint8_t* y8[kMaxBatch];
+    float4* A[kMaxBatch];
+    float2* b[kMaxBatch];
+};
+
+struct FlowBatch {                                // expansions at level 0; the launcher adds the level offset
+    const float4* A1[kMaxBatch];
+    const float2* b1[kMaxBatch];
+    const float4* A2[kMaxBatch];
+    const float2* b2[kMaxBatch];
+    const float2* d_in[kMaxBatch];
+    float2* d_out[kMaxBatch];
+};
+
+struct PoolBatch {
+    const uint8_t* cls[kMaxBatch];
+    const uint32_t* parent[kMaxBatch];
+    const uint32_t* var[kMaxBatch];
+    const unsigned long long* msum[kMaxBatch];
+    float* scores[kMaxBatch];
+    const float2* flow[kMaxBatch];                // NULL: no predecessor (never redundant)
+    float* dp[kMaxBatch];
+    sali_gate* gate[kMaxBatch];
 };
 
 struct FlowWeights {
@@ -94,24 +133,24 @@ hipError_t launch_unpack(const sali_frame_row* d_rows, int frame_id, const uint1
                          void* d_out, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes, hipStream_t s);
 
 // saliency_kernels.hip
-hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
-                       uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
-                       unsigned long long* d_msum_clear, const uint16_t* d_lut, int lo2, int hi2, hipStream_t s);
-hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, hipStream_t s);
-hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
-                       const unsigned long long* d_msum, int h, int w, float* d_scores, uint8_t* d_salmap_or_null,
-                       const TierLaunch* tier_or_null, const float2* d_flow_or_null, float tau_t, float theta_r,
-                       float* d_dp, sali_gate* d_gate, uint32_t* d_done_counter, hipStream_t s);
+// n = frames in the batch (1..kMaxBatch); with_saliency = false converts to gray only (n must be 1)
+hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool with_saliency, const uint16_t* d_lut, int lo2,
+                       int hi2, hipStream_t s);
+hipError_t launch_union(const PrepBatch& f, int n, int h, int w, hipStream_t s);
+// d_salmap_or_null applies to frame 0 (stand-alone call); with `tier` the last block also evaluates
+// the gate and assigns tiers for the n frames in order
+hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salmap_or_null,
+                       const TierLaunch* tier_or_null, float tau_t, float theta_r, uint32_t* d_done_counter,
+                       hipStream_t s);
 
 // flow_kernels.hip
 hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
                            int dh, int dw, hipStream_t s);
 hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
                           float2* d_b, hipStream_t s);
-hipError_t launch_expand(const uint8_t* d_y8, LevelGeom g, FlowWeights fw, float4* d_A, float2* d_b, hipStream_t s);
-hipError_t launch_flow_iter(const float4* A1, const float2* b1, const float4* A2, const float2* b2,
-                            const float2* d_in, float2* d_out, int h, int w, int ch, int cw, int prior_mode,
-                            FlowWeights fw, hipStream_t s);
+hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
+hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
+                            int prior_mode, FlowWeights fw, hipStream_t s);
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,
                              sali_gate* d_gate, uint32_t* d_done_counter, float* d_flow_uv_or_null, hipStream_t s);
 

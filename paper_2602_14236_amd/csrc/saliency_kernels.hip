@@ -95,12 +95,16 @@ constexpr int kPrepThreads = 256;
 constexpr int kPrepPx = kTile * kTile / kPrepThreads;                          // 4
 constexpr int kPrepCells = (kReg * kReg + kPrepThreads - 1) / kPrepThreads;   // 7
 
-__global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict__ rgb, int h, int w,
-                                                       uint8_t* __restrict__ y8_out, uint8_t* __restrict__ cls_out,
-                                                       uint32_t* __restrict__ var_out,
-                                                       uint32_t* __restrict__ parent_out,
-                                                       unsigned long long* msum_acc, unsigned long long* msum_clear,
+__global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w,
                                                        const uint32_t* __restrict__ lut_words, int lo2, int hi2) {
+    // blockIdx.z = frame of the batch
+    const uint8_t* __restrict__ rgb = f.rgb[blockIdx.z];
+    uint8_t* __restrict__ y8_out = f.y8[blockIdx.z];
+    uint8_t* __restrict__ cls_out = f.cls[blockIdx.z];
+    uint32_t* __restrict__ var_out = f.var[blockIdx.z];
+    uint32_t* __restrict__ parent_out = f.parent[blockIdx.z];
+    unsigned long long* msum_acc = f.msum_acc[blockIdx.z];
+    unsigned long long* msum_clear = f.msum_clear[blockIdx.z];
     __shared__ uint32_t s_lut[(256 + 4096) / 2];          // lin[256] then fl[4096], 16-bit entries
     __shared__ uint8_t s_y[kReg][kReg];
     __shared__ uint8_t s_b[kRegB][kRegB];
@@ -332,7 +336,9 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const uint8_t* __restrict
 }
 
 // hysteresis, cross-tile part: only pairs of neighbours that lie in different k_prep tiles
-__global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, uint32_t* parent, int h, int w) {
+__global__ __launch_bounds__(256) void k_union(PrepBatch f, int h, int w) {
+    const uint8_t* __restrict__ cls = f.cls[blockIdx.z];
+    uint32_t* parent = f.parent[blockIdx.z];
     const int x = blockIdx.x * 64 + (threadIdx.x & 63);
     const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (x >= w || y >= h) return;
@@ -363,14 +369,9 @@ __global__ __launch_bounds__(256) void k_union(const uint8_t* __restrict__ cls, 
 // row of a redundant frame or assigns tiers and compaction indices.  So one launch replaces three,
 // with one device-scope fence per block.
 template <int kWaves>
-__global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict__ cls, const uint32_t* __restrict__ parent,
-                                                  const uint32_t* __restrict__ var, const unsigned long long* msum,
-                                                  int h, int w, float* scores, uint8_t* __restrict__ salmap,
-                                                  int do_tier, const float2* __restrict__ flow, float tau_t,
-                                                  float theta_r, float* dp_out, sali_gate* gate_out, TierParams tp,
-                                                  int frame_id, sali_frame_row* rows, uint8_t* tier_out,
-                                                  uint16_t* slot_out, uint16_t* order_out, Cursors* cur, int cap16,
-                                                  int cap8, int cap4, uint32_t* done_counter) {
+__global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w, uint8_t* __restrict__ salmap,
+                                                  int do_tier, float tau_t, float theta_r, TierLaunch tl,
+                                                  uint32_t* done_counter) {
     static_assert(kTierThreads == 256, "four waves, one patch each");
     static_assert(kWaves == 1 || kWaves == 4, "");
     __shared__ TierShared sh;
@@ -379,129 +380,137 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(const uint8_t* __restrict
     __shared__ float s_pm[kTierThreads / 64];
     __shared__ int s_last;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int token = kWaves == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
-    const int pr = token / kGrid, pc = token % kGrid;
-    const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
-    const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
-    const int pw = xb - xa, area = pw * (yb - ya);
-    const unsigned long long m = *msum;
-    const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
-    uint32_t q = 0;
-    float mag = 0.0f;
-    for (int p = (kWaves == 1 ? lane : (int)threadIdx.x); p < area; p += 64 * kWaves) {
-        const int y = ya + p / pw, x = xa + p % pw;
-        const size_t gi = (size_t)y * w + x;
-        const int c = cls[gi];
-        uint32_t e = 0;
-        if (c == 2) e = 1;
-        else if (c == 1) e = (uf_find_settled(parent, (uint32_t)gi | kWeakBit) & kWeakBit) ? 0u : 1u;
-        const uint32_t v = var[gi];
-        const uint32_t cm = ((unsigned long long)v * hw > m && v >= kVMin) ? 1u : 0u;
-        q += e + cm;
-        if (salmap != nullptr) salmap[gi] = (uint8_t)(e + cm);
-        if (flow != nullptr) {
-            const float2 d = flow[gi];
-            mag += d.x * d.x + d.y * d.y;
+    {
+        // blockIdx.y = frame of the batch
+        const uint8_t* __restrict__ cls = f.cls[blockIdx.y];
+        const uint32_t* __restrict__ parent = f.parent[blockIdx.y];
+        const uint32_t* __restrict__ var = f.var[blockIdx.y];
+        const float2* __restrict__ flow = f.flow[blockIdx.y];
+        const int token = kWaves == 1 ? blockIdx.x * 4 + wave : blockIdx.x;
+        const int pr = token / kGrid, pc = token % kGrid;
+        const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
+        const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
+        const int pw = xb - xa, area = pw * (yb - ya);
+        const unsigned long long m = *f.msum[blockIdx.y];
+        const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
+        uint32_t q = 0;
+        float mag = 0.0f;
+        for (int p = (kWaves == 1 ? lane : (int)threadIdx.x); p < area; p += 64 * kWaves) {
+            const int y = ya + p / pw, x = xa + p % pw;
+            const size_t gi = (size_t)y * w + x;
+            const int c = cls[gi];
+            uint32_t e = 0;
+            if (c == 2) e = 1;
+            else if (c == 1) e = (uf_find_settled(parent, (uint32_t)gi | kWeakBit) & kWeakBit) ? 0u : 1u;
+            const uint32_t v = var[gi];
+            const uint32_t cm = ((unsigned long long)v * hw > m && v >= kVMin) ? 1u : 0u;
+            q += e + cm;
+            if (salmap != nullptr) salmap[gi] = (uint8_t)(e + cm);
+            if (flow != nullptr) {
+                const float2 d = flow[gi];
+                mag += d.x * d.x + d.y * d.y;
+            }
         }
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        q += __shfl_down(q, off);
-        mag += __shfl_down(mag, off);
-    }
-    if (kWaves == 4) {
-        if (lane == 0) {
-            s_pq[wave] = q;
-            s_pm[wave] = mag;
+        for (int off = 32; off > 0; off >>= 1) {
+            q += __shfl_down(q, off);
+            mag += __shfl_down(mag, off);
         }
-        __syncthreads();
-        q = s_pq[0] + s_pq[1] + s_pq[2] + s_pq[3];
-        mag = (s_pm[0] + s_pm[1]) + (s_pm[2] + s_pm[3]);
-    }
-    if (lane == 0 && (kWaves == 1 || wave == 0)) {
-        const uint32_t s_fix = (uint32_t)(((unsigned long long)q << 15) / (unsigned long long)area);
-        const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
-        __hip_atomic_store(scores + token, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (do_tier)
-            __hip_atomic_store(dp_out + token, flow != nullptr ? sqrtf(mag / (float)area) : 0.0f, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+        if (kWaves == 4) {
+            if (lane == 0) {
+                s_pq[wave] = q;
+                s_pm[wave] = mag;
+            }
+            __syncthreads();
+            q = s_pq[0] + s_pq[1] + s_pq[2] + s_pq[3];
+            mag = (s_pm[0] + s_pm[1]) + (s_pm[2] + s_pm[3]);
+        }
+        if (lane == 0 && (kWaves == 1 || wave == 0)) {
+            const uint32_t s_fix = (uint32_t)(((unsigned long long)q << 15) / (unsigned long long)area);
+            const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
+            __hip_atomic_store(f.scores[blockIdx.y] + token, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (do_tier)
+                __hip_atomic_store(f.dp[blockIdx.y] + token, flow != nullptr ? sqrtf(mag / (float)area) : 0.0f,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         int last = 0;
         if (do_tier) {
             __threadfence();
-            last = (atomicAdd(done_counter, 1u) == gridDim.x - 1u) ? 1 : 0;
+            last = (atomicAdd(done_counter, 1u) == gridDim.x * gridDim.y - 1u) ? 1 : 0;
         }
         s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; the first
-    // frame of a sequence (no flow) is never redundant
-    int n = 0;
-    if (flow != nullptr) {
-        for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
-            const float v = __hip_atomic_load(dp_out + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            n += (v < tau_t) ? 1 : 0;
+    if (threadIdx.x == 0) *done_counter = 0u;       // ready for the next launch
+    // The frames of the batch in video order (tiers and pool cursors are handed out in that order).
+    // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; a frame
+    // without predecessor (no flow) is never redundant
+    for (int b = 0; b < (int)gridDim.y; ++b) {
+        const bool have_flow = f.flow[b] != nullptr;
+        int n = 0;
+        if (have_flow) {
+            for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
+                const float v = __hip_atomic_load(f.dp[b] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                n += (v < tau_t) ? 1 : 0;
+            }
         }
+        for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
+        __syncthreads();        // the previous frame's reads of s_cnt and of the tier scratch are over
+        if (lane == 0) s_cnt[wave] = n;
+        __syncthreads();
+        const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        const float r = (float)n_static / (float)kTokens;
+        const bool redundant = have_flow && r > theta_r;
+        if (threadIdx.x == 0) {
+            sali_gate gt;
+            gt.n_static = n_static;
+            gt.r_frame = have_flow ? r : 0.0f;
+            gt.redundant = redundant ? 1 : 0;
+            gt.reserved = 0;
+            *f.gate[b] = gt;
+        }
+        tier_body(sh, f.scores[b], redundant, tl.tp, tl.frame_id + b, tl.rows, tl.tier + (size_t)b * kTokens,
+                  tl.slot + (size_t)b * kTokens, tl.order + (size_t)b * kTokens, tl.cur, tl.cap16, tl.cap8, tl.cap4);
     }
-    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
-    if (lane == 0) s_cnt[wave] = n;
-    __syncthreads();
-    const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-    const float r = (float)n_static / (float)kTokens;
-    const bool redundant = flow != nullptr && r > theta_r;
-    if (threadIdx.x == 0) {
-        sali_gate gt;
-        gt.n_static = n_static;
-        gt.r_frame = flow != nullptr ? r : 0.0f;
-        gt.redundant = redundant ? 1 : 0;
-        gt.reserved = 0;
-        *gate_out = gt;
-        *done_counter = 0u;       // ready for the next launch
-    }
-    tier_body(sh, scores, redundant, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4);
 }
 
 // ---------------------------------------------------------------------------------------------
-hipError_t launch_prep(const uint8_t* d_rgb, int h, int w, bool with_saliency, uint8_t* d_y8, uint8_t* d_cls,
-                       uint32_t* d_var, uint32_t* d_parent, unsigned long long* d_msum_acc,
-                       unsigned long long* d_msum_clear, const uint16_t* d_lut, int lo2, int hi2, hipStream_t s) {
+hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool with_saliency, const uint16_t* d_lut, int lo2,
+                       int hi2, hipStream_t s) {
     if (!with_saliency) {
-        const int n = h * w;
-        hipLaunchKernelGGL(k_gray, dim3((n + 255) / 256), dim3(256), 0, s, d_rgb, n, d_y8);
+        const int px = h * w;
+        hipLaunchKernelGGL(k_gray, dim3((px + 255) / 256), dim3(256), 0, s, f.rgb[0], px, f.y8[0]);
         return hipGetLastError();
     }
-    dim3 grid((w + kTile - 1) / kTile, (h + kTile - 1) / kTile);
-    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, d_rgb, h, w, d_y8, d_cls, d_var, d_parent, d_msum_acc,
-                       d_msum_clear, reinterpret_cast<const uint32_t*>(d_lut), lo2, hi2);
+    dim3 grid((w + kTile - 1) / kTile, (h + kTile - 1) / kTile, n);
+    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, f, h, w, reinterpret_cast<const uint32_t*>(d_lut), lo2,
+                       hi2);
     return hipGetLastError();
 }
 
-hipError_t launch_union(const uint8_t* d_cls, uint32_t* d_parent, int h, int w, hipStream_t s) {
-    dim3 grid((w + 63) / 64, (h + 3) / 4);
-    hipLaunchKernelGGL(k_union, grid, dim3(256), 0, s, d_cls, d_parent, h, w);
+hipError_t launch_union(const PrepBatch& f, int n, int h, int w, hipStream_t s) {
+    dim3 grid((w + 63) / 64, (h + 3) / 4, n);
+    hipLaunchKernelGGL(k_union, grid, dim3(256), 0, s, f, h, w);
     return hipGetLastError();
 }
 
-hipError_t launch_pool(const uint8_t* d_cls, const uint32_t* d_parent, const uint32_t* d_var,
-                       const unsigned long long* d_msum, int h, int w, float* d_scores, uint8_t* d_salmap_or_null,
-                       const TierLaunch* tier_or_null, const float2* d_flow_or_null, float tau_t, float theta_r,
-                       float* d_dp, sali_gate* d_gate, uint32_t* d_done_counter, hipStream_t s) {
+hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salmap_or_null,
+                       const TierLaunch* tier_or_null, float tau_t, float theta_r, uint32_t* d_done_counter,
+                       hipStream_t s) {
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
+    const int do_tier = tier_or_null != nullptr ? 1 : 0;
     // patches of up to 1024 pixels: one wave each (a quarter of the blocks and of the fences)
     if ((long long)h * w <= 1024ll * kTokens)
-        hipLaunchKernelGGL(k_pool<1>, dim3(kTokens / 4), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
-                           d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r,
-                           d_dp, d_gate, t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8,
-                           t.cap4, d_done_counter);
+        hipLaunchKernelGGL(k_pool<1>, dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null,
+                           do_tier, tau_t, theta_r, t, d_done_counter);
     else
-        hipLaunchKernelGGL(k_pool<4>, dim3(kTokens), dim3(kTierThreads), 0, s, d_cls, d_parent, d_var, d_msum, h, w,
-                           d_scores, d_salmap_or_null, tier_or_null != nullptr ? 1 : 0, d_flow_or_null, tau_t, theta_r,
-                           d_dp, d_gate, t.tp, t.frame_id, t.rows, t.tier, t.slot, t.order, t.cur, t.cap16, t.cap8,
-                           t.cap4, d_done_counter);
+        hipLaunchKernelGGL(k_pool<4>, dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null, do_tier,
+                           tau_t, theta_r, t, d_done_counter);
     return hipGetLastError();
 }
 

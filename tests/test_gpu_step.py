@@ -167,3 +167,49 @@ def test_pipelined_step_matches_oracle(lookahead):
         ctx.store(kvs[0], 3, s_kv)
     assert e.value.code == -5
     ctx.close()
+
+
+def test_batched_analysis_matches_oracle():
+    """sali_analyze_batch (the frame is a grid dimension of every image kernel) with batches of mixed
+    sizes on two alternating streams, more frames than scratch copies, must leave exactly the state
+    the frame-by-frame path leaves: scene cuts, duplicate runs and noise frames included."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[5]
+    n = 36
+    v = synth.video(5, n)
+    p = workload_params(wl, frames=n, n_layers=1, n_heads=1)
+    scale = synth.kv_channel_scale(wl, 1, 1)
+    rgbs = [torch.from_numpy(v.frame(t)).cuda() for t in range(n)]
+    kvs = [synth.kv_frame(wl, t, device="cuda", n_layers=1, n_heads=1, scale=scale) for t in range(n)]
+    orc = SaliCacheOracle(oracle_config(p))
+    for t in range(n):
+        orc.step(v.frame(t), kvs[t].cpu().numpy(), t)
+    print("oracle done", flush=True)
+    assert binding.MAX_BATCH == 8
+    sizes = [8, 8, 4, 3, 1, 8, 4]
+    assert sum(sizes) == n
+    ctx = binding.SaliContext(lib_config(p))
+    s_imgs = [torch.cuda.Stream(), torch.cuda.Stream()]
+    s_kv = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    first = 0
+    pending = []                             # frames analysed but not yet stored
+    for b, size in enumerate(sizes):
+        print(f"batch {b}: frames {first}..{first + size - 1}", flush=True)
+        ctx.analyze_batch(rgbs[first:first + size], first, s_imgs[b % 2])
+        for t in pending:
+            ctx.store(kvs[t], t, s_kv)
+        pending = list(range(first, first + size))
+        first += size
+    for t in pending:
+        ctx.store(kvs[t], t, s_kv)
+    torch.cuda.synchronize()
+    _compare_all(ctx, orc, range(n))
+    # argument checks
+    with pytest.raises(binding.SaliError) as e:
+        ctx.analyze_batch(rgbs[:9], 0, s_imgs[0])
+    assert e.value.code == -2
+    with pytest.raises(binding.SaliError) as e:
+        ctx.analyze_batch(rgbs[:4], n - 2, s_imgs[0])
+    assert e.value.code == -2
+    ctx.close()
