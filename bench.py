@@ -114,7 +114,10 @@ def main():
     scale = synth.kv_channel_scale(wl, n_layers)
     rgbs = [torch.from_numpy(video.frame(t)).to(dev) for t in range(n_src)]
     kvs = [synth.kv_frame(wl, t, device=dev, n_layers=n_layers, scale=scale) for t in range(n_src)]
-    out = torch.empty((n_layers, 2, wl.n_heads, 576, 128), dtype=torch.float16, device=dev)
+    BATCH = int(os.environ.get("SALI_BENCH_BATCH", "4"))
+    outs = [torch.empty((n_layers, 2, wl.n_heads, 576, 128), dtype=torch.float16, device=dev)
+            for _ in range(max(1, BATCH))]
+    out = outs[0]
     torch.cuda.synchronize()
 
     def make_events(n):
@@ -125,14 +128,37 @@ def main():
         torch.cuda.synchronize()
         return evs
 
-    LOOKAHEAD = int(os.environ.get("SALI_BENCH_LOOKAHEAD", "2"))   # image-side analyses in flight ahead of the K/V store (<= SALI_ANALYSIS_LANES)
-    s_imgs = [torch.cuda.Stream() for _ in range(LOOKAHEAD)]
+    # image-side analysis runs ahead of the K/V store: BATCH frames per sali_analyze_batch call, the
+    # next batch being analysed on an image stream while the current one is stored on s_kv
+    # (BATCH = 1: sali_step_pipelined with LOOKAHEAD single-frame analyses in flight)
+    LOOKAHEAD = int(os.environ.get("SALI_BENCH_LOOKAHEAD", "2"))
+    AHEAD = int(os.environ.get("SALI_BENCH_AHEAD", "1"))          # batches analysed ahead of the store
+    s_imgs = [torch.cuda.Stream() for _ in range(max(2, LOOKAHEAD, AHEAD))]
     s_kv = torch.cuda.Stream()
 
     def run(n, with_unpack, pack_events=None, unpack_events=None):
-        """sali_step_pipelined: frames t+1 .. t+LOOKAHEAD are analysed on the image streams while
-        frame t is stored (and read back) on s_kv.  Same kernels and same results as sali_step
-        frame by frame."""
+        """Frames are analysed ahead on the image streams while frame t is stored (and read back)
+        on s_kv.  Same kernels and same results as sali_step frame by frame."""
+        def analyze(b):
+            frames = range(b * BATCH, min(n, (b + 1) * BATCH))
+            if len(frames) > 0:
+                ctx.analyze_batch([rgbs[t % n_src] for t in frames], frames[0], s_imgs[b % len(s_imgs)])
+
+        if BATCH > 1:
+            # batch b + 1 is analysed while batch b is stored and read back, each in one launch
+            for b in range(AHEAD):
+                analyze(b)
+            for b in range((n + BATCH - 1) // BATCH):
+                frames = range(b * BATCH, min(n, (b + 1) * BATCH))
+                analyze(b + AHEAD)
+                if pack_events is not None:
+                    ctx.set_profile_events(0, *pack_events[b])
+                ctx.store_batch([kvs[t % n_src] for t in frames], frames[0], s_kv)
+                if with_unpack:
+                    if unpack_events is not None:
+                        ctx.set_profile_events(1, *unpack_events[b])
+                    ctx.kv_decompress_batch(frames[0], outs[:len(frames)], None, s_kv)
+            return
         for t in range(min(LOOKAHEAD, n)):
             ctx.step_pipelined(rgbs[t % n_src], t, None, -1, s_imgs[t % LOOKAHEAD], s_kv)
         for t in range(n):
@@ -177,7 +203,8 @@ def main():
     # (recorded by the library on the launch stream).  Kept out of the region above because each
     # event record costs several microseconds of stream time.
     ctx.reset()
-    pack_ev, unpack_ev = make_events(steps), make_events(steps)
+    n_launch = (steps + BATCH - 1) // BATCH if BATCH > 1 else steps      # launches of each K/V kernel
+    pack_ev, unpack_ev = make_events(n_launch), make_events(n_launch)
     torch.cuda.synchronize()
     run(steps, True, pack_ev, unpack_ev)
     torch.cuda.synchronize()
@@ -230,16 +257,20 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "frames": steps, "source": f"{wl.width}x{wl.height}",
                    "kv_shape": [n_layers, 2, wl.n_heads, 576, 128], "tier_mode": wl.tier_mode,
-                   "k": [wl.k_fp16, wl.k_int8, wl.k_int4], "step": f"sali_step_pipelined (image analysis runs {LOOKAHEAD} frames ahead of the K/V store) + sali_kv_decompress",
+                   "k": [wl.k_fp16, wl.k_int8, wl.k_int4], "step": (f"sali_analyze_batch ({BATCH} frames per call, {AHEAD} batch(es) ahead of the K/V side) + sali_store_batch"
+                            if BATCH > 1 else
+                            f"sali_step_pipelined (image analysis runs {LOOKAHEAD} frames ahead of the K/V store)")
+                   + (" + sali_kv_decompress_batch" if BATCH > 1 else " + sali_kv_decompress"),
                    "stored_frames": n_stored, "status_word": status},
         "roofline": {"bound": "hbm", "kernel": "k_pack", "achieved": pack_gbps, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": pack_gbps / (HBM_PEAK / 1e9), "traffic": traffic,
-                     "avg_launch_us": pack_s / steps * 1e6, "algorithmic_bytes_per_launch": pack_b / steps,
+                     "avg_launch_us": pack_s / n_launch * 1e6, "algorithmic_bytes_per_launch": pack_b / n_launch,
+                     "frames_per_launch": max(1, BATCH),
                      "timing": "HIP events around each k_pack launch, second pass over the same steps"},
         "kv_compress_gbps": pack_gbps,
         "kv_compress_pct_of_hbm_peak": 100.0 * pack_gbps / (HBM_PEAK / 1e9),
         "kv_decompress_gbps": unpack_gbps,
-        "kv_decompress_avg_launch_us": unpack_s / steps * 1e6,
+        "kv_decompress_avg_launch_us": unpack_s / n_launch * 1e6,
         "step_hbm_frac": (img_b + pack_b + unpack_b) / elapsed / HBM_PEAK,
         "host_enqueue_us_per_step": host_enqueue[("run", steps, True)] / steps * 1e6,
     }

@@ -214,6 +214,21 @@ int sali_analyze_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, int32_
                        void* stream);
 int sali_store(sali_ctx* ctx, const void* d_kv_fp16, int32_t frame_id, void* stream);
 
+/* The K/V side in batches, for the same two reasons.  Frame i of a call has id first_frame_id + i;
+ * the pointer arrays are HOST arrays of n_frames (1..SALI_MAX_BATCH) device pointers (each K/V
+ * buffer dense fp16 [n_layers][2][n_heads][576][128], 16-byte aligned), read before the call
+ * returns.  One launch each; results identical to n_frames single calls.
+ *   sali_store_batch          packs the frames according to their rows (all must have been analysed)
+ *   sali_kv_decompress_batch  dequantise-on-read of n_frames frames; d_valid_or_null, if given,
+ *                             receives n_frames * 576 bytes (1 = token present)
+ *   sali_step_batch           sali_analyze_batch followed by sali_store_batch on one stream */
+int sali_store_batch(sali_ctx* ctx, const void* const* d_kv_frames, int32_t first_frame_id, int32_t n_frames,
+                     void* stream);
+int sali_kv_decompress_batch(sali_ctx* ctx, int32_t first_frame_id, int32_t n_frames,
+                             void* const* d_kv_fp16_out_frames, uint8_t* d_valid_or_null, void* stream);
+int sali_step_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, const void* const* d_kv_frames,
+                    int32_t first_frame_id, int32_t n_frames, void* stream);
+
 /* One loop body of Algorithm 1 with look-ahead on caller-owned streams: analyses a later
  * frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
  * `image_stream` and stores the K/V of the already analysed frame `frame_id` (d_kv, may be NULL

@@ -82,6 +82,11 @@ EXPORTS = {
     "sali_analyze": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sali_analyze_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_void_p]),
     "sali_store": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sali_store_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_void_p]),
+    "sali_kv_decompress_batch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.c_void_p,
+                                           C.c_void_p]),
+    "sali_step_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
+                                  C.c_void_p]),
     "sali_step_pipelined": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p]),
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
@@ -124,6 +129,11 @@ def _check(code: int, what: str):
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr_array(tensors):
+    """Host array of device pointers (the batched entry points read it before they return)."""
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -217,9 +227,25 @@ class SaliContext:
 
     def analyze_batch(self, rgb_frames, first_frame_id: int, stream: Optional[torch.cuda.Stream] = None):
         s = _stream() if stream is None else stream.cuda_stream
-        ptrs = (C.c_void_p * len(rgb_frames))(*[f.data_ptr() for f in rgb_frames])
-        _check(self.lib.sali_analyze_batch(self.handle, ptrs, first_frame_id, len(rgb_frames), s),
+        _check(self.lib.sali_analyze_batch(self.handle, _ptr_array(rgb_frames), first_frame_id, len(rgb_frames), s),
                "sali_analyze_batch")
+
+    def store_batch(self, kv_frames, first_frame_id: int, stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_store_batch(self.handle, _ptr_array(kv_frames), first_frame_id, len(kv_frames), s),
+               "sali_store_batch")
+
+    def kv_decompress_batch(self, first_frame_id: int, out_frames, valid=None,
+                            stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_kv_decompress_batch(self.handle, first_frame_id, len(out_frames), _ptr_array(out_frames),
+                                                 _ptr(valid), s), "sali_kv_decompress_batch")
+
+    def step_batch(self, rgb_frames, kv_frames, first_frame_id: int, stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        assert len(rgb_frames) == len(kv_frames)
+        _check(self.lib.sali_step_batch(self.handle, _ptr_array(rgb_frames), _ptr_array(kv_frames), first_frame_id,
+                                        len(rgb_frames), s), "sali_step_batch")
 
     def store(self, kv, frame_id: int, stream: Optional[torch.cuda.Stream] = None):
         s = _stream() if stream is None else stream.cuda_stream

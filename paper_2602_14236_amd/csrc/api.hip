@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include "sali_internal.h"
+#include "tier_body.h"
 
 namespace sali {
 
@@ -26,7 +27,7 @@ constexpr int kRing = 2 * kLanes;     // bookkeeping of the most recent analyses
 static_assert(kLanes >= 2 * kMaxBatch, "two batches in flight");
 
 struct LaneLayout {
-    size_t y8, pyr, flow[2], cls, var, parent, msum, dp, scores, gate, counters;
+    size_t y8, pyr, flow[2], cls, var, parent, msum, dp, scores, gate, counters, tcounts;
 };
 
 struct ScratchLayout {
@@ -39,9 +40,10 @@ struct TableLayout {
     size_t lut, cursors, rows, tier, slot, order, total;      // lut = lin[256] followed by fl[4096]
 };
 
-struct LaneCounters {
-    uint32_t patch_done;      // arrival counter of the patch-motion kernel (self-resetting)
-    uint32_t pool_done;       // arrival counter of the pooling kernel (self-resetting)
+struct LaneCounters {         // arrival counters, all self-resetting
+    uint32_t patch_done;      // blocks of the stand-alone patch-motion kernel
+    uint32_t pool_done;       // blocks of the pooling kernel that work on the frame in this lane
+    uint32_t batch_done;      // frames of a pooling launch whose first frame sits in this lane
 };
 
 int check_config(const sali_config* c) {
@@ -148,6 +150,7 @@ ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
         L.scores = take(kTokens * sizeof(float));
         L.gate = take(sizeof(sali_gate));
         L.counters = take(sizeof(LaneCounters));
+        L.tcounts = take(8 * sizeof(int32_t));
     }
     for (int i = 0; i < kExpSlots; ++i) {
         s.expA[i] = take(px * sizeof(float4));
@@ -216,7 +219,7 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, Lane
             lanes.lane[l].msum[1] = 0ull;
             sali_gate g = {0, 0.0f, 0, 0};
             *lanes.lane[l].gate = g;
-            LaneCounters z = {0u, 0u};
+            LaneCounters z = {0u, 0u, 0u};
             *lanes.lane[l].counters = z;
         }
     }
@@ -399,9 +402,11 @@ int enqueue_pool(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, uint
         f.flow[i] = flow != nullptr ? flow[i] : nullptr;
         f.dp[i] = lp.dp;
         f.gate[i] = lp.gate;
+        f.frame_done[i] = &lp.counters->pool_done;
+        f.tcounts[i] = c->sc<TierCounts>(L.tcounts);
     }
     SALI_TRY(launch_pool(f, bp.n, c->cfg.src_h, c->cfg.src_w, d_salmap, tier, c->cfg.tau_t, c->cfg.theta_r,
-                         &c->lane_ptrs(bp.lane[0]).counters->pool_done, s));
+                         &c->lane_ptrs(bp.lane[0]).counters->batch_done, s));
     return SALI_OK;
 }
 
@@ -432,11 +437,15 @@ TierLaunch tier_launch(sali_ctx* c, int frame_id) {
     return t;
 }
 
-// the storage kernel of frame `frame_id`; its frame-table row and order list must be in place
-int enqueue_pack(sali_ctx* c, const void* d_kv, int frame_id, hipStream_t s) {
+// the storage kernel of frames first_frame_id .. + n - 1; their frame-table rows and order lists
+// must be in place
+int enqueue_pack(sali_ctx* c, const void* const* d_kv, int first_frame_id, int n, hipStream_t s) {
+    KvBatch f = {};
+    for (int i = 0; i < n; ++i) f.kv[i] = const_cast<void*>(d_kv[i]);
     hipEvent_t* ev = c->prof[SALI_PROF_PACK];
     if (ev[0] != nullptr) SALI_TRY(hipEventRecord(ev[0], s));
-    SALI_TRY(launch_pack(d_kv, c->rows() + frame_id, c->order(frame_id), c->pools, c->cursors(), c->n_planes, s));
+    SALI_TRY(launch_pack(f, n, c->rows(), first_frame_id, c->tb<uint16_t>(c->tl.order), c->pools, c->cursors(),
+                         c->n_planes, s));
     if (ev[1] != nullptr) SALI_TRY(hipEventRecord(ev[1], s));
     ev[0] = ev[1] = nullptr;
     return SALI_OK;
@@ -628,22 +637,34 @@ int sali_kv_compress(sali_ctx* c, const void* d_kv_fp16, const float* d_scores57
     hipStream_t s = static_cast<hipStream_t>(stream);
     SALI_TRY(launch_tier(d_scores576, nullptr, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
                          c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, s));
-    return enqueue_pack(c, d_kv_fp16, frame_id, s);
+    return enqueue_pack(c, &d_kv_fp16, frame_id, 1, s);
+}
+
+int sali_kv_decompress_batch(sali_ctx* c, int32_t first_frame_id, int32_t n_frames, void* const* d_kv_fp16_out_frames,
+                             uint8_t* d_valid_or_null, void* stream) {
+    if (c == nullptr || d_kv_fp16_out_frames == nullptr) return SALI_ERR_NULL;
+    if (n_frames < 1 || n_frames > kMaxBatch) return SALI_ERR_SHAPE;
+    if (first_frame_id < 0 || (long long)first_frame_id + n_frames > c->cfg.max_frames) return SALI_ERR_SHAPE;
+    KvBatch out = {};
+    for (int i = 0; i < n_frames; ++i) {
+        if (d_kv_fp16_out_frames[i] == nullptr) return SALI_ERR_NULL;
+        if (!aligned16(d_kv_fp16_out_frames[i])) return SALI_ERR_ALIGN;
+        out.kv[i] = d_kv_fp16_out_frames[i];
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t* ev = c->prof[SALI_PROF_UNPACK];
+    if (ev[0] != nullptr) SALI_TRY(hipEventRecord(ev[0], s));
+    SALI_TRY(launch_unpack(c->rows(), first_frame_id, c->tb<uint16_t>(c->tl.order), c->pools, out, n_frames,
+                           d_valid_or_null, c->cursors(), c->n_planes, s));
+    if (ev[1] != nullptr) SALI_TRY(hipEventRecord(ev[1], s));
+    ev[0] = ev[1] = nullptr;
+    return SALI_OK;
 }
 
 int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8_t* d_valid576_or_null,
                        void* stream) {
     if (c == nullptr || d_kv_fp16_out == nullptr) return SALI_ERR_NULL;
-    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
-    if (!aligned16(d_kv_fp16_out)) return SALI_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipEvent_t* ev = c->prof[SALI_PROF_UNPACK];
-    if (ev[0] != nullptr) SALI_TRY(hipEventRecord(ev[0], s));
-    SALI_TRY(launch_unpack(c->rows(), frame_id, c->tb<uint16_t>(c->tl.order), c->pools, d_kv_fp16_out,
-                           d_valid576_or_null, c->cursors(), c->n_planes, s));
-    if (ev[1] != nullptr) SALI_TRY(hipEventRecord(ev[1], s));
-    ev[0] = ev[1] = nullptr;
-    return SALI_OK;
+    return sali_kv_decompress_batch(c, frame_id, 1, &d_kv_fp16_out, d_valid576_or_null, stream);
 }
 
 int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t first_frame_id, int32_t n_frames,
@@ -716,18 +737,37 @@ int sali_analyze(sali_ctx* c, const uint8_t* d_rgb, int32_t frame_id, void* stre
     return sali_analyze_batch(c, &d_rgb, frame_id, 1, stream);
 }
 
+int sali_store_batch(sali_ctx* c, const void* const* d_kv_frames, int32_t first_frame_id, int32_t n_frames,
+                     void* stream) {
+    if (c == nullptr || d_kv_frames == nullptr) return SALI_ERR_NULL;
+    if (n_frames < 1 || n_frames > kMaxBatch) return SALI_ERR_SHAPE;
+    if (first_frame_id < 0 || (long long)first_frame_id + n_frames > c->cfg.max_frames) return SALI_ERR_SHAPE;
+    for (int i = 0; i < n_frames; ++i) {
+        if (d_kv_frames[i] == nullptr) return SALI_ERR_NULL;
+        if (!aligned16(d_kv_frames[i])) return SALI_ERR_ALIGN;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // every frame must have been analysed recently; wait once per batch of analyses
+    const AnalysisRecord* waits[kMaxBatch];
+    int n_waits = 0;
+    for (int f = 0; f < n_frames; ++f) {
+        const AnalysisRecord* rec = nullptr;
+        for (int i = 0; i < kRing; ++i)
+            if (c->ring[i].frame_id == first_frame_id + f) rec = &c->ring[i];
+        if (rec == nullptr) return SALI_ERR_STATE;      // not analysed (or too long ago)
+        const AnalysisRecord* ev = &c->ring[rec->batch_last];
+        if (n_waits == 0 || waits[n_waits - 1] != ev) waits[n_waits++] = ev;
+    }
+    for (int i = 0; i < n_waits; ++i) {
+        const int rc = wait_unless_same(s, waits[i]->stream, waits[i]->done);
+        if (rc != SALI_OK) return rc;
+    }
+    return enqueue_pack(c, d_kv_frames, first_frame_id, n_frames, s);
+}
+
 int sali_store(sali_ctx* c, const void* d_kv, int32_t frame_id, void* stream) {
     if (c == nullptr || d_kv == nullptr) return SALI_ERR_NULL;
-    if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
-    if (!aligned16(d_kv)) return SALI_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const AnalysisRecord* rec = nullptr;
-    for (int i = 0; i < kRing; ++i)
-        if (c->ring[i].frame_id == frame_id) rec = &c->ring[i];
-    if (rec == nullptr) return SALI_ERR_STATE;      // not analysed (or too long ago)
-    const int rc = wait_unless_same(s, rec->stream, c->ring[rec->batch_last].done);
-    if (rc != SALI_OK) return rc;
-    return enqueue_pack(c, d_kv, frame_id, s);
+    return sali_store_batch(c, &d_kv, frame_id, 1, stream);
 }
 
 int sali_step(sali_ctx* c, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id, void* stream) {
@@ -736,6 +776,19 @@ int sali_step(sali_ctx* c, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t f
     const int rc = sali_analyze(c, d_rgb_t, frame_id, stream);
     if (rc != SALI_OK) return rc;
     return sali_store(c, d_kv_t, frame_id, stream);
+}
+
+int sali_step_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, const void* const* d_kv_frames,
+                    int32_t first_frame_id, int32_t n_frames, void* stream) {
+    if (c == nullptr || d_rgb_frames == nullptr || d_kv_frames == nullptr) return SALI_ERR_NULL;
+    if (n_frames < 1 || n_frames > kMaxBatch) return SALI_ERR_SHAPE;
+    for (int i = 0; i < n_frames; ++i) {
+        if (d_kv_frames[i] == nullptr) return SALI_ERR_NULL;
+        if (!aligned16(d_kv_frames[i])) return SALI_ERR_ALIGN;
+    }
+    const int rc = sali_analyze_batch(c, d_rgb_frames, first_frame_id, n_frames, stream);
+    if (rc != SALI_OK) return rc;
+    return sali_store_batch(c, d_kv_frames, first_frame_id, n_frames, stream);
 }
 
 int sali_step_pipelined(sali_ctx* c, const uint8_t* d_rgb_next_or_null, int32_t next_frame_id,

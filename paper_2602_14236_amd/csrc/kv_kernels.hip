@@ -74,13 +74,17 @@ __global__ __launch_bounds__(kTierThreads) void k_tier(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pack: grid (ceil(576 / 64), planes); plane = (layer, K|V, head).
+// Pack: grid (ceil(576 / 64), planes, frames); plane = (layer, K|V, head); frame i of the launch has
+// id first_frame_id + i.
 // ---------------------------------------------------------------------------------------------
 // kNTL / kNTS: non-temporal loads / stores
 template <bool kNTL, bool kNTS>
-__global__ __launch_bounds__(256) void k_pack(const u32x4* __restrict__ kv, const sali_frame_row* __restrict__ row_p,
-                                              const uint16_t* __restrict__ order, Pools pools, Cursors* cur) {
-    const sali_frame_row row = *row_p;
+__global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* __restrict__ rows, int first_frame_id,
+                                              const uint16_t* __restrict__ order_base, Pools pools, Cursors* cur) {
+    const int frame_id = first_frame_id + (int)blockIdx.z;
+    const u32x4* __restrict__ kv = reinterpret_cast<const u32x4*>(f.kv[blockIdx.z]);
+    const uint16_t* __restrict__ order = order_base + (size_t)frame_id * kTokens;
+    const sali_frame_row row = rows[frame_id];
     if (row.stored == 0) return;
     const int n16 = row.n16, n8 = row.n8;
     const int nkeep = n16 + n8 + row.n4;
@@ -179,12 +183,16 @@ __global__ __launch_bounds__(256) void k_pack(const u32x4* __restrict__ kv, cons
 }
 
 // ---------------------------------------------------------------------------------------------
-// Unpack: grid (576 / 64, planes); rebuilds the dense fp16 frame in token order.
+// Unpack: grid (576 / 64, planes, frames); rebuilds the dense fp16 frames in token order; frame i of
+// the launch has id first_frame_id + i and its validity mask at valid_base + i * 576.
 // ---------------------------------------------------------------------------------------------
 template <bool kNTL, bool kNTS>
-__global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict__ rows, int frame_id,
-                                                const uint16_t* __restrict__ order_base, Pools pools,
-                                                u32x4* __restrict__ out, uint8_t* valid, Cursors* cur) {
+__global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict__ rows, int first_frame_id,
+                                                const uint16_t* __restrict__ order_base, Pools pools, KvBatch f,
+                                                uint8_t* valid_base, Cursors* cur) {
+    const int frame_id = first_frame_id + (int)blockIdx.z;
+    u32x4* __restrict__ out = reinterpret_cast<u32x4*>(f.kv[blockIdx.z]);
+    uint8_t* valid = valid_base != nullptr ? valid_base + (size_t)blockIdx.z * kTokens : nullptr;
     const int src = rows[frame_id].src;
     const size_t plane = blockIdx.y;
     const int g = threadIdx.x >> 4;
@@ -270,22 +278,23 @@ hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, T
     return hipGetLastError();
 }
 
-hipError_t launch_pack(const void* d_kv, const sali_frame_row* d_row, const uint16_t* d_order, Pools pools,
-                       Cursors* d_cur, int n_planes, hipStream_t s) {
-    dim3 grid((kTokens + kRowsPerBlock - 1) / kRowsPerBlock, n_planes);
+hipError_t launch_pack(const KvBatch& f, int n, const sali_frame_row* d_rows, int first_frame_id,
+                       const uint16_t* d_order_base, Pools pools, Cursors* d_cur, int n_planes, hipStream_t s) {
+    dim3 grid((kTokens + kRowsPerBlock - 1) / kRowsPerBlock, n_planes, n);
     // streaming both ways: non-temporal loads and stores.  (Ordinary stores keep the new pool rows in
     // the last-level cache, which speeds up an immediate read-back by about as much as it slows this
     // kernel; without an immediate read-back non-temporal stores measured 10 % faster.)
-    hipLaunchKernelGGL((k_pack<true, true>), grid, dim3(256), 0, s, reinterpret_cast<const u32x4*>(d_kv), d_row, d_order,
-                       pools, d_cur);
+    hipLaunchKernelGGL((k_pack<true, true>), grid, dim3(256), 0, s, f, d_rows, first_frame_id, d_order_base, pools,
+                       d_cur);
     return hipGetLastError();
 }
 
-hipError_t launch_unpack(const sali_frame_row* d_rows, int frame_id, const uint16_t* d_order_base, Pools pools,
-                         void* d_out, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes, hipStream_t s) {
-    dim3 grid(kTokens / kRowsPerBlock, n_planes);
-    hipLaunchKernelGGL((k_unpack<true, true>), grid, dim3(256), 0, s, d_rows, frame_id, d_order_base, pools,
-                       reinterpret_cast<u32x4*>(d_out), d_valid_or_null, d_cur);
+hipError_t launch_unpack(const sali_frame_row* d_rows, int first_frame_id, const uint16_t* d_order_base, Pools pools,
+                         const KvBatch& out, int n, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes,
+                         hipStream_t s) {
+    dim3 grid(kTokens / kRowsPerBlock, n_planes, n);
+    hipLaunchKernelGGL((k_unpack<true, true>), grid, dim3(256), 0, s, d_rows, first_frame_id, d_order_base, pools, out,
+                       d_valid_or_null, d_cur);
     return hipGetLastError();
 }
 

@@ -111,6 +111,12 @@ struct PoolBatch {
     const float2* flow[kMaxBatch];                // NULL: no predecessor (never redundant)
     float* dp[kMaxBatch];
     sali_gate* gate[kMaxBatch];
+    uint32_t* frame_done[kMaxBatch];              // arrival counter of the frame's blocks (self-resetting)
+    struct TierCounts* tcounts[kMaxBatch];        // hand-over from the frame's ranking to the row writer
+};
+
+struct KvBatch {
+    void* kv[kMaxBatch];
 };
 
 struct FlowWeights {
@@ -127,10 +133,13 @@ struct FlowWeights {
 hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,
                        sali_frame_row* d_rows, uint8_t* d_tier, uint16_t* d_slot, uint16_t* d_order,
                        Cursors* d_cur, Pools pools, hipStream_t s);
-hipError_t launch_pack(const void* d_kv, const sali_frame_row* d_row, const uint16_t* d_order, Pools pools,
-                       Cursors* d_cur, int n_planes, hipStream_t s);
-hipError_t launch_unpack(const sali_frame_row* d_rows, int frame_id, const uint16_t* d_order_base, Pools pools,
-                         void* d_out, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes, hipStream_t s);
+// frame i of a batched launch has id first_frame_id + i; f.kv[i] is its dense fp16 K/V (source of
+// the pack, destination of the unpack)
+hipError_t launch_pack(const KvBatch& f, int n, const sali_frame_row* d_rows, int first_frame_id,
+                       const uint16_t* d_order_base, Pools pools, Cursors* d_cur, int n_planes, hipStream_t s);
+hipError_t launch_unpack(const sali_frame_row* d_rows, int first_frame_id, const uint16_t* d_order_base, Pools pools,
+                         const KvBatch& out, int n, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes,
+                         hipStream_t s);
 
 // saliency_kernels.hip
 // n = frames in the batch (1..kMaxBatch); with_saliency = false converts to gray only (n must be 1)

@@ -371,7 +371,7 @@ __global__ __launch_bounds__(256) void k_union(PrepBatch f, int h, int w) {
 template <int kWaves>
 __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w, uint8_t* __restrict__ salmap,
                                                   int do_tier, float tau_t, float theta_r, TierLaunch tl,
-                                                  uint32_t* done_counter) {
+                                                  uint32_t* batch_done) {
     static_assert(kTierThreads == 256, "four waves, one patch each");
     static_assert(kWaves == 1 || kWaves == 4, "");
     __shared__ TierShared sh;
@@ -433,48 +433,71 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+    // Arrival counters, nobody waits.  The last block of a FRAME evaluates the frame's gate and ranks
+    // its tokens (frames in parallel); the last of those blocks in the whole launch then writes the
+    // frame-table rows and advances the pool cursors in video order.
     __syncthreads();
     if (threadIdx.x == 0) {
         int last = 0;
         if (do_tier) {
             __threadfence();
-            last = (atomicAdd(done_counter, 1u) == gridDim.x * gridDim.y - 1u) ? 1 : 0;
+            last = (atomicAdd(f.frame_done[blockIdx.y], 1u) == gridDim.x - 1u) ? 1 : 0;
         }
         s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    if (threadIdx.x == 0) *done_counter = 0u;       // ready for the next launch
-    // The frames of the batch in video order (tiers and pool cursors are handed out in that order).
+    const int b = blockIdx.y;
     // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; a frame
     // without predecessor (no flow) is never redundant
-    for (int b = 0; b < (int)gridDim.y; ++b) {
-        const bool have_flow = f.flow[b] != nullptr;
-        int n = 0;
-        if (have_flow) {
-            for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
-                const float v = __hip_atomic_load(f.dp[b] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                n += (v < tau_t) ? 1 : 0;
+    const bool have_flow = f.flow[b] != nullptr;
+    int n = 0;
+    if (have_flow) {
+        for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
+            const float v = __hip_atomic_load(f.dp[b] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            n += (v < tau_t) ? 1 : 0;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
+    if (lane == 0) s_cnt[wave] = n;
+    __syncthreads();
+    const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    const float r = (float)n_static / (float)kTokens;
+    const bool redundant = have_flow && r > theta_r;
+    TierCounts tc = {};
+    tc.state = 1;
+    if (!redundant)
+        tc = tier_rank(sh, f.scores[b], tl.tp, tl.tier + (size_t)b * kTokens, tl.slot + (size_t)b * kTokens,
+                       tl.order + (size_t)b * kTokens);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sali_gate gt;
+        gt.n_static = n_static;
+        gt.r_frame = have_flow ? r : 0.0f;
+        gt.redundant = redundant ? 1 : 0;
+        gt.reserved = 0;
+        *f.gate[b] = gt;
+        *f.frame_done[b] = 0u;          // ready for the next launch
+        int32_t* out = reinterpret_cast<int32_t*>(f.tcounts[b]);
+        __hip_atomic_store(out + 0, tc.state, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            __hip_atomic_store(out + 1 + t, tc.cnt[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();                // counts, tiers, slots and order lists before the arrival
+        if (atomicAdd(batch_done, 1u) == gridDim.y - 1u) {
+            __threadfence();
+            *batch_done = 0u;
+            for (int i = 0; i < (int)gridDim.y; ++i) {
+                const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
+                TierCounts ti;
+                ti.state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    ti.cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tier_commit(ti, tl.frame_id + i, tl.rows, tl.cur, tl.cap16, tl.cap8, tl.cap4);
             }
         }
-        for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
-        __syncthreads();        // the previous frame's reads of s_cnt and of the tier scratch are over
-        if (lane == 0) s_cnt[wave] = n;
-        __syncthreads();
-        const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-        const float r = (float)n_static / (float)kTokens;
-        const bool redundant = have_flow && r > theta_r;
-        if (threadIdx.x == 0) {
-            sali_gate gt;
-            gt.n_static = n_static;
-            gt.r_frame = have_flow ? r : 0.0f;
-            gt.redundant = redundant ? 1 : 0;
-            gt.reserved = 0;
-            *f.gate[b] = gt;
-        }
-        tier_body(sh, f.scores[b], redundant, tl.tp, tl.frame_id + b, tl.rows, tl.tier + (size_t)b * kTokens,
-                  tl.slot + (size_t)b * kTokens, tl.order + (size_t)b * kTokens, tl.cur, tl.cap16, tl.cap8, tl.cap4);
     }
 }
 

@@ -1,8 +1,10 @@
 // Tier assignment (Eq. 8 or top-k counts), compaction indices and frame-table row for one frame.
-// Shared by the stand-alone tier kernel and by the last block of the pooling kernel; must be
-// entered by a whole block of exactly kTierThreads threads.  Thread t owns tokens t, t + 256 and
-// (for t < 64) t + 512, so the 64 tokens of "group" g = token / 64 sit in one wave.  Only
-// comparisons and integer arithmetic: the result does not depend on floating-point contraction.
+// Shared by the stand-alone tier kernel and by the pooling kernel.  Two parts: tier_rank (a whole
+// block of exactly kTierThreads threads; everything that depends on the frame's scores only) and
+// tier_commit (one thread; the part that depends on the pool cursors, so it runs in frame order).
+// In tier_rank thread t owns tokens t, t + 256 and (for t < 64) t + 512, so the 64 tokens of
+// "group" g = token / 64 sit in one wave.  Only comparisons and integer arithmetic: the result does
+// not depend on floating-point contraction.
 //
 // Workgroups are kept at 256 threads on purpose: larger ones wait for many free wave slots on
 // one compute unit and starve next to a bandwidth kernel that keeps every unit busy.
@@ -16,30 +18,26 @@ constexpr int kTierThreads = 256;
 constexpr int kTierSlots = (kTokens + kTierThreads - 1) / kTierThreads;      // tokens per thread (3)
 constexpr int kTierGroups = kTokens / 64;                                    // 9
 
+// what tier_rank hands to tier_commit
+struct TierCounts {
+    int32_t state;          // 0 = tiers assigned, 1 = redundant frame, 2 = a score was NaN
+    int32_t cnt[4];         // tokens per tier
+};
+
 struct TierShared {
     uint4 key4[kTokens / 4];        // order-preserving integer image of the scores
     int group_cnt[kTierGroups][4];
     int nan_flag;
 };
 
-__device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, bool redundant, const TierParams& tp,
-                                          int frame_id, sali_frame_row* rows, uint8_t* __restrict__ tier_out,
-                                          uint16_t* __restrict__ slot_out, uint16_t* __restrict__ order_out,
-                                          Cursors* cur, int cap16, int cap8, int cap4) {
+// Assigns tier, slot (rank inside the tier in token order) and the pool-order token list of one
+// non-redundant frame.  Returns the per-tier counts (every thread gets the same value).
+__device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const float* scores, const TierParams& tp,
+                                                uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
+                                                uint16_t* __restrict__ order_out) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-
-    if (redundant) {
-        // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame.
-        if (tid == 0) {
-            sali_frame_row r = {};
-            r.frame_id = frame_id;
-            r.src = cur->last_src;
-            r.stored = 0;
-            rows[frame_id] = r;
-        }
-        return;
-    }
+    TierCounts res = {};
 
     if (tid == 0) sh.nan_flag = 0;
     float s[kTierSlots];
@@ -63,14 +61,8 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
     if (has_nan) sh.nan_flag = 1;
     __syncthreads();
     if (sh.nan_flag) {
-        if (tid == 0) {
-            atomicOr(&cur->status, SALI_FAULT_NAN_SCORE);
-            sali_frame_row r = {};
-            r.frame_id = frame_id;
-            r.src = -1;
-            rows[frame_id] = r;
-        }
-        return;
+        res.state = 2;
+        return res;
     }
 
     int tier[kTierSlots];
@@ -150,22 +142,6 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
         }
     }
 
-    // capacity check (uniform: every thread reads the same cursors)
-    const int c16 = cur->c16, c8 = cur->c8, c4 = cur->c4;
-    const bool overflow = (long long)c16 + cnt[0] > cap16 || (long long)c8 + cnt[1] > cap8 ||
-                          (long long)c4 + cnt[2] > cap4;
-    __syncthreads();    // all cursor reads precede the update below
-    if (overflow) {
-        if (tid == 0) {
-            atomicOr(&cur->status, SALI_FAULT_OVERFLOW);
-            sali_frame_row r = {};
-            r.frame_id = frame_id;
-            r.src = -1;
-            rows[frame_id] = r;
-        }
-        return;
-    }
-
 #pragma unroll
     for (int k = 0; k < kTierSlots; ++k) {
         const int i = tid + k * kTierThreads;
@@ -176,25 +152,61 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
         const int tier_base = (tier[k] > 0 ? cnt[0] : 0) + (tier[k] > 1 ? cnt[1] : 0) + (tier[k] > 2 ? cnt[2] : 0);
         order_out[tier_base + slot] = (uint16_t)i;
     }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) res.cnt[t] = cnt[t];
+    return res;
+}
 
-    if (tid == 0) {
-        sali_frame_row r = {};
-        r.frame_id = frame_id;
-        r.src = frame_id;
-        r.stored = 1;
-        r.base16 = c16;
-        r.base8 = c8;
-        r.base4 = c4;
-        r.n16 = cnt[0];
-        r.n8 = cnt[1];
-        r.n4 = cnt[2];
-        r.n_pruned = cnt[3];
+// Frame-table row and pool cursors of one frame; ONE thread, frames in video order.
+__device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, sali_frame_row* rows, Cursors* cur,
+                                            int cap16, int cap8, int cap4) {
+    sali_frame_row r = {};
+    r.frame_id = frame_id;
+    if (tc.state == 1) {
+        // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame.
+        r.src = cur->last_src;
+        r.stored = 0;
         rows[frame_id] = r;
-        cur->c16 = c16 + cnt[0];
-        cur->c8 = c8 + cnt[1];
-        cur->c4 = c4 + cnt[2];
-        cur->last_src = frame_id;
+        return;
     }
+    if (tc.state == 2) {
+        atomicOr(&cur->status, SALI_FAULT_NAN_SCORE);
+        r.src = -1;
+        rows[frame_id] = r;
+        return;
+    }
+    const int c16 = cur->c16, c8 = cur->c8, c4 = cur->c4;
+    if ((long long)c16 + tc.cnt[0] > cap16 || (long long)c8 + tc.cnt[1] > cap8 || (long long)c4 + tc.cnt[2] > cap4) {
+        atomicOr(&cur->status, SALI_FAULT_OVERFLOW);
+        r.src = -1;
+        rows[frame_id] = r;
+        return;
+    }
+    r.src = frame_id;
+    r.stored = 1;
+    r.base16 = c16;
+    r.base8 = c8;
+    r.base4 = c4;
+    r.n16 = tc.cnt[0];
+    r.n8 = tc.cnt[1];
+    r.n4 = tc.cnt[2];
+    r.n_pruned = tc.cnt[3];
+    rows[frame_id] = r;
+    cur->c16 = c16 + tc.cnt[0];
+    cur->c8 = c8 + tc.cnt[1];
+    cur->c4 = c4 + tc.cnt[2];
+    cur->last_src = frame_id;
+}
+
+// both parts for one frame (whole block)
+__device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, bool redundant, const TierParams& tp,
+                                          int frame_id, sali_frame_row* rows, uint8_t* __restrict__ tier_out,
+                                          uint16_t* __restrict__ slot_out, uint16_t* __restrict__ order_out,
+                                          Cursors* cur, int cap16, int cap8, int cap4) {
+    TierCounts tc = {};
+    tc.state = 1;
+    if (!redundant) tc = tier_rank(sh, scores, tp, tier_out, slot_out, order_out);
+    if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4);
 }
 
 }  // namespace sali

@@ -197,14 +197,23 @@ def test_batched_analysis_matches_oracle():
     for b, size in enumerate(sizes):
         print(f"batch {b}: frames {first}..{first + size - 1}", flush=True)
         ctx.analyze_batch(rgbs[first:first + size], first, s_imgs[b % 2])
-        for t in pending:
-            ctx.store(kvs[t], t, s_kv)
+        if pending:
+            ctx.store_batch([kvs[t] for t in pending], pending[0], s_kv)
         pending = list(range(first, first + size))
         first += size
-    for t in pending:
+    for t in pending:                        # the last batch frame by frame
         ctx.store(kvs[t], t, s_kv)
     torch.cuda.synchronize()
     _compare_all(ctx, orc, range(n))
+    # batched read-back (pointer frames and scene cuts inside the range) against the oracle
+    outs = [torch.empty_like(kvs[0]) for _ in range(8)]
+    valid = torch.empty(8 * 576, dtype=torch.uint8, device="cuda")
+    ctx.kv_decompress_batch(2, outs, valid, s_kv)
+    torch.cuda.synchronize()
+    for i in range(8):
+        exp, exp_valid = orc.kv_decompress(2 + i)
+        assert_same(outs[i].cpu().numpy(), exp, f"batched read-back of frame {2 + i}")
+        assert_same(valid[576 * i:576 * (i + 1)].cpu().numpy(), exp_valid, f"batched valid mask {2 + i}")
     # argument checks
     with pytest.raises(binding.SaliError) as e:
         ctx.analyze_batch(rgbs[:9], 0, s_imgs[0])
@@ -212,4 +221,30 @@ def test_batched_analysis_matches_oracle():
     with pytest.raises(binding.SaliError) as e:
         ctx.analyze_batch(rgbs[:4], n - 2, s_imgs[0])
     assert e.value.code == -2
+    ctx.close()
+
+
+def test_step_batch_matches_oracle():
+    """sali_step_batch: config 1 (one duplicate frame) in two calls of five and three frames."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[1]
+    p = workload_params(wl, n_heads=2)
+    v = synth.video(1)
+    n = 8
+    scale = synth.kv_channel_scale(wl, 1, 2)
+    rgbs = [torch.from_numpy(v.frame(t)).cuda() for t in range(n)]
+    kvs = [synth.kv_frame(wl, t, device="cuda", n_layers=1, n_heads=2, scale=scale) for t in range(n)]
+    orc = SaliCacheOracle(oracle_config(p))
+    for t in range(n):
+        orc.step(v.frame(t), kvs[t].cpu().numpy(), t)
+    ctx = binding.SaliContext(lib_config(p))
+    ctx.step_batch(rgbs[:5], kvs[:5], 0)
+    ctx.step_batch(rgbs[5:], kvs[5:], 5)
+    torch.cuda.synchronize()
+    assert sum(1 for t in range(n) if not orc.rows[t].stored) == 1
+    _compare_all(ctx, orc, range(n))
+    # a frame that was never analysed cannot be stored
+    with pytest.raises(binding.SaliError) as e:
+        ctx.store_batch(kvs[:2], 20)
+    assert e.value.code in (-2, -5)
     ctx.close()
