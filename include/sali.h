@@ -247,17 +247,19 @@ int sali_read_frame_table(sali_ctx* ctx, sali_frame_row* h_rows, int32_t first, 
 int sali_read_frame_tiers(sali_ctx* ctx, int32_t frame_id, uint8_t* h_tier576, uint16_t* h_slot576,
                           void* stream);
 
-/* Results the last sali_step left in device memory, copied to host: per-patch motion
- * (fp32[576]), the gate, and the saliency scores (fp32[576]); any pointer may be NULL.
- * Motion and gate are zeros if the step had no previous frame; scores are stale if the
- * frame was redundant.  Waits for `stream`. */
+/* Results that the most recently analysed frame (the last one of a batch) left in device
+ * memory, copied to host: per-patch motion (fp32[576]), the gate, and the saliency scores
+ * (fp32[576], computed for redundant frames too); any pointer may be NULL.  Motion and gate
+ * are zeros if the frame had no predecessor.  Waits for `stream`, which must be the stream
+ * of that analysis (or ordered after it). */
 int sali_read_last_step(sali_ctx* ctx, float* h_patch_motion576, sali_gate* h_gate,
                         float* h_scores576, void* stream);
 
 /* Measurement hook.  Arms one pair of caller-created HIP events (hipEvent_t, passed as void*):
  * the next launch of the chosen kernel records `start` just before and `stop` just after it on
  * the call's stream, then the pair is disarmed.  which: SALI_PROF_PACK = the storage kernel of
- * sali_step / sali_kv_compress, SALI_PROF_UNPACK = the kernel of sali_kv_decompress.  NULL
+ * sali_step / sali_store[_batch] / sali_kv_compress, SALI_PROF_UNPACK = the kernel of
+ * sali_kv_decompress[_batch] (one launch per call, whatever the batch size).  NULL
  * events disarm.  The caller reads the elapsed time after synchronising. */
 #define SALI_PROF_PACK   0
 #define SALI_PROF_UNPACK 1
