@@ -23,4 +23,7 @@ Pins (tests/test_oracle_*.py, CPU only):
             step edges, hysteresis chains, uniform-variance image.
   quant     round-trip error <= scale/2, power-of-two scaling invariance, negation,
             extreme codes, closed-form byte counts, brute-force ranks on tiny inputs.
+  attention (single-query attention over the cache, float64) a library scaled-dot-product
+            attention on an all-FP16 cache, uniform-logits and dominant-key closed forms,
+            brute-force loops with a pointer frame and pruned tokens, log-sum-exp merge.
 """

@@ -1,0 +1,74 @@
+"""Oracle: single-query attention over the mixed-precision cache.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+Just-In-Time Dequantization says that quantised cache entries are dequantised
+while attention is computed, and Implementation Details that the
+dequantisation is fused with the attention computation.  The paper gives no
+formula beyond that, so the oracle is the plain definition written out:
+
+  for one layer and every head h, with one query vector q_h,
+    s_j   = softmax_scale * <q_h, K^_j>           over the cached tokens j
+    p     = softmax(s)
+    out_h = sum_j p_j V^_j,      lse_h = log sum_j exp(s_j)
+
+where K^, V^ are exactly what dequantise-on-read returns (oracle.cache:
+fp16-rounded values; FP16-tier rows verbatim) and everything else is float64.
+
+Readings (the paper is silent on all three):
+  * the cached sequence is the LOGICAL one: frames frame_lo .. frame_hi - 1 in
+    order, each contributing the kept tokens of its cache entry.  A redundant
+    frame's entry is a pointer (Algorithm 1), so the tokens of its source
+    frame appear once more: reuse saves memory, it does not drop the frame
+    from the sequence;
+  * pruned tokens are not in the cache and take no part in the softmax;
+  * frames that hold no data (never stored, or dropped on overflow)
+    contribute nothing; with no token at all out = 0 and lse = -inf.
+
+Pins (tests/test_oracle_attention.py): a library scaled-dot-product attention
+on an all-FP16 cache, the uniform-logits closed form (mean of V^, lse = log n),
+a dominant key, brute-force Python loops with a pointer frame and pruned
+tokens, and the log-sum-exp merge of two frame ranges.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def cached_tokens(cache, layer, frame_lo, frame_hi):
+    """K^, V^ of the logical token sequence of frames [frame_lo, frame_hi):
+    two float64 arrays [n_heads, n_tokens, head_dim] (n_tokens may be 0)."""
+    ks, vs = [], []
+    for f in range(frame_lo, frame_hi):
+        row = cache.rows.get(f)
+        if row is None or row.src < 0:
+            continue
+        kv, valid = cache.kv_decompress(f)
+        keep = np.nonzero(valid)[0]
+        ks.append(kv[layer, 0][:, keep, :].astype(np.float64))
+        vs.append(kv[layer, 1][:, keep, :].astype(np.float64))
+    c = cache.cfg
+    if not ks:
+        empty = np.zeros((c.n_heads, 0, c.head_dim), dtype=np.float64)
+        return empty, empty.copy()
+    return np.concatenate(ks, axis=1), np.concatenate(vs, axis=1)
+
+
+def attend_decode(cache, layer, q, frame_lo, frame_hi, softmax_scale):
+    """q: [n_heads, head_dim] (fp16 values).  -> (out float64 [n_heads, head_dim],
+    lse float64 [n_heads])."""
+    k, v = cached_tokens(cache, layer, frame_lo, frame_hi)
+    qf = np.asarray(q).astype(np.float64)
+    n_heads, n_tok, d = k.shape
+    out = np.zeros((n_heads, d), dtype=np.float64)
+    lse = np.full(n_heads, -np.inf, dtype=np.float64)
+    if n_tok == 0:
+        return out, lse
+    for h in range(n_heads):
+        s = float(softmax_scale) * (k[h] @ qf[h])
+        m = s.max()
+        e = np.exp(s - m)
+        z = e.sum()
+        out[h] = (e / z) @ v[h]
+        lse[h] = m + np.log(z)
+    return out, lse
