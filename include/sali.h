@@ -229,6 +229,23 @@ int sali_kv_decompress_batch(sali_ctx* ctx, int32_t first_frame_id, int32_t n_fr
 int sali_step_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, const void* const* d_kv_frames,
                     int32_t first_frame_id, int32_t n_frames, void* stream);
 
+/* Just-In-Time Dequantization, fused with attention (Implementation Details): single-query
+ * attention of one layer over the cache, reading the mixed-precision pools directly.  For every
+ * head h:  s_j = softmax_scale * <q_h, K^_j>,  out_h = sum_j softmax(s)_j V^_j,
+ * lse_h = log sum_j exp(s_j), over the logical token sequence of frames frame_lo .. frame_hi - 1:
+ * every frame contributes the kept tokens of its cache entry, a redundant frame (pointer entry)
+ * those of its source frame once more, pruned tokens and frames without data nothing.  K^, V^ are
+ * exactly the values sali_kv_decompress returns.  With lse the caller can merge the result with
+ * attention over other keys (text tokens).
+ *   d_q_fp16   device, fp16 [n_heads][128], 16-byte aligned
+ *   d_out      device, fp32 [n_heads][128]; zeros where the range holds no token
+ *   d_lse_or_null  device, fp32 [n_heads]; -inf where the range holds no token
+ * Asynchronous on `stream`, which must be ordered after the stores of the frames read.  Uses one
+ * partial-result area of the context: calls on one context must not overlap each other.
+ * SALI_ERR_SHAPE if layer or the frame range is out of range (frame_lo == frame_hi is allowed). */
+int sali_attend_decode(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
+                       float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
+
 /* One loop body of Algorithm 1 with look-ahead on caller-owned streams: analyses a later
  * frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
  * `image_stream` and stores the K/V of the already analysed frame `frame_id` (d_kv, may be NULL
@@ -259,10 +276,12 @@ int sali_read_last_step(sali_ctx* ctx, float* h_patch_motion576, sali_gate* h_ga
  * the next launch of the chosen kernel records `start` just before and `stop` just after it on
  * the call's stream, then the pair is disarmed.  which: SALI_PROF_PACK = the storage kernel of
  * sali_step / sali_store[_batch] / sali_kv_compress, SALI_PROF_UNPACK = the kernel of
- * sali_kv_decompress[_batch] (one launch per call, whatever the batch size).  NULL
+ * sali_kv_decompress[_batch] (one launch per call, whatever the batch size), SALI_PROF_ATTEND =
+ * the main kernel of sali_attend_decode.  NULL
  * events disarm.  The caller reads the elapsed time after synchronising. */
 #define SALI_PROF_PACK   0
 #define SALI_PROF_UNPACK 1
+#define SALI_PROF_ATTEND 2   /* the main kernel of sali_attend_decode */
 int sali_set_profile_events(sali_ctx* ctx, int which, void* start_event, void* stop_event);
 
 /* Read and keep the sticky device status word.  Waits for `stream`. */

@@ -87,6 +87,8 @@ EXPORTS = {
                                            C.c_void_p]),
     "sali_step_batch": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
                                   C.c_void_p]),
+    "sali_attend_decode": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]),
     "sali_step_pipelined": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p]),
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
@@ -229,6 +231,12 @@ class SaliContext:
         s = _stream() if stream is None else stream.cuda_stream
         _check(self.lib.sali_analyze_batch(self.handle, _ptr_array(rgb_frames), first_frame_id, len(rgb_frames), s),
                "sali_analyze_batch")
+
+    def attend_decode(self, layer: int, q, frame_lo: int, frame_hi: int, softmax_scale: float, out, lse=None,
+                      stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_attend_decode(self.handle, layer, _ptr(q), frame_lo, frame_hi, softmax_scale, _ptr(out),
+                                           _ptr(lse), s), "sali_attend_decode")
 
     def store_batch(self, kv_frames, first_frame_id: int, stream: Optional[torch.cuda.Stream] = None):
         s = _stream() if stream is None else stream.cuda_stream

@@ -25,6 +25,7 @@ COMMON = [
 SOURCES = {
     "api.hip": [],
     "kv_kernels.hip": ["-ffp-contract=off"],
+    "attn_kernels.hip": ["-ffp-contract=off"],      # dequantised values must equal the unpack kernel's bit for bit
     "saliency_kernels.hip": [],
     "flow_kernels.hip": ["-ffp-contract=fast"],
 }

@@ -33,6 +33,7 @@ struct LaneLayout {
 struct ScratchLayout {
     LaneLayout lane[kLanes];
     size_t expA[kExpSlots], expB[kExpSlots];
+    size_t attn_partial;
     size_t total;
 };
 
@@ -156,6 +157,7 @@ ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
         s.expA[i] = take(px * sizeof(float4));
         s.expB[i] = take(px * sizeof(float2));
     }
+    s.attn_partial = take((size_t)c.n_heads * kAttnPartials * (kHeadDim + 2) * sizeof(float));
     s.total = o;
     return s;
 }
@@ -258,7 +260,7 @@ struct sali_ctx {
     unsigned n_analysed;      // analyses since create / reset; analysis n uses lane n % kLanes
     unsigned lane_uses[kLanes];   // saliency passes run in each lane; the parity selects the frame-sum accumulator
     AnalysisRecord ring[kRing];
-    hipEvent_t prof[2][2];    // [SALI_PROF_*][start, stop], armed for one launch
+    hipEvent_t prof[3][2];    // [SALI_PROF_*][start, stop], armed for one launch
 
     template <typename T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
     template <typename T> T* tb(size_t off) const { return reinterpret_cast<T*>(tables + off); }
@@ -537,7 +539,7 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->n_planes = cfg->n_layers * 2 * cfg->n_heads;
     c->n_analysed = 0;
     for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
-    c->prof[0][0] = c->prof[0][1] = c->prof[1][0] = c->prof[1][1] = nullptr;
+    for (int i = 0; i < 3; ++i) c->prof[i][0] = c->prof[i][1] = nullptr;
     for (int i = 0; i < kRing; ++i) {
         c->ring[i].frame_id = -1;
         c->ring[i].batch_last = i;
@@ -665,6 +667,22 @@ int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8
                        void* stream) {
     if (c == nullptr || d_kv_fp16_out == nullptr) return SALI_ERR_NULL;
     return sali_kv_decompress_batch(c, frame_id, 1, &d_kv_fp16_out, d_valid576_or_null, stream);
+}
+
+int sali_attend_decode(sali_ctx* c, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
+                       float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
+    if (c == nullptr || d_q_fp16 == nullptr || d_out == nullptr) return SALI_ERR_NULL;
+    if (layer < 0 || layer >= c->cfg.n_layers) return SALI_ERR_SHAPE;
+    if (frame_lo < 0 || frame_hi < frame_lo || frame_hi > c->cfg.max_frames) return SALI_ERR_SHAPE;
+    if (!aligned16(d_q_fp16)) return SALI_ERR_ALIGN;
+    if (!(softmax_scale == softmax_scale)) return SALI_ERR_CONFIG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t* ev = c->prof[SALI_PROF_ATTEND];
+    const hipError_t e = launch_attend(c->rows(), c->pools, layer, c->cfg.n_heads, d_q_fp16, frame_lo, frame_hi,
+                                       softmax_scale, c->sc<float>(c->sl.attn_partial), d_out, d_lse_or_null, ev[0],
+                                       ev[1], s);
+    ev[0] = ev[1] = nullptr;
+    return e == hipSuccess ? SALI_OK : SALI_ERR_HIP;
 }
 
 int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t first_frame_id, int32_t n_frames,
@@ -839,7 +857,7 @@ int sali_read_last_step(sali_ctx* c, float* h_patch_motion576, sali_gate* h_gate
 
 int sali_set_profile_events(sali_ctx* c, int which, void* start_event, void* stop_event) {
     if (c == nullptr) return SALI_ERR_NULL;
-    if (which != SALI_PROF_PACK && which != SALI_PROF_UNPACK) return SALI_ERR_SHAPE;
+    if (which != SALI_PROF_PACK && which != SALI_PROF_UNPACK && which != SALI_PROF_ATTEND) return SALI_ERR_SHAPE;
     c->prof[which][0] = static_cast<hipEvent_t>(start_event);
     c->prof[which][1] = static_cast<hipEvent_t>(stop_event);
     return SALI_OK;

@@ -17,6 +17,7 @@ constexpr int kGroup = 32;                  // quantisation group along head_dim
 constexpr int kGroupsPerRow = kHeadDim / kGroup;
 constexpr int kMaxLevels = 6;
 constexpr int kMaxIters = 8;
+constexpr int kAttnPartials = 128;          // partial softmax states per head in the attention kernel
 constexpr int kMaxBatch = SALI_MAX_BATCH;   // frames analysed by one set of launches (blockIdx.z / .y)
 
 // flow constants (polynomial expansion 7x7 sigma 1.5; aggregation window 11x11 sigma 2.5;
@@ -140,6 +141,13 @@ hipError_t launch_pack(const KvBatch& f, int n, const sali_frame_row* d_rows, in
 hipError_t launch_unpack(const sali_frame_row* d_rows, int first_frame_id, const uint16_t* d_order_base, Pools pools,
                          const KvBatch& out, int n, uint8_t* d_valid_or_null, Cursors* d_cur, int n_planes,
                          hipStream_t s);
+
+// attn_kernels.hip: single-query attention of one layer over frames [frame_lo, frame_hi);
+// d_partial holds n_heads * kAttnPartials * (kHeadDim + 2) floats; the events (may be NULL) bracket
+// the main kernel
+hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, int n_heads, const void* d_q,
+                         int frame_lo, int frame_hi, float softmax_scale, float* d_partial, float* d_out,
+                         float* d_lse_or_null, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s);
 
 // saliency_kernels.hip
 // n = frames in the batch (1..kMaxBatch); with_saliency = false converts to gray only (n must be 1)

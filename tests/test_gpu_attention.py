@@ -1,0 +1,166 @@
+"""GPU parity of sali_attend_decode (single-query attention that dequantises the mixed-precision
+pools on the fly) against the attention oracle, through the C ABI.
+
+Tolerance: the kernel works in fp32 on the same dequantise-on-read values as the oracle (float64).
+A logit is a sum of 128 exact fp16 x fp16 products, the softmax sums run over up to ~10^5 tokens;
+both stay far below the 1e-3 relative + 1e-4 absolute bound used for floating-point results here
+(the largest error met is printed)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.attention import attend_decode
+from oracle.cache import SaliCacheOracle
+from paper_2602_14236_amd import synth
+
+from _util import lib_config, oracle_config, params, workload_params
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-3, 1e-4
+
+
+def _check(ctx, orc, layer, q, lo, hi, scale, what):
+    n_heads = q.shape[0]
+    out = torch.full((n_heads, 128), 7.0, dtype=torch.float32, device="cuda")
+    lse = torch.full((n_heads,), 7.0, dtype=torch.float32, device="cuda")
+    ctx.attend_decode(layer, q, lo, hi, scale, out, lse)
+    torch.cuda.synchronize()
+    exp_out, exp_lse = attend_decode(orc, layer, q.cpu().numpy(), lo, hi, scale)
+    got, got_lse = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    err = np.abs(got - exp_out)
+    assert np.all(err <= ATOL + RTOL * np.abs(exp_out)), f"{what}: out, max error {err.max():.3e}"
+    if np.all(np.isneginf(exp_lse)):
+        assert np.all(np.isneginf(got_lse)) and not got.any(), f"{what}: empty range"
+    else:
+        assert np.all(np.abs(got_lse - exp_lse) <= ATOL + RTOL * np.abs(exp_lse)), f"{what}: lse"
+    return float(err.max())
+
+
+def _q(seed, n_heads):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return torch.randn((n_heads, 128), generator=g).to(torch.float16).cuda()
+
+
+def test_attend_after_chained_steps_all_tiers_pointers_and_cuts():
+    """Config 5 frames 0..11: threshold tiers (FP16, INT8, INT4 and pruned tokens), exact duplicates
+    5..8 (pointer entries), two layers and three heads; whole range, ranges that start inside the
+    pointer run, a pointer frame alone, an empty range."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[5]
+    n, nl, nh = 12, 2, 3
+    v = synth.video(5, 32)
+    p = workload_params(wl, frames=n, n_layers=nl, n_heads=nh)
+    scale_c = synth.kv_channel_scale(wl, nl, nh)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    for t in range(n):
+        print(f"frame {t} ({v.kind(t)})", flush=True)
+        kv = synth.kv_frame(wl, t, device="cuda", n_layers=nl, n_heads=nh, scale=scale_c)
+        ctx.step(torch.from_numpy(v.frame(t)).cuda(), kv, t)
+        orc.step(v.frame(t), kv.cpu().numpy(), t)
+    torch.cuda.synchronize()
+    stored = [orc.rows[t].stored for t in range(n)]
+    assert stored[5:9] == [0, 0, 0, 0] and stored[4] == 1
+    assert any(int((orc.tier[t] == 3).sum()) > 0 for t in orc.tier) and any(int((orc.tier[t] == 2).sum()) > 0 for t in orc.tier)
+    sm = 1.0 / math.sqrt(128.0)
+    worst = 0.0
+    for layer in range(nl):
+        q = _q(100 + layer, nh)
+        for lo, hi in ((0, n), (6, 9), (5, 6), (7, n), (0, 1), (3, 3), (4, 10)):
+            worst = max(worst, _check(ctx, orc, layer, q, lo, hi, sm, f"layer {layer} frames [{lo}, {hi})"))
+    # a large softmax scale: one token dominates
+    worst = max(worst, _check(ctx, orc, 0, _q(7, nh), 0, n, 4.0, "sharp softmax"))
+    print(f"largest |out - oracle| = {worst:.3e}", flush=True)
+    assert ctx.get_status() == 0
+    ctx.close()
+
+
+def test_attend_long_range_many_frames_per_block():
+    """150 stored frames of one head (top-k tiers 173 / 259 / 100, 44 pruned): more frames than
+    partial slots, so a block walks several frames; also a range that is not a multiple of the
+    chunk size."""
+    from paper_2602_14236_amd import binding
+    n = 150
+    p = params(96, 96, tier_mode=1, k_fp16=173, k_int8=259, k_int4=100, n_layers=1, n_heads=1, cap_fp16=173 * n,
+               cap_int8=259 * n, cap_int4=100 * n, max_frames=n)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    g = torch.Generator(device="cpu").manual_seed(5)
+    for t in range(n):
+        kv = (torch.randn((1, 2, 1, 576, 128), generator=g) * 0.7).to(torch.float16)
+        scores = torch.rand(576, generator=g)
+        ctx.kv_compress(kv.cuda(), scores.cuda(), t)
+        orc.kv_compress(kv.numpy(), scores.numpy(), t)
+    torch.cuda.synchronize()
+    q = _q(9, 1)
+    sm = 1.0 / math.sqrt(128.0)
+    worst = max(_check(ctx, orc, 0, q, 0, n, sm, "150 frames"), _check(ctx, orc, 0, q, 11, 140, sm, "129 frames"),
+                _check(ctx, orc, 0, q, 20, 33, sm, "13 frames"))
+    print(f"largest |out - oracle| = {worst:.3e}", flush=True)
+    ctx.close()
+
+
+def test_attend_full_shape_sampled_layers():
+    """The benchmark's K/V shape (32 layers x 32 heads, config 2's 173 fp16 / 403 int8 split) for 8
+    frames in the launch configuration bench.py times; the oracle holds one sampled layer at a time."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[2]
+    n = 8
+    p = workload_params(wl, frames=n)
+    ctx = binding.SaliContext(lib_config(p))
+    scale_c = synth.kv_channel_scale(wl, wl.n_layers)
+    g = torch.Generator(device="cpu").manual_seed(3)
+    scores = [torch.rand(576, generator=g) for _ in range(n)]
+    layers = (0, 17, 31)
+    p1 = dict(p)
+    p1["n_layers"] = 1
+    orcs = {L: SaliCacheOracle(oracle_config(p1)) for L in layers}
+    for t in range(n):
+        print(f"frame {t}", flush=True)
+        kv = synth.kv_frame(wl, t, device="cuda", scale=scale_c)
+        ctx.kv_compress(kv, scores[t].cuda(), t)
+        for L in layers:
+            orcs[L].kv_compress(kv[L:L + 1].cpu().numpy(), scores[t].numpy(), t)
+        del kv
+    torch.cuda.synchronize()
+    sm = 1.0 / math.sqrt(128.0)
+    worst = 0.0
+    for L in layers:
+        q = _q(40 + L, wl.n_heads)
+        n_heads = wl.n_heads
+        out = torch.empty((n_heads, 128), dtype=torch.float32, device="cuda")
+        lse = torch.empty((n_heads,), dtype=torch.float32, device="cuda")
+        ctx.attend_decode(L, q, 0, n, sm, out, lse)
+        torch.cuda.synchronize()
+        exp_out, exp_lse = attend_decode(orcs[L], 0, q.cpu().numpy(), 0, n, sm)
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exp_out)
+        assert np.all(err <= ATOL + RTOL * np.abs(exp_out)), f"layer {L}: max error {err.max():.3e}"
+        assert np.all(np.abs(lse.cpu().numpy().astype(np.float64) - exp_lse) <= ATOL + RTOL * np.abs(exp_lse))
+        worst = max(worst, float(err.max()))
+    print(f"largest |out - oracle| = {worst:.3e}", flush=True)
+    assert ctx.get_status() == 0
+    ctx.close()
+
+
+def test_attend_argument_checks():
+    from paper_2602_14236_amd import binding
+    p = params(96, 96, n_layers=2, n_heads=2, cap_fp16=576, cap_int8=576, cap_int4=576, max_frames=4)
+    ctx = binding.SaliContext(lib_config(p))
+    q = _q(1, 2)
+    out = torch.empty((2, 128), dtype=torch.float32, device="cuda")
+    for args in ((2, q, 0, 1), (-1, q, 0, 1), (0, q, 2, 1), (0, q, 0, 5), (0, q, -1, 2)):
+        with pytest.raises(binding.SaliError) as e:
+            ctx.attend_decode(args[0], args[1], args[2], args[3], 1.0, out)
+        assert e.value.code == -2
+    with pytest.raises(binding.SaliError) as e:
+        ctx.attend_decode(0, None, 0, 1, 1.0, out)
+    assert e.value.code == -1
+    # nothing stored yet: zeros and -inf
+    lse = torch.empty(2, dtype=torch.float32, device="cuda")
+    ctx.attend_decode(1, q, 0, 4, 1.0, out, lse)
+    torch.cuda.synchronize()
+    assert not out.cpu().numpy().any() and np.all(np.isneginf(lse.cpu().numpy()))
+    ctx.close()
