@@ -12,10 +12,15 @@ formula beyond that, so the oracle is the plain definition written out:
     p     = softmax(s)
     out_h = sum_j p_j V^_j,      lse_h = log sum_j exp(s_j)
 
-where K^, V^ are exactly what dequantise-on-read returns (oracle.cache:
-fp16-rounded values; FP16-tier rows verbatim) and everything else is float64.
+where K^, V^ are the dequantised cache entries and everything is float64.
 
-Readings (the paper is silent on all three):
+Readings (the paper is silent on all four):
+  * "fused" (Implementation Details) is read as: the dequantised values never
+    exist as an fp16 tensor.  K^ = code * scale (INT8), code * scale + zero
+    (INT4), taken as exact real numbers of the stored codes, fp32 scales and
+    fp16 zero-points; FP16-tier rows are used as stored.  This differs from
+    attention over the output of dequantise-on-read (which rounds every value
+    to fp16) by at most 2^-11 relative per element; a pin bounds the gap;
   * the cached sequence is the LOGICAL one: frames frame_lo .. frame_hi - 1 in
     order, each contributing the kept tokens of its cache entry.  A redundant
     frame's entry is a pointer (Algorithm 1), so the tokens of its source
@@ -27,12 +32,28 @@ Readings (the paper is silent on all three):
 
 Pins (tests/test_oracle_attention.py): a library scaled-dot-product attention
 on an all-FP16 cache, the uniform-logits closed form (mean of V^, lse = log n),
-a dominant key, brute-force Python loops with a pointer frame and pruned
-tokens, and the log-sum-exp merge of two frame ranges.
+a dominant key, brute-force Python loops from the raw codes with a pointer
+frame and pruned tokens, the log-sum-exp merge of two frame ranges, and the
+bounded gap to attention over the dequantise-on-read output.
 """
 from __future__ import annotations
 
 import numpy as np
+
+from . import quant as oq
+
+
+def _dequantised_rows(cache, layer, which, row):
+    """The kept tokens of stored frame `row` in pool order, K (which = 0) or V (1):
+    float64 [n_heads, n16 + n8 + n4, head_dim], no rounding."""
+    g = oq.GROUP
+    p16 = cache.pool16[layer, which][:, row.base16:row.base16 + row.n16, :].astype(np.float64)
+    c8 = cache.codes8[layer, which][:, row.base8:row.base8 + row.n8, :].astype(np.float64)
+    s8 = np.repeat(cache.scale8[layer, which][:, row.base8:row.base8 + row.n8, :].astype(np.float64), g, axis=-1)
+    c4 = oq.unpack_nibbles(cache.codes4[layer, which][:, row.base4:row.base4 + row.n4, :]).astype(np.float64)
+    s4 = np.repeat(cache.scale4[layer, which][:, row.base4:row.base4 + row.n4, :].astype(np.float64), g, axis=-1)
+    z4 = np.repeat(cache.zero4[layer, which][:, row.base4:row.base4 + row.n4, :].astype(np.float64), g, axis=-1)
+    return np.concatenate([p16, c8 * s8, c4 * s4 + z4], axis=1)
 
 
 def cached_tokens(cache, layer, frame_lo, frame_hi):
@@ -43,10 +64,9 @@ def cached_tokens(cache, layer, frame_lo, frame_hi):
         row = cache.rows.get(f)
         if row is None or row.src < 0:
             continue
-        kv, valid = cache.kv_decompress(f)
-        keep = np.nonzero(valid)[0]
-        ks.append(kv[layer, 0][:, keep, :].astype(np.float64))
-        vs.append(kv[layer, 1][:, keep, :].astype(np.float64))
+        src = cache.rows[row.src]
+        ks.append(_dequantised_rows(cache, layer, 0, src))
+        vs.append(_dequantised_rows(cache, layer, 1, src))
     c = cache.cfg
     if not ks:
         empty = np.zeros((c.n_heads, 0, c.head_dim), dtype=np.float64)

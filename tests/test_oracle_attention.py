@@ -35,6 +35,29 @@ def _mixed_scores(seed):
     return (rng.integers(0, 40, 576) / 64.0).astype(np.float32)
 
 
+def _token_value(cache, src, tok, which, head=0, layer=0):
+    """Dequantised K (which = 0) or V (1) of one token of stored frame `src`, from the raw pool
+    entries: 128 Python floats, no rounding (None if the token is pruned)."""
+    tier, slot = int(cache.tier[src][tok]), int(cache.slot[src][tok])
+    row = cache.rows[src]
+    if tier == oq.T_PRUNE:
+        return None
+    if tier == oq.T_FP16:
+        return [float(x) for x in cache.pool16[layer, which, head, row.base16 + slot]]
+    if tier == oq.T_INT8:
+        codes = cache.codes8[layer, which, head, row.base8 + slot]
+        scale = cache.scale8[layer, which, head, row.base8 + slot]
+        return [int(codes[d]) * float(scale[d // 32]) for d in range(128)]
+    packed = cache.codes4[layer, which, head, row.base4 + slot]
+    scale = cache.scale4[layer, which, head, row.base4 + slot]
+    zero = cache.zero4[layer, which, head, row.base4 + slot]
+    out = []
+    for d in range(128):
+        code = (int(packed[d // 2]) >> (4 * (d % 2))) & 0xF        # element 2k in the low nibble of byte k
+        out.append(code * float(scale[d // 32]) + float(zero[d // 32]))
+    return out
+
+
 def _pointer(cache, frame_id):
     """Algorithm 1, redundant frame: the entry is a pointer to the last stored frame."""
     cache.rows[frame_id] = FrameRow(frame_id, cache.last_src, 0)
@@ -67,9 +90,14 @@ def test_zero_query_gives_mean_of_cached_values_and_log_count():
     tier = oq.tiers_threshold(scores, 0.30, 0.15, 0.03)
     n_kept = int((tier != oq.T_PRUNE).sum())
     assert 0 < n_kept < 576
-    dense = [c.kv_decompress(f)[0] for f in (0, 1)]
-    mean_v = sum(d[0, 1][:, tier != oq.T_PRUNE, :].astype(np.float64).sum(axis=1) for d in dense) / (2 * n_kept)
-    assert np.allclose(out, mean_v, rtol=1e-12, atol=1e-14)
+    for head in (0, 1):
+        total = np.zeros(128)
+        for f in (0, 1):
+            for tok in range(576):
+                v = _token_value(c, f, tok, 1, head=head)
+                if v is not None:
+                    total += np.array(v)
+        assert np.allclose(out[head], total / (2 * n_kept), rtol=1e-12, atol=1e-14)
     assert np.allclose(lse, math.log(2 * n_kept), rtol=1e-13)
 
 
@@ -96,14 +124,12 @@ def test_brute_force_loops_with_pointer_frame_and_pruned_tokens():
     logits, values = [], []
     for f in (0, 1, 2):
         src = c.rows[f].src
-        dense, _ = c.kv_decompress(src)
-        tier = c.tier[src]
         for tok in range(576):
-            if tier[tok] == oq.T_PRUNE:
+            kvec = _token_value(c, src, tok, 0)
+            if kvec is None:
                 continue
-            kvec, vvec = dense[0, 0, 0, tok], dense[0, 1, 0, tok]
-            logits.append(scale * sum(float(a) * float(b) for a, b in zip(q[0], kvec)))
-            values.append([float(x) for x in vvec])
+            logits.append(scale * sum(float(a) * b for a, b in zip(q[0], kvec)))
+            values.append(_token_value(c, src, tok, 1))
     m = max(logits)
     w = [math.exp(x - m) for x in logits]
     z = sum(w)
@@ -174,3 +200,28 @@ def test_empty_cache_range():
     c.rows[1] = FrameRow(1, -1, 0)                                 # dropped frame
     out, lse = attend_decode(c, 0, _q(61), 0, 3, 1.0)
     assert not out.any() and np.all(np.isneginf(lse))
+
+
+def test_gap_to_attention_over_dequantise_on_read_output_is_bounded():
+    """The fused reading uses unrounded dequantised values; dequantise-on-read rounds each to fp16
+    (relative 2^-11).  The two attentions must agree to about that, and they must not be equal
+    (otherwise the reading would not matter)."""
+    c = _cache(frames=2)
+    for f in range(2):
+        c.kv_compress(_kv(70 + f), _mixed_scores(20 + f), f)
+    q = _q(71)
+    scale = 1.0 / math.sqrt(128.0)
+    out, _ = attend_decode(c, 0, q, 0, 2, scale)
+    ks, vs = [], []
+    for f in range(2):
+        dense, valid = c.kv_decompress(f)
+        ks.append(dense[0, 0][:, valid == 1, :].astype(np.float64))
+        vs.append(dense[0, 1][:, valid == 1, :].astype(np.float64))
+    k, v = np.concatenate(ks, axis=1), np.concatenate(vs, axis=1)
+    ref = np.zeros_like(out)
+    for h in range(2):
+        s_ = scale * (k[h] @ q[h].astype(np.float64))
+        e = np.exp(s_ - s_.max())
+        ref[h] = (e / e.sum()) @ v[h]
+    gap = np.abs(out - ref).max()
+    assert 0.0 < gap < 2e-3 * np.abs(v).max()
