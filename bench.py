@@ -283,6 +283,34 @@ def main():
             "one_stream_sali_step_only_fps": steps / elapsed_serial_step_only,
             "one_stream_sali_step_only_hbm_frac": (img_b + pack_b) / elapsed_serial_step_only / HBM_PEAK,
         }
+    # Just-In-Time Dequantization fused with attention: one decode step = sali_attend_decode of every
+    # layer over all cached frames (the state the last pass left in the pools), HIP events around the
+    # main kernel of each call.  Algorithmic bytes = the compressed K and V rows of the layer, once.
+    attn_ev = make_events(n_layers)
+    q = torch.randn((wl.n_heads, 128), device=dev).to(torch.float16)
+    attn_out = torch.empty((wl.n_heads, 128), dtype=torch.float32, device=dev)
+    attn_lse = torch.empty((wl.n_heads,), dtype=torch.float32, device=dev)
+    sm_scale = 1.0 / 128.0 ** 0.5
+    for rep in range(2):                    # the first repetition warms up
+        torch.cuda.synchronize()
+        t_attn = time.perf_counter()
+        for layer in range(n_layers):
+            if rep == 1:
+                ctx.set_profile_events(2, *attn_ev[layer])
+            ctx.attend_decode(layer, q, 0, steps, sm_scale, attn_out, attn_lse, s_kv)
+        torch.cuda.synchronize()
+        t_attn = time.perf_counter() - t_attn
+    attn_ms = [a.elapsed_time(b) for a, b in attn_ev]
+    row_bytes = (256.0, 144.0, 88.0)        # fp16 row; int8 codes + scales; int4 codes + scales + zero-points
+    attn_b = sum(2.0 * wl.n_heads * sum(n * b for n, b in zip((r.n16, r.n8, r.n4), row_bytes)) for r in rows if r.stored)
+    attn_s = sum(attn_ms) / 1e3 / n_layers
+    result["attend_decode"] = {
+        "bound": "hbm", "kernel": "k_attn_partial", "avg_launch_us": attn_s * 1e6,
+        "algorithmic_bytes_per_launch": attn_b, "achieved": attn_b / attn_s / 1e9 if attn_s > 0 else 0.0,
+        "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": attn_b / attn_s / HBM_PEAK if attn_s > 0 else 0.0,
+        "decode_step_ms_all_layers": t_attn * 1e3, "frames": steps,
+        "what": "single-query attention of one layer over all cached frames, pools read directly",
+    }
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)

