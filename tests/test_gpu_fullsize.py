@@ -1,5 +1,6 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
-(sali_step_pipelined with look-ahead 2 on three streams + sali_kv_decompress).
+(sali_analyze_batch of four frames one batch ahead on two image streams; sali_store_batch and
+sali_kv_decompress_batch on a third).
 
 The oracle cannot hold the full pools, so it runs the image side in full (flow, gate, saliency,
 tiers, slots: bit-exact rows / tiers / slots) and quantises a random sample of (layer, K|V, head)
@@ -58,18 +59,22 @@ def _run_fullsize(cfg_id, n_frames, n_sample_planes, seed):
     rgbs = [torch.from_numpy(video.frame(t)).cuda() for t in range(n_frames)]
     kvs = [synth.kv_frame(wl, t, device="cuda", scale=scale) for t in range(n_frames)]
     outs = [torch.empty_like(kvs[0]) for _ in range(n_frames)]
-    look = 2
-    s_imgs = [torch.cuda.Stream() for _ in range(look)]
+    batch = 4
+    s_imgs = [torch.cuda.Stream(), torch.cuda.Stream()]
     s_kv = torch.cuda.Stream()
     torch.cuda.synchronize()
-    print(f"{wl.name}: GPU pipelined run", flush=True)
-    for t in range(min(look, n_frames)):
-        ctx.step_pipelined(rgbs[t], t, None, -1, s_imgs[t % look], s_kv)
-    for t in range(n_frames):
-        a = t + look
-        ctx.step_pipelined(rgbs[a] if a < n_frames else None, a, kvs[t], t, s_imgs[a % look], s_kv)
-        with torch.cuda.stream(s_kv):
-            ctx.kv_decompress(t, outs[t])
+    print(f"{wl.name}: GPU run, {batch} frames per launch, analysis one batch ahead", flush=True)
+    n_batches = (n_frames + batch - 1) // batch
+
+    def analyze(b):
+        if b < n_batches:
+            ctx.analyze_batch(rgbs[b * batch:(b + 1) * batch], b * batch, s_imgs[b % 2])
+
+    analyze(0)
+    for b in range(n_batches):
+        analyze(b + 1)
+        ctx.store_batch(kvs[b * batch:(b + 1) * batch], b * batch, s_kv)
+        ctx.kv_decompress_batch(b * batch, outs[b * batch:(b + 1) * batch], None, s_kv)
     torch.cuda.synchronize()
     assert ctx.get_status() == 0
 
@@ -134,8 +139,8 @@ def _run_fullsize(cfg_id, n_frames, n_sample_planes, seed):
 
 
 def test_config2_full_shape_sampled_planes():
-    """64-frame workload's shape: 336x336, 32 x 2 x 32 planes, top-k 173 fp16 / 403 int8; 4 frames."""
-    ora, rows = _run_fullsize(2, 4, 12, seed=1)
+    """64-frame workload's shape: 336x336, 32 x 2 x 32 planes, top-k 173 fp16 / 403 int8; 6 frames (a batch of four and one of two)."""
+    ora, rows = _run_fullsize(2, 6, 12, seed=1)
     assert all(o["stored"] for o in ora)
 
 
