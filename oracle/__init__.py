@@ -17,8 +17,10 @@ Pins (tests/test_oracle_*.py, CPU only):
   flow      zero flow on identical frames; exact recovery of the expansion of a quadratic
             image and of its translate; integer translation of a textured image; the
             lambda = 0 single-iteration case against an independently written weighted
-            least-squares solve; rational gate boundary.  Flow on general textures has no
-            library equal: beyond these invariants it is PARITY UNPINNED.
+            least-squares solve; rational gate boundary; and the whole coarse-to-fine
+            estimate on a tiny sub-pixel-shifted texture against a second, pixel-by-pixel
+            implementation of the definition (per-pixel lstsq expansion, direct 2-D window
+            sums of 2x2 matrix products, np.linalg.solve), to 1e-9.
   saliency  brute-force loops on 8x8 images, CIE L*a*b* closed form within one level,
             step edges, hysteresis chains, uniform-variance image.
   quant     round-trip error <= scale/2, power-of-two scaling invariance, negation,
