@@ -488,15 +488,24 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
         if (atomicAdd(batch_done, 1u) == gridDim.y - 1u) {
             __threadfence();
             *batch_done = 0u;
-            for (int i = 0; i < (int)gridDim.y; ++i) {
-                const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
-                TierCounts ti;
-                ti.state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // all counts first (independent loads), then the rows with the cursors in registers
+            TierCounts all[kMaxBatch];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    ti.cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                tier_commit(ti, tl.frame_id + i, tl.rows, tl.cur, tl.cap16, tl.cap8, tl.cap4);
+            for (int i = 0; i < kMaxBatch; ++i) {
+                all[i] = {};
+                if (i < (int)gridDim.y) {
+                    const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
+                    all[i].state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        all[i].cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
+            CursorRegs cr = cursor_load(tl.cur);
+#pragma unroll
+            for (int i = 0; i < kMaxBatch; ++i)
+                if (i < (int)gridDim.y) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4);
+            cursor_store(tl.cur, cr);
         }
     }
 }

@@ -27,8 +27,42 @@ struct TierCounts {
 struct TierShared {
     uint4 key4[kTokens / 4];        // order-preserving integer image of the scores
     int group_cnt[kTierGroups][4];
+    int part_rank[4][64];           // partial ranks of tokens 512..575, one row per wave
     int nan_flag;
 };
+
+// Number of tokens j in key blocks [j4_lo, j4_hi) (four keys per block) that precede token i in
+// (key descending, index ascending) order; `me` = key of token i.  Blocks before the token's own
+// 64-token group count with >=, blocks after it with >, and only the 16 blocks of the own group
+// need the index test.  128-bit broadcast LDS reads, eight in flight.
+__device__ __forceinline__ int tier_count_above(const TierShared& sh, uint32_t me, int i, int j4_lo, int j4_hi) {
+    const int own0 = (i >> 6) * 16, own1 = own0 + 16;
+    int rank = 0;
+    const int a1 = own0 < j4_hi ? own0 : j4_hi;          // [j4_lo, a1): earlier groups
+    const int b0 = own0 > j4_lo ? own0 : j4_lo;          // [b0, b1): own group
+    const int b1 = own1 < j4_hi ? own1 : j4_hi;
+    const int c0 = own1 > j4_lo ? own1 : j4_lo;          // [c0, j4_hi): later groups
+#pragma unroll 8
+    for (int j4 = j4_lo; j4 < a1; ++j4) {
+        const uint4 v = sh.key4[j4];
+        rank += (v.x >= me ? 1 : 0) + (v.y >= me ? 1 : 0) + (v.z >= me ? 1 : 0) + (v.w >= me ? 1 : 0);
+    }
+#pragma unroll 8
+    for (int j4 = b0; j4 < b1; ++j4) {
+        const uint4 v = sh.key4[j4];
+        const int j = 4 * j4;
+        rank += (v.x > me || (v.x == me && j < i)) ? 1 : 0;
+        rank += (v.y > me || (v.y == me && j + 1 < i)) ? 1 : 0;
+        rank += (v.z > me || (v.z == me && j + 2 < i)) ? 1 : 0;
+        rank += (v.w > me || (v.w == me && j + 3 < i)) ? 1 : 0;
+    }
+#pragma unroll 8
+    for (int j4 = c0; j4 < j4_hi; ++j4) {
+        const uint4 v = sh.key4[j4];
+        rank += (v.x > me ? 1 : 0) + (v.y > me ? 1 : 0) + (v.z > me ? 1 : 0) + (v.w > me ? 1 : 0);
+    }
+    return rank;
+}
 
 // Assigns tier, slot (rank inside the tier in token order) and the pool-order token list of one
 // non-redundant frame.  Returns the per-tier counts (every thread gets the same value).
@@ -66,46 +100,43 @@ __device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const float* sco
     }
 
     int tier[kTierSlots];
+    if (tp.mode == 0) {
 #pragma unroll
-    for (int k = 0; k < kTierSlots; ++k) {
-        const int i = tid + k * kTierThreads;
-        tier[k] = SALI_TIER_PRUNE;
-        if (i >= kTokens) continue;
-        if (tp.mode == 0) {
+        for (int k = 0; k < kTierSlots; ++k) {
+            const int i = tid + k * kTierThreads;
+            tier[k] = SALI_TIER_PRUNE;
+            if (i >= kTokens) continue;
             // Eq. 8, inequalities as printed
             if (s[k] > tp.tau_low) tier[k] = SALI_TIER_INT4;
             if (s[k] > tp.tau_med) tier[k] = SALI_TIER_INT8;
             if (s[k] > tp.tau_high) tier[k] = SALI_TIER_FP16;
-        } else {
-            // rank by (score descending, token index ascending) = number of tokens j with a larger
-            // key, or an equal key and j < i.  Tokens of earlier groups count with >=, of later
-            // groups with >, so only the 64 tokens of the own group need the index test.  All
-            // lanes of a wave share the group, hence the loop bounds; 128-bit broadcast LDS reads.
-            const uint32_t me = key[k];
-            int rank = 0;
-            const int own0 = (i >> 6) * 16, own1 = own0 + 16;
-#pragma unroll 4
-            for (int j4 = 0; j4 < own0; ++j4) {
-                const uint4 v = sh.key4[j4];
-                rank += (v.x >= me ? 1 : 0) + (v.y >= me ? 1 : 0) + (v.z >= me ? 1 : 0) + (v.w >= me ? 1 : 0);
-            }
-#pragma unroll 4
-            for (int j4 = own0; j4 < own1; ++j4) {
-                const uint4 v = sh.key4[j4];
-                const int j = 4 * j4;
-                rank += (v.x > me || (v.x == me && j < i)) ? 1 : 0;
-                rank += (v.y > me || (v.y == me && j + 1 < i)) ? 1 : 0;
-                rank += (v.z > me || (v.z == me && j + 2 < i)) ? 1 : 0;
-                rank += (v.w > me || (v.w == me && j + 3 < i)) ? 1 : 0;
-            }
-#pragma unroll 4
-            for (int j4 = own1; j4 < kTokens / 4; ++j4) {
-                const uint4 v = sh.key4[j4];
-                rank += (v.x > me ? 1 : 0) + (v.y > me ? 1 : 0) + (v.z > me ? 1 : 0) + (v.w > me ? 1 : 0);
-            }
-            if (rank < tp.k16 + tp.k8 + tp.k4) tier[k] = SALI_TIER_INT4;
-            if (rank < tp.k16 + tp.k8) tier[k] = SALI_TIER_INT8;
-            if (rank < tp.k16) tier[k] = SALI_TIER_FP16;
+        }
+    } else {
+        // rank by (score descending, token index ascending) = number of tokens j with a larger key,
+        // or an equal key and j < i.  Work is dealt evenly: tokens 0..511 are two per thread against
+        // all 576 keys; the last 64 tokens are taken by all four waves, a quarter of the keys each
+        // (partial counts meet in LDS).  All lanes of a wave share the 64-token group of their
+        // token, so the comparison regime of a key block is uniform in the wave.
+        int rank[kTierSlots];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) rank[k] = tier_count_above(sh, key[k], tid + k * kTierThreads, 0, kTokens / 4);
+        {
+            const int wave = tid >> 6;
+            const int i = 2 * kTierThreads + lane;                      // 512 + lane, every wave
+            const uint32_t me = reinterpret_cast<const uint32_t*>(sh.key4)[i];
+            const int part = tier_count_above(sh, me, i, wave * (kTokens / 16), (wave + 1) * (kTokens / 16));
+            sh.part_rank[wave][lane] = part;
+        }
+        __syncthreads();
+        rank[2] = sh.part_rank[0][lane] + sh.part_rank[1][lane] + sh.part_rank[2][lane] + sh.part_rank[3][lane];
+#pragma unroll
+        for (int k = 0; k < kTierSlots; ++k) {
+            const int i = tid + k * kTierThreads;
+            tier[k] = SALI_TIER_PRUNE;
+            if (i >= kTokens) continue;
+            if (rank[k] < tp.k16 + tp.k8 + tp.k4) tier[k] = SALI_TIER_INT4;
+            if (rank[k] < tp.k16 + tp.k8) tier[k] = SALI_TIER_INT8;
+            if (rank[k] < tp.k16) tier[k] = SALI_TIER_FP16;
         }
     }
 
@@ -157,45 +188,70 @@ __device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const float* sco
     return res;
 }
 
-// Frame-table row and pool cursors of one frame; ONE thread, frames in video order.
-__device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, sali_frame_row* rows, Cursors* cur,
-                                            int cap16, int cap8, int cap4) {
+// Cursor state carried in registers through the frames of one commit pass.
+struct CursorRegs {
+    int32_t c16, c8, c4, last_src;
+    uint32_t faults;
+};
+
+// Frame-table row of one frame from its counts and the running cursors; ONE thread, frames in
+// video order.
+__device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_id, sali_frame_row* rows,
+                                                CursorRegs& cr, int cap16, int cap8, int cap4) {
     sali_frame_row r = {};
     r.frame_id = frame_id;
     if (tc.state == 1) {
         // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame.
-        r.src = cur->last_src;
+        r.src = cr.last_src;
         r.stored = 0;
-        rows[frame_id] = r;
-        return;
-    }
-    if (tc.state == 2) {
-        atomicOr(&cur->status, SALI_FAULT_NAN_SCORE);
+    } else if (tc.state == 2) {
+        cr.faults |= SALI_FAULT_NAN_SCORE;
         r.src = -1;
-        rows[frame_id] = r;
-        return;
-    }
-    const int c16 = cur->c16, c8 = cur->c8, c4 = cur->c4;
-    if ((long long)c16 + tc.cnt[0] > cap16 || (long long)c8 + tc.cnt[1] > cap8 || (long long)c4 + tc.cnt[2] > cap4) {
-        atomicOr(&cur->status, SALI_FAULT_OVERFLOW);
+    } else if ((long long)cr.c16 + tc.cnt[0] > cap16 || (long long)cr.c8 + tc.cnt[1] > cap8 ||
+               (long long)cr.c4 + tc.cnt[2] > cap4) {
+        cr.faults |= SALI_FAULT_OVERFLOW;
         r.src = -1;
-        rows[frame_id] = r;
-        return;
+    } else {
+        r.src = frame_id;
+        r.stored = 1;
+        r.base16 = cr.c16;
+        r.base8 = cr.c8;
+        r.base4 = cr.c4;
+        r.n16 = tc.cnt[0];
+        r.n8 = tc.cnt[1];
+        r.n4 = tc.cnt[2];
+        r.n_pruned = tc.cnt[3];
+        cr.c16 += tc.cnt[0];
+        cr.c8 += tc.cnt[1];
+        cr.c4 += tc.cnt[2];
+        cr.last_src = frame_id;
     }
-    r.src = frame_id;
-    r.stored = 1;
-    r.base16 = c16;
-    r.base8 = c8;
-    r.base4 = c4;
-    r.n16 = tc.cnt[0];
-    r.n8 = tc.cnt[1];
-    r.n4 = tc.cnt[2];
-    r.n_pruned = tc.cnt[3];
     rows[frame_id] = r;
-    cur->c16 = c16 + tc.cnt[0];
-    cur->c8 = c8 + tc.cnt[1];
-    cur->c4 = c4 + tc.cnt[2];
-    cur->last_src = frame_id;
+}
+
+__device__ __forceinline__ CursorRegs cursor_load(const Cursors* cur) {
+    CursorRegs cr;
+    cr.c16 = cur->c16;
+    cr.c8 = cur->c8;
+    cr.c4 = cur->c4;
+    cr.last_src = cur->last_src;
+    cr.faults = 0u;
+    return cr;
+}
+
+__device__ __forceinline__ void cursor_store(Cursors* cur, const CursorRegs& cr) {
+    cur->c16 = cr.c16;
+    cur->c8 = cr.c8;
+    cur->c4 = cr.c4;
+    cur->last_src = cr.last_src;
+    if (cr.faults != 0u) atomicOr(&cur->status, cr.faults);
+}
+
+__device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, sali_frame_row* rows, Cursors* cur,
+                                            int cap16, int cap8, int cap4) {
+    CursorRegs cr = cursor_load(cur);
+    tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4);
+    cursor_store(cur, cr);
 }
 
 // both parts for one frame (whole block)
