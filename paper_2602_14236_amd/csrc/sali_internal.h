@@ -130,6 +130,32 @@ struct FlowWeights {
     float m2;
 };
 
+// XCD-aware block order.  The hardware deals the workgroups of a launch round-robin to the 8 XCDs
+// in linear-id order (x fastest), and every XCD has an L2 of its own: with the plain order
+// neighbouring tiles land on different XCDs and every L2 ends up holding every frame.  This maps
+// the hardware id to a logical (x, y, z) such that each XCD works through one contiguous run of the
+// (z, y, x) order: tiles that share halos share an L2, and an L2 holds an eighth of the data.
+struct BlockId {
+    int x, y, z;
+};
+#ifdef __HIPCC__
+__device__ __forceinline__ BlockId xcd_block_id() {
+    constexpr int kXcds = 8;
+    const int gx = (int)gridDim.x, gy = (int)gridDim.y;
+    const int total = gx * gy * (int)gridDim.z;
+    const int linear = (int)blockIdx.x + gx * ((int)blockIdx.y + gy * (int)blockIdx.z);
+    const int q = total / kXcds, r = total % kXcds;
+    const int xcd = linear % kXcds, slot = linear / kXcds;
+    const int logical = xcd * q + (xcd < r ? xcd : r) + slot;      // XCDs 0..r-1 hold q + 1 blocks
+    BlockId b;
+    b.z = logical / (gx * gy);
+    const int rem = logical - b.z * (gx * gy);
+    b.y = rem / gx;
+    b.x = rem - b.y * gx;
+    return b;
+}
+#endif
+
 // ---- launchers (each returns hipGetLastError()) ---------------------------------------------
 // kv_kernels.hip
 hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,

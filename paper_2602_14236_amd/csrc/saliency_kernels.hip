@@ -395,20 +395,35 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
         const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
         uint32_t q = 0;
         float mag = 0.0f;
-        for (int p = (kWaves == 1 ? lane : (int)threadIdx.x); p < area; p += 64 * kWaves) {
-            const int y = ya + p / pw, x = xa + p % pw;
-            const size_t gi = (size_t)y * w + x;
-            const int c = cls[gi];
-            uint32_t e = 0;
-            if (c == 2) e = 1;
-            else if (c == 1) e = (uf_find_settled(parent, (uint32_t)gi | kWeakBit) & kWeakBit) ? 0u : 1u;
-            const uint32_t v = var[gi];
-            const uint32_t cm = ((unsigned long long)v * hw > m && v >= kVMin) ? 1u : 0u;
-            q += e + cm;
-            if (salmap != nullptr) salmap[gi] = (uint8_t)(e + cm);
-            if (flow != nullptr) {
-                const float2 d = flow[gi];
-                mag += d.x * d.x + d.y * d.y;
+        // four pixels per pass, all their loads issued before any is used (the loop is bound by
+        // memory latency, not by work)
+        constexpr int kStride = 64 * kWaves, kUnroll = 4;
+        for (int p0 = (kWaves == 1 ? lane : (int)threadIdx.x); p0 < area; p0 += kStride * kUnroll) {
+            size_t gi[kUnroll];
+            int c[kUnroll];
+            uint32_t v[kUnroll];
+            float2 d[kUnroll];
+            bool ok[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int p = p0 + u * kStride;
+                ok[u] = p < area;
+                const int pp = ok[u] ? p : 0;
+                gi[u] = (size_t)(ya + pp / pw) * w + (xa + pp % pw);
+                c[u] = cls[gi[u]];
+                v[u] = var[gi[u]];
+                d[u] = flow != nullptr ? flow[gi[u]] : make_float2(0.0f, 0.0f);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (!ok[u]) continue;
+                uint32_t e = 0;
+                if (c[u] == 2) e = 1;
+                else if (c[u] == 1) e = (uf_find_settled(parent, (uint32_t)gi[u] | kWeakBit) & kWeakBit) ? 0u : 1u;
+                const uint32_t cm = ((unsigned long long)v[u] * hw > m && v[u] >= kVMin) ? 1u : 0u;
+                q += e + cm;
+                if (salmap != nullptr) salmap[gi[u]] = (uint8_t)(e + cm);
+                mag += d[u].x * d[u].x + d[u].y * d[u].y;
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
