@@ -246,6 +246,14 @@ int sali_step_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, const voi
 int sali_attend_decode(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
                        float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
 
+/* The same with grouped-query attention: the cache holds n_heads K/V heads (the context's
+ * n_heads) and q_per_kv in {1, 2, 4, 8} query heads share each of them; query head j reads K/V
+ * head j / q_per_kv.  d_q_fp16 is [n_heads * q_per_kv][128], d_out [n_heads * q_per_kv][128],
+ * d_lse_or_null [n_heads * q_per_kv].  Every compressed row is still read once per call.
+ * SALI_ERR_SHAPE for another q_per_kv. */
+int sali_attend_decode_gqa(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t q_per_kv, int32_t frame_lo,
+                           int32_t frame_hi, float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
+
 /* One loop body of Algorithm 1 with look-ahead on caller-owned streams: analyses a later
  * frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
  * `image_stream` and stores the K/V of the already analysed frame `frame_id` (d_kv, may be NULL

@@ -14,7 +14,7 @@ formula beyond that, so the oracle is the plain definition written out:
 
 where K^, V^ are the dequantised cache entries and everything is float64.
 
-Readings (the paper is silent on all four):
+Readings (the paper is silent on all of them):
   * "fused" (Implementation Details) is read as: the dequantised values never
     exist as an fp16 tensor.  K^ = code * scale (INT8), code * scale + zero
     (INT4), taken as exact real numbers of the stored codes, fp32 scales and
@@ -27,6 +27,8 @@ Readings (the paper is silent on all four):
     frame appear once more: reuse saves memory, it does not drop the frame
     from the sequence;
   * pruned tokens are not in the cache and take no part in the softmax;
+  * grouped-query attention (the 8-KV-head variants of the model family the paper uses): query
+    head j reads K/V head j // q_per_kv, nothing else changes;
   * frames that hold no data (never stored, or dropped on overflow)
     contribute nothing; with no token at all out = 0 and lse = -inf.
 
@@ -74,21 +76,24 @@ def cached_tokens(cache, layer, frame_lo, frame_hi):
     return np.concatenate(ks, axis=1), np.concatenate(vs, axis=1)
 
 
-def attend_decode(cache, layer, q, frame_lo, frame_hi, softmax_scale):
-    """q: [n_heads, head_dim] (fp16 values).  -> (out float64 [n_heads, head_dim],
-    lse float64 [n_heads])."""
+def attend_decode(cache, layer, q, frame_lo, frame_hi, softmax_scale, q_per_kv=1):
+    """q: [n_heads * q_per_kv, head_dim] (fp16 values); with grouped-query attention query head j
+    reads K/V head j // q_per_kv.  -> (out float64 [n_q, head_dim], lse float64 [n_q])."""
     k, v = cached_tokens(cache, layer, frame_lo, frame_hi)
     qf = np.asarray(q).astype(np.float64)
     n_heads, n_tok, d = k.shape
-    out = np.zeros((n_heads, d), dtype=np.float64)
-    lse = np.full(n_heads, -np.inf, dtype=np.float64)
+    n_q = n_heads * q_per_kv
+    assert qf.shape == (n_q, d)
+    out = np.zeros((n_q, d), dtype=np.float64)
+    lse = np.full(n_q, -np.inf, dtype=np.float64)
     if n_tok == 0:
         return out, lse
-    for h in range(n_heads):
-        s = float(softmax_scale) * (k[h] @ qf[h])
+    for j in range(n_q):
+        h = j // q_per_kv
+        s = float(softmax_scale) * (k[h] @ qf[j])
         m = s.max()
         e = np.exp(s - m)
         z = e.sum()
-        out[h] = (e / z) @ v[h]
-        lse[h] = m + np.log(z)
+        out[j] = (e / z) @ v[h]
+        lse[j] = m + np.log(z)
     return out, lse

@@ -89,6 +89,8 @@ EXPORTS = {
                                   C.c_void_p]),
     "sali_attend_decode": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                      C.c_void_p, C.c_void_p]),
+    "sali_attend_decode_gqa": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_step_pipelined": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p]),
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
@@ -237,6 +239,12 @@ class SaliContext:
         s = _stream() if stream is None else stream.cuda_stream
         _check(self.lib.sali_attend_decode(self.handle, layer, _ptr(q), frame_lo, frame_hi, softmax_scale, _ptr(out),
                                            _ptr(lse), s), "sali_attend_decode")
+
+    def attend_decode_gqa(self, layer: int, q, q_per_kv: int, frame_lo: int, frame_hi: int, softmax_scale: float, out,
+                          lse=None, stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_attend_decode_gqa(self.handle, layer, _ptr(q), q_per_kv, frame_lo, frame_hi, softmax_scale,
+                                               _ptr(out), _ptr(lse), s), "sali_attend_decode_gqa")
 
     def store_batch(self, kv_frames, first_frame_id: int, stream: Optional[torch.cuda.Stream] = None):
         s = _stream() if stream is None else stream.cuda_stream

@@ -157,7 +157,7 @@ ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
         s.expA[i] = take(px * sizeof(float4));
         s.expB[i] = take(px * sizeof(float2));
     }
-    s.attn_partial = take((size_t)c.n_heads * kAttnPartials * kAttnPartialStride * sizeof(float));
+    s.attn_partial = take((size_t)c.n_heads * kAttnMaxQPerKv * kAttnPartials * kAttnPartialStride * sizeof(float));
     s.total = o;
     return s;
 }
@@ -669,20 +669,27 @@ int sali_kv_decompress(sali_ctx* c, int32_t frame_id, void* d_kv_fp16_out, uint8
     return sali_kv_decompress_batch(c, frame_id, 1, &d_kv_fp16_out, d_valid576_or_null, stream);
 }
 
-int sali_attend_decode(sali_ctx* c, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
-                       float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
+int sali_attend_decode_gqa(sali_ctx* c, int32_t layer, const void* d_q_fp16, int32_t q_per_kv, int32_t frame_lo,
+                           int32_t frame_hi, float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
     if (c == nullptr || d_q_fp16 == nullptr || d_out == nullptr) return SALI_ERR_NULL;
     if (layer < 0 || layer >= c->cfg.n_layers) return SALI_ERR_SHAPE;
+    if (q_per_kv != 1 && q_per_kv != 2 && q_per_kv != 4 && q_per_kv != 8) return SALI_ERR_SHAPE;
     if (frame_lo < 0 || frame_hi < frame_lo || frame_hi > c->cfg.max_frames) return SALI_ERR_SHAPE;
     if (!aligned16(d_q_fp16)) return SALI_ERR_ALIGN;
     if (!(softmax_scale == softmax_scale)) return SALI_ERR_CONFIG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipEvent_t* ev = c->prof[SALI_PROF_ATTEND];
-    const hipError_t e = launch_attend(c->rows(), c->pools, layer, c->cfg.n_heads, d_q_fp16, frame_lo, frame_hi,
-                                       softmax_scale, c->sc<float>(c->sl.attn_partial), d_out, d_lse_or_null, ev[0],
-                                       ev[1], s);
+    const hipError_t e = launch_attend(c->rows(), c->pools, layer, c->cfg.n_heads, q_per_kv, d_q_fp16, frame_lo,
+                                       frame_hi, softmax_scale, c->sc<float>(c->sl.attn_partial), d_out,
+                                       d_lse_or_null, ev[0], ev[1], s);
     ev[0] = ev[1] = nullptr;
     return e == hipSuccess ? SALI_OK : SALI_ERR_HIP;
+}
+
+int sali_attend_decode(sali_ctx* c, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
+                       float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
+    return sali_attend_decode_gqa(c, layer, d_q_fp16, 1, frame_lo, frame_hi, softmax_scale, d_out, d_lse_or_null,
+                                  stream);
 }
 
 int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t first_frame_id, int32_t n_frames,

@@ -21,7 +21,8 @@
 // online-softmax state (running max, sum and 8 output values per lane); a block merges its 16 lane
 // groups through LDS and writes one partial (max, sum, 128 values); a second small kernel merges
 // the partials of a head.  The three tiers of a frame are walked by three instances of one loop
-// specialised on the row format.
+// specialised on the row format.  With grouped-query attention the kQ query heads that share a K/V
+// head are handled by the same block, so every compressed row is still read once.
 
 #include "sali_internal.h"
 
@@ -99,67 +100,57 @@ __device__ __forceinline__ void load_row(const Pools& pools, size_t plane, size_
     r.zero = (float)__builtin_bit_cast(_Float16, pools.z4[p * kGroupsPerRow + (l >> 2)]);
 }
 
-// the lane's part of <q, K^_row>
-__device__ __forceinline__ float dot_piece(const RawRow<SALI_TIER_FP16>& r, const QueryPiece& q) {
+// The lane's 8 stored values of a row as fp32: the halves of an FP16 row, the raw codes of an
+// INT8 / INT4 row (scale and zero-point are applied once per row, see finish_dot / weight_of).
+__device__ __forceinline__ void row_values(const RawRow<SALI_TIER_FP16>& r, float x[8]) {
     Row16B v;
     v.u = r.u;
-    float d = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) d = __builtin_amdgcn_fdot2(q.h2[e], v.h2[e], d, false);
-    return d;
+    for (int e = 0; e < 8; ++e) x[e] = (float)v.h[e];
 }
-__device__ __forceinline__ float dot_piece(const RawRow<SALI_TIER_INT8>& r, const QueryPiece& q) {
-    float d = 0.0f;
+__device__ __forceinline__ void row_values(const RawRow<SALI_TIER_INT8>& r, float x[8]) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const uint32_t word = e < 4 ? r.u.x : r.u.y;
-        d += q.f[e] * (float)(int)(int8_t)((word >> (8 * (e & 3))) & 0xFF);
+        x[e] = (float)(int)(int8_t)((word >> (8 * (e & 3))) & 0xFF);
     }
+}
+__device__ __forceinline__ void row_values(const RawRow<SALI_TIER_INT4>& r, float x[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (float)((r.u >> (4 * e)) & 0xF);
+}
+
+// <q, K^_row> of the lane from the sum over its raw values: K^ = code * scale (+ zero)
+__device__ __forceinline__ float finish_dot(const RawRow<SALI_TIER_FP16>&, float d, const QueryPiece&) { return d; }
+__device__ __forceinline__ float finish_dot(const RawRow<SALI_TIER_INT8>& r, float d, const QueryPiece&) {
     return d * r.scale;
 }
-__device__ __forceinline__ float dot_piece(const RawRow<SALI_TIER_INT4>& r, const QueryPiece& q) {
-    float d = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) d += q.f[e] * (float)((r.u >> (4 * e)) & 0xF);
+__device__ __forceinline__ float finish_dot(const RawRow<SALI_TIER_INT4>& r, float d, const QueryPiece& q) {
     return d * r.scale + q.sum * r.zero;
 }
 
-// online-softmax state of a lane group (max and sum are equal in its 16 lanes); the INT4
-// zero-points are summed apart (zacc, the same for the lane's 8 values) and folded in at the end
+// p * V^_row = (p * scale) * code + p * zero: weight on the raw values, and the constant part
+__device__ __forceinline__ float weight_of(const RawRow<SALI_TIER_FP16>&, float p) { return p; }
+__device__ __forceinline__ float weight_of(const RawRow<SALI_TIER_INT8>& r, float p) { return p * r.scale; }
+__device__ __forceinline__ float weight_of(const RawRow<SALI_TIER_INT4>& r, float p) { return p * r.scale; }
+__device__ __forceinline__ float offset_of(const RawRow<SALI_TIER_FP16>&, float) { return 0.0f; }
+__device__ __forceinline__ float offset_of(const RawRow<SALI_TIER_INT8>&, float) { return 0.0f; }
+__device__ __forceinline__ float offset_of(const RawRow<SALI_TIER_INT4>& r, float p) { return p * r.zero; }
+
+// online-softmax state of a lane group for one query (max and sum are equal in its 16 lanes); the
+// INT4 zero-points are summed apart (zacc, the same for the lane's 8 values) and folded in at the end
 struct SoftmaxState {
     float mx, lsum, zacc;
     float acc[8];
 };
 
-// acc += p * V^_row for the lane's 8 values
-__device__ __forceinline__ void add_value(const RawRow<SALI_TIER_FP16>& r, float p, SoftmaxState& st) {
-    Row16B v;
-    v.u = r.u;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e] += p * (float)v.h[e];
-}
-__device__ __forceinline__ void add_value(const RawRow<SALI_TIER_INT8>& r, float p, SoftmaxState& st) {
-    const float ps = p * r.scale;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint32_t word = e < 4 ? r.u.x : r.u.y;
-        st.acc[e] += ps * (float)(int)(int8_t)((word >> (8 * (e & 3))) & 0xFF);
-    }
-}
-__device__ __forceinline__ void add_value(const RawRow<SALI_TIER_INT4>& r, float p, SoftmaxState& st) {
-    const float ps = p * r.scale;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e] += ps * (float)((r.u >> (4 * e)) & 0xF);
-    st.zacc += p * r.zero;
-}
-
 // The rows of one tier of one stored frame that fall to this block: 64-row groups split, split +
 // n_splits, ...; lane group g takes rows jb + g, jb + 16 + g, ...  `base` = first pool row of the
-// frame in this tier, `count` = its rows.
-template <int kTier>
+// frame in this tier, `count` = its rows.  kQ queries share every row that is read.
+template <int kTier, int kQ>
 __device__ __forceinline__ void attend_tier(const Pools& pools, size_t plane_k, size_t plane_v, int base, int count,
-                                            int split, int n_splits, int g, int l, const QueryPiece& q,
-                                            float softmax_scale, float mult, SoftmaxState& st) {
+                                            int split, int n_splits, int g, int l, const QueryPiece (&q)[kQ],
+                                            float softmax_scale, float mult, SoftmaxState (&st)[kQ]) {
     for (int jb = split * 64; jb < count; jb += n_splits * 64) {
         RawRow<kTier> rk[kRowsPerStep], rv[kRowsPerStep];
         bool valid[kRowsPerStep];
@@ -174,36 +165,71 @@ __device__ __forceinline__ void attend_tier(const Pools& pools, size_t plane_k, 
                 load_row(pools, plane_v, (size_t)(base + j), l, rv[r]);
             }
         }
-        float s[kRowsPerStep];
-        float bm = -INFINITY;
+        float s[kQ][kRowsPerStep];
 #pragma unroll
         for (int r = 0; r < kRowsPerStep; ++r) {
-            const float d = row16_sum(dot_piece(rk[r], q));
-            s[r] = valid[r] ? softmax_scale * d : -INFINITY;
-            bm = fmaxf(bm, s[r]);
-        }
-        const float new_mx = fmaxf(st.mx, bm);
-        if (new_mx == -INFINITY) continue;          // no row for this lane group yet (uniform inside it)
-        const float corr = __expf(st.mx - new_mx);  // first rows: exp(-inf) = 0
-        st.lsum *= corr;
-        st.zacc *= corr;
+            float x[8];
+            row_values(rk[r], x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st.acc[e] *= corr;
+            for (int iq = 0; iq < kQ; ++iq) {
+                float d = 0.0f;
+                if constexpr (kTier == SALI_TIER_FP16) {
+                    Row16B v;
+                    v.u = rk[r].u;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) d = __builtin_amdgcn_fdot2(q[iq].h2[e], v.h2[e], d, false);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) d += q[iq].f[e] * x[e];
+                }
+                d = row16_sum(finish_dot(rk[r], d, q[iq]));
+                s[iq][r] = valid[r] ? softmax_scale * d : -INFINITY;
+            }
+        }
+        float p[kQ][kRowsPerStep];
+#pragma unroll
+        for (int iq = 0; iq < kQ; ++iq) {
+            float bm = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < kRowsPerStep; ++r) bm = fmaxf(bm, s[iq][r]);
+            const float new_mx = fmaxf(st[iq].mx, bm);
+            // nothing seen yet for this lane group: keep the state (every weight below is exp(-inf) = 0,
+            // and the reference maximum must stay finite for that)
+            const float ref = new_mx == -INFINITY ? 0.0f : new_mx;
+            const float corr = __expf(st[iq].mx - ref);     // first rows: exp(-inf) = 0
+            st[iq].lsum *= corr;
+            st[iq].zacc *= corr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st[iq].acc[e] *= corr;
+#pragma unroll
+            for (int r = 0; r < kRowsPerStep; ++r) {
+                p[iq][r] = mult * __expf(s[iq][r] - ref);   // absent row: exp(-inf) = 0
+                st[iq].lsum += p[iq][r];
+            }
+            st[iq].mx = new_mx;
+        }
 #pragma unroll
         for (int r = 0; r < kRowsPerStep; ++r) {
-            const float p = mult * __expf(s[r] - new_mx);   // absent row: exp(-inf) = 0
-            st.lsum += p;
-            add_value(rv[r], p, st);
+            float x[8];
+            row_values(rv[r], x);
+#pragma unroll
+            for (int iq = 0; iq < kQ; ++iq) {
+                const float wgt = weight_of(rv[r], p[iq][r]);
+                st[iq].zacc += offset_of(rv[r], p[iq][r]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st[iq].acc[e] += wgt * x[e];
+            }
         }
-        st.mx = new_mx;
     }
 }
 
 }  // namespace
 
-// grid (n_chunks * n_splits, n_heads).  Block (c, s) of head h takes the frames
+// grid (n_chunks * n_splits, n_heads).  Block (c, s) of K/V head h takes the frames
 // [frame_lo + c * frames_per_chunk, ...) and of each source frame the 64-row groups s, s + n_splits, ...
-// of every tier, and writes one partial.
+// of every tier, for kQ of the query heads that share the K/V head (gridDim.z such sets:
+// q_per_kv = kQ * gridDim.z), and writes one partial per query head.
+template <int kQ>
 __global__ __launch_bounds__(256) void k_attn_partial(const sali_frame_row* __restrict__ rows, Pools pools, int layer,
                                                       int n_heads, const _Float16* __restrict__ q, int frame_lo,
                                                       int frame_hi, int frames_per_chunk, int n_splits,
@@ -212,31 +238,32 @@ __global__ __launch_bounds__(256) void k_attn_partial(const sali_frame_row* __re
     __shared__ float s_acc[16][kHeadDim];
 
     const int h = blockIdx.y;
+    const int q_first = (h * (int)gridDim.z + (int)blockIdx.z) * kQ;      // first query head of this block
     const int chunk = blockIdx.x / n_splits, split = blockIdx.x % n_splits;
     const int g = threadIdx.x >> 4, l = threadIdx.x & 15;
     const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + h;
     const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + h;
 
-    QueryPiece qp;
-    {
+    QueryPiece qp[kQ];
+    SoftmaxState st[kQ];
+#pragma unroll
+    for (int iq = 0; iq < kQ; ++iq) {
         Row16B qv;
-        qv.u = reinterpret_cast<const u32x4*>(q)[h * 16 + l];
-        qp.sum = 0.0f;
+        qv.u = reinterpret_cast<const u32x4*>(q)[(q_first + iq) * 16 + l];
+        qp[iq].sum = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            qp.f[e] = (float)qv.h[e];
-            qp.sum += qp.f[e];
+            qp[iq].f[e] = (float)qv.h[e];
+            qp[iq].sum += qp[iq].f[e];
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) qp.h2[e] = qv.h2[e];
-    }
-
-    SoftmaxState st;
-    st.mx = -INFINITY;
-    st.lsum = 0.0f;
-    st.zacc = 0.0f;
+        for (int e = 0; e < 4; ++e) qp[iq].h2[e] = qv.h2[e];
+        st[iq].mx = -INFINITY;
+        st[iq].lsum = 0.0f;
+        st[iq].zacc = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e] = 0.0f;
+        for (int e = 0; e < 8; ++e) st[iq].acc[e] = 0.0f;
+    }
 
     const int f0 = frame_lo + chunk * frames_per_chunk;
     const int f1 = min(frame_hi, f0 + frames_per_chunk);
@@ -260,43 +287,45 @@ __global__ __launch_bounds__(256) void k_attn_partial(const sali_frame_row* __re
             if (rows[t].src == src) ++n_uses;
         const float mult = (float)n_uses;
         const sali_frame_row row = rows[src];
-        attend_tier<SALI_TIER_FP16>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, g, l, qp,
-                                    softmax_scale, mult, st);
-        attend_tier<SALI_TIER_INT8>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, g, l, qp,
-                                    softmax_scale, mult, st);
-        attend_tier<SALI_TIER_INT4>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, g, l, qp,
-                                    softmax_scale, mult, st);
+        attend_tier<SALI_TIER_FP16, kQ>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, g, l, qp,
+                                        softmax_scale, mult, st);
+        attend_tier<SALI_TIER_INT8, kQ>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, g, l, qp,
+                                        softmax_scale, mult, st);
+        attend_tier<SALI_TIER_INT4, kQ>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, g, l, qp,
+                                        softmax_scale, mult, st);
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e] += st.zacc;
 
-    // merge the 16 lane groups
-    if (l == 0) {
-        s_m[g] = st.mx;
-        s_l[g] = st.lsum;
-    }
+    // merge the 16 lane groups, one query head after the other
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_acc[g][8 * l + e] = st.acc[e];
-    __syncthreads();
-    float* mine = partial + ((size_t)h * kAttnPartials + blockIdx.x) * kPartialStride;
-    if (threadIdx.x < kHeadDim) {
-        float big = -INFINITY;
+    for (int iq = 0; iq < kQ; ++iq) {
+        if (iq > 0) __syncthreads();
+        if (l == 0) {
+            s_m[g] = st[iq].mx;
+            s_l[g] = st[iq].lsum;
+        }
 #pragma unroll
-        for (int k = 0; k < 16; ++k) big = fmaxf(big, s_m[k]);
-        float lt = 0.0f, at = 0.0f;
-        if (big != -INFINITY) {
+        for (int e = 0; e < 8; ++e) s_acc[g][8 * l + e] = st[iq].acc[e] + st[iq].zacc;
+        __syncthreads();
+        float* mine = partial + ((size_t)(q_first + iq) * kAttnPartials + blockIdx.x) * kPartialStride;
+        if (threadIdx.x < kHeadDim) {
+            float big = -INFINITY;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const float w = __expf(s_m[k] - big);
-                lt += w * s_l[k];
-                at += w * s_acc[k][threadIdx.x];
+            for (int k = 0; k < 16; ++k) big = fmaxf(big, s_m[k]);
+            float lt = 0.0f, at = 0.0f;
+            if (big != -INFINITY) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const float w = __expf(s_m[k] - big);
+                    lt += w * s_l[k];
+                    at += w * s_acc[k][threadIdx.x];
+                }
             }
+            if (threadIdx.x == 0) {
+                mine[0] = big;
+                mine[1] = lt;
+            }
+            mine[2 + threadIdx.x] = at;
         }
-        if (threadIdx.x == 0) {
-            mine[0] = big;
-            mine[1] = lt;
-        }
-        mine[2 + threadIdx.x] = at;
     }
 }
 
@@ -340,9 +369,9 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
     }
 }
 
-hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, int n_heads, const void* d_q,
-                         int frame_lo, int frame_hi, float softmax_scale, float* d_partial, float* d_out,
-                         float* d_lse_or_null, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s) {
+hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, int n_heads, int q_per_kv,
+                         const void* d_q, int frame_lo, int frame_hi, float softmax_scale, float* d_partial,
+                         float* d_out, float* d_lse_or_null, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s) {
     const int n_range = frame_hi - frame_lo;
     int n_partials = 0;
     if (n_range > 0) {
@@ -358,14 +387,33 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
         n_splits = n_splits < 1 ? 1 : (n_splits > 9 ? 9 : n_splits);
         n_partials = n_chunks * n_splits;
         if (ev_start != nullptr && hipEventRecord(ev_start, s) != hipSuccess) return hipErrorUnknown;
-        hipLaunchKernelGGL(k_attn_partial, dim3(n_partials, n_heads), dim3(256), 0, s, d_rows, pools, layer, n_heads,
-                           reinterpret_cast<const _Float16*>(d_q), frame_lo, frame_hi, fpc, n_splits, softmax_scale,
-                           d_partial);
+        // eight queries per K/V head run as two sets of four (two blocks read the same rows, the second
+        // mostly from cache): a block with eight query states needs 256 registers per lane and was slower
+        const int kq = q_per_kv == 8 ? 4 : q_per_kv;
+        const dim3 grid(n_partials, n_heads, q_per_kv / kq);
+        const _Float16* q = reinterpret_cast<const _Float16*>(d_q);
+        switch (kq) {
+            case 1:
+                hipLaunchKernelGGL(k_attn_partial<1>, grid, dim3(256), 0, s, d_rows, pools, layer, n_heads, q, frame_lo,
+                                   frame_hi, fpc, n_splits, softmax_scale, d_partial);
+                break;
+            case 2:
+                hipLaunchKernelGGL(k_attn_partial<2>, grid, dim3(256), 0, s, d_rows, pools, layer, n_heads, q, frame_lo,
+                                   frame_hi, fpc, n_splits, softmax_scale, d_partial);
+                break;
+            case 4:
+                hipLaunchKernelGGL(k_attn_partial<4>, grid, dim3(256), 0, s, d_rows, pools, layer, n_heads, q, frame_lo,
+                                   frame_hi, fpc, n_splits, softmax_scale, d_partial);
+                break;
+            default:
+                return hipErrorInvalidValue;
+        }
         if (ev_stop != nullptr && hipEventRecord(ev_stop, s) != hipSuccess) return hipErrorUnknown;
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k_attn_merge, dim3(n_heads), dim3(256), 0, s, d_partial, n_partials, d_out, d_lse_or_null);
+    hipLaunchKernelGGL(k_attn_merge, dim3(n_heads * q_per_kv), dim3(256), 0, s, d_partial, n_partials, d_out,
+                       d_lse_or_null);
     return hipGetLastError();
 }
 

@@ -225,3 +225,22 @@ def test_gap_to_attention_over_dequantise_on_read_output_is_bounded():
         ref[h] = (e / e.sum()) @ v[h]
     gap = np.abs(out - ref).max()
     assert 0.0 < gap < 2e-3 * np.abs(v).max()
+
+
+def test_grouped_queries_equal_plain_attention_on_a_cache_with_repeated_heads():
+    """q_per_kv query heads share one K/V head: the same numbers must come out of the plain path
+    on a cache whose K/V heads were repeated q_per_kv times before storing."""
+    g = 4
+    kv = _kv(80, nh=2)
+    scores = _mixed_scores(30)
+    c = _cache(frames=1, n_heads=2)
+    c.kv_compress(kv, scores, 0)
+    q = _q(81, nh=2 * g)
+    out, lse = attend_decode(c, 0, q, 0, 1, 0.11, q_per_kv=g)
+    wide = _cache(frames=1, n_heads=2 * g)
+    wide.kv_compress(np.repeat(kv, g, axis=2), scores, 0)          # head j of the wide cache = head j // g
+    ref, ref_lse = attend_decode(wide, 0, q, 0, 1, 0.11)
+    assert out.shape == (2 * g, 128)
+    assert np.array_equal(out, ref) and np.array_equal(lse, ref_lse)
+    # and the heads of a group really see different queries
+    assert not np.allclose(out[0], out[1])
