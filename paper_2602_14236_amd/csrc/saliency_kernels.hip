@@ -17,8 +17,12 @@
 //   k_union  joins components across tile borders with global atomics (border pixels only).
 //   k_pool   per patch: E = edge pixel whose root is strong, C = V above the frame mean and
 //            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.  In the
-//            chained step it also reduces the flow field to the patch's motion (Eq. 5), and the
-//            last block to finish evaluates the gate (Eq. 6) and assigns tiers and indices.
+//            chained step it also reduces the flow field to the patch's motion (Eq. 5); the last
+//            block of a frame to finish evaluates the gate (Eq. 6) and ranks the frame's tokens,
+//            and the last of those in the launch writes the frame-table rows in video order.
+//
+// Every kernel takes the frame as a grid dimension (per-frame pointers in a by-value struct): one
+// small frame cannot fill 256 compute units.
 //
 // All stencils replicate the border; non-maximum suppression treats out-of-image neighbours
 // as magnitude 0.
