@@ -164,6 +164,30 @@ __device__ __forceinline__ void pyr_level_lds(const float* src, int o_src_y, int
         dst[ry * kDstStride + rx] = acc;
     }
 }
+// Gray patch of kSide x kSide pixels with origin (qy, qx) (coordinates clamped to the image) into LDS
+// as gray / 255, row stride kStride.  All of a thread's loads are issued before the first one is
+// used: written as one loop the compiler waits for every byte in turn, up to 37 dependent round
+// trips, and next to a kernel that saturates the memory system each of them takes microseconds.
+template <int kSide, int kStride>
+__device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, int h0, int w0, int qy, int qx,
+                                                float* __restrict__ dst) {
+    constexpr int kN = (kSide * kSide + 255) / 256;
+    uint8_t v[kN];
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        const int p = (int)threadIdx.x + 256 * k;
+        const int pp = p < kSide * kSide ? p : 0;
+        const int ry = pp / kSide, rx = pp % kSide;
+        const int gy = clampi(qy + ry, 0, h0 - 1), gx = clampi(qx + rx, 0, w0 - 1);
+        v[k] = y8[(size_t)gy * w0 + gx];
+    }
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        const int p = (int)threadIdx.x + 256 * k;
+        if (p < kSide * kSide) dst[(p / kSide) * kStride + (p % kSide)] = (float)v[k] / 255.0f;
+    }
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int t1, int t2, int tx0, int tx1, int tx2,
@@ -191,29 +215,17 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     const int h0 = g.h[0], w0 = g.w[0];
 
     if (lvl == 0) {
-        for (int p = tid; p < kER * kER; p += 256) {
-            const int ry = p / kER, rx = p % kER;
-            const int gy = clampi(oy + ry, 0, h - 1), gx = clampi(ox + rx, 0, w - 1);
-            s_f[ry][rx] = (float)y8[(size_t)gy * w + gx] / 255.0f;
-        }
+        load_gray_patch<kER, kER + 1>(y8, h, w, oy, ox, &s_f[0][0]);
     } else if (lvl == 1) {
         const int qy = 2 * oy - 2, qx = 2 * ox - 2;              // origin of the gray patch (47 x 47)
-        for (int p = tid; p < kEP * kEP; p += 256) {
-            const int ry = p / kEP, rx = p % kEP;
-            const int gy = clampi(qy + ry, 0, h0 - 1), gx = clampi(qx + rx, 0, w0 - 1);
-            s_q[ry * (kEP + 1) + rx] = (float)y8[(size_t)gy * w0 + gx] / 255.0f;
-        }
+        load_gray_patch<kEP, kEP + 1>(y8, h0, w0, qy, qx, s_q);
         __syncthreads();
         pyr_level_lds<kEP + 1, kER + 1>(s_q, qy, qx, &s_f[0][0], oy, ox, kER, h, w);
     } else {
         const int h1 = g.h[1], w1 = g.w[1];
         const int py = 2 * oy - 2, px = 2 * ox - 2;              // origin of the level-1 patch (47 x 47)
         const int qy = 2 * py - 2, qx = 2 * px - 2;              // origin of the gray patch (97 x 97)
-        for (int p = tid; p < kEQ * kEQ; p += 256) {
-            const int ry = p / kEQ, rx = p % kEQ;
-            const int gy = clampi(qy + ry, 0, h0 - 1), gx = clampi(qx + rx, 0, w0 - 1);
-            s_q[ry * (kEQ + 1) + rx] = (float)y8[(size_t)gy * w0 + gx] / 255.0f;
-        }
+        load_gray_patch<kEQ, kEQ + 1>(y8, h0, w0, qy, qx, s_q);
         __syncthreads();
         pyr_level_lds<kEQ + 1, kEP + 1>(s_q, qy, qx, s_p, py, px, kEP, h1, w1);
         __syncthreads();
