@@ -333,16 +333,16 @@ int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, hipStream_t s) {
         SALI_TRY(launch_expand(f, bp.n, g, c->fw, s));
         return SALI_OK;
     }
+    PyrBatch f = {};
     for (int i = 0; i < bp.n; ++i) {
         const LaneLayout& L = c->sl.lane[bp.lane[i]];
-        float* pyr = c->sc<float>(L.pyr);
-        for (int l = 1; l < g.levels; ++l) {
-            SALI_TRY(launch_pyr_down(l == 1 ? c->sc<uint8_t>(L.y8) : nullptr, l == 1 ? nullptr : pyr + g.off[l - 1],
-                                     g.h[l - 1], g.w[l - 1], pyr + g.off[l], g.h[l], g.w[l], s));
-        }
-        SALI_TRY(launch_polyexp(c->sc<uint8_t>(L.y8), pyr, g, c->fw, c->sc<float4>(c->sl.expA[bp.slot[i]]),
-                                c->sc<float2>(c->sl.expB[bp.slot[i]]), s));
+        f.y8[i] = c->sc<uint8_t>(L.y8);
+        f.pyr[i] = c->sc<float>(L.pyr);
+        f.A[i] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
+        f.b[i] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
     }
+    for (int l = 1; l < g.levels; ++l) SALI_TRY(launch_pyr_down(f, bp.n, g, l, s));
+    SALI_TRY(launch_polyexp(f, bp.n, g, c->fw, s));
     return SALI_OK;
 }
 

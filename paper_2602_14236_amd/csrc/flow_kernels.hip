@@ -38,8 +38,13 @@ __device__ __forceinline__ float clampf(float v, float lo, float hi) { return fm
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_pyr_down(const uint8_t* __restrict__ y8, const float* __restrict__ src,
-                                                  int sh, int sw, float* __restrict__ dst, int dh, int dw) {
+// One pyramid level of every frame of the batch (blockIdx.z): level `lvl` of f.pyr[z] from level
+// lvl - 1 (from the gray image f.y8[z] for lvl = 1).
+__global__ __launch_bounds__(256) void k_pyr_down(PyrBatch f, int from_gray, long long src_off, long long dst_off,
+                                                  int sh, int sw, int dh, int dw) {
+    const uint8_t* __restrict__ y8 = from_gray ? f.y8[blockIdx.z] : nullptr;
+    const float* __restrict__ src = f.pyr[blockIdx.z] + src_off;
+    float* __restrict__ dst = f.pyr[blockIdx.z] + dst_off;
     const int x = blockIdx.x * 64 + (threadIdx.x & 63);
     const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (x >= dw || y >= dh) return;
@@ -65,9 +70,12 @@ __global__ __launch_bounds__(256) void k_pyr_down(const uint8_t* __restrict__ y8
 // With separable symmetric weights (sum 1, second moment m2, fourth moment m4) the normal
 // equations decouple:  b = (sx, sy) / m2,  A_xx = (sxx - m2 s0) / (m4 - m2^2),  A_yy likewise,
 // A_xy = sxy / (2 m2^2), where s* are the weighted correlations of f with 1, x, y, x^2, y^2, xy.
-__global__ __launch_bounds__(256) void k_polyexp(const uint8_t* __restrict__ y8, const float* __restrict__ pyr,
-                                                 LevelGeom g, FlowWeights fw, float4* __restrict__ A_out,
-                                                 float2* __restrict__ b_out) {
+__global__ __launch_bounds__(256) void k_polyexp(PyrBatch f, LevelGeom g, FlowWeights fw) {
+    // blockIdx.y = frame of the batch
+    const uint8_t* __restrict__ y8 = f.y8[blockIdx.y];
+    const float* __restrict__ pyr = f.pyr[blockIdx.y];
+    float4* __restrict__ A_out = f.A[blockIdx.y];
+    float2* __restrict__ b_out = f.b[blockIdx.y];
     __shared__ float s_f[kPR][kPR + 1];
     __shared__ float s_v[3][kT][kPR + 1];
 
@@ -460,16 +468,15 @@ __global__ __launch_bounds__(256) void k_patch_gate(const float2* __restrict__ f
 }
 
 // ---------------------------------------------------------------------------------------------
-hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
-                           int dh, int dw, hipStream_t s) {
-    dim3 grid((dw + 63) / 64, (dh + 3) / 4);
-    hipLaunchKernelGGL(k_pyr_down, grid, dim3(256), 0, s, d_y8_or_null, d_src_or_null, sh, sw, d_dst, dh, dw);
+hipError_t launch_pyr_down(const PyrBatch& f, int n, const LevelGeom& g, int lvl, hipStream_t s) {
+    dim3 grid((g.w[lvl] + 63) / 64, (g.h[lvl] + 3) / 4, n);
+    hipLaunchKernelGGL(k_pyr_down, grid, dim3(256), 0, s, f, lvl == 1 ? 1 : 0, (long long)g.off[lvl - 1],
+                       (long long)g.off[lvl], g.h[lvl - 1], g.w[lvl - 1], g.h[lvl], g.w[lvl]);
     return hipGetLastError();
 }
 
-hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
-                          float2* d_b, hipStream_t s) {
-    hipLaunchKernelGGL(k_polyexp, dim3(g.tile_start[g.levels]), dim3(256), 0, s, d_y8, d_pyr, g, fw, d_A, d_b);
+hipError_t launch_polyexp(const PyrBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s) {
+    hipLaunchKernelGGL(k_polyexp, dim3(g.tile_start[g.levels], n), dim3(256), 0, s, f, g, fw);
     return hipGetLastError();
 }
 

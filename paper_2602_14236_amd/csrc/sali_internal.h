@@ -96,6 +96,13 @@ struct ExpandBatch {
     float2* b[kMaxBatch];
 };
 
+struct PyrBatch {                                 // per-level path (more than three levels)
+    const uint8_t* y8[kMaxBatch];
+    float* pyr[kMaxBatch];                        // all levels of the frame's pyramid, LevelGeom offsets
+    float4* A[kMaxBatch];
+    float2* b[kMaxBatch];
+};
+
 struct FlowBatch {                                // expansions at level 0; the launcher adds the level offset
     const float4* A1[kMaxBatch];
     const float2* b1[kMaxBatch];
@@ -190,10 +197,8 @@ hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salma
                        hipStream_t s);
 
 // flow_kernels.hip
-hipError_t launch_pyr_down(const uint8_t* d_y8_or_null, const float* d_src_or_null, int sh, int sw, float* d_dst,
-                           int dh, int dw, hipStream_t s);
-hipError_t launch_polyexp(const uint8_t* d_y8, const float* d_pyr, LevelGeom g, FlowWeights fw, float4* d_A,
-                          float2* d_b, hipStream_t s);
+hipError_t launch_pyr_down(const PyrBatch& f, int n, const LevelGeom& g, int lvl, hipStream_t s);
+hipError_t launch_polyexp(const PyrBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
 hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
 hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
                             int prior_mode, FlowWeights fw, hipStream_t s);
