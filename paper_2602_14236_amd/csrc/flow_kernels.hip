@@ -10,7 +10,7 @@
 //                values a tile needs are rebuilt from the gray image in LDS; separable moments,
 //                closed-form solution of the 6-unknown weighted least-squares fit
 //   k_pyr_down, k_polyexp   the same per level (pyramid in HBM), used for more than three levels
-//   k_flow_iter  one displacement update: per cell of a 16x16 (or 32x32) tile + 5-pixel halo, sample
+//   k_flow_iter  one displacement update: per cell of a 16x16 tile + 5-pixel halo, sample
 //                the new frame's expansion bilinearly at x + prior, build A^T A (3 values) and
 //                A^T db (2 values) in LDS, separable 11x11 Gaussian aggregation in LDS, 2x2 ridge
 //                solve.  The coarse-to-fine transfer (2 * bilinear of the coarser flow) is folded
@@ -315,8 +315,8 @@ __device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int 
 
 }  // namespace
 
-// T = tile side: 32 for large levels, 16 for small ones (more blocks and fewer cells per thread:
-// the small levels are latency-bound, not throughput-bound).
+// T = tile side (16 in every launch; 32 measured slower at all image sizes once tiles were handed to
+// the XCDs in contiguous runs).
 template <int T>
 __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_off, int h, int w, int ch, int cw,
                                                    int prior_mode, FlowWeights fw) {
@@ -497,16 +497,10 @@ hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights f
 
 hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
                             int prior_mode, FlowWeights fw, hipStream_t s) {
-    // small levels: 16x16 tiles so that the level spreads over many compute units
-    if ((long long)((w + 31) / 32) * ((h + 31) / 32) < 1024) {
-        dim3 grid((w + 15) / 16, (h + 15) / 16, n);
-        hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, f, (long long)level_off, h, w, ch, cw, prior_mode,
-                           fw);
-    } else {
-        dim3 grid((w + 31) / 32, (h + 31) / 32, n);
-        hipLaunchKernelGGL(k_flow_iter<32>, grid, dim3(256), 0, s, f, (long long)level_off, h, w, ch, cw, prior_mode,
-                           fw);
-    }
+    // 16x16 tiles at every size: with the XCD-aware order they measured faster than 32x32 tiles from
+    // 84x84 up to 1920x1080 (less LDS per block, so more blocks per compute unit hide the gathers)
+    dim3 grid((w + 15) / 16, (h + 15) / 16, n);
+    hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, f, (long long)level_off, h, w, ch, cw, prior_mode, fw);
     return hipGetLastError();
 }
 
