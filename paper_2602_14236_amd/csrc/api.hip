@@ -299,7 +299,8 @@ struct BatchPlan {
 
 // gray (+ saliency pre-pass) of the batch's frames; the other frame-sum accumulator of each lane is
 // cleared for the lane's next use
-int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool with_saliency, hipStream_t s) {
+int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool with_saliency,
+                 bool union_with_expansion, hipStream_t s) {
     const sali_config& cfg = c->cfg;
     PrepBatch f = {};
     for (int i = 0; i < bp.n; ++i) {
@@ -315,22 +316,28 @@ int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, 
     }
     SALI_TRY(launch_prep(f, bp.n, cfg.src_h, cfg.src_w, with_saliency, c->tb<uint16_t>(c->tl.lut),
                          cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
-    // cross-tile hysteresis (a kernel boundary is the cheapest device-wide ordering there is)
-    if (with_saliency) SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
+    // cross-tile hysteresis after a kernel boundary (the cheapest device-wide ordering there is): a
+    // launch of its own, unless the expansion launch that follows will carry it
+    if (with_saliency && !(union_with_expansion && c->geom.levels <= 3))
+        SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
     return SALI_OK;
 }
 
-// pyramid and polynomial expansion of each frame's gray image into its expansion slot
-int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, hipStream_t s) {
+// pyramid and polynomial expansion of each frame's gray image into its expansion slot; with_union:
+// the frames' saliency pre-pass has run and its cross-tile hysteresis pass is still due
+int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, bool with_union, hipStream_t s) {
     const LevelGeom& g = c->geom;
     if (g.levels <= 3) {
         ExpandBatch f = {};
         for (int i = 0; i < bp.n; ++i) {
-            f.y8[i] = c->sc<uint8_t>(c->sl.lane[bp.lane[i]].y8);
+            const LaneLayout& L = c->sl.lane[bp.lane[i]];
+            f.y8[i] = c->sc<uint8_t>(L.y8);
             f.A[i] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
             f.b[i] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
+            f.cls[i] = c->sc<uint8_t>(L.cls);
+            f.parent[i] = c->sc<uint32_t>(L.parent);
         }
-        SALI_TRY(launch_expand(f, bp.n, g, c->fw, s));
+        SALI_TRY(launch_expand(f, bp.n, g, c->fw, with_union, s));
         return SALI_OK;
     }
     PyrBatch f = {};
@@ -607,10 +614,10 @@ int sali_flow_score(sali_ctx* c, const uint8_t* d_prev_rgb, const uint8_t* d_cur
     pa.prev_slot[0] = -1;
     pb.slot[0] = kStepSlots + 1;
     pb.prev_slot[0] = kStepSlots;
-    int rc = enqueue_prep(c, &d_prev_rgb, pa, false, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, pa, s);
-    if (rc == SALI_OK) rc = enqueue_prep(c, &d_cur_rgb, pb, false, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, pb, s);
+    int rc = enqueue_prep(c, &d_prev_rgb, pa, false, false, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, pa, false, s);
+    if (rc == SALI_OK) rc = enqueue_prep(c, &d_cur_rgb, pb, false, false, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, pb, false, s);
     if (rc != SALI_OK) return rc;
     const float2* flow = nullptr;
     rc = enqueue_flow(c, pb, &flow, s);
@@ -627,7 +634,7 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
     BatchPlan bp = {};
     bp.n = 1;
     bp.parity[0] = c->lane_uses[0]++ & 1u;
-    int rc = enqueue_prep(c, &d_rgb, bp, true, s);
+    int rc = enqueue_prep(c, &d_rgb, bp, true, false, s);
     if (rc == SALI_OK) rc = enqueue_pool(c, bp, d_scores576, d_salmap_or_null, nullptr, nullptr, s);
     return rc;
 }
@@ -721,8 +728,8 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
         rc = wait_unless_same(s, old.stream, old.done);
         if (rc != SALI_OK) return rc;
     }
-    rc = enqueue_prep(c, d_rgb_frames, bp, true, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, bp, s);
+    rc = enqueue_prep(c, d_rgb_frames, bp, true, true, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, bp, true, s);
     if (rc != SALI_OK) return rc;
     // the batch's events live in the ring entry of its last frame
     AnalysisRecord& rec = c->ring[n_last % kRing];

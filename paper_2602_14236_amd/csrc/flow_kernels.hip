@@ -24,6 +24,7 @@
 // The batched kernels take the frame as a grid dimension.  All stencils replicate the border.
 
 #include "sali_internal.h"
+#include "hysteresis.h"
 
 namespace sali {
 
@@ -198,8 +199,17 @@ __device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, 
 
 }  // namespace
 
+// The first n_union blocks of every frame do something unrelated that has the same predecessor (the
+// saliency pre-pass) and nothing else to wait for: the cross-tile pass of the Canny hysteresis, one
+// 64 x 4 pixel strip per block.  Hosting it here saves a launch and its 10 us of latency-bound run
+// time on the critical path of a frame batch.
 __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int t1, int t2, int tx0, int tx1, int tx2,
-                                                FlowWeights fw) {
+                                                FlowWeights fw, int n_union, int strips_x) {
+    if ((int)blockIdx.x < n_union) {
+        union_strip(f.cls[blockIdx.y], f.parent[blockIdx.y], g.h[0], g.w[0], (int)blockIdx.x % strips_x,
+                    (int)blockIdx.x / strips_x);
+        return;
+    }
     // blockIdx.y = frame of the batch.  (Plain block order on purpose: the tiles of the three levels
     // cost very different amounts, and the XCD-aware order puts all of a frame's expensive level-2
     // tiles on one XCD; measured 6 % slower.)
@@ -212,7 +222,7 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     __shared__ float s_v[3][kET][kER + 1];
 
     // block -> (level, tile)
-    const int b = blockIdx.x;
+    const int b = (int)blockIdx.x - n_union;
     const int lvl = b < t1 ? 0 : (b < t2 ? 1 : 2);
     const int t = b - (lvl == 0 ? 0 : (lvl == 1 ? t1 : t2));
     const int tiles_x = lvl == 0 ? tx0 : (lvl == 1 ? tx1 : tx2);
@@ -480,7 +490,7 @@ hipError_t launch_polyexp(const PyrBatch& f, int n, LevelGeom g, FlowWeights fw,
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s) {
+hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, bool with_union, hipStream_t s) {
     // up to three levels, 16x16 tiles, one launch
     int tx[3] = {1, 1, 1}, start[4] = {0, 0, 0, 0};
     for (int l = 0; l < 3; ++l) {
@@ -491,7 +501,10 @@ hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights f
         }
         start[l + 1] = start[l] + tiles;
     }
-    hipLaunchKernelGGL(k_expand, dim3(start[3], n), dim3(256), 0, s, f, g, start[1], start[2], tx[0], tx[1], tx[2], fw);
+    const int strips_x = (g.w[0] + 63) / 64;
+    const int n_union = with_union ? strips_x * ((g.h[0] + 3) / 4) : 0;
+    hipLaunchKernelGGL(k_expand, dim3(n_union + start[3], n), dim3(256), 0, s, f, g, start[1], start[2], tx[0], tx[1],
+                       tx[2], fw, n_union, strips_x);
     return hipGetLastError();
 }
 

@@ -94,6 +94,8 @@ struct ExpandBatch {
     const uint8_t* y8[kMaxBatch];
     float4* A[kMaxBatch];
     float2* b[kMaxBatch];
+    const uint8_t* cls[kMaxBatch];                // for the hosted cross-tile hysteresis pass
+    uint32_t* parent[kMaxBatch];
 };
 
 struct PyrBatch {                                 // per-level path (more than three levels)
@@ -199,7 +201,8 @@ hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salma
 // flow_kernels.hip
 hipError_t launch_pyr_down(const PyrBatch& f, int n, const LevelGeom& g, int lvl, hipStream_t s);
 hipError_t launch_polyexp(const PyrBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
-hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
+// with_union: the launch also carries the blocks of the cross-tile hysteresis pass (f.cls / f.parent)
+hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, bool with_union, hipStream_t s);
 hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
                             int prior_mode, FlowWeights fw, hipStream_t s);
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,

@@ -28,59 +28,20 @@
 // as magnitude 0.
 
 #include "sali_internal.h"
+#include "hysteresis.h"
 #include "tier_body.h"
 
 namespace sali {
 
 namespace {
 
-constexpr int kTile = 32;
 constexpr int kHalo = 4;
 constexpr int kReg = kTile + 2 * kHalo;        // 40: gray region
 constexpr int kRegB = kTile + 4;               // 36: blur / LAB region (halo 2)
 constexpr int kRegM = kTile + 2;               // 34: gradient-magnitude region (halo 1)
-constexpr uint32_t kWeakBit = 0x80000000u;
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// union-find on a parent array (LDS or global); key = index | weak bit; links go to smaller keys
-template <int kScope>
-__device__ __forceinline__ uint32_t uf_load(const uint32_t* parent, uint32_t idx) {
-    return __hip_atomic_load(parent + idx, __ATOMIC_RELAXED, kScope);
-}
-
-template <int kScope>
-__device__ __forceinline__ uint32_t uf_find(const uint32_t* parent, uint32_t key) {
-    uint32_t k = key;               // keys strictly decrease along links, so this terminates
-    for (;;) {
-        const uint32_t p = uf_load<kScope>(parent, k & ~kWeakBit);
-        if (p == k) return k;
-        k = p;
-    }
-}
-
-// for kernels that run after all links are final: ordinary cached loads
-__device__ __forceinline__ uint32_t uf_find_settled(const uint32_t* __restrict__ parent, uint32_t key) {
-    uint32_t k = key;
-    for (;;) {
-        const uint32_t p = parent[k & ~kWeakBit];
-        if (p == k) return k;
-        k = p;
-    }
-}
-
-template <int kScope>
-__device__ __forceinline__ void uf_unite(uint32_t* parent, uint32_t ka, uint32_t kb) {
-    for (;;) {
-        ka = uf_find<kScope>(parent, ka);
-        kb = uf_find<kScope>(parent, kb);
-        if (ka == kb) return;
-        if (ka < kb) { const uint32_t t = ka; ka = kb; kb = t; }      // ka is the larger key
-        const uint32_t old = atomicMin(parent + (ka & ~kWeakBit), kb);
-        if (old == ka) return;      // ka was a root and now points at kb
-        ka = old;                   // somebody linked ka first: continue from where it pointed
-    }
-}
 
 }  // namespace
 
@@ -339,31 +300,10 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
     }
 }
 
-// hysteresis, cross-tile part: only pairs of neighbours that lie in different k_prep tiles
+// hysteresis, cross-tile part as a kernel of its own (the stand-alone saliency call and the
+// per-level expansion path; the chained step runs it inside k_expand's launch)
 __global__ __launch_bounds__(256) void k_union(PrepBatch f, int h, int w) {
-    const uint8_t* __restrict__ cls = f.cls[blockIdx.z];
-    uint32_t* parent = f.parent[blockIdx.z];
-    const int x = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
-    if (x >= w || y >= h) return;
-    const int lx = x % kTile, ly = y % kTile;
-    if (lx != 0 && lx != kTile - 1 && ly != kTile - 1) return;      // all forward neighbours in the same tile
-    const size_t gi = (size_t)y * w + x;
-    const int c = cls[gi];
-    if (c == 0) return;
-    const uint32_t me = (uint32_t)gi | (c == 1 ? kWeakBit : 0u);
-    const int ny[4] = {0, 1, 1, 1};
-    const int nx[4] = {1, -1, 0, 1};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int yy = y + ny[k], xx = x + nx[k];
-        if (yy >= h || xx < 0 || xx >= w) continue;
-        if (yy / kTile == y / kTile && xx / kTile == x / kTile) continue;     // joined in LDS already
-        const size_t gj = (size_t)yy * w + xx;
-        const int cj = cls[gj];
-        if (cj == 0) continue;
-        uf_unite<__HIP_MEMORY_SCOPE_AGENT>(parent, me, (uint32_t)gj | (cj == 1 ? kWeakBit : 0u));
-    }
+    union_strip(f.cls[blockIdx.z], f.parent[blockIdx.z], h, w, blockIdx.x, blockIdx.y);
 }
 
 // Eq. 7 score of each patch and, in the chained step (do_tier), also its motion (Eq. 5) from the
