@@ -203,3 +203,42 @@ def test_two_runs_are_byte_identical():
         outs.append((ctx.pools.cpu().numpy().copy(), ctx.tables.cpu().numpy().copy()))
         ctx.close()
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_topk_ranking_patterns_with_ties_signs_and_infinities():
+    """Top-k tier assignment on score patterns chosen to stress the rank count: all equal, sorted
+    both ways, two values, negative and mixed-sign values, +0 / -0, infinities, denormals, and ties
+    that straddle every cut, also inside the last 64 tokens (which the kernel ranks differently from
+    the first 512).  Tiers and slots must equal the oracle's sort by (score descending, index)."""
+    from paper_2602_14236_amd import binding
+    rng = np.random.default_rng(11)
+    n = 576
+    idx = np.arange(n)
+    patterns = {
+        "all equal": np.full(n, 0.25),
+        "ascending": idx / 1000.0,
+        "descending": (n - idx) / 1000.0,
+        "two values": (idx % 2).astype(np.float64),
+        "negative": -rng.uniform(0, 1, n),
+        "mixed sign with zeros": np.where(idx % 3 == 0, 0.0, np.where(idx % 3 == 1, -0.0, rng.normal(0, 1, n))),
+        "infinities": np.where(idx % 50 == 0, np.inf, np.where(idx % 50 == 1, -np.inf, rng.uniform(0, 1, n))),
+        "denormals": rng.integers(0, 8, n) * 1e-45,
+        "ties in the tail": np.where(idx >= 500, 0.5, rng.integers(0, 4, n) / 4.0),
+        "few levels": rng.integers(0, 5, n) / 8.0,
+    }
+    cuts = [(173, 150, 200), (100, 412, 60), (512, 32, 16), (1, 0, 574), (300, 0, 0)]
+    kv = _kv(9, 1, 1)
+    for name, sc in patterns.items():
+        sc = sc.astype(np.float32)
+        for ks in cuts:
+            p = params(tier_mode=1, k_fp16=ks[0], k_int8=ks[1], k_int4=ks[2], n_layers=1, n_heads=1,
+                       cap_fp16=600, cap_int8=600, cap_int4=600)
+            ctx = binding.SaliContext(lib_config(p))
+            orc = SaliCacheOracle(oracle_config(p))
+            ctx.kv_compress(kv, torch.from_numpy(sc).cuda(), 0)
+            orc.kv_compress(kv.cpu().numpy(), sc, 0)
+            tier, slot = ctx.read_frame_tiers(0)
+            assert_same(tier, orc.tier[0], f"tier, {name}, k = {ks}")
+            assert_same(slot.astype(np.int32), orc.slot[0], f"slot, {name}, k = {ks}")
+            assert ctx.read_frame_table(0, 1)[0].as_tuple() == orc.rows[0].as_tuple()
+            ctx.close()
