@@ -248,3 +248,61 @@ def test_step_batch_matches_oracle():
         ctx.store_batch(kvs[:2], 20)
     assert e.value.code in (-2, -5)
     ctx.close()
+
+
+def test_random_batch_schedules_equal_the_one_stream_path():
+    """Property test of the scheduling layer: 120 frames (config 5's scene cuts, duplicate runs and
+    noise frames, cycled) analysed in batches of random size 1..8 on three alternating image
+    streams, stored in batches of other random sizes on a fourth stream with the analysis up to two
+    batches ahead, must leave the frame table, tier tables and pools of the one-stream
+    frame-by-frame path (which the other tests tie to the oracle).  More frames than scratch copies
+    and ring entries, so every reuse wait is exercised."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[5]
+    n, n_src = 120, 24
+    v = synth.video(5, 32)
+    p = workload_params(wl, frames=n, n_layers=1, n_heads=1)
+    scale = synth.kv_channel_scale(wl, 1, 1)
+    rgbs = [torch.from_numpy(v.frame(t)).cuda() for t in range(n_src)]
+    kvs = [synth.kv_frame(wl, t, device="cuda", n_layers=1, n_heads=1, scale=scale) for t in range(n_src)]
+
+    ref = binding.SaliContext(lib_config(p))
+    for t in range(n):
+        ref.step(rgbs[t % n_src], kvs[t % n_src], t)
+    torch.cuda.synchronize()
+    ref_rows = [r.as_tuple() for r in ref.read_frame_table(0, n)]
+    ref_pools = {k: a.clone() for k, a in ref.pool_views().items()}
+    assert 0 < sum(1 for r in ref_rows if r[2] == 0) < n          # some pointer frames, not all
+
+    for seed in (1, 2):
+        rng = np.random.default_rng(seed)
+        ctx = binding.SaliContext(lib_config(p))
+        s_imgs = [torch.cuda.Stream() for _ in range(3)]
+        s_kv = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        analysed = stored = 0
+        b = 0
+        while stored < n:
+            # keep the analysis between 1 and 16 frames ahead of the store
+            while analysed < n and analysed - stored < 9:
+                size = int(min(rng.integers(1, 9), n - analysed))
+                ctx.analyze_batch([rgbs[t % n_src] for t in range(analysed, analysed + size)], analysed, s_imgs[b % 3])
+                analysed += size
+                b += 1
+            size = int(min(rng.integers(1, 9), analysed - stored))
+            ctx.store_batch([kvs[t % n_src] for t in range(stored, stored + size)], stored, s_kv)
+            stored += size
+        torch.cuda.synchronize()
+        print(f"schedule {seed}: {b} analysis batches", flush=True)
+        assert ctx.get_status() == 0
+        rows = [r.as_tuple() for r in ctx.read_frame_table(0, n)]
+        assert rows == ref_rows
+        for t in range(n):
+            if ref_rows[t][2]:
+                a, c = ctx.read_frame_tiers(t), ref.read_frame_tiers(t)
+                assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1]), f"tiers of frame {t}"
+        pools = ctx.pool_views()
+        for k in ref_pools:
+            assert torch.equal(pools[k], ref_pools[k]), f"pool {k}"
+        ctx.close()
+    ref.close()
