@@ -76,7 +76,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=64,
+                    help="untimed steps before the timed ones; one pass over the 64-frame workload, so that every scratch "
+                         "copy, pool region and clock is warm (8 steps left 2-20 %% of cold-start cost in the timed region)")
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (BASELINE configs); 2 is the metric's")
     ap.add_argument("--layers", type=int, default=None, help="cut the K/V down to this many layers (not a valid bench)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
