@@ -78,7 +78,7 @@ def main():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=64,
                     help="untimed steps before the timed ones; one pass over the 64-frame workload, so that every scratch "
-                         "copy, pool region and clock is warm (8 steps left 2-20 %% of cold-start cost in the timed region)")
+                         "copy, pool region and clock is warm")
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (BASELINE configs); 2 is the metric's")
     ap.add_argument("--layers", type=int, default=None, help="cut the K/V down to this many layers (not a valid bench)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -139,6 +139,11 @@ def main():
     AHEAD = int(os.environ.get("SALI_BENCH_AHEAD", "1"))          # batches analysed ahead of the store
     s_imgs = [torch.cuda.Stream() for _ in range(max(2, LOOKAHEAD, AHEAD))]
     s_kv = torch.cuda.Stream()
+    # a stream gets its hardware queue on first use (milliseconds): use each once before any timing
+    for st in s_imgs + [s_kv]:
+        with torch.cuda.stream(st):
+            torch.zeros(1, device=dev)
+    torch.cuda.synchronize()
 
     def run(n, with_unpack, pack_events=None, unpack_events=None):
         """Frames are analysed ahead on the image streams while frame t is stored (and read back)
