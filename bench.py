@@ -72,6 +72,39 @@ def cpu_baseline(wl, video, max_frames=16, budget_s=12.0):
                       f"{total:.1f} s of CPU work, one thread"}
 
 
+def image_only(args, wl):
+    """The image side alone: `steps` frames through sali_analyze_batch, four per call, one stream,
+    an idle GPU otherwise (K/V shape cut to one plane: the K/V side is not run)."""
+    import torch
+    from paper_2602_14236_amd import binding, synth
+    batch = int(os.environ.get("SALI_BENCH_BATCH", "4"))
+    n = max(args.steps, batch)
+    cfg = binding.make_config(wl.height, wl.width, flow_levels=wl.flow_levels, tier_mode=wl.tier_mode,
+                              k_fp16=wl.k_fp16, k_int8=wl.k_int8, k_int4=wl.k_int4, n_layers=1, n_heads=1,
+                              cap_fp16=576 * n, cap_int8=576 * n, cap_int4=576 * n, max_frames=n)
+    ctx = binding.SaliContext(cfg, "cuda:0")
+    n_src = min(16, n)
+    video = synth.video(args.config, n_src)
+    rgbs = [torch.from_numpy(video.frame(t)).to("cuda:0") for t in range(n_src)]
+
+    def run():
+        ctx.reset()
+        for first in range(0, n, batch):
+            frames = range(first, min(n, first + batch))
+            ctx.analyze_batch([rgbs[t % n_src] for t in frames], first)
+
+    run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.close()
+    print(json.dumps({"what": "image side alone (sali_analyze_batch, one stream, idle GPU)", "workload": wl.name,
+                      "source": f"{wl.width}x{wl.height}", "frames": n, "frames_per_call": batch,
+                      "us_per_frame": dt / n * 1e6}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,6 +117,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--extras", action="store_true",
                     help="also time the path without the read-back and the one-stream frame-by-frame path")
+    ap.add_argument("--image-only", action="store_true",
+                    help="time only the image side (sali_analyze_batch on one stream, nothing else on the GPU) and "
+                         "print its cost per frame; not the benchmark, a reference figure for profiling")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -96,6 +132,9 @@ def main():
     from paper_2602_14236_amd import binding, synth
 
     wl = synth.WORKLOADS[args.config]
+    if args.image_only:
+        image_only(args, wl)
+        return
     n_layers = wl.n_layers if args.layers is None else args.layers
     steps, warmup = args.steps, args.warmup
     n_src = min(wl.frames, max(steps, warmup))          # distinct input frames kept resident
