@@ -78,7 +78,8 @@ typedef struct sali_config {
     int32_t n_layers, n_heads;       /* K/V shape [n_layers][2][n_heads][576][head_dim]                */
     int32_t head_dim;                /* must be 128                                                    */
     int32_t group;                   /* quantisation group along head_dim; must be 32                  */
-    int64_t cap_fp16, cap_int8, cap_int4;    /* pool capacities in tokens (rows per layer/K|V/head)    */
+    int64_t cap_fp16, cap_int8, cap_int4;    /* pool capacities in tokens (rows per layer/K|V/head),
+                                                each below 2^24 (one plane of a pool stays under 4 GiB)  */
     int32_t max_frames;              /* frame ids are 0 .. max_frames-1                                */
     int32_t reserved;
 } sali_config;

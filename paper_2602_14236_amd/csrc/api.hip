@@ -65,7 +65,8 @@ int check_config(const sali_config* c) {
     }
     if (c->n_layers < 1 || c->n_heads < 1 || (long long)c->n_layers * 2 * c->n_heads > 65535) return SALI_ERR_CONFIG;
     if (c->cap_fp16 < 0 || c->cap_int8 < 0 || c->cap_int4 < 0) return SALI_ERR_CONFIG;
-    if (c->cap_fp16 > 0x7FFFFFFFll || c->cap_int8 > 0x7FFFFFFFll || c->cap_int4 > 0x7FFFFFFFll) return SALI_ERR_CONFIG;
+    // one plane of a pool stays below 4 GiB (16 Mi rows of 256 B): the kernels address inside a plane with 32 bits
+    if (c->cap_fp16 >= (1ll << 24) || c->cap_int8 >= (1ll << 24) || c->cap_int4 >= (1ll << 24)) return SALI_ERR_CONFIG;
     if (c->max_frames < 1 || c->max_frames > (1 << 24)) return SALI_ERR_CONFIG;
     // the smallest pyramid level must still be an image
     int h = c->src_h, w = c->src_w;

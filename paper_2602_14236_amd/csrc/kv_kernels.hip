@@ -5,14 +5,15 @@
 // and Just-In-Time Dequantization.
 //
 // This file must be compiled with -ffp-contract=off: every quantisation step is one IEEE
-// fp32 operation (divide, multiply, subtract, round-half-even) and the only fused
-// multiply-add is the one written out in the INT4 dequantiser.
+// fp32 operation (divide, multiply, subtract, round-half-even); the only fused multiply-adds
+// are written out: the one of the INT4 dequantiser and the exact integer packing of INT4 codes.
 //
 // Data movement: a K/V row (one token in one layer / K|V / head) is 128 halves = 256 B and is
 // handled by 16 adjacent lanes, 16 B each, so a wave moves four rows per instruction and a
 // 32-value quantisation group sits in one lane quad (reductions are two DPP quad swaps).
 // Rows are visited in pool order (all FP16 tokens, then INT8, then INT4, in token order inside
-// a tier), so pool writes are contiguous runs and pruned tokens are never read.
+// a tier), so pool writes are contiguous runs and pruned tokens are never read; a lane group takes
+// four consecutive pool rows.
 
 #include "sali_internal.h"
 #include "tier_body.h"
@@ -57,6 +58,26 @@ __device__ __forceinline__ float quad_min(float v) {
     v = fminf(v, quad_swap1(v));
     return fminf(v, quad_swap2(v));
 }
+// max over a quad of values >= 0 (never NaN): their bit patterns order like the numbers
+__device__ __forceinline__ float quad_max_nonneg(float v) {
+    uint32_t b = __builtin_bit_cast(uint32_t, v);
+    b = max(b, (uint32_t)__builtin_amdgcn_mov_dpp((int)b, 0xB1, 0xF, 0xF, true));
+    b = max(b, (uint32_t)__builtin_amdgcn_mov_dpp((int)b, 0x4E, 0xF, 0xF, true));
+    return __builtin_bit_cast(float, b);
+}
+// the value held by the odd lane of each lane pair (quad_perm [1, 1, 3, 3])
+__device__ __forceinline__ float quad_from_odd(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xF5, 0xF, 0xF, true));
+}
+// 1.5 * 2^23: adding it to |p| < 2^22 rounds p to the nearest integer (ties to even) and leaves that
+// integer, two's complement, in the low mantissa bits of the sum
+constexpr float kRoundMagic = 12582912.0f;
+// the low bytes of four words, a in bits 0..7 up to d in bits 24..31
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);      // bytes: 0 = a.b0, 1 = b.b0, 2 = 3 = zero
+    const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return ab | (cd << 16);
+}
 
 }  // namespace
 
@@ -78,11 +99,26 @@ __global__ __launch_bounds__(kTierThreads) void k_tier(const float* __restrict__
 // id first_frame_id + i.
 // ---------------------------------------------------------------------------------------------
 // kNTL / kNTS: non-temporal loads / stores
+//
+// Instruction budget.  The kernel streams at HBM speed only while its vector ALU work stays well
+// under the memory time, so the per-row arithmetic is kept short without changing one result bit:
+//   * inf/NaN detection is integer work on the packed halves: (w & 0x7FFF7FFF) + 0x04000400 has bit
+//     15 (31) set exactly when the low (high) half has an all-ones exponent; the sums of all rows of
+//     a thread are OR-ed and tested once;
+//   * the two IEEE divisions of a group (scale = m / 127, inv = 127 / m) are shared by a lane pair:
+//     even lanes divide for the scale, odd lanes for the inverse, one quad permute hands the
+//     inverse over (every lane of a quad holds the same m, so the quotients are the same numbers);
+//   * round-half-even of x * inv is the fp32 addition of 1.5 * 2^23, whose low mantissa bits are the
+//     two's-complement integer; |x * inv| <= 127 (1 + 2^-22) rounds to at most 127, so the clamp to
+//     [-127, 127] of the definition never acts on finite input and is not executed.  INT4 likewise:
+//     0 <= (x - min) * inv <= 15 (1 + 2^-22); its eight codes are packed with exact fp32
+//     multiply-adds (integers below 2^16) before one conversion.
+//   A group that holds an inf or NaN raises SALI_FAULT_NONFINITE; its codes are then unspecified.
 template <bool kNTL, bool kNTS>
 __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* __restrict__ rows, int first_frame_id,
                                               const uint16_t* __restrict__ order_base, Pools pools, Cursors* cur) {
-    const int frame_id = first_frame_id + (int)blockIdx.z;
-    const u32x4* __restrict__ kv = reinterpret_cast<const u32x4*>(f.kv[blockIdx.z]);
+    const int bz = blockIdx.z;
+    const int frame_id = first_frame_id + bz;
     const uint16_t* __restrict__ order = order_base + (size_t)frame_id * kTokens;
     const sali_frame_row row = rows[frame_id];
     if (row.stored == 0) return;
@@ -91,34 +127,52 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
     const int j0 = blockIdx.x * kRowsPerBlock;
     if (j0 >= nkeep) return;
     const size_t plane = blockIdx.y;
-    const int g = threadIdx.x >> 4;     // lane group = one row per step
+    const int g = threadIdx.x >> 4;     // lane group: four consecutive rows of the tile
     const int l = threadIdx.x & 15;     // 16-byte chunk of the row
+    // plane bases are uniform (scalar registers); offsets inside a plane fit 32 bits (checked on the host)
+    const char* __restrict__ kv_plane = reinterpret_cast<const char*>(f.kv[bz]) + plane * (size_t)(kTokens * kHeadDim * 2);
+    char* __restrict__ p16_plane = reinterpret_cast<char*>(pools.p16) + plane * (size_t)pools.cap16 * (kHeadDim * 2);
+    char* __restrict__ c8_plane = reinterpret_cast<char*>(pools.c8) + plane * (size_t)pools.cap8 * kHeadDim;
+    char* __restrict__ c4_plane = reinterpret_cast<char*>(pools.c4) + plane * (size_t)pools.cap4 * (kHeadDim / 2);
+    float* __restrict__ s8_plane = pools.s8 + plane * (size_t)pools.cap8 * kGroupsPerRow;
+    float* __restrict__ s4_plane = pools.s4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
+    uint16_t* __restrict__ z4_plane = pools.z4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
 
+    // Three phases, so that the in-order memory counter never makes a wave wait for more than it
+    // needs: (1) all row loads are issued back to back: a lane group takes four consecutive pool rows,
+    // whose tokens are one aligned 8-byte read of the order table, and rows past the end re-read the
+    // block's first row instead of branching; (2) the rows are quantised in registers as their loads
+    // arrive, with no memory operation in between; (3) all stores are issued.
+    const u32x2 tok2 = *reinterpret_cast<const u32x2*>(order + j0 + kRowsPerLaneGroup * g);
+    const uint32_t tok_first = order[j0];
+    const uint32_t tok[kRowsPerLaneGroup] = {tok2.x & 0xFFFFu, tok2.x >> 16, tok2.y & 0xFFFFu, tok2.y >> 16};
     Row16B v[kRowsPerLaneGroup];
-    int jj[kRowsPerLaneGroup];
 #pragma unroll
     for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + r * 16 + g;
-        jj[r] = j;
-        if (j < nkeep) {
-            const int tok = order[j];
-            v[r].u = kNTL ? __builtin_nontemporal_load(&kv[(plane * kTokens + tok) * 16 + l]) : kv[(plane * kTokens + tok) * 16 + l];
-        } else {
-            v[r].u = zero4();
-        }
+        const int j = j0 + kRowsPerLaneGroup * g + r;
+        const uint32_t off = (j < nkeep ? tok[r] : tok_first) * (kHeadDim * 2) + (uint32_t)l * 16u;
+        const u32x4* src = reinterpret_cast<const u32x4*>(kv_plane + off);
+        v[r].u = kNTL ? __builtin_nontemporal_load(src) : *src;
     }
 
-    bool bad = false;
+    uint32_t expo = 0;                  // bit 15 / 31 set <=> some half of this thread's rows is inf or NaN
+    const bool odd = (l & 1) != 0;
+    float meta[kRowsPerLaneGroup];      // the group's scale (even lanes)
+    uint16_t zero[kRowsPerLaneGroup];   // INT4: the group's zero-point, fp16 bits
 #pragma unroll
     for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = jj[r];
-        if (j >= nkeep) continue;
+        const int j = j0 + kRowsPerLaneGroup * g + r;
+        meta[r] = 0.0f;
+        zero[r] = 0;
+        // rows past the end hold a copy of the block's first row and are quantised like any other (and
+        // not stored): a skip here would leave a path on which the row's load is never waited for, and
+        // the stores below would then each wait for the whole memory counter
+        expo |= (v[r].u.x & 0x7FFF7FFFu) + 0x04000400u;
+        expo |= (v[r].u.y & 0x7FFF7FFFu) + 0x04000400u;
+        expo |= (v[r].u.z & 0x7FFF7FFFu) + 0x04000400u;
+        expo |= (v[r].u.w & 0x7FFF7FFFu) + 0x04000400u;
         if (j < n16) {
             // FP16 tier: verbatim copy
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bad |= (v[r].s[e] & 0x7C00u) == 0x7C00u;
-            u32x4* dst = reinterpret_cast<u32x4*>(pools.p16) + ((plane * pools.cap16 + row.base16 + j) * 16 + l);
-            if (kNTS) __builtin_nontemporal_store(v[r].u, dst); else *dst = v[r].u;
         } else if (j < n16 + n8) {
             // INT8, symmetric: scale = max|x| / 127, q = rne(x * (127 / max|x|))
             float x[8];
@@ -127,24 +181,18 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
             for (int e = 0; e < 8; ++e) {
                 x[e] = (float)v[r].h[e];
                 m = fmaxf(m, fabsf(x[e]));
-                bad |= (v[r].s[e] & 0x7C00u) == 0x7C00u;
             }
-            m = quad_max(m);
+            m = quad_max_nonneg(m);
             const bool nz = m > 0.0f;
-            const float scale = nz ? m / 127.0f : 0.0f;
-            const float inv = nz ? 127.0f / m : 0.0f;
-            uint32_t lo = 0, hi = 0;
+            const float quot = (odd ? 127.0f : m) / (odd ? m : 127.0f);      // even lanes: scale, odd lanes: inverse
+            const float mine = nz ? quot : 0.0f;
+            const float inv = quad_from_odd(mine);
+            uint32_t t[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                int q = (int)rintf(x[e] * inv);
-                q = min(127, max(-127, q));
-                if (e < 4) lo |= (uint32_t)(q & 0xFF) << (8 * e);
-                else hi |= (uint32_t)(q & 0xFF) << (8 * (e - 4));
-            }
-            const size_t prow = plane * pools.cap8 + row.base8 + (j - n16);
-            u32x2* dst = reinterpret_cast<u32x2*>(pools.c8 + prow * kHeadDim) + l;
-            if (kNTS) __builtin_nontemporal_store((u32x2){lo, hi}, dst); else *dst = (u32x2){lo, hi};
-            if ((l & 3) == 0) pools.s8[prow * kGroupsPerRow + (l >> 2)] = scale;
+            for (int e = 0; e < 8; ++e) t[e] = __builtin_bit_cast(uint32_t, x[e] * inv + kRoundMagic);
+            v[r].u.x = pack_low_bytes(t[0], t[1], t[2], t[3]);
+            v[r].u.y = pack_low_bytes(t[4], t[5], t[6], t[7]);
+            meta[r] = mine;
         } else {
             // INT4, asymmetric: scale = (max - min) / 15, q = rne((x - min) * (15 / (max - min)))
             float x[8];
@@ -154,32 +202,129 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
                 x[e] = (float)v[r].h[e];
                 mn = fminf(mn, x[e]);
                 mx = fmaxf(mx, x[e]);
-                bad |= (v[r].s[e] & 0x7C00u) == 0x7C00u;
             }
             mn = quad_min(mn);
             mx = quad_max(mx);
             const float range = mx - mn;
             const bool nz = range > 0.0f;
-            const float scale = nz ? range / 15.0f : 0.0f;
-            const float inv = nz ? 15.0f / range : 0.0f;
-            uint32_t packed = 0;
+            const float quot = (odd ? 15.0f : range) / (odd ? range : 15.0f);
+            const float mine = nz ? quot : 0.0f;
+            const float inv = quad_from_odd(mine);
+            float q[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float d = x[e] - mn;
-                int q = (int)rintf(d * inv);
-                q = min(15, max(0, q));
-                packed |= (uint32_t)q << (4 * e);       // element 2k low nibble, 2k+1 high nibble of byte k
-            }
-            const size_t prow = plane * pools.cap4 + row.base4 + (j - n16 - n8);
-            uint32_t* dst = reinterpret_cast<uint32_t*>(pools.c4 + prow * (kHeadDim / 2)) + l;
-            if (kNTS) __builtin_nontemporal_store(packed, dst); else *dst = packed;
+            for (int e = 0; e < 8; ++e) q[e] = rintf((x[e] - mn) * inv);
+            // element 2k low nibble, 2k+1 high nibble of byte k: exact integer arithmetic in fp32
+            const float lo = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(q[3], 16.0f, q[2]), 16.0f, q[1]), 16.0f, q[0]);
+            const float hi = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(q[7], 16.0f, q[6]), 16.0f, q[5]), 16.0f, q[4]);
+            v[r].u.x = (uint32_t)lo | ((uint32_t)hi << 16);
+            meta[r] = mine;
+            zero[r] = __builtin_bit_cast(uint16_t, (_Float16)mn);
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
+        const int j = j0 + kRowsPerLaneGroup * g + r;
+        if (j >= nkeep) continue;
+        if (j < n16) {
+            u32x4* dst = reinterpret_cast<u32x4*>(p16_plane + ((uint32_t)(row.base16 + j) * (kHeadDim * 2) + (uint32_t)l * 16u));
+            if (kNTS) __builtin_nontemporal_store(v[r].u, dst); else *dst = v[r].u;
+        } else if (j < n16 + n8) {
+            const uint32_t prow = (uint32_t)(row.base8 + (j - n16));
+            u32x2* dst = reinterpret_cast<u32x2*>(c8_plane + (prow * (uint32_t)kHeadDim + (uint32_t)l * 8u));
+            const u32x2 codes = {v[r].u.x, v[r].u.y};
+            if (kNTS) __builtin_nontemporal_store(codes, dst); else *dst = codes;
+            if ((l & 3) == 0) s8_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = meta[r];
+        } else {
+            const uint32_t prow = (uint32_t)(row.base4 + (j - n16 - n8));
+            uint32_t* dst = reinterpret_cast<uint32_t*>(c4_plane + (prow * (uint32_t)(kHeadDim / 2) + (uint32_t)l * 4u));
+            if (kNTS) __builtin_nontemporal_store(v[r].u.x, dst); else *dst = v[r].u.x;
             if ((l & 3) == 0) {
-                pools.s4[prow * kGroupsPerRow + (l >> 2)] = scale;
-                pools.z4[prow * kGroupsPerRow + (l >> 2)] = __builtin_bit_cast(uint16_t, (_Float16)mn);
+                s4_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = meta[r];
+                z4_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = zero[r];
             }
         }
     }
-    if (bad) atomicOr(&cur->status, SALI_FAULT_NONFINITE);
+    if ((expo & 0x80008000u) != 0) atomicOr(&cur->status, SALI_FAULT_NONFINITE);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dequantise-on-read of the four consecutive pool rows of one lane group.  kTier >= 0: every row of
+// the wave is of that tier (0 FP16, 1 INT8, 2 INT4, 3 pruned); kTier < 0: tiers are tested per row.
+// Three phases as in the pack kernel: all loads, then the arithmetic, then the stores.
+struct UnpackPlanes {
+    const char* p16;
+    const char* c8;
+    const char* c4;
+    const float* s8;
+    const float* s4;
+    const uint16_t* z4;
+    char* out;
+};
+
+template <bool kNTL, bool kNTS, int kTier>
+__device__ __forceinline__ void unpack_rows(const UnpackPlanes& pl, const sali_frame_row& row,
+                                            const uint16_t* __restrict__ order, uint8_t* valid, bool first_plane,
+                                            int j0, int g, int l) {
+    const int n16 = row.n16, n8 = row.n8, n4 = row.n4;
+    const u32x2 tok2 = *reinterpret_cast<const u32x2*>(order + j0 + kRowsPerLaneGroup * g);
+    const uint32_t tok[kRowsPerLaneGroup] = {tok2.x & 0xFFFFu, tok2.x >> 16, tok2.y & 0xFFFFu, tok2.y >> 16};
+    Row16B raw[kRowsPerLaneGroup];
+    float scale[kRowsPerLaneGroup];
+    uint16_t zbits[kRowsPerLaneGroup];
+    int tier[kRowsPerLaneGroup];
+#pragma unroll
+    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
+        const int j = j0 + kRowsPerLaneGroup * g + r;          // always < 576
+        tier[r] = kTier >= 0 ? kTier : (j < n16 ? 0 : (j < n16 + n8 ? 1 : (j < n16 + n8 + n4 ? 2 : 3)));
+        raw[r].u = zero4();
+        scale[r] = 0.0f;
+        zbits[r] = 0;
+        if (tier[r] == 0) {
+            const u32x4* srcp = reinterpret_cast<const u32x4*>(pl.p16 + ((uint32_t)(row.base16 + j) * (kHeadDim * 2) + (uint32_t)l * 16u));
+            raw[r].u = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
+        } else if (tier[r] == 1) {
+            const uint32_t prow = (uint32_t)(row.base8 + (j - n16));
+            const u32x2* srcp = reinterpret_cast<const u32x2*>(pl.c8 + (prow * (uint32_t)kHeadDim + (uint32_t)l * 8u));
+            const u32x2 c = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
+            raw[r].u.x = c.x;
+            raw[r].u.y = c.y;
+            scale[r] = pl.s8[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)];
+        } else if (tier[r] == 2) {
+            const uint32_t prow = (uint32_t)(row.base4 + (j - n16 - n8));
+            const uint32_t* srcp = reinterpret_cast<const uint32_t*>(pl.c4 + (prow * (uint32_t)(kHeadDim / 2) + (uint32_t)l * 4u));
+            raw[r].u.x = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
+            scale[r] = pl.s4[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)];
+            zbits[r] = pl.z4[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
+        Row16B o;
+        o.u = raw[r].u;                                         // FP16 tier: as stored; pruned: zeros
+        if (tier[r] == 1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t word = e < 4 ? raw[r].u.x : raw[r].u.y;
+                const int q = (int)(int8_t)((word >> (8 * (e & 3))) & 0xFF);
+                o.h[e] = to_half_after_f32((float)q * scale[r]);          // one fp32 multiply, then RNE to fp16
+            }
+        } else if (tier[r] == 2) {
+            const float zero = (float)__builtin_bit_cast(_Float16, zbits[r]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int q = (int)((raw[r].u.x >> (4 * e)) & 0xF);
+                o.h[e] = to_half_after_f32(__builtin_fmaf((float)q, scale[r], zero));   // fused: one fp32 rounding
+            }
+        }
+        raw[r].u = o.u;
+    }
+#pragma unroll
+    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
+        u32x4* dst = reinterpret_cast<u32x4*>(pl.out + (tok[r] * (uint32_t)(kHeadDim * 2) + (uint32_t)l * 16u));
+        if (kNTS) __builtin_nontemporal_store(raw[r].u, dst); else *dst = raw[r].u;
+        if (valid != nullptr && first_plane && l == 0) valid[tok[r]] = tier[r] != 3 ? 1 : 0;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -202,7 +347,7 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
         // nothing stored under this id: read back as an all-pruned frame
 #pragma unroll
         for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-            const int tok = j0 + r * 16 + g;
+            const int tok = j0 + kRowsPerLaneGroup * g + r;
             out[(plane * kTokens + tok) * 16 + l] = zero4();
             if (valid != nullptr && plane == 0 && l == 0) valid[tok] = 0;
         }
@@ -212,61 +357,28 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
     const sali_frame_row row = rows[src];
     const uint16_t* order = order_base + (size_t)src * kTokens;
     const int n16 = row.n16, n8 = row.n8, n4 = row.n4;
+    // plane bases are uniform; offsets inside a plane fit 32 bits
+    const char* __restrict__ p16_plane = reinterpret_cast<const char*>(pools.p16) + plane * (size_t)pools.cap16 * (kHeadDim * 2);
+    const char* __restrict__ c8_plane = reinterpret_cast<const char*>(pools.c8) + plane * (size_t)pools.cap8 * kHeadDim;
+    const char* __restrict__ c4_plane = reinterpret_cast<const char*>(pools.c4) + plane * (size_t)pools.cap4 * (kHeadDim / 2);
+    const float* __restrict__ s8_plane = pools.s8 + plane * (size_t)pools.cap8 * kGroupsPerRow;
+    const float* __restrict__ s4_plane = pools.s4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
+    const uint16_t* __restrict__ z4_plane = pools.z4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
+    char* __restrict__ out_plane = reinterpret_cast<char*>(out) + plane * (size_t)(kTokens * kHeadDim * 2);
 
-    int tok[kRowsPerLaneGroup];
-    Row16B raw[kRowsPerLaneGroup];
-    float scale[kRowsPerLaneGroup], zero[kRowsPerLaneGroup];
-#pragma unroll
-    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + r * 16 + g;          // always < 576
-        tok[r] = order[j];
-        raw[r].u = zero4();
-        scale[r] = 0.0f;
-        zero[r] = 0.0f;
-        if (j < n16) {
-            const u32x4* srcp = reinterpret_cast<const u32x4*>(pools.p16) + ((plane * pools.cap16 + row.base16 + j) * 16 + l);
-            raw[r].u = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
-        } else if (j < n16 + n8) {
-            const size_t prow = plane * pools.cap8 + row.base8 + (j - n16);
-            const u32x2* srcp = reinterpret_cast<const u32x2*>(pools.c8 + prow * kHeadDim) + l;
-            const u32x2 c = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
-            raw[r].u.x = c.x;
-            raw[r].u.y = c.y;
-            scale[r] = pools.s8[prow * kGroupsPerRow + (l >> 2)];
-        } else if (j < n16 + n8 + n4) {
-            const size_t prow = plane * pools.cap4 + row.base4 + (j - n16 - n8);
-            const uint32_t* srcp = reinterpret_cast<const uint32_t*>(pools.c4 + prow * (kHeadDim / 2)) + l;
-            raw[r].u.x = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
-            scale[r] = pools.s4[prow * kGroupsPerRow + (l >> 2)];
-            zero[r] = (float)__builtin_bit_cast(_Float16, pools.z4[prow * kGroupsPerRow + (l >> 2)]);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + r * 16 + g;
-        Row16B o;
-        if (j < n16) {
-            o.u = raw[r].u;
-        } else if (j < n16 + n8) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t word = e < 4 ? raw[r].u.x : raw[r].u.y;
-                const int q = (int)(int8_t)((word >> (8 * (e & 3))) & 0xFF);
-                o.h[e] = to_half_after_f32((float)q * scale[r]);          // one fp32 multiply, then RNE to fp16
-            }
-        } else if (j < n16 + n8 + n4) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = (int)((raw[r].u.x >> (4 * e)) & 0xF);
-                o.h[e] = to_half_after_f32(__builtin_fmaf((float)q, scale[r], zero[r]));   // fused: one fp32 rounding
-            }
-        } else {
-            o.u = zero4();
-        }
-        if (kNTS) __builtin_nontemporal_store(o.u, &out[(plane * kTokens + tok[r]) * 16 + l]);
-        else out[(plane * kTokens + tok[r]) * 16 + l] = o.u;
-        if (valid != nullptr && plane == 0 && l == 0) valid[tok[r]] = (j < n16 + n8 + n4) ? 1 : 0;
-    }
+    UnpackPlanes pl = {p16_plane, c8_plane, c4_plane, s8_plane, s4_plane, z4_plane, out_plane};
+    // A wave covers 16 consecutive pool rows, nearly always of one tier: those waves take a path
+    // without tier branches (the scalar test below), where the compiler can issue all loads back to
+    // back and wait for each exactly when it is used; a wave that straddles a tier boundary takes
+    // the general path.
+    const int w0 = j0 + 16 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int w1 = w0 + 16;
+    const int e16 = n16, e8 = n16 + n8, e4 = n16 + n8 + n4;
+    if (w1 <= e16) unpack_rows<kNTL, kNTS, 0>(pl, row, order, valid, plane == 0, j0, g, l);
+    else if (w0 >= e16 && w1 <= e8) unpack_rows<kNTL, kNTS, 1>(pl, row, order, valid, plane == 0, j0, g, l);
+    else if (w0 >= e8 && w1 <= e4) unpack_rows<kNTL, kNTS, 2>(pl, row, order, valid, plane == 0, j0, g, l);
+    else if (w0 >= e4) unpack_rows<kNTL, kNTS, 3>(pl, row, order, valid, plane == 0, j0, g, l);
+    else unpack_rows<kNTL, kNTS, -1>(pl, row, order, valid, plane == 0, j0, g, l);
 }
 
 // ---------------------------------------------------------------------------------------------
