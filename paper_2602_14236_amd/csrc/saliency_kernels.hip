@@ -306,13 +306,84 @@ __global__ __launch_bounds__(256) void k_union(PrepBatch f, int h, int w) {
     union_strip(f.cls[blockIdx.z], f.parent[blockIdx.z], h, w, blockIdx.x, blockIdx.y);
 }
 
+// Gate (Eq. 6), tier assignment and compaction indices of frame `b` of a launch of `n_frames`, by
+// one block of 256 threads, after every patch score and patch motion of the frame has been written:
+// n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; a frame without
+// predecessor (no flow) is never redundant.  The last such block of the launch (arrival counter,
+// nobody waits) writes the frame-table rows and advances the pool cursors in video order.
+__device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const PoolBatch& f, int b, int n_frames,
+                                          float tau_t, float theta_r, const TierLaunch& tl, uint32_t* batch_done) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; a frame
+    // without predecessor (no flow) is never redundant
+    const bool have_flow = f.flow[b] != nullptr;
+    int n = 0;
+    if (have_flow) {
+        for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
+            const float v = __hip_atomic_load(f.dp[b] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            n += (v < tau_t) ? 1 : 0;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
+    if (lane == 0) s_cnt[wave] = n;
+    __syncthreads();
+    const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    const float r = (float)n_static / (float)kTokens;
+    const bool redundant = have_flow && r > theta_r;
+    TierCounts tc = {};
+    tc.state = 1;
+    if (!redundant)
+        tc = tier_rank(sh, f.scores[b], tl.tp, tl.tier + (size_t)b * kTokens, tl.slot + (size_t)b * kTokens,
+                       tl.order + (size_t)b * kTokens);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sali_gate gt;
+        gt.n_static = n_static;
+        gt.r_frame = have_flow ? r : 0.0f;
+        gt.redundant = redundant ? 1 : 0;
+        gt.reserved = 0;
+        *f.gate[b] = gt;
+        *f.frame_done[b] = 0u;          // ready for the next launch
+        int32_t* out = reinterpret_cast<int32_t*>(f.tcounts[b]);
+        __hip_atomic_store(out + 0, tc.state, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            __hip_atomic_store(out + 1 + t, tc.cnt[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();                // counts, tiers, slots and order lists before the arrival
+        if (atomicAdd(batch_done, 1u) == (uint32_t)n_frames - 1u) {
+            __threadfence();
+            *batch_done = 0u;
+            // all counts first (independent loads), then the rows with the cursors in registers
+            TierCounts all[kMaxBatch];
+#pragma unroll
+            for (int i = 0; i < kMaxBatch; ++i) {
+                all[i] = {};
+                if (i < n_frames) {
+                    const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
+                    all[i].state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        all[i].cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            CursorRegs cr = cursor_load(tl.cur);
+#pragma unroll
+            for (int i = 0; i < kMaxBatch; ++i)
+                if (i < n_frames) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4);
+            cursor_store(tl.cur, cr);
+        }
+    }
+}
+
 // Eq. 7 score of each patch and, in the chained step (do_tier), also its motion (Eq. 5) from the
 // flow field.  kWaves = 1: one wave per patch, four patches per block of 256 threads (small
-// patches); kWaves = 4: the whole block works on one patch (large frames).  The last block to finish
-// (atomic arrival counter, nobody waits) evaluates the gate (Eq. 6) and either writes the pointer
-// row of a redundant frame or assigns tiers and compaction indices.  So one launch replaces three,
-// with one device-scope fence per block.
-template <int kWaves>
+// patches); kWaves = 4: the whole block works on one patch (large frames).
+// kFusedTail: the last block of a FRAME to finish (atomic arrival counter, nobody waits) runs
+// pool_tail for it, so one launch replaces three, at the price of one device-scope fence per
+// block.  That pays for 144 blocks per frame; with 576 per frame (large frames) the fences and
+// arrivals cost 110 us per four-frame launch at 1920x1080 against 33 us of pooling, so there the
+// tail is a second small launch (k_pool_tail) and the blocks just end.
+template <int kWaves, bool kFusedTail>
 __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w, uint8_t* __restrict__ salmap,
                                                   int do_tier, float tau_t, float theta_r, TierLaunch tl,
                                                   uint32_t* batch_done) {
@@ -392,81 +463,25 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // Arrival counters, nobody waits.  The last block of a FRAME evaluates the frame's gate and ranks
-    // its tokens (frames in parallel); the last of those blocks in the whole launch then writes the
-    // frame-table rows and advances the pool cursors in video order.
+    if (!do_tier || !kFusedTail) return;
+    // Arrival counter, nobody waits: the last block of a frame goes on
     __syncthreads();
     if (threadIdx.x == 0) {
-        int last = 0;
-        if (do_tier) {
-            __threadfence();
-            last = (atomicAdd(f.frame_done[blockIdx.y], 1u) == gridDim.x - 1u) ? 1 : 0;
-        }
-        s_last = last;
+        __threadfence();
+        s_last = (atomicAdd(f.frame_done[blockIdx.y], 1u) == gridDim.x - 1u) ? 1 : 0;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    const int b = blockIdx.y;
-    // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; a frame
-    // without predecessor (no flow) is never redundant
-    const bool have_flow = f.flow[b] != nullptr;
-    int n = 0;
-    if (have_flow) {
-        for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
-            const float v = __hip_atomic_load(f.dp[b] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            n += (v < tau_t) ? 1 : 0;
-        }
-    }
-    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
-    if (lane == 0) s_cnt[wave] = n;
-    __syncthreads();
-    const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-    const float r = (float)n_static / (float)kTokens;
-    const bool redundant = have_flow && r > theta_r;
-    TierCounts tc = {};
-    tc.state = 1;
-    if (!redundant)
-        tc = tier_rank(sh, f.scores[b], tl.tp, tl.tier + (size_t)b * kTokens, tl.slot + (size_t)b * kTokens,
-                       tl.order + (size_t)b * kTokens);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        sali_gate gt;
-        gt.n_static = n_static;
-        gt.r_frame = have_flow ? r : 0.0f;
-        gt.redundant = redundant ? 1 : 0;
-        gt.reserved = 0;
-        *f.gate[b] = gt;
-        *f.frame_done[b] = 0u;          // ready for the next launch
-        int32_t* out = reinterpret_cast<int32_t*>(f.tcounts[b]);
-        __hip_atomic_store(out + 0, tc.state, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            __hip_atomic_store(out + 1 + t, tc.cnt[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();                // counts, tiers, slots and order lists before the arrival
-        if (atomicAdd(batch_done, 1u) == gridDim.y - 1u) {
-            __threadfence();
-            *batch_done = 0u;
-            // all counts first (independent loads), then the rows with the cursors in registers
-            TierCounts all[kMaxBatch];
-#pragma unroll
-            for (int i = 0; i < kMaxBatch; ++i) {
-                all[i] = {};
-                if (i < (int)gridDim.y) {
-                    const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
-                    all[i].state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        all[i].cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-            CursorRegs cr = cursor_load(tl.cur);
-#pragma unroll
-            for (int i = 0; i < kMaxBatch; ++i)
-                if (i < (int)gridDim.y) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4);
-            cursor_store(tl.cur, cr);
-        }
-    }
+    pool_tail(sh, s_cnt, f, (int)blockIdx.y, (int)gridDim.y, tau_t, theta_r, tl, batch_done);
+}
+
+// the tail as a launch of its own: one block per frame
+__global__ __launch_bounds__(kTierThreads) void k_pool_tail(PoolBatch f, float tau_t, float theta_r, TierLaunch tl,
+                                                            uint32_t* batch_done) {
+    __shared__ TierShared sh;
+    __shared__ int s_cnt[kTierThreads / 64];
+    pool_tail(sh, s_cnt, f, (int)blockIdx.x, (int)gridDim.x, tau_t, theta_r, tl, batch_done);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -495,13 +510,19 @@ hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salma
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
     const int do_tier = tier_or_null != nullptr ? 1 : 0;
-    // patches of up to 1024 pixels: one wave each (a quarter of the blocks and of the fences)
-    if ((long long)h * w <= 1024ll * kTokens)
-        hipLaunchKernelGGL(k_pool<1>, dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null,
+    // patches of up to 1024 pixels: one wave each, tail in the same launch
+    if ((long long)h * w <= 1024ll * kTokens) {
+        hipLaunchKernelGGL((k_pool<1, true>), dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null,
                            do_tier, tau_t, theta_r, t, d_done_counter);
-    else
-        hipLaunchKernelGGL(k_pool<4>, dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null, do_tier,
-                           tau_t, theta_r, t, d_done_counter);
+    } else {
+        hipLaunchKernelGGL((k_pool<4, false>), dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null,
+                           do_tier, tau_t, theta_r, t, d_done_counter);
+        if (do_tier) {
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(k_pool_tail, dim3(n), dim3(kTierThreads), 0, s, f, tau_t, theta_r, t, d_done_counter);
+        }
+    }
     return hipGetLastError();
 }
 
