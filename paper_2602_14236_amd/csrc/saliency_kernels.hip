@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
     __shared__ uint8_t s_y[kReg][kReg];
     __shared__ uint8_t s_b[kRegB][kRegB];
     __shared__ int s_m2[kRegM][kRegM];
-    __shared__ uint8_t s_lab[3][kRegB][kRegB];
+    __shared__ __align__(16) uint8_t s_lab[3][kRegB][kRegB];     // read as 32-bit words by the variance stage
     __shared__ unsigned long long s_sum[kPrepThreads / 64];
     __shared__ uint32_t s_lbl[kTile * kTile];             // tile-local union-find links, key = local index | weak bit
     __shared__ uint8_t s_cls[kTile][kTile];
@@ -201,30 +201,51 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
             const int n2 = s_m2[ty + 1 - dy1][tx + 1 - dx1];
             if (m2 > n1 && m2 >= n2) cls[q] = m2 >= hi2 ? 2 : (m2 >= lo2 ? 1 : 0);
 
-            // 5x5 colour variance: 25 * sum v^2 - (sum v)^2 per channel
-            uint32_t v = 0;
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                int s1 = 0, sq = 0;
-#pragma unroll
-                for (int a = -2; a <= 2; ++a) {
-                    const int yy = clampi(gy + a, 0, h - 1) - oy_b;
-#pragma unroll
-                    for (int b = -2; b <= 2; ++b) {
-                        const int xx = clampi(gx + b, 0, w - 1) - ox_b;
-                        const int val = s_lab[c][yy][xx];
-                        s1 += val;
-                        sq += val * val;
-                    }
-                }
-                v += (uint32_t)(25 * sq - s1 * s1);
-            }
-            const size_t gi = (size_t)gy * w + gx;
-            cls_out[gi] = (uint8_t)cls[q];
-            var_out[gi] = v;
-            local_sum += v;
+            cls_out[(size_t)gy * w + gx] = (uint8_t)cls[q];
         }
         s_cls[ty][tx] = (uint8_t)cls[q];
+    }
+    // 5x5 colour variance, 25 * sum v^2 - (sum v)^2 per channel, with its own pixel mapping: a thread
+    // takes a strip of four pixels of one tile row.  The cells of s_lab already hold the colour at the
+    // clamped image coordinate, so the window of pixel (ty, sx + i) is rows ty .. ty + 4, columns
+    // sx + i .. sx + i + 4 of the region: two aligned words per row cover all four windows, and
+    // sums and sums of squares of four bytes at a time are byte dot products.
+    {
+        const int vy = tid >> 3, sx = (tid & 7) * 4;
+        const int gy = y0 + vy, gx0 = x0 + sx;
+        uint32_t v[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            uint32_t s1[4] = {0u, 0u, 0u, 0u}, s2[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int a = 0; a < 5; ++a) {
+                const uint32_t* rowp = reinterpret_cast<const uint32_t*>(&s_lab[c][vy + a][sx]);
+                const uint32_t w0 = rowp[0], w1 = rowp[1];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t a4 = i == 0 ? w0 : __builtin_amdgcn_alignbyte(w1, w0, i);     // columns i .. i + 3
+                    const uint32_t b5 = (w1 >> (8 * i)) & 0xFFu;                                   // column i + 4
+                    s1[i] = __builtin_amdgcn_udot4(a4, 0x01010101u, s1[i], false) + b5;
+                    s2[i] = __builtin_amdgcn_udot4(a4, a4, s2[i], false) + b5 * b5;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] += 25u * s2[i] - s1[i] * s1[i];
+        }
+        if (gy < h) {
+            uint32_t* dst = var_out + (size_t)gy * w + gx0;
+            if (gx0 + 3 < w && (w & 3) == 0) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(v[0], v[1], v[2], v[3]);
+                local_sum += (unsigned long long)v[0] + v[1] + v[2] + v[3];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (gx0 + i < w) {
+                        dst[i] = v[i];
+                        local_sum += v[i];
+                    }
+            }
+        }
     }
     // block sum of V -> one atomic
     for (int off = 32; off > 0; off >>= 1) local_sum += __shfl_down(local_sum, off);
