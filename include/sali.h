@@ -79,7 +79,7 @@ typedef struct sali_config {
     int32_t head_dim;                /* must be 128                                                    */
     int32_t group;                   /* quantisation group along head_dim; must be 32                  */
     int64_t cap_fp16, cap_int8, cap_int4;    /* pool capacities in tokens (rows per layer/K|V/head),
-                                                each below 2^24 (one plane of a pool stays under 4 GiB)  */
+                                                each below 2^24                                          */
     int32_t max_frames;              /* frame ids are 0 .. max_frames-1                                */
     int32_t reserved;
 } sali_config;
@@ -97,15 +97,19 @@ typedef struct sali_frame_row {
     int32_t frame_id;
     int32_t src;                     /* frame whose pool rows hold this frame's K/V; -1 = none         */
     int32_t stored;                  /* 1: this frame wrote pool rows; 0: pointer or failed            */
-    int32_t base16, base8, base4;    /* first pool row of this frame in each pool                      */
+    int32_t base16, base8, base4;    /* first pool row (per plane) of this frame in each pool          */
     int32_t n16, n8, n4, n_pruned;   /* tokens per tier; sum = 576 when stored                         */
     int32_t reserved[2];
 } sali_frame_row;
 
-/* Byte offsets of the six arrays inside the caller's pool buffer, each
- * [n_layers][2][n_heads][cap][row]:  fp16 rows (head_dim halves), int8 codes (head_dim
- * bytes), int8 scales (head_dim/32 fp32), int4 codes (head_dim/2 bytes, element 2j in the
- * low nibble of byte j), int4 scales (fp32), int4 zero-points (fp16). */
+/* Byte offsets of the six arrays inside the caller's pool buffer: fp16 rows (head_dim halves),
+ * int8 codes (head_dim bytes), int8 scales (head_dim/32 fp32), int4 codes (head_dim/2 bytes,
+ * element 2j in the low nibble of byte j), int4 scales (fp32), int4 zero-points (fp16).
+ * Each array holds cap * P rows, P = n_layers * 2 * n_heads planes (plane = (layer * 2 + K|V) *
+ * n_heads + head), laid out frame by frame: a stored frame whose frame-table row says base = b and
+ * n rows for that pool owns rows [b * P, (b + n) * P) of the array, and plane p of the frame owns
+ * rows [b * P + p * n, b * P + (p + 1) * n) in compaction order.  So all a frame writes to one
+ * array is a single contiguous range. */
 typedef struct sali_pool_layout {
     uint64_t off_fp16, off_codes8, off_scale8, off_codes4, off_scale4, off_zero4;
     uint64_t total_bytes;

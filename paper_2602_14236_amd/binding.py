@@ -306,7 +306,9 @@ class SaliContext:
         return f.value
 
     # ---- views of the pool buffer (for inspection; the layout is part of the ABI) ----------------
-    def pool_views(self):
+    def pool_views_flat(self):
+        """The six pool arrays as they lie in memory: [cap * n_planes, row], frame-major (a stored frame
+        with base b and n rows owns rows [b * P, (b + n) * P), plane p of it rows [b * P + p * n, ...))."""
         c, L, P = self.cfg, self.layout, self.n_planes
         g = c.head_dim // c.group
         buf = self.pools
@@ -316,11 +318,35 @@ class SaliContext:
             return buf[off:off + nbytes].view(dtype).view(shape)
 
         return {
-            "fp16": view(L.off_fp16, P * c.cap_fp16 * c.head_dim, torch.float16, (P, c.cap_fp16, c.head_dim)),
-            "codes8": view(L.off_codes8, P * c.cap_int8 * c.head_dim, torch.int8, (P, c.cap_int8, c.head_dim)),
-            "scale8": view(L.off_scale8, P * c.cap_int8 * g, torch.float32, (P, c.cap_int8, g)),
+            "fp16": view(L.off_fp16, P * c.cap_fp16 * c.head_dim, torch.float16, (P * c.cap_fp16, c.head_dim)),
+            "codes8": view(L.off_codes8, P * c.cap_int8 * c.head_dim, torch.int8, (P * c.cap_int8, c.head_dim)),
+            "scale8": view(L.off_scale8, P * c.cap_int8 * g, torch.float32, (P * c.cap_int8, g)),
             "codes4": view(L.off_codes4, P * c.cap_int4 * c.head_dim // 2, torch.uint8,
-                           (P, c.cap_int4, c.head_dim // 2)),
-            "scale4": view(L.off_scale4, P * c.cap_int4 * g, torch.float32, (P, c.cap_int4, g)),
-            "zero4": view(L.off_zero4, P * c.cap_int4 * g, torch.float16, (P, c.cap_int4, g)),
+                           (P * c.cap_int4, c.head_dim // 2)),
+            "scale4": view(L.off_scale4, P * c.cap_int4 * g, torch.float32, (P * c.cap_int4, g)),
+            "zero4": view(L.off_zero4, P * c.cap_int4 * g, torch.float16, (P * c.cap_int4, g)),
         }
+
+    def pool_views(self, planes=None):
+        """Copies of the pools regrouped per plane, [n_planes (or len(planes)), rows used, row], the
+        rows of a plane in the order of the frame table (what a plain [plane][cap][row] cache would
+        hold): for inspection and tests.  Synchronises the device."""
+        torch.cuda.synchronize(self.device)
+        P = self.n_planes
+        flat = self.pool_views_flat()
+        rows = [r for r in self.read_frame_table(0, self.cfg.max_frames) if r.stored]
+        which = {"fp16": ("base16", "n16"), "codes8": ("base8", "n8"), "scale8": ("base8", "n8"),
+                 "codes4": ("base4", "n4"), "scale4": ("base4", "n4"), "zero4": ("base4", "n4")}
+        sel = slice(None) if planes is None else torch.as_tensor(list(planes), device=self.device)
+        n_sel = P if planes is None else len(planes)
+        out = {}
+        for k, a in flat.items():
+            fb, fn = which[k]
+            used = max([getattr(r, fb) + getattr(r, fn) for r in rows], default=0)
+            t = torch.zeros((n_sel, used, a.shape[1]), dtype=a.dtype, device=a.device)
+            for r in rows:
+                b, n = getattr(r, fb), getattr(r, fn)
+                if n > 0:
+                    t[:, b:b + n] = a[b * P:(b + n) * P].view(P, n, a.shape[1])[sel]
+            out[k] = t
+        return out

@@ -65,7 +65,7 @@ int check_config(const sali_config* c) {
     }
     if (c->n_layers < 1 || c->n_heads < 1 || (long long)c->n_layers * 2 * c->n_heads > 65535) return SALI_ERR_CONFIG;
     if (c->cap_fp16 < 0 || c->cap_int8 < 0 || c->cap_int4 < 0) return SALI_ERR_CONFIG;
-    // one plane of a pool stays below 4 GiB (16 Mi rows of 256 B): the kernels address inside a plane with 32 bits
+    // a frame's rows of one plane stay far below 4 GiB: the kernels address inside them with 32 bits
     if (c->cap_fp16 >= (1ll << 24) || c->cap_int8 >= (1ll << 24) || c->cap_int4 >= (1ll << 24)) return SALI_ERR_CONFIG;
     if (c->max_frames < 1 || c->max_frames > (1 << 24)) return SALI_ERR_CONFIG;
     // the smallest pyramid level must still be an image
@@ -545,6 +545,7 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->pools.cap8 = (int32_t)cfg->cap_int8;
     c->pools.cap4 = (int32_t)cfg->cap_int4;
     c->n_planes = cfg->n_layers * 2 * cfg->n_heads;
+    c->pools.n_planes = c->n_planes;
     c->n_analysed = 0;
     for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
     for (int i = 0; i < 3; ++i) c->prof[i][0] = c->prof[i][1] = nullptr;

@@ -84,20 +84,19 @@ struct RawRow<SALI_TIER_INT4> {
     float scale, zero;
 };
 
-// prow = row index inside the plane's pool of that tier
-__device__ __forceinline__ void load_row(const Pools& pools, size_t plane, size_t prow, int l, RawRow<SALI_TIER_FP16>& r) {
-    r.u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pools.p16) + ((plane * pools.cap16 + prow) * 16 + l));
+// frow = row index in the flat pool array of that tier (pool_row0 of the frame and plane + the row
+// inside the frame's run)
+__device__ __forceinline__ void load_row(const Pools& pools, size_t frow, int l, RawRow<SALI_TIER_FP16>& r) {
+    r.u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pools.p16) + (frow * 16 + l));
 }
-__device__ __forceinline__ void load_row(const Pools& pools, size_t plane, size_t prow, int l, RawRow<SALI_TIER_INT8>& r) {
-    const size_t p = plane * pools.cap8 + prow;
-    r.u = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(pools.c8 + p * kHeadDim) + l);
-    r.scale = pools.s8[p * kGroupsPerRow + (l >> 2)];
+__device__ __forceinline__ void load_row(const Pools& pools, size_t frow, int l, RawRow<SALI_TIER_INT8>& r) {
+    r.u = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(pools.c8 + frow * kHeadDim) + l);
+    r.scale = pools.s8[frow * kGroupsPerRow + (l >> 2)];
 }
-__device__ __forceinline__ void load_row(const Pools& pools, size_t plane, size_t prow, int l, RawRow<SALI_TIER_INT4>& r) {
-    const size_t p = plane * pools.cap4 + prow;
-    r.u = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(pools.c4 + p * (kHeadDim / 2)) + l);
-    r.scale = pools.s4[p * kGroupsPerRow + (l >> 2)];
-    r.zero = (float)__builtin_bit_cast(_Float16, pools.z4[p * kGroupsPerRow + (l >> 2)]);
+__device__ __forceinline__ void load_row(const Pools& pools, size_t frow, int l, RawRow<SALI_TIER_INT4>& r) {
+    r.u = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(pools.c4 + frow * (kHeadDim / 2)) + l);
+    r.scale = pools.s4[frow * kGroupsPerRow + (l >> 2)];
+    r.zero = (float)__builtin_bit_cast(_Float16, pools.z4[frow * kGroupsPerRow + (l >> 2)]);
 }
 
 // The lane's 8 stored values of a row as fp32: the halves of an FP16 row, the raw codes of an
@@ -151,6 +150,7 @@ template <int kTier, int kQ>
 __device__ __forceinline__ void attend_tier(const Pools& pools, size_t plane_k, size_t plane_v, int base, int count,
                                             int split, int n_splits, int g, int l, const QueryPiece (&q)[kQ],
                                             float softmax_scale, float mult, SoftmaxState (&st)[kQ]) {
+    const size_t row0_k = pool_row0(pools, base, count, plane_k), row0_v = pool_row0(pools, base, count, plane_v);
     for (int jb = split * 64; jb < count; jb += n_splits * 64) {
         RawRow<kTier> rk[kRowsPerStep], rv[kRowsPerStep];
         bool valid[kRowsPerStep];
@@ -161,8 +161,8 @@ __device__ __forceinline__ void attend_tier(const Pools& pools, size_t plane_k, 
             rk[r] = {};
             rv[r] = {};
             if (valid[r]) {
-                load_row(pools, plane_k, (size_t)(base + j), l, rk[r]);
-                load_row(pools, plane_v, (size_t)(base + j), l, rv[r]);
+                load_row(pools, row0_k + (size_t)j, l, rk[r]);
+                load_row(pools, row0_v + (size_t)j, l, rv[r]);
             }
         }
         float s[kQ][kRowsPerStep];

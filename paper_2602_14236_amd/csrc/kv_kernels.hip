@@ -129,14 +129,16 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
     const size_t plane = blockIdx.y;
     const int g = threadIdx.x >> 4;     // lane group: four consecutive rows of the tile
     const int l = threadIdx.x & 15;     // 16-byte chunk of the row
-    // plane bases are uniform (scalar registers); offsets inside a plane fit 32 bits (checked on the host)
+    // the bases of this frame's rows of this plane are uniform (scalar registers); offsets from them fit 32 bits
     const char* __restrict__ kv_plane = reinterpret_cast<const char*>(f.kv[bz]) + plane * (size_t)(kTokens * kHeadDim * 2);
-    char* __restrict__ p16_plane = reinterpret_cast<char*>(pools.p16) + plane * (size_t)pools.cap16 * (kHeadDim * 2);
-    char* __restrict__ c8_plane = reinterpret_cast<char*>(pools.c8) + plane * (size_t)pools.cap8 * kHeadDim;
-    char* __restrict__ c4_plane = reinterpret_cast<char*>(pools.c4) + plane * (size_t)pools.cap4 * (kHeadDim / 2);
-    float* __restrict__ s8_plane = pools.s8 + plane * (size_t)pools.cap8 * kGroupsPerRow;
-    float* __restrict__ s4_plane = pools.s4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
-    uint16_t* __restrict__ z4_plane = pools.z4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
+    const size_t r16 = pool_row0(pools, row.base16, n16, plane), r8 = pool_row0(pools, row.base8, n8, plane),
+                 r4 = pool_row0(pools, row.base4, row.n4, plane);
+    char* __restrict__ p16_plane = reinterpret_cast<char*>(pools.p16) + r16 * (kHeadDim * 2);
+    char* __restrict__ c8_plane = reinterpret_cast<char*>(pools.c8) + r8 * kHeadDim;
+    char* __restrict__ c4_plane = reinterpret_cast<char*>(pools.c4) + r4 * (kHeadDim / 2);
+    float* __restrict__ s8_plane = pools.s8 + r8 * kGroupsPerRow;
+    float* __restrict__ s4_plane = pools.s4 + r4 * kGroupsPerRow;
+    uint16_t* __restrict__ z4_plane = pools.z4 + r4 * kGroupsPerRow;
 
     // Three phases, so that the in-order memory counter never makes a wave wait for more than it
     // needs: (1) all row loads are issued back to back: a lane group takes four consecutive pool rows,
@@ -227,16 +229,16 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
         const int j = j0 + kRowsPerLaneGroup * g + r;
         if (j >= nkeep) continue;
         if (j < n16) {
-            u32x4* dst = reinterpret_cast<u32x4*>(p16_plane + ((uint32_t)(row.base16 + j) * (kHeadDim * 2) + (uint32_t)l * 16u));
+            u32x4* dst = reinterpret_cast<u32x4*>(p16_plane + ((uint32_t)j * (kHeadDim * 2) + (uint32_t)l * 16u));
             if (kNTS) __builtin_nontemporal_store(v[r].u, dst); else *dst = v[r].u;
         } else if (j < n16 + n8) {
-            const uint32_t prow = (uint32_t)(row.base8 + (j - n16));
+            const uint32_t prow = (uint32_t)(j - n16);
             u32x2* dst = reinterpret_cast<u32x2*>(c8_plane + (prow * (uint32_t)kHeadDim + (uint32_t)l * 8u));
             const u32x2 codes = {v[r].u.x, v[r].u.y};
             if (kNTS) __builtin_nontemporal_store(codes, dst); else *dst = codes;
             if ((l & 3) == 0) s8_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = meta[r];
         } else {
-            const uint32_t prow = (uint32_t)(row.base4 + (j - n16 - n8));
+            const uint32_t prow = (uint32_t)(j - n16 - n8);
             uint32_t* dst = reinterpret_cast<uint32_t*>(c4_plane + (prow * (uint32_t)(kHeadDim / 2) + (uint32_t)l * 4u));
             if (kNTS) __builtin_nontemporal_store(v[r].u.x, dst); else *dst = v[r].u.x;
             if ((l & 3) == 0) {
@@ -281,17 +283,17 @@ __device__ __forceinline__ void unpack_rows(const UnpackPlanes& pl, const sali_f
         scale[r] = 0.0f;
         zbits[r] = 0;
         if (tier[r] == 0) {
-            const u32x4* srcp = reinterpret_cast<const u32x4*>(pl.p16 + ((uint32_t)(row.base16 + j) * (kHeadDim * 2) + (uint32_t)l * 16u));
+            const u32x4* srcp = reinterpret_cast<const u32x4*>(pl.p16 + ((uint32_t)j * (kHeadDim * 2) + (uint32_t)l * 16u));
             raw[r].u = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
         } else if (tier[r] == 1) {
-            const uint32_t prow = (uint32_t)(row.base8 + (j - n16));
+            const uint32_t prow = (uint32_t)(j - n16);
             const u32x2* srcp = reinterpret_cast<const u32x2*>(pl.c8 + (prow * (uint32_t)kHeadDim + (uint32_t)l * 8u));
             const u32x2 c = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
             raw[r].u.x = c.x;
             raw[r].u.y = c.y;
             scale[r] = pl.s8[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)];
         } else if (tier[r] == 2) {
-            const uint32_t prow = (uint32_t)(row.base4 + (j - n16 - n8));
+            const uint32_t prow = (uint32_t)(j - n16 - n8);
             const uint32_t* srcp = reinterpret_cast<const uint32_t*>(pl.c4 + (prow * (uint32_t)(kHeadDim / 2) + (uint32_t)l * 4u));
             raw[r].u.x = kNTL ? __builtin_nontemporal_load(srcp) : *srcp;
             scale[r] = pl.s4[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)];
@@ -357,13 +359,15 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
     const sali_frame_row row = rows[src];
     const uint16_t* order = order_base + (size_t)src * kTokens;
     const int n16 = row.n16, n8 = row.n8, n4 = row.n4;
-    // plane bases are uniform; offsets inside a plane fit 32 bits
-    const char* __restrict__ p16_plane = reinterpret_cast<const char*>(pools.p16) + plane * (size_t)pools.cap16 * (kHeadDim * 2);
-    const char* __restrict__ c8_plane = reinterpret_cast<const char*>(pools.c8) + plane * (size_t)pools.cap8 * kHeadDim;
-    const char* __restrict__ c4_plane = reinterpret_cast<const char*>(pools.c4) + plane * (size_t)pools.cap4 * (kHeadDim / 2);
-    const float* __restrict__ s8_plane = pools.s8 + plane * (size_t)pools.cap8 * kGroupsPerRow;
-    const float* __restrict__ s4_plane = pools.s4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
-    const uint16_t* __restrict__ z4_plane = pools.z4 + plane * (size_t)pools.cap4 * kGroupsPerRow;
+    // the bases of the source frame's rows of this plane are uniform; offsets from them fit 32 bits
+    const size_t r16 = pool_row0(pools, row.base16, n16, plane), r8 = pool_row0(pools, row.base8, n8, plane),
+                 r4 = pool_row0(pools, row.base4, n4, plane);
+    const char* __restrict__ p16_plane = reinterpret_cast<const char*>(pools.p16) + r16 * (kHeadDim * 2);
+    const char* __restrict__ c8_plane = reinterpret_cast<const char*>(pools.c8) + r8 * kHeadDim;
+    const char* __restrict__ c4_plane = reinterpret_cast<const char*>(pools.c4) + r4 * (kHeadDim / 2);
+    const float* __restrict__ s8_plane = pools.s8 + r8 * kGroupsPerRow;
+    const float* __restrict__ s4_plane = pools.s4 + r4 * kGroupsPerRow;
+    const uint16_t* __restrict__ z4_plane = pools.z4 + r4 * kGroupsPerRow;
     char* __restrict__ out_plane = reinterpret_cast<char*>(out) + plane * (size_t)(kTokens * kHeadDim * 2);
 
     UnpackPlanes pl = {p16_plane, c8_plane, c4_plane, s8_plane, s4_plane, z4_plane, out_plane};

@@ -41,6 +41,12 @@ struct Cursors {
     uint32_t pad[3];
 };
 
+// The six pool arrays.  Layout of each: frame-major.  A stored frame with first row `base` and
+// `n` rows in a pool owns rows [base * n_planes, (base + n) * n_planes) of the flat array, and inside
+// that run plane p (layer, K|V, head) owns rows [p * n, (p + 1) * n): everything one frame writes
+// to a pool is one contiguous range, whatever the capacity (with one big [plane][cap] array per
+// pool a frame touched n_planes ranges megabytes apart, which cost the pack kernel 8-16 % of its
+// bandwidth).
 struct Pools {
     uint16_t* p16;              // fp16 bit patterns
     int8_t* c8;
@@ -49,7 +55,13 @@ struct Pools {
     float* s4;
     uint16_t* z4;
     int32_t cap16, cap8, cap4;
+    int32_t n_planes;
 };
+
+// first flat row of plane `plane` of a frame whose run starts at `base` and has `n` rows per plane
+__host__ __device__ inline size_t pool_row0(const Pools& p, int base, int n, size_t plane) {
+    return (size_t)base * (size_t)p.n_planes + plane * (size_t)n;
+}
 
 struct TierParams {
     int32_t mode;

@@ -79,10 +79,10 @@ def _run_fullsize(cfg_id, n_frames, n_sample_planes, seed):
     assert ctx.get_status() == 0
 
     rows = ctx.read_frame_table(0, n_frames)
-    pv = ctx.pool_views()
     n_planes = wl.n_layers * 2 * wl.n_heads
     rng = np.random.default_rng(seed)
     planes = sorted(rng.choice(n_planes, n_sample_planes, replace=False).tolist())
+    pv = ctx.pool_views(planes)          # the sampled planes' rows, regrouped per plane
     base = [0, 0, 0]
     last_src = -1
     for t in range(n_frames):
@@ -105,19 +105,19 @@ def _run_fullsize(cfg_id, n_frames, n_sample_planes, seed):
         ip = np.nonzero(tier == 3)[0]
         exp_out = np.zeros_like(kv_planes)
         if i16.size:
-            got = pv["fp16"][planes, base[0]:base[0] + i16.size].cpu().numpy()
+            got = pv["fp16"][:, base[0]:base[0] + i16.size].cpu().numpy()
             assert_same(got, kv_planes[:, i16], f"frame {t} fp16 pool rows")
             exp_out[:, i16] = kv_planes[:, i16]
         if i8.size:
             q, s = oq.quant_int8(kv_planes[:, i8])
-            assert_same(pv["codes8"][planes, base[1]:base[1] + i8.size].cpu().numpy(), q, f"frame {t} int8 codes")
-            assert_same(pv["scale8"][planes, base[1]:base[1] + i8.size].cpu().numpy(), s, f"frame {t} int8 scales")
+            assert_same(pv["codes8"][:, base[1]:base[1] + i8.size].cpu().numpy(), q, f"frame {t} int8 codes")
+            assert_same(pv["scale8"][:, base[1]:base[1] + i8.size].cpu().numpy(), s, f"frame {t} int8 scales")
             exp_out[:, i8] = oq.dequant_int8(q, s)
         if i4.size:
             q, s, z = oq.quant_int4(kv_planes[:, i4])
-            assert_same(pv["codes4"][planes, base[2]:base[2] + i4.size].cpu().numpy(), oq.pack_nibbles(q), f"frame {t} int4 codes")
-            assert_same(pv["scale4"][planes, base[2]:base[2] + i4.size].cpu().numpy(), s, f"frame {t} int4 scales")
-            assert_same(pv["zero4"][planes, base[2]:base[2] + i4.size].cpu().numpy(), z, f"frame {t} int4 zero-points")
+            assert_same(pv["codes4"][:, base[2]:base[2] + i4.size].cpu().numpy(), oq.pack_nibbles(q), f"frame {t} int4 codes")
+            assert_same(pv["scale4"][:, base[2]:base[2] + i4.size].cpu().numpy(), s, f"frame {t} int4 scales")
+            assert_same(pv["zero4"][:, base[2]:base[2] + i4.size].cpu().numpy(), z, f"frame {t} int4 zero-points")
             exp_out[:, i4] = oq.dequant_int4(q, s, z)
         assert_same(out_planes, exp_out, f"frame {t} dequantised planes")
         assert not out_planes[:, ip].any()
