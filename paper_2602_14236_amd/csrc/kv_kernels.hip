@@ -13,7 +13,7 @@
 // 32-value quantisation group sits in one lane quad (reductions are two DPP quad swaps).
 // Rows are visited in pool order (all FP16 tokens, then INT8, then INT4, in token order inside
 // a tier), so pool writes are contiguous runs and pruned tokens are never read; a lane group takes
-// four consecutive pool rows.
+// consecutive pool rows (two when packing, four when unpacking).
 
 #include "sali_internal.h"
 #include "tier_body.h"
@@ -22,8 +22,15 @@ namespace sali {
 
 namespace {
 
-constexpr int kRowsPerBlock = 64;      // 16 lane-groups x 4 rows
+constexpr int kRowsPerBlock = 64;      // unpack: 16 lane-groups x 4 rows
 constexpr int kRowsPerLaneGroup = 4;
+// Pack: two rows per lane group, 32 per block.  With four (all other things equal) the kernel is 3 %
+// faster when it has the GPU to itself (83 against 86 us per frame of the 7B shape), but it then
+// needs 52 registers instead of 34, and next to it the image-analysis kernels of other streams
+// (69 to 120 registers) hardly get onto a compute unit while it runs: analysis + store without
+// read-back reaches 8 450 frames/s with four rows and 9 400 (60 % of HBM peak) with two; with the
+// read-back in the step both give the same frames/s.  Three rows (43 registers) behave like four.
+constexpr int kPackRows = 2;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -114,7 +121,7 @@ __global__ __launch_bounds__(kTierThreads) void k_tier(const float* __restrict__
 //     0 <= (x - min) * inv <= 15 (1 + 2^-22); its eight codes are packed with exact fp32
 //     multiply-adds (integers below 2^16) before one conversion.
 //   A group that holds an inf or NaN raises SALI_FAULT_NONFINITE; its codes are then unspecified.
-template <bool kNTL, bool kNTS>
+template <bool kNTL, bool kNTS, int kRows>
 __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* __restrict__ rows, int first_frame_id,
                                               const uint16_t* __restrict__ order_base, Pools pools, Cursors* cur) {
     const int bz = blockIdx.z;
@@ -124,7 +131,7 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
     if (row.stored == 0) return;
     const int n16 = row.n16, n8 = row.n8;
     const int nkeep = n16 + n8 + row.n4;
-    const int j0 = blockIdx.x * kRowsPerBlock;
+    const int j0 = blockIdx.x * (16 * kRows);
     if (j0 >= nkeep) return;
     const size_t plane = blockIdx.y;
     const int g = threadIdx.x >> 4;     // lane group: four consecutive rows of the tile
@@ -141,17 +148,26 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
     uint16_t* __restrict__ z4_plane = pools.z4 + r4 * kGroupsPerRow;
 
     // Three phases, so that the in-order memory counter never makes a wave wait for more than it
-    // needs: (1) all row loads are issued back to back: a lane group takes four consecutive pool rows,
-    // whose tokens are one aligned 8-byte read of the order table, and rows past the end re-read the
+    // needs: (1) all row loads are issued back to back: a lane group takes kRows consecutive pool rows,
+    // whose tokens are one aligned read of the order table, and rows past the end re-read the
     // block's first row instead of branching; (2) the rows are quantised in registers as their loads
     // arrive, with no memory operation in between; (3) all stores are issued.
-    const u32x2 tok2 = *reinterpret_cast<const u32x2*>(order + j0 + kRowsPerLaneGroup * g);
-    const uint32_t tok_first = order[j0];
-    const uint32_t tok[kRowsPerLaneGroup] = {tok2.x & 0xFFFFu, tok2.x >> 16, tok2.y & 0xFFFFu, tok2.y >> 16};
-    Row16B v[kRowsPerLaneGroup];
+    uint32_t tok[kRows];
+    if constexpr (kRows == 4) {
+        const u32x2 tok2 = *reinterpret_cast<const u32x2*>(order + j0 + kRows * g);
+        tok[0] = tok2.x & 0xFFFFu, tok[1] = tok2.x >> 16, tok[2] = tok2.y & 0xFFFFu, tok[3] = tok2.y >> 16;
+    } else if constexpr (kRows == 2) {
+        const uint32_t tok1 = *reinterpret_cast<const uint32_t*>(order + j0 + kRows * g);
+        tok[0] = tok1 & 0xFFFFu, tok[1] = tok1 >> 16;
+    } else {
 #pragma unroll
-    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + kRowsPerLaneGroup * g + r;
+        for (int r = 0; r < kRows; ++r) tok[r] = order[min(j0 + kRows * g + r, kTokens - 1)];
+    }
+    const uint32_t tok_first = order[j0];
+    Row16B v[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const int j = j0 + kRows * g + r;
         const uint32_t off = (j < nkeep ? tok[r] : tok_first) * (kHeadDim * 2) + (uint32_t)l * 16u;
         const u32x4* src = reinterpret_cast<const u32x4*>(kv_plane + off);
         v[r].u = kNTL ? __builtin_nontemporal_load(src) : *src;
@@ -159,13 +175,11 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
 
     uint32_t expo = 0;                  // bit 15 / 31 set <=> some half of this thread's rows is inf or NaN
     const bool odd = (l & 1) != 0;
-    float meta[kRowsPerLaneGroup];      // the group's scale (even lanes)
-    uint16_t zero[kRowsPerLaneGroup];   // INT4: the group's zero-point, fp16 bits
+    // (a quantised row needs one or two of its four registers for the codes: the group's scale goes to
+    // word z, the INT4 zero-point to word y, which keeps the register count down)
 #pragma unroll
-    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + kRowsPerLaneGroup * g + r;
-        meta[r] = 0.0f;
-        zero[r] = 0;
+    for (int r = 0; r < kRows; ++r) {
+        const int j = j0 + kRows * g + r;
         // rows past the end hold a copy of the block's first row and are quantised like any other (and
         // not stored): a skip here would leave a path on which the row's load is never waited for, and
         // the stores below would then each wait for the whole memory counter
@@ -194,7 +208,7 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
             for (int e = 0; e < 8; ++e) t[e] = __builtin_bit_cast(uint32_t, x[e] * inv + kRoundMagic);
             v[r].u.x = pack_low_bytes(t[0], t[1], t[2], t[3]);
             v[r].u.y = pack_low_bytes(t[4], t[5], t[6], t[7]);
-            meta[r] = mine;
+            v[r].u.z = __builtin_bit_cast(uint32_t, mine);
         } else {
             // INT4, asymmetric: scale = (max - min) / 15, q = rne((x - min) * (15 / (max - min)))
             float x[8];
@@ -219,14 +233,14 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
             const float lo = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(q[3], 16.0f, q[2]), 16.0f, q[1]), 16.0f, q[0]);
             const float hi = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(q[7], 16.0f, q[6]), 16.0f, q[5]), 16.0f, q[4]);
             v[r].u.x = (uint32_t)lo | ((uint32_t)hi << 16);
-            meta[r] = mine;
-            zero[r] = __builtin_bit_cast(uint16_t, (_Float16)mn);
+            v[r].u.z = __builtin_bit_cast(uint32_t, mine);
+            v[r].u.y = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)mn);
         }
     }
 
 #pragma unroll
-    for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + kRowsPerLaneGroup * g + r;
+    for (int r = 0; r < kRows; ++r) {
+        const int j = j0 + kRows * g + r;
         if (j >= nkeep) continue;
         if (j < n16) {
             u32x4* dst = reinterpret_cast<u32x4*>(p16_plane + ((uint32_t)j * (kHeadDim * 2) + (uint32_t)l * 16u));
@@ -236,14 +250,16 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
             u32x2* dst = reinterpret_cast<u32x2*>(c8_plane + (prow * (uint32_t)kHeadDim + (uint32_t)l * 8u));
             const u32x2 codes = {v[r].u.x, v[r].u.y};
             if (kNTS) __builtin_nontemporal_store(codes, dst); else *dst = codes;
-            if ((l & 3) == 0) s8_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = meta[r];
+            const uint32_t scale_bits = v[r].u.z;       // (a copy: bit_cast of a vector element reads element 0)
+            if ((l & 3) == 0) s8_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = __builtin_bit_cast(float, scale_bits);
         } else {
             const uint32_t prow = (uint32_t)(j - n16 - n8);
             uint32_t* dst = reinterpret_cast<uint32_t*>(c4_plane + (prow * (uint32_t)(kHeadDim / 2) + (uint32_t)l * 4u));
             if (kNTS) __builtin_nontemporal_store(v[r].u.x, dst); else *dst = v[r].u.x;
+            const uint32_t scale_bits = v[r].u.z;
             if ((l & 3) == 0) {
-                s4_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = meta[r];
-                z4_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = zero[r];
+                s4_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = __builtin_bit_cast(float, scale_bits);
+                z4_plane[prow * (uint32_t)kGroupsPerRow + (uint32_t)(l >> 2)] = (uint16_t)v[r].u.y;
             }
         }
     }
@@ -396,12 +412,11 @@ hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, T
 
 hipError_t launch_pack(const KvBatch& f, int n, const sali_frame_row* d_rows, int first_frame_id,
                        const uint16_t* d_order_base, Pools pools, Cursors* d_cur, int n_planes, hipStream_t s) {
-    dim3 grid((kTokens + kRowsPerBlock - 1) / kRowsPerBlock, n_planes, n);
     // streaming both ways: non-temporal loads and stores.  (Ordinary stores keep the new pool rows in
     // the last-level cache, which speeds up an immediate read-back by about as much as it slows this
     // kernel; without an immediate read-back non-temporal stores measured 10 % faster.)
-    hipLaunchKernelGGL((k_pack<true, true>), grid, dim3(256), 0, s, f, d_rows, first_frame_id, d_order_base, pools,
-                       d_cur);
+    hipLaunchKernelGGL((k_pack<true, true, kPackRows>), dim3(kTokens / (16 * kPackRows), n_planes, n), dim3(256), 0, s, f,
+                       d_rows, first_frame_id, d_order_base, pools, d_cur);
     return hipGetLastError();
 }
 
