@@ -140,6 +140,15 @@ int sali_reset(sali_ctx* ctx, void* stream);
  * video domain).  Applies to calls issued afterwards. */
 int sali_set_gate_thresholds(sali_ctx* ctx, float tau_t, float theta_r);
 
+/* Change the spatial thresholds or the top-k counts that turn scores into tiers (Eq. 8; the
+ * Discussion and the Conclusion name adaptive threshold tuning as the next step: the policy that
+ * picks the values is the caller's, this call only installs them).  tier_mode, thresholds and
+ * counts as in sali_config, same consistency rules (SALI_ERR_CONFIG otherwise, nothing changes).
+ * Applies to frames analysed or compressed by calls issued afterwards; frames already in the
+ * cache keep their tiers. */
+int sali_set_tier_params(sali_ctx* ctx, int32_t tier_mode, float tau_high, float tau_med, float tau_low,
+                         int32_t k_fp16, int32_t k_int8, int32_t k_int4);
+
 /* Temporal filter on an explicit frame pair (Temporal Filtering via Optical Flow; Eq. 5,
  * Eq. 6): dense flow from d_prev_rgb to d_cur_rgb (uint8 [H][W][3]), then
  *   d_patch_motion576[i] = sqrt(mean over patch i of u^2 + v^2)        (fp32, 576 values)

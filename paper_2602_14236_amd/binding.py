@@ -73,6 +73,8 @@ EXPORTS = {
     "sali_destroy": (None, [C.c_void_p]),
     "sali_reset": (C.c_int, [C.c_void_p, C.c_void_p]),
     "sali_set_gate_thresholds": (C.c_int, [C.c_void_p, C.c_float, C.c_float]),
+    "sali_set_tier_params": (C.c_int, [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_float, C.c_int32, C.c_int32,
+                                       C.c_int32]),
     "sali_flow_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_void_p]),
     "sali_saliency_pool": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -205,6 +207,10 @@ class SaliContext:
 
     def set_gate_thresholds(self, tau_t: float, theta_r: float):
         _check(self.lib.sali_set_gate_thresholds(self.handle, tau_t, theta_r), "sali_set_gate_thresholds")
+
+    def set_tier_params(self, tier_mode, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0):
+        _check(self.lib.sali_set_tier_params(self.handle, tier_mode, tau_high, tau_med, tau_low, k_fp16, k_int8,
+                                             k_int4), "sali_set_tier_params")
 
     def flow_score(self, prev_rgb, cur_rgb, flow_uv, patch_motion, gate_out):
         _check(self.lib.sali_flow_score(self.handle, _ptr(prev_rgb), _ptr(cur_rgb), _ptr(flow_uv),

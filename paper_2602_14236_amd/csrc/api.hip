@@ -604,6 +604,23 @@ int sali_set_gate_thresholds(sali_ctx* c, float tau_t, float theta_r) {
     return SALI_OK;
 }
 
+int sali_set_tier_params(sali_ctx* c, int32_t tier_mode, float tau_high, float tau_med, float tau_low, int32_t k_fp16,
+                         int32_t k_int8, int32_t k_int4) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    sali_config trial = c->cfg;
+    trial.tier_mode = tier_mode;
+    trial.tau_high = tau_high;
+    trial.tau_med = tau_med;
+    trial.tau_low = tau_low;
+    trial.k_fp16 = k_fp16;
+    trial.k_int8 = k_int8;
+    trial.k_int4 = k_int4;
+    const int rc = check_config(&trial);
+    if (rc != SALI_OK) return rc;
+    c->cfg = trial;
+    return SALI_OK;
+}
+
 int sali_flow_score(sali_ctx* c, const uint8_t* d_prev_rgb, const uint8_t* d_cur_rgb, float* d_flow_uv_or_null,
                     float* d_patch_motion576, sali_gate* d_gate_out, void* stream) {
     if (c == nullptr || d_prev_rgb == nullptr || d_cur_rgb == nullptr || d_patch_motion576 == nullptr ||

@@ -86,6 +86,45 @@ def test_config1_whole():
     ctx.close()
 
 
+def test_tier_params_changed_between_frames():
+    """sali_set_tier_params: thresholds -> top-k counts -> other thresholds while the video runs; the
+    oracle's configuration is changed at the same frames.  Pool capacities are sized for any mix."""
+    from paper_2602_14236_amd import binding
+    wl = synth.WORKLOADS[1]
+    p = workload_params(wl, n_layers=1, n_heads=3)
+    v = synth.video(1)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    kv_scale = synth.kv_channel_scale(wl, 1, 3)
+    changes = {3: dict(tier_mode=1, k_fp16=100, k_int8=200, k_int4=150),
+               5: dict(tier_mode=0, tau_high=0.5, tau_med=0.2, tau_low=0.1),
+               7: dict(tier_mode=1, k_fp16=0, k_int8=0, k_int4=576)}
+    for t in range(8):
+        if t in changes:
+            c = dict(tier_mode=0, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0)
+            c.update(changes[t])
+            ctx.set_tier_params(**c)
+            for k, val in c.items():
+                setattr(orc.cfg, k, val)
+        rgb = v.frame(t)
+        kv = synth.kv_frame(wl, t, device="cuda", n_layers=1, n_heads=3, scale=kv_scale)
+        ctx.step(torch.from_numpy(rgb).cuda(), kv, t)
+        orc.step(rgb, kv.cpu().numpy(), t)
+    torch.cuda.synchronize()
+    rows = {t: orc.rows[t] for t in range(8)}
+    assert (rows[4].n16, rows[4].n8, rows[4].n4) == (100, 200, 150) and rows[7].n4 == 576
+    assert (rows[5].n16, rows[5].n8, rows[5].n4) != (rows[2].n16, rows[2].n8, rows[2].n4)
+    _compare_all(ctx, orc, range(8))
+    # an inconsistent set is refused and changes nothing
+    with pytest.raises(binding.SaliError) as e:
+        ctx.set_tier_params(0, tau_high=0.1, tau_med=0.2, tau_low=0.05)
+    assert e.value.code == -4
+    with pytest.raises(binding.SaliError) as e:
+        ctx.set_tier_params(1, k_fp16=300, k_int8=300, k_int4=1)
+    assert e.value.code == -4
+    ctx.close()
+
+
 def test_config3_prefix_near_static_runs():
     """640x360 source, paper-mix top-k tiers; a prefix long enough to hold moving and near-static frames."""
     wl = synth.WORKLOADS[3]
