@@ -260,10 +260,16 @@ int sali_step_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, const voi
 int sali_attend_decode(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
                        float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
 
-/* The same with grouped-query attention: the cache holds n_heads K/V heads (the context's
- * n_heads) and q_per_kv in {1, 2, 4, 8} query heads share each of them; query head j reads K/V
- * head j / q_per_kv.  d_q_fp16 is [n_heads * q_per_kv][128], d_out [n_heads * q_per_kv][128],
- * d_lse_or_null [n_heads * q_per_kv].  Every compressed row is still read once per call.
+/* The same with several queries per K/V head: the cache holds n_heads K/V heads (the context's
+ * n_heads) and q_per_kv queries share each of them; query j reads K/V head j / q_per_kv.
+ * d_q_fp16 is [n_heads * q_per_kv][128], d_out [n_heads * q_per_kv][128], d_lse_or_null
+ * [n_heads * q_per_kv].  Every compressed row is still read once per call.
+ *   q_per_kv in {1, 2, 4, 8}: grouped-query decode, the streaming kernel of sali_attend_decode
+ *                (K^, V^ never rounded to fp16).
+ *   q_per_kv in 9 .. 64:      many queries against the cache (the tokens of a prompt, or of several
+ *                query heads, laid out per K/V head); the two products run on the matrix cores,
+ *                for which K^, V^ (the values sali_kv_decompress returns) and the softmax weights
+ *                are fp16 operands; accumulation is fp32.
  * SALI_ERR_SHAPE for another q_per_kv. */
 int sali_attend_decode_gqa(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t q_per_kv, int32_t frame_lo,
                            int32_t frame_hi, float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);

@@ -699,7 +699,8 @@ int sali_attend_decode_gqa(sali_ctx* c, int32_t layer, const void* d_q_fp16, int
                            int32_t frame_hi, float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
     if (c == nullptr || d_q_fp16 == nullptr || d_out == nullptr) return SALI_ERR_NULL;
     if (layer < 0 || layer >= c->cfg.n_layers) return SALI_ERR_SHAPE;
-    if (q_per_kv != 1 && q_per_kv != 2 && q_per_kv != 4 && q_per_kv != 8) return SALI_ERR_SHAPE;
+    if (q_per_kv != 1 && q_per_kv != 2 && q_per_kv != 4 && q_per_kv != 8 && !(q_per_kv > kAttnMaxQPerKv && q_per_kv <= 64))
+        return SALI_ERR_SHAPE;
     if (frame_lo < 0 || frame_hi < frame_lo || frame_hi > c->cfg.max_frames) return SALI_ERR_SHAPE;
     if (!aligned16(d_q_fp16)) return SALI_ERR_ALIGN;
     if (!(softmax_scale == softmax_scale)) return SALI_ERR_CONFIG;

@@ -334,12 +334,12 @@ __global__ __launch_bounds__(256) void k_attn_partial(const sali_frame_row* __re
 // device-wide ordering this needs, and a device-scope fence in each of the ~2000 blocks of the
 // main kernel (last-block hand-over) measured 4.5x slower, because on this chip such a fence writes
 // back and invalidates the L2 of the issuing XCD under the stream that the other blocks are reading.
-__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ partial, int n_partials,
+__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ partial, int n_partials, int slots,
                                                     float* __restrict__ out, float* __restrict__ lse) {
     __shared__ float s_w[kAttnPartials];
     __shared__ float s_part[2][kHeadDim];
     const int h = blockIdx.x;
-    const float* p = partial + (size_t)h * kAttnPartials * kPartialStride;
+    const float* p = partial + (size_t)h * slots * kPartialStride;      // `slots` partials are reserved per query head
     for (int k = threadIdx.x; k < n_partials; k += 256) s_w[k] = p[(size_t)k * kPartialStride];
     __syncthreads();
     float big = -INFINITY;
@@ -369,11 +369,266 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Many queries per K/V head (16, 32 or 64: the tokens of a prompt attending to the cached video, or
+// large query groups): Q K^T and P V are real matrix products, so they run on the matrix cores
+// (v_mfma_f32_32x32x8_f16) and every compressed row is still read once for all queries.
+//
+// One wave = one work item (a chunk of frames x a row split, as in the single-query kernel) x one
+// K/V head x one tile of 32 queries.  Per tile of 32 cached rows:
+//   S^T = K^ Q^T : A operand = K^ tile (lane = row n, registers = head-dim values), B operand = the
+//        queries (lane = query m); the result has lane = query, registers = rows, so the softmax
+//        over rows is a reduction over the lane's 16 registers and one exchange between the two
+//        lane halves, and P in that layout IS the B operand of the second product;
+//   out^T = V^^T P^T : A operand = V^^T (lane = head-dim value d, registers = 4 consecutive rows),
+//        read column-wise from the wave's own LDS copy of the V^ tile.
+// The head-dim index of the contraction is permuted (lane half hh of a row holds values
+// [64 hh, 64 hh + 64), k-step t takes 4 of them from each half) so that a lane reads one contiguous
+// piece of its row; Q uses the same permutation.  Here the dequantised values DO exist as fp16
+// (K^ = fp16(code * scale), fp16(code * scale + zero), the values dequantise-on-read produces) because
+// the matrix cores take fp16 operands; the softmax weights are rounded to fp16 for the second product
+// as well.  Both stay inside the tolerance of the floating-point results (largest error printed by
+// the tests).  Accumulation, softmax state and partials are fp32; partials have the layout of the
+// single-query kernel and are merged by the same k_attn_merge.
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kPfRows = 32;                       // cached rows per tile
+constexpr int kPfVStride = kHeadDim + 8;          // halves per LDS row of the V^ tile (skewed against bank conflicts)
+
+union Half8 {
+    u32x4 u;
+    half4_t h4[2];
+    _Float16 h[8];
+};
+
+// The lane's half of pool row `frow` as fp16: x[t] = values 64 hh + 4 t .. 64 hh + 4 t + 3.
+template <int kTier>
+__device__ __forceinline__ void pf_load_row(const Pools& pools, size_t frow, int hh, half4_t (&x)[16]) {
+    if constexpr (kTier == SALI_TIER_FP16) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(pools.p16 + frow * kHeadDim + 64 * hh);
+        Half8 c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u].u = __builtin_nontemporal_load(src + u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            x[2 * u] = c[u].h4[0];
+            x[2 * u + 1] = c[u].h4[1];
+        }
+    } else if constexpr (kTier == SALI_TIER_INT8) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(pools.c8 + frow * kHeadDim + 64 * hh);
+        u32x4 c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = __builtin_nontemporal_load(src + u);
+        const float sc0 = pools.s8[frow * kGroupsPerRow + 2 * hh], sc1 = pools.s8[frow * kGroupsPerRow + 2 * hh + 1];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float sc = u < 2 ? sc0 : sc1;                   // 16 codes of chunk u: group 2 hh + u / 2
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t word = w == 0 ? c[u].x : (w == 1 ? c[u].y : (w == 2 ? c[u].z : c[u].w));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    x[4 * u + w][i] = (_Float16)((float)(int)(int8_t)((word >> (8 * i)) & 0xFF) * sc);
+            }
+        }
+    } else {
+        const u32x4* src = reinterpret_cast<const u32x4*>(pools.c4 + frow * (kHeadDim / 2) + 32 * hh);
+        u32x4 c[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) c[u] = __builtin_nontemporal_load(src + u);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {                               // 32 values of chunk u: group 2 hh + u
+            const float sc = pools.s4[frow * kGroupsPerRow + 2 * hh + u];
+            const float zp = (float)__builtin_bit_cast(_Float16, pools.z4[frow * kGroupsPerRow + 2 * hh + u]);
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {                           // 4 values = 2 bytes
+                const uint32_t word = (w >> 1) == 0 ? c[u].x : ((w >> 1) == 1 ? c[u].y : ((w >> 1) == 2 ? c[u].z : c[u].w));
+                const uint32_t two = (word >> (16 * (w & 1))) & 0xFFFFu;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    x[8 * u + w][i] = (_Float16)__builtin_fmaf((float)((two >> (4 * i)) & 0xFu), sc, zp);
+            }
+        }
+    }
+}
+
+struct PfState {
+    float mx, lsum;
+    float16_t acc[4];           // acc[dt][r] = out[m][32 dt + 8 (r / 4) + 4 hh + r % 4], not yet normalised
+};
+
+// the tiles of one tier of one stored frame that fall to this wave
+template <int kTier>
+__device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size_t plane_v, int base, int count,
+                                        int split, int n_splits, int m, int hh, const half4_t (&qb)[16],
+                                        float softmax_scale, float mult, _Float16 (*s_v)[kPfVStride], PfState& st) {
+    const size_t row0_k = pool_row0(pools, base, count, plane_k), row0_v = pool_row0(pools, base, count, plane_v);
+    for (int jb = split * kPfRows; jb < count; jb += n_splits * kPfRows) {
+        const size_t j = (size_t)min(jb + m, count - 1);            // rows past the end: a copy of the last row, weight 0
+        half4_t x[16];
+        pf_load_row<kTier>(pools, row0_k + j, hh, x);
+        float16_t s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) s = __builtin_amdgcn_mfma_f32_32x32x8f16(x[t], qb[t], s, 0, 0, 0);
+        // s[r] = <K^ row jb + n(r), query m>, n(r) = 8 (r / 4) + 4 hh + r % 4
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int n = 8 * (r / 4) + 4 * hh + (r % 4);
+            s[r] = (jb + n < count) ? s[r] * softmax_scale : -INFINITY;
+            tmax = fmaxf(tmax, s[r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float mnew = fmaxf(st.mx, tmax);
+        const float corr = __expf(st.mx - mnew);
+        float psum = 0.0f;
+        half4_t pb[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = mult * __expf(s[4 * jj + i] - mnew);
+                psum += p;
+                pb[jj][i] = (_Float16)p;
+            }
+        psum += __shfl_xor(psum, 32);
+        st.lsum = st.lsum * corr + psum;
+        st.mx = mnew;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.acc[dt][r] *= corr;
+        // V^ tile: registers -> the wave's LDS tile (row-major) -> column reads.  LDS operations of one
+        // wave execute in order, so no barrier is needed; the compiler may not move them across this point.
+        pf_load_row<kTier>(pools, row0_v + j, hh, x);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t = 0; t < 16; ++t) *reinterpret_cast<half4_t*>(&s_v[m][64 * hh + 4 * t]) = x[t];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                half4_t va;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) va[i] = s_v[8 * jj + 4 * hh + i][32 * dt + m];
+                st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x8f16(va, pb[jj], st.acc[dt], 0, 0, 0);
+            }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+}  // namespace
+
+// grid (ceil(n_partials / 4), n_heads, ceil(q_per_kv / 32)), 256 threads = four independent waves
+__global__ __launch_bounds__(256) void k_attn_prefill(const sali_frame_row* __restrict__ rows, Pools pools, int layer,
+                                                      int n_heads, const _Float16* __restrict__ q, int q_per_kv,
+                                                      int frame_lo, int frame_hi, int frames_per_chunk, int n_splits,
+                                                      int n_partials, float softmax_scale, float* __restrict__ partial) {
+    __shared__ _Float16 s_v_all[4][kPfRows][kPfVStride];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = lane & 31, hh = lane >> 5;
+    const int item = (int)blockIdx.x * 4 + wave;
+    if (item >= n_partials) return;
+    const int chunk = item / n_splits, split = item % n_splits;
+    const int h = blockIdx.y;
+    const int qi = (int)blockIdx.z * 32 + m;                 // this lane's query among the q_per_kv of the K/V head
+    const bool q_valid = qi < q_per_kv;
+    const size_t q_head = (size_t)h * q_per_kv + (q_valid ? qi : 0);
+    const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + h;
+    const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + h;
+
+    half4_t qb[16];
+    {
+        const u32x4* src = reinterpret_cast<const u32x4*>(q + q_head * kHeadDim + 64 * hh);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            Half8 c;
+            c.u = src[u];
+            if (!q_valid) c.u = (u32x4){0u, 0u, 0u, 0u};
+            qb[2 * u] = c.h4[0];
+            qb[2 * u + 1] = c.h4[1];
+        }
+    }
+    PfState st;
+    st.mx = -INFINITY;
+    st.lsum = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.acc[dt][r] = 0.0f;
+
+    const int f0 = frame_lo + chunk * frames_per_chunk;
+    const int f1 = min(frame_hi, f0 + frames_per_chunk);
+    for (int f = f0; f < f1; ++f) {
+        // which stored frame frame f brings in, and how often: as in k_attn_partial
+        const sali_frame_row r = rows[f];
+        bool leader = r.stored != 0;
+        if (!leader && r.src >= 0 && r.src < frame_lo) {
+            leader = true;
+            for (int t = frame_lo; t < f; ++t)
+                if (rows[t].src == r.src) leader = false;
+        }
+        if (!leader) continue;
+        const int src = r.src;
+        int n_uses = 1;
+        for (int t = f + 1; t < frame_hi && rows[t].stored == 0; ++t)
+            if (rows[t].src == src) ++n_uses;
+        const float mult = (float)n_uses;
+        const sali_frame_row row = rows[src];
+        pf_tier<SALI_TIER_FP16>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, m, hh, qb, softmax_scale,
+                                mult, s_v_all[wave], st);
+        pf_tier<SALI_TIER_INT8>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, m, hh, qb, softmax_scale,
+                                mult, s_v_all[wave], st);
+        pf_tier<SALI_TIER_INT4>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, m, hh, qb, softmax_scale,
+                                mult, s_v_all[wave], st);
+    }
+    if (!q_valid) return;
+    float* mine = partial + (q_head * (size_t)n_partials + item) * kPartialStride;
+    if (hh == 0) {
+        mine[0] = st.mx;
+        mine[1] = st.lsum;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[2 + 32 * dt + 8 * (r / 4) + 4 * hh + (r % 4)] = st.acc[dt][r];
+}
+
 hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, int n_heads, int q_per_kv,
                          const void* d_q, int frame_lo, int frame_hi, float softmax_scale, float* d_partial,
                          float* d_out, float* d_lse_or_null, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s) {
     const int n_range = frame_hi - frame_lo;
     int n_partials = 0;
+    if (n_range > 0 && q_per_kv > kAttnMaxQPerKv) {
+        // matrix-core path: 32 queries per wave; the scratch holds kAttnMaxQPerKv * kAttnPartials partials
+        // per K/V head, shared out over the q_per_kv query heads
+        int per_head = (kAttnMaxQPerKv * kAttnPartials) / q_per_kv;
+        per_head = per_head > kAttnPartials ? kAttnPartials : per_head;
+        const int fpc = (n_range + per_head - 1) / per_head;
+        const int n_chunks = (n_range + fpc - 1) / fpc;
+        int n_splits = per_head / n_chunks;
+        n_splits = n_splits < 1 ? 1 : (n_splits > kTokens / kPfRows ? kTokens / kPfRows : n_splits);
+        n_partials = n_chunks * n_splits;
+        if (ev_start != nullptr && hipEventRecord(ev_start, s) != hipSuccess) return hipErrorUnknown;
+        const dim3 grid((n_partials + 3) / 4, n_heads, (q_per_kv + 31) / 32);
+        hipLaunchKernelGGL(k_attn_prefill, grid, dim3(256), 0, s, d_rows, pools, layer, n_heads,
+                           reinterpret_cast<const _Float16*>(d_q), q_per_kv, frame_lo, frame_hi, fpc, n_splits, n_partials,
+                           softmax_scale, d_partial);
+        if (ev_stop != nullptr && hipEventRecord(ev_stop, s) != hipSuccess) return hipErrorUnknown;
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_attn_merge, dim3(n_heads * q_per_kv), dim3(256), 0, s, d_partial, n_partials, n_partials,
+                           d_out, d_lse_or_null);
+        return hipGetLastError();
+    }
     if (n_range > 0) {
         // One resident round of blocks: at 8 blocks of 256 threads per compute unit the chip holds
         // kResidentBlocks; more blocks than that leave a second, nearly empty round at the end of a
@@ -412,8 +667,8 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k_attn_merge, dim3(n_heads * q_per_kv), dim3(256), 0, s, d_partial, n_partials, d_out,
-                       d_lse_or_null);
+    hipLaunchKernelGGL(k_attn_merge, dim3(n_heads * q_per_kv), dim3(256), 0, s, d_partial, n_partials, kAttnPartials,
+                       d_out, d_lse_or_null);
     return hipGetLastError();
 }
 
