@@ -404,53 +404,98 @@ union Half8 {
     _Float16 h[8];
 };
 
-// The lane's half of pool row `frow` as fp16: x[t] = values 64 hh + 4 t .. 64 hh + 4 t + 3.
+// A tile of 32 pool rows is read with fully coalesced 16-byte loads (consecutive lanes read
+// consecutive memory: a lane-per-row pattern, which the matrix-core operands would suggest, was
+// measured at 1.6 TB/s), dequantised to fp16 where it lies, and written to the wave's LDS tile
+// [32 rows][128 values]; the operands are then read from LDS in the layout the instruction wants.
+// Piece `idx` of a tile = 16 bytes of row idx / (pieces per row).  Rows past the end of the run
+// repeat its last row (their softmax weight is zero).
 template <int kTier>
-__device__ __forceinline__ void pf_load_row(const Pools& pools, size_t frow, int hh, half4_t (&x)[16]) {
-    if constexpr (kTier == SALI_TIER_FP16) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(pools.p16 + frow * kHeadDim + 64 * hh);
-        Half8 c[8];
+struct PfRaw;
+template <>
+struct PfRaw<SALI_TIER_FP16> {
+    u32x4 c[8];                 // 8 values each
+};
+template <>
+struct PfRaw<SALI_TIER_INT8> {
+    u32x4 c[4];                 // 16 codes each
+    float sc[4];
+};
+template <>
+struct PfRaw<SALI_TIER_INT4> {
+    u32x4 c[2];                 // 32 codes each = one quantisation group
+    float sc[2], zp[2];
+};
+
+__device__ __forceinline__ void pf_load_tile(const Pools& pools, size_t row0, int jb, int count, int lane,
+                                             PfRaw<SALI_TIER_FP16>& r) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) c[u].u = __builtin_nontemporal_load(src + u);
+    for (int u = 0; u < 8; ++u) {
+        const int idx = u * 64 + lane;
+        const size_t frow = row0 + (size_t)min(jb + (idx >> 4), count - 1);
+        r.c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pools.p16 + frow * kHeadDim) + (idx & 15));
+    }
+}
+__device__ __forceinline__ void pf_load_tile(const Pools& pools, size_t row0, int jb, int count, int lane,
+                                             PfRaw<SALI_TIER_INT8>& r) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            x[2 * u] = c[u].h4[0];
-            x[2 * u + 1] = c[u].h4[1];
+    for (int u = 0; u < 4; ++u) {
+        const int idx = u * 64 + lane;
+        const size_t frow = row0 + (size_t)min(jb + (idx >> 3), count - 1);
+        r.c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pools.c8 + frow * kHeadDim) + (idx & 7));
+        r.sc[u] = pools.s8[frow * kGroupsPerRow + ((idx & 7) >> 1)];
+    }
+}
+__device__ __forceinline__ void pf_load_tile(const Pools& pools, size_t row0, int jb, int count, int lane,
+                                             PfRaw<SALI_TIER_INT4>& r) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int idx = u * 64 + lane;
+        const size_t frow = row0 + (size_t)min(jb + (idx >> 2), count - 1);
+        r.c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pools.c4 + frow * (kHeadDim / 2)) + (idx & 3));
+        r.sc[u] = pools.s4[frow * kGroupsPerRow + (idx & 3)];
+        r.zp[u] = (float)__builtin_bit_cast(_Float16, pools.z4[frow * kGroupsPerRow + (idx & 3)]);
+    }
+}
+
+// dequantise the lane's pieces and put them where they belong in the LDS tile
+__device__ __forceinline__ void pf_store_tile(const PfRaw<SALI_TIER_FP16>& r, int lane, _Float16 (*tile)[kPfVStride]) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int idx = u * 64 + lane;
+        *reinterpret_cast<u32x4*>(&tile[idx >> 4][8 * (idx & 15)]) = r.c[u];
+    }
+}
+__device__ __forceinline__ void pf_store_tile(const PfRaw<SALI_TIER_INT8>& r, int lane, _Float16 (*tile)[kPfVStride]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int idx = u * 64 + lane;
+        Half8 o[2];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t word = w == 0 ? r.c[u].x : (w == 1 ? r.c[u].y : (w == 2 ? r.c[u].z : r.c[u].w));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                o[w >> 1].h[4 * (w & 1) + i] = (_Float16)((float)(int)(int8_t)((word >> (8 * i)) & 0xFF) * r.sc[u]);
         }
-    } else if constexpr (kTier == SALI_TIER_INT8) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(pools.c8 + frow * kHeadDim + 64 * hh);
-        u32x4 c[4];
+        u32x4* dst = reinterpret_cast<u32x4*>(&tile[idx >> 3][16 * (idx & 7)]);
+        dst[0] = o[0].u;
+        dst[1] = o[1].u;
+    }
+}
+__device__ __forceinline__ void pf_store_tile(const PfRaw<SALI_TIER_INT4>& r, int lane, _Float16 (*tile)[kPfVStride]) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) c[u] = __builtin_nontemporal_load(src + u);
-        const float sc0 = pools.s8[frow * kGroupsPerRow + 2 * hh], sc1 = pools.s8[frow * kGroupsPerRow + 2 * hh + 1];
+    for (int u = 0; u < 2; ++u) {
+        const int idx = u * 64 + lane;
+        u32x4* dst = reinterpret_cast<u32x4*>(&tile[idx >> 2][32 * (idx & 3)]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float sc = u < 2 ? sc0 : sc1;                   // 16 codes of chunk u: group 2 hh + u / 2
+        for (int w = 0; w < 4; ++w) {                               // 8 values = one word of codes
+            const uint32_t word = w == 0 ? r.c[u].x : (w == 1 ? r.c[u].y : (w == 2 ? r.c[u].z : r.c[u].w));
+            Half8 o;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const uint32_t word = w == 0 ? c[u].x : (w == 1 ? c[u].y : (w == 2 ? c[u].z : c[u].w));
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    x[4 * u + w][i] = (_Float16)((float)(int)(int8_t)((word >> (8 * i)) & 0xFF) * sc);
-            }
-        }
-    } else {
-        const u32x4* src = reinterpret_cast<const u32x4*>(pools.c4 + frow * (kHeadDim / 2) + 32 * hh);
-        u32x4 c[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) c[u] = __builtin_nontemporal_load(src + u);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {                               // 32 values of chunk u: group 2 hh + u
-            const float sc = pools.s4[frow * kGroupsPerRow + 2 * hh + u];
-            const float zp = (float)__builtin_bit_cast(_Float16, pools.z4[frow * kGroupsPerRow + 2 * hh + u]);
-#pragma unroll
-            for (int w = 0; w < 8; ++w) {                           // 4 values = 2 bytes
-                const uint32_t word = (w >> 1) == 0 ? c[u].x : ((w >> 1) == 1 ? c[u].y : ((w >> 1) == 2 ? c[u].z : c[u].w));
-                const uint32_t two = (word >> (16 * (w & 1))) & 0xFFFFu;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    x[8 * u + w][i] = (_Float16)__builtin_fmaf((float)((two >> (4 * i)) & 0xFu), sc, zp);
-            }
+            for (int i = 0; i < 8; ++i)
+                o.h[i] = (_Float16)__builtin_fmaf((float)((word >> (4 * i)) & 0xFu), r.sc[u], r.zp[u]);
+            dst[w] = o.u;
         }
     }
 }
@@ -460,21 +505,39 @@ struct PfState {
     float16_t acc[4];           // acc[dt][r] = out[m][32 dt + 8 (r / 4) + 4 hh + r % 4], not yet normalised
 };
 
+// LDS operations of one wave execute in order, so the wave's private tiles need no barrier, only
+// that the compiler keeps the order
+__device__ __forceinline__ void pf_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // the tiles of one tier of one stored frame that fall to this wave
 template <int kTier>
 __device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size_t plane_v, int base, int count,
-                                        int split, int n_splits, int m, int hh, const half4_t (&qb)[16],
-                                        float softmax_scale, float mult, _Float16 (*s_v)[kPfVStride], PfState& st) {
+                                        int split, int n_splits, int lane, const half4_t (&qb)[16],
+                                        float softmax_scale, float mult, _Float16 (*s_k)[kPfVStride],
+                                        _Float16 (*s_v)[kPfVStride], PfState& st) {
+    const int m = lane & 31, hh = lane >> 5;
     const size_t row0_k = pool_row0(pools, base, count, plane_k), row0_v = pool_row0(pools, base, count, plane_v);
     for (int jb = split * kPfRows; jb < count; jb += n_splits * kPfRows) {
-        const size_t j = (size_t)min(jb + m, count - 1);            // rows past the end: a copy of the last row, weight 0
-        half4_t x[16];
-        pf_load_row<kTier>(pools, row0_k + j, hh, x);
+        // all loads of the tile first: one memory latency per tile
+        PfRaw<kTier> rk, rv;
+        pf_load_tile(pools, row0_k, jb, count, lane, rk);
+        pf_load_tile(pools, row0_v, jb, count, lane, rv);
+        pf_lds_order();                                            // the previous tile's reads are done
+        pf_store_tile(rk, lane, s_k);
+        pf_lds_order();
+        // S^T = K^ Q^T: lane (row n = m, half hh), k-step t: values 64 hh + 4 t .. + 3 of the row
         float16_t s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.0f;
 #pragma unroll
-        for (int t = 0; t < 16; ++t) s = __builtin_amdgcn_mfma_f32_32x32x8f16(x[t], qb[t], s, 0, 0, 0);
+        for (int t = 0; t < 16; ++t) {
+            const half4_t ka = *reinterpret_cast<const half4_t*>(&s_k[m][64 * hh + 4 * t]);
+            s = __builtin_amdgcn_mfma_f32_32x32x8f16(ka, qb[t], s, 0, 0, 0);
+        }
         // s[r] = <K^ row jb + n(r), query m>, n(r) = 8 (r / 4) + 4 hh + r % 4
         float tmax = -INFINITY;
 #pragma unroll
@@ -499,19 +562,17 @@ __device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size
         psum += __shfl_xor(psum, 32);
         st.lsum = st.lsum * corr + psum;
         st.mx = mnew;
+        // the 64 accumulators are rescaled only when some query of the wave saw a new maximum (rare after
+        // the first tiles); the test is wave-uniform
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+            for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) st.acc[dt][r] *= corr;
-        // V^ tile: registers -> the wave's LDS tile (row-major) -> column reads.  LDS operations of one
-        // wave execute in order, so no barrier is needed; the compiler may not move them across this point.
-        pf_load_row<kTier>(pools, row0_v + j, hh, x);
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int t = 0; t < 16; ++t) *reinterpret_cast<half4_t*>(&s_v[m][64 * hh + 4 * t]) = x[t];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                for (int r = 0; r < 16; ++r) st.acc[dt][r] *= corr;
+        }
+        // out^T += V^^T P^T: A operand lane (value d = 32 dt + m, half hh): rows 8 jj + 4 hh + 0..3 of column d
+        pf_store_tile(rv, lane, s_v);
+        pf_lds_order();
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -521,18 +582,18 @@ __device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size
                 for (int i = 0; i < 4; ++i) va[i] = s_v[8 * jj + 4 * hh + i][32 * dt + m];
                 st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x8f16(va, pb[jj], st.acc[dt], 0, 0, 0);
             }
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
 }  // namespace
 
 // grid (ceil(n_partials / 4), n_heads, ceil(q_per_kv / 32)), 256 threads = four independent waves
-__global__ __launch_bounds__(256) void k_attn_prefill(const sali_frame_row* __restrict__ rows, Pools pools, int layer,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_prefill(const sali_frame_row* __restrict__ rows, Pools pools, int layer,
                                                       int n_heads, const _Float16* __restrict__ q, int q_per_kv,
                                                       int frame_lo, int frame_hi, int frames_per_chunk, int n_splits,
                                                       int n_partials, float softmax_scale, float* __restrict__ partial) {
-    __shared__ _Float16 s_v_all[4][kPfRows][kPfVStride];
+    __shared__ __align__(16) _Float16 s_k_all[4][kPfRows][kPfVStride];
+    __shared__ __align__(16) _Float16 s_v_all[4][kPfRows][kPfVStride];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m = lane & 31, hh = lane >> 5;
     const int item = (int)blockIdx.x * 4 + wave;
@@ -583,12 +644,12 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const sali_frame_row* __re
             if (rows[t].src == src) ++n_uses;
         const float mult = (float)n_uses;
         const sali_frame_row row = rows[src];
-        pf_tier<SALI_TIER_FP16>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, m, hh, qb, softmax_scale,
-                                mult, s_v_all[wave], st);
-        pf_tier<SALI_TIER_INT8>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, m, hh, qb, softmax_scale,
-                                mult, s_v_all[wave], st);
-        pf_tier<SALI_TIER_INT4>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, m, hh, qb, softmax_scale,
-                                mult, s_v_all[wave], st);
+        pf_tier<SALI_TIER_FP16>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, lane, qb, softmax_scale, mult,
+                                s_k_all[wave], s_v_all[wave], st);
+        pf_tier<SALI_TIER_INT8>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, lane, qb, softmax_scale, mult,
+                                s_k_all[wave], s_v_all[wave], st);
+        pf_tier<SALI_TIER_INT4>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, lane, qb, softmax_scale, mult,
+                                s_k_all[wave], s_v_all[wave], st);
     }
     if (!q_valid) return;
     float* mine = partial + (q_head * (size_t)n_partials + item) * kPartialStride;
