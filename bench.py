@@ -359,6 +359,29 @@ def main():
         "decode_step_ms_all_layers": t_attn * 1e3, "frames": steps,
         "what": "single-query attention of one layer over all cached frames, pools read directly",
     }
+    # the same with 32 queries per K/V head (a prompt's tokens against the cached video): matrix-core kernel
+    NQ = 32
+    q32 = torch.randn((wl.n_heads * NQ, 128), device=dev).to(torch.float16)
+    out32 = torch.empty((wl.n_heads * NQ, 128), dtype=torch.float32, device=dev)
+    lse32 = torch.empty((wl.n_heads * NQ,), dtype=torch.float32, device=dev)
+    pf_ev = make_events(n_layers)
+    for rep in range(2):
+        torch.cuda.synchronize()
+        for layer in range(n_layers):
+            if rep == 1:
+                ctx.set_profile_events(2, *pf_ev[layer])
+            ctx.attend_decode_gqa(layer, q32, NQ, 0, steps, sm_scale, out32, lse32, s_kv)
+        torch.cuda.synchronize()
+    pf_s = sum(a.elapsed_time(b) for a, b in pf_ev) / 1e3 / n_layers
+    pf_flops = 4.0 * 128.0 * NQ * wl.n_heads * sum(r.n16 + r.n8 + r.n4 for r in rows if r.stored)    # Q K^T and P V
+    result["attend_32_queries"] = {
+        "kernel": "k_attn_prefill", "queries_per_kv_head": NQ, "avg_launch_us": pf_s * 1e6,
+        "algorithmic_bytes_per_launch": attn_b, "achieved_gbps": attn_b / pf_s / 1e9 if pf_s > 0 else 0.0,
+        "hbm_frac": attn_b / pf_s / HBM_PEAK if pf_s > 0 else 0.0,
+        "mfma_tflops_f16": pf_flops / pf_s / 1e12 if pf_s > 0 else 0.0,
+        "what": "32 queries per K/V head, one layer over all cached frames, v_mfma_f32_32x32x8_f16 on fp16 operands",
+    }
+    del q32, out32, lse32
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)

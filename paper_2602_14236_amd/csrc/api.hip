@@ -158,7 +158,7 @@ ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
         s.expA[i] = take(px * sizeof(float4));
         s.expB[i] = take(px * sizeof(float2));
     }
-    s.attn_partial = take((size_t)c.n_heads * kAttnMaxQPerKv * kAttnPartials * kAttnPartialStride * sizeof(float));
+    s.attn_partial = take((size_t)c.n_heads * kAttnSlotsPerHead * kAttnPartialStride * sizeof(float));
     s.total = o;
     return s;
 }

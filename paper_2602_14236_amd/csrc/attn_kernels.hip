@@ -669,9 +669,12 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
     const int n_range = frame_hi - frame_lo;
     int n_partials = 0;
     if (n_range > 0 && q_per_kv > kAttnMaxQPerKv) {
-        // matrix-core path: 32 queries per wave; the scratch holds kAttnMaxQPerKv * kAttnPartials partials
-        // per K/V head, shared out over the q_per_kv query heads
-        int per_head = (kAttnMaxQPerKv * kAttnPartials) / q_per_kv;
+        // matrix-core path: 32 queries per wave; the scratch holds kAttnSlotsPerHead partials per K/V head,
+        // shared out over the q_per_kv query heads
+        // and one resident round of waves (two per SIMD: 2048 on the chip) is the target, as for the streaming kernel
+        int per_head = kAttnSlotsPerHead / q_per_kv;
+        const int round = (2 * 4 * 256) / (n_heads * ((q_per_kv + 31) / 32));
+        per_head = per_head > round ? (round < 1 ? 1 : round) : per_head;
         per_head = per_head > kAttnPartials ? kAttnPartials : per_head;
         const int fpc = (n_range + per_head - 1) / per_head;
         const int n_chunks = (n_range + fpc - 1) / fpc;

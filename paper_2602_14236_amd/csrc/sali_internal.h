@@ -19,6 +19,7 @@ constexpr int kMaxLevels = 6;
 constexpr int kMaxIters = 8;
 constexpr int kAttnPartials = 256;          // partial softmax states per head in the attention kernel
 constexpr int kAttnMaxQPerKv = 8;           // query heads that may share one K/V head
+constexpr int kAttnSlotsPerHead = 4096;     // partial-result slots of the scratch per K/V head (shared out over its queries)
 constexpr int kAttnPartialStride = 160;     // floats per partial: max, sum, 128 values; 640 B = five whole 128-byte lines
 constexpr int kMaxBatch = SALI_MAX_BATCH;   // frames analysed by one set of launches (blockIdx.z / .y)
 
@@ -192,8 +193,8 @@ hipError_t launch_unpack(const sali_frame_row* d_rows, int first_frame_id, const
                          hipStream_t s);
 
 // attn_kernels.hip: single-query attention of one layer over frames [frame_lo, frame_hi) for
-// n_heads * q_per_kv query heads (q_per_kv in {1, 2, 4, 8} share one K/V head); d_partial holds
-// n_heads * q_per_kv * kAttnPartials * kAttnPartialStride floats; the events (may be NULL) bracket
+// n_heads * q_per_kv queries (q_per_kv in {1, 2, 4, 8}: streaming kernel; 9 .. 64: matrix-core kernel); d_partial holds
+// n_heads * kAttnSlotsPerHead * kAttnPartialStride floats; the events (may be NULL) bracket
 // the main kernel
 hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, int n_heads, int q_per_kv,
                          const void* d_q, int frame_lo, int frame_hi, float softmax_scale, float* d_partial,
