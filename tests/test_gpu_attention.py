@@ -100,6 +100,22 @@ def test_attend_long_range_many_frames_per_block():
     worst = max(_check(ctx, orc, 0, q, 0, n, sm, "150 frames"), _check(ctx, orc, 0, q, 11, 140, sm, "129 frames"),
                 _check(ctx, orc, 0, q, 20, 33, sm, "13 frames"))
     print(f"largest |out - oracle| = {worst:.3e}", flush=True)
+    # the matrix-core path over the same cache: 32 queries on the one K/V head; several frames per
+    # wave, ranges that end inside a tile, all three tiers
+    q32 = _q(77, 32)
+    out = torch.empty((32, 128), dtype=torch.float32, device="cuda")
+    lse = torch.empty((32,), dtype=torch.float32, device="cuda")
+    for lo, hi in ((0, n), (11, 140), (20, 21)):
+        ctx.attend_decode_gqa(0, q32, 32, lo, hi, sm, out, lse)
+        torch.cuda.synchronize()
+        exp_out, exp_lse = attend_decode(orc, 0, q32.cpu().numpy(), lo, hi, sm, q_per_kv=32)
+        bound, lse_bound = _fp16_operand_bounds(orc, q32.cpu().numpy(), lo, hi, sm, 32)
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exp_out)
+        assert np.all(err <= bound), f"32 queries, frames [{lo}, {hi}): max error {err.max():.3e}"
+        assert np.all(np.abs(lse.cpu().numpy() - exp_lse) <= lse_bound)
+        rms = math.sqrt(float((err ** 2).mean())) / math.sqrt(float((exp_out ** 2).mean()))
+        assert rms <= 1e-3, rms
+        print(f"32 queries, frames [{lo}, {hi}): largest error {err.max():.3e}, relative rms {rms:.2e}", flush=True)
     ctx.close()
 
 
