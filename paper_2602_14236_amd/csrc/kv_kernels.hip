@@ -13,7 +13,7 @@
 // 32-value quantisation group sits in one lane quad (reductions are two DPP quad swaps).
 // Rows are visited in pool order (all FP16 tokens, then INT8, then INT4, in token order inside
 // a tier), so pool writes are contiguous runs and pruned tokens are never read.  A wave covers a
-// run of consecutive pool rows (8 when packing, 16 when unpacking) and each of its memory
+// run of 8 consecutive pool rows (two per lane group, in both kernels) and each of its memory
 // instructions four consecutive rows of it (lane group k of the wave takes rows k, k + 4, ...):
 // the 64-byte INT4 code rows and the 16- and 8-byte scale / zero-point rows then fill whole cache
 // lines per instruction (all-INT4 frames: pack 5.4 -> 5.7 TB/s, unpack 5.6 -> 6.05 TB/s).
@@ -25,8 +25,10 @@ namespace sali {
 
 namespace {
 
-constexpr int kRowsPerBlock = 64;      // unpack: 16 lane-groups x 4 rows
-constexpr int kRowsPerLaneGroup = 4;
+// unpack: two rows per lane group as well (alone it is 2-6 % faster than with four: 83.8 against
+// 86.0 us per frame of the 7B shape, and it leaves more registers to the kernels of other streams)
+constexpr int kRowsPerLaneGroup = 2;
+constexpr int kRowsPerBlock = 16 * kRowsPerLaneGroup;
 // Pack: two rows per lane group, 32 per block.  With four (all other things equal) the kernel is 3 %
 // faster when it has the GPU to itself (83 against 86 us per frame of the 7B shape), but it then
 // needs 52 registers instead of 34, and next to it the image-analysis kernels of other streams
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(256) void k_pack(KvBatch f, const sali_frame_row* _
 }
 
 // ---------------------------------------------------------------------------------------------
-// Dequantise-on-read of the four pool rows of one lane group.  kTier >= 0: every row of
+// Dequantise-on-read of the pool rows of one lane group.  kTier >= 0: every row of
 // the wave is of that tier (0 FP16, 1 INT8, 2 INT4, 3 pruned); kTier < 0: tiers are tested per row.
 // Three phases as in the pack kernel: all loads, then the arithmetic, then the stores.
 struct UnpackPlanes {
@@ -282,14 +284,14 @@ __device__ __forceinline__ void unpack_rows(const UnpackPlanes& pl, const sali_f
     const int n16 = row.n16, n8 = row.n8, n4 = row.n4;
     uint32_t tok[kRowsPerLaneGroup];
 #pragma unroll
-    for (int r = 0; r < kRowsPerLaneGroup; ++r) tok[r] = order[j0 + 16 * (g >> 2) + 4 * r + (g & 3)];
+    for (int r = 0; r < kRowsPerLaneGroup; ++r) tok[r] = order[j0 + 4 * kRowsPerLaneGroup * (g >> 2) + 4 * r + (g & 3)];
     Row16B raw[kRowsPerLaneGroup];
     float scale[kRowsPerLaneGroup];
     uint16_t zbits[kRowsPerLaneGroup];
     int tier[kRowsPerLaneGroup];
 #pragma unroll
     for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-        const int j = j0 + 16 * (g >> 2) + 4 * r + (g & 3);          // always < 576
+        const int j = j0 + 4 * kRowsPerLaneGroup * (g >> 2) + 4 * r + (g & 3);          // always < 576
         tier[r] = kTier >= 0 ? kTier : (j < n16 ? 0 : (j < n16 + n8 ? 1 : (j < n16 + n8 + n4 ? 2 : 3)));
         raw[r].u = zero4();
         scale[r] = 0.0f;
@@ -361,7 +363,7 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
         // nothing stored under this id: read back as an all-pruned frame
 #pragma unroll
         for (int r = 0; r < kRowsPerLaneGroup; ++r) {
-            const int tok = j0 + 16 * (g >> 2) + 4 * r + (g & 3);
+            const int tok = j0 + 4 * kRowsPerLaneGroup * (g >> 2) + 4 * r + (g & 3);
             out[(plane * kTokens + tok) * 16 + l] = zero4();
             if (valid != nullptr && plane == 0 && l == 0) valid[tok] = 0;
         }
@@ -383,12 +385,12 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
     char* __restrict__ out_plane = reinterpret_cast<char*>(out) + plane * (size_t)(kTokens * kHeadDim * 2);
 
     UnpackPlanes pl = {p16_plane, c8_plane, c4_plane, s8_plane, s4_plane, z4_plane, out_plane};
-    // A wave covers 16 consecutive pool rows, nearly always of one tier: those waves take a path
+    // A wave covers 8 consecutive pool rows, nearly always of one tier: those waves take a path
     // without tier branches (the scalar test below), where the compiler can issue all loads back to
     // back and wait for each exactly when it is used; a wave that straddles a tier boundary takes
     // the general path.
-    const int w0 = j0 + 16 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int w1 = w0 + 16;
+    const int w0 = j0 + 4 * kRowsPerLaneGroup * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int w1 = w0 + 4 * kRowsPerLaneGroup;
     const int e16 = n16, e8 = n16 + n8, e4 = n16 + n8 + n4;
     if (w1 <= e16) unpack_rows<kNTL, kNTS, 0>(pl, row, order, valid, plane == 0, j0, g, l);
     else if (w0 >= e16 && w1 <= e8) unpack_rows<kNTL, kNTS, 1>(pl, row, order, valid, plane == 0, j0, g, l);
