@@ -11,6 +11,8 @@
  *     "Store (K_i, V_i) with precision Q(s_i)"; Implementation Details: symmetric min-max
  *     INT8, asymmetric INT4) in compacted pools, and expanding them again on read
  *     (Just-In-Time Dequantization).
+ *   - attention of one layer over the compressed cache with the dequantisation fused in
+ *     (Implementation Details), for one query per head up to 64 queries per K/V head.
  *
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller.  The library never
