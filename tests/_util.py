@@ -70,3 +70,24 @@ def assert_same(got, exp, name):
         first = [tuple(int(v) for v in b) for b in bad[:4]]
         vals = [(got[b], exp[b]) for b in first]
         raise AssertionError(f"{name}: {len(bad)} of {got.size} differ; first at {first}: (got, expected) = {vals}")
+
+
+def fp16_operand_bounds(orc, q, lo, hi, sm, q_per_kv):
+    """Elementwise error bounds of attention whose operands are rounded to fp16 (the matrix-core path;
+    derivation in tests/test_gpu_attention.py::test_attend_grouped_queries):
+    (bound on out [n_q, 128], bound on lse [n_q]) from the oracle's dequantised rows."""
+    from oracle.attention import cached_tokens
+    u = 2.0 ** -11
+    k, v = cached_tokens(orc, 0, lo, hi)                       # float64 [n_heads, n_tok, 128]
+    qf = np.asarray(q, dtype=np.float64)
+    bound = np.zeros((qf.shape[0], 128))
+    lse_bound = np.zeros(qf.shape[0])
+    for j in range(qf.shape[0]):
+        h = j // q_per_kv
+        s = sm * (k[h] @ qf[j])
+        s_abs = sm * (np.abs(k[h]) @ np.abs(qf[j]))
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        bound[j] = 2.0 * u * (2.0 + 2.0 * s_abs.max()) * (p @ np.abs(v[h])) + 1e-6
+        lse_bound[j] = 2.0 * u * (1.0 + s_abs.max()) + 1e-6
+    return bound, lse_bound

@@ -15,7 +15,7 @@ from oracle.attention import attend_decode
 from oracle.cache import SaliCacheOracle
 from paper_2602_14236_amd import synth
 
-from _util import lib_config, oracle_config, params, workload_params
+from _util import fp16_operand_bounds as _fp16_operand_bounds, lib_config, oracle_config, params, workload_params
 
 pytestmark = pytest.mark.gpu
 
@@ -159,26 +159,6 @@ def test_attend_full_shape_sampled_layers():
     print(f"largest |out - oracle| = {worst:.3e}", flush=True)
     assert ctx.get_status() == 0
     ctx.close()
-
-
-def _fp16_operand_bounds(orc, q, lo, hi, sm, q_per_kv):
-    """Elementwise error bounds of attention with fp16 operands (see test_attend_grouped_queries):
-    (bound on out [n_q, 128], bound on lse [n_q]) from the oracle's dequantised rows."""
-    from oracle.attention import cached_tokens
-    u = 2.0 ** -11
-    k, v = cached_tokens(orc, 0, lo, hi)                       # float64 [n_heads, n_tok, 128]
-    qf = np.asarray(q, dtype=np.float64)
-    bound = np.zeros((qf.shape[0], 128))
-    lse_bound = np.zeros(qf.shape[0])
-    for j in range(qf.shape[0]):
-        h = j // q_per_kv
-        s = sm * (k[h] @ qf[j])
-        s_abs = sm * (np.abs(k[h]) @ np.abs(qf[j]))
-        p = np.exp(s - s.max())
-        p /= p.sum()
-        bound[j] = 2.0 * u * (2.0 + 2.0 * s_abs.max()) * (p @ np.abs(v[h])) + 1e-6
-        lse_bound[j] = 2.0 * u * (1.0 + s_abs.max()) + 1e-6
-    return bound, lse_bound
 
 
 @pytest.mark.parametrize("q_per_kv", [2, 4, 8, 16, 32, 40, 64])

@@ -244,3 +244,37 @@ def test_grouped_queries_equal_plain_attention_on_a_cache_with_repeated_heads():
     assert np.array_equal(out, ref) and np.array_equal(lse, ref_lse)
     # and the heads of a group really see different queries
     assert not np.allclose(out[0], out[1])
+
+
+def test_fp16_operand_error_bound_holds_for_an_emulated_matrix_core_path():
+    """The tolerance used for the matrix-core attention kernel (operands K^, V^ and the softmax
+    weights rounded to fp16, accumulation in higher precision) is derived to first order; here the
+    same roundings are applied in NumPy and the result must stay inside the bound, with room to
+    spare, on a cache with all tiers, a pointer frame and a sharp softmax."""
+    from _util import fp16_operand_bounds
+    cache = _cache(frames=4)
+    for f in range(3):
+        cache.kv_compress(_kv(50 + f, amp=0.8), _mixed_scores(60 + f), f)
+    _pointer(cache, 3)
+    for scale, seed in ((1.0 / math.sqrt(128.0), 1), (0.6, 2)):       # the second one: a few tokens dominate
+        q = np.concatenate([_q(seed, nh=2), _q(seed + 10, nh=2)]).reshape(2, 2, 128).transpose(1, 0, 2).reshape(4, 128)
+        exact, exact_lse = attend_decode(cache, 0, q, 0, 4, scale, q_per_kv=2)
+        k, v = cached_tokens(cache, 0, 0, 4)
+        k16 = k.astype(np.float16).astype(np.float64)
+        v16 = v.astype(np.float16).astype(np.float64)
+        out = np.zeros_like(exact)
+        lse = np.zeros_like(exact_lse)
+        for j in range(4):
+            h = j // 2
+            s = scale * (k16[h] @ q[j].astype(np.float64))
+            m = s.max()
+            p = np.exp(s - m)
+            p16 = p.astype(np.float16).astype(np.float64)
+            out[j] = (p16 @ v16[h]) / p.sum()
+            lse[j] = m + math.log(p.sum())
+        bound, lse_bound = fp16_operand_bounds(cache, q, 0, 4, scale, 2)
+        err = np.abs(out - exact)
+        assert err.max() > 0.0 and np.all(err <= bound), (err.max(), float((bound / np.maximum(err, 1e-300)).min()))
+        assert np.all(np.abs(lse - exact_lse) <= lse_bound)
+        assert float((bound / np.maximum(err, 1e-300)).min()) > 4.0      # the worst case is not what typically happens
+
