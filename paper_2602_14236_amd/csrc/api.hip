@@ -156,7 +156,7 @@ ScratchLayout scratch_layout(const sali_config& c, const LevelGeom& g) {
     }
     for (int i = 0; i < kExpSlots; ++i) {
         s.expA[i] = take(px * sizeof(float4));
-        s.expB[i] = take(px * sizeof(float2));
+        s.expB[i] = take(px * sizeof(float));
     }
     s.attn_partial = take((size_t)c.n_heads * kAttnSlotsPerHead * kAttnPartialStride * sizeof(float));
     s.total = o;
@@ -334,7 +334,7 @@ int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, bool with_union, hipStre
             const LaneLayout& L = c->sl.lane[bp.lane[i]];
             f.y8[i] = c->sc<uint8_t>(L.y8);
             f.A[i] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
-            f.b[i] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
+            f.b[i] = c->sc<float>(c->sl.expB[bp.slot[i]]);
             f.cls[i] = c->sc<uint8_t>(L.cls);
             f.parent[i] = c->sc<uint32_t>(L.parent);
         }
@@ -347,7 +347,7 @@ int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, bool with_union, hipStre
         f.y8[i] = c->sc<uint8_t>(L.y8);
         f.pyr[i] = c->sc<float>(L.pyr);
         f.A[i] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
-        f.b[i] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
+        f.b[i] = c->sc<float>(c->sl.expB[bp.slot[i]]);
     }
     for (int l = 1; l < g.levels; ++l) SALI_TRY(launch_pyr_down(f, bp.n, g, l, s));
     SALI_TRY(launch_polyexp(f, bp.n, g, c->fw, s));
@@ -367,9 +367,9 @@ int enqueue_flow(sali_ctx* c, const BatchPlan& bp, const float2** flow, hipStrea
         const LaneLayout& L = c->sl.lane[bp.lane[i]];
         for (int k = 0; k < 2; ++k) {
             f[k].A1[m] = c->sc<float4>(c->sl.expA[bp.prev_slot[i]]);
-            f[k].b1[m] = c->sc<float2>(c->sl.expB[bp.prev_slot[i]]);
+            f[k].b1[m] = c->sc<float>(c->sl.expB[bp.prev_slot[i]]);
             f[k].A2[m] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
-            f[k].b2[m] = c->sc<float2>(c->sl.expB[bp.slot[i]]);
+            f[k].b2[m] = c->sc<float>(c->sl.expB[bp.slot[i]]);
             f[k].d_in[m] = c->sc<float2>(L.flow[k]);
             f[k].d_out[m] = c->sc<float2>(L.flow[k ^ 1]);
         }

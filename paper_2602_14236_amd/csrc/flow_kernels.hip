@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void k_polyexp(PyrBatch f, LevelGeom g, FlowWe
     const uint8_t* __restrict__ y8 = f.y8[blockIdx.y];
     const float* __restrict__ pyr = f.pyr[blockIdx.y];
     float4* __restrict__ A_out = f.A[blockIdx.y];
-    float2* __restrict__ b_out = f.b[blockIdx.y];
+    float* __restrict__ b_out = f.b[blockIdx.y];
     __shared__ float s_f[kPR][kPR + 1];
     __shared__ float s_v[3][kT][kPR + 1];
 
@@ -136,8 +136,8 @@ __global__ __launch_bounds__(256) void k_polyexp(PyrBatch f, LevelGeom g, FlowWe
         const float axx = (sxx - fw.m2 * s0) * fw.inv_den;
         const float ayy = (syy - fw.m2 * s0) * fw.inv_den;
         const float axy = sxy * fw.inv_2m2sq;
-        A_out[gi] = make_float4(axx, axy, ayy, 0.0f);
-        b_out[gi] = make_float2(sx * fw.inv_m2, sy * fw.inv_m2);
+        A_out[gi] = make_float4(axx, axy, ayy, sx * fw.inv_m2);
+        b_out[gi] = sy * fw.inv_m2;
     }
 }
 
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     // tiles on one XCD; measured 6 % slower.)
     const uint8_t* __restrict__ y8 = f.y8[blockIdx.y];
     float4* __restrict__ A_out = f.A[blockIdx.y];
-    float2* __restrict__ b_out = f.b[blockIdx.y];
+    float* __restrict__ b_out = f.b[blockIdx.y];
     __shared__ float s_q[kEQ * (kEQ + 1)];          // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
     __shared__ float s_p[kEP * (kEP + 1)];          // level-1 patch of a level-2 block
     __shared__ float s_f[kER][kER + 1];
@@ -287,8 +287,8 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
             }
             const size_t gi = g.off[lvl] + (size_t)gy * w + gx;
             A_out[gi] = make_float4((sxx - fw.m2 * s0) * fw.inv_den, sxy * fw.inv_2m2sq, (syy - fw.m2 * s0) * fw.inv_den,
-                                    0.0f);
-            b_out[gi] = make_float2(sx * fw.inv_m2, sy * fw.inv_m2);
+                                    sx * fw.inv_m2);
+            b_out[gi] = sy * fw.inv_m2;
         }
     }
 }
@@ -333,9 +333,9 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
     // blk.z = frame of the batch, (blk.x, blk.y) = tile
     const BlockId blk = xcd_block_id();
     const float4* __restrict__ A1 = f.A1[blk.z] + level_off;
-    const float2* __restrict__ b1 = f.b1[blk.z] + level_off;
+    const float* __restrict__ b1 = f.b1[blk.z] + level_off;
     const float4* __restrict__ A2 = f.A2[blk.z] + level_off;
-    const float2* __restrict__ b2 = f.b2[blk.z] + level_off;
+    const float* __restrict__ b2 = f.b2[blk.z] + level_off;
     const float2* __restrict__ d_in = f.d_in[blk.z];
     float2* __restrict__ d_out = f.d_out[blk.z];
     constexpr int R = T + 2 * kWinR;
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
         const size_t gi = (size_t)gy * w + gx;
         const float2 dp = prior_at(d_in, prior_mode, gy, gx, w, ch, cw);
         const float4 a1 = A1[gi];
-        const float2 bb1 = b1[gi];
+        const float2 bb1 = make_float2(a1.w, b1[gi]);
         // sample the new frame's expansion at x + prior
         const float sy = clampf((float)gy + dp.y, 0.0f, (float)(h - 1));
         const float sx = clampf((float)gx + dp.x, 0.0f, (float)(w - 1));
@@ -364,7 +364,8 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
         const size_t i00 = (size_t)iy0 * w + ix0, i01 = (size_t)iy0 * w + ix1;
         const size_t i10 = (size_t)iy1 * w + ix0, i11 = (size_t)iy1 * w + ix1;
         const float4 a00 = A2[i00], a01 = A2[i01], a10 = A2[i10], a11 = A2[i11];
-        const float2 c00 = b2[i00], c01 = b2[i01], c10 = b2[i10], c11 = b2[i11];
+        const float2 c00 = make_float2(a00.w, b2[i00]), c01 = make_float2(a01.w, b2[i01]);
+        const float2 c10 = make_float2(a10.w, b2[i10]), c11 = make_float2(a11.w, b2[i11]);
         const float w00 = (1.0f - wx) * (1.0f - wy), w01 = wx * (1.0f - wy), w10 = (1.0f - wx) * wy, w11 = wx * wy;
         const float a2xx = a00.x * w00 + a01.x * w01 + a10.x * w10 + a11.x * w11;
         const float a2xy = a00.y * w00 + a01.y * w01 + a10.y * w10 + a11.y * w11;

@@ -103,10 +103,14 @@ struct PrepBatch {
     unsigned long long* msum_clear[kMaxBatch];    // the accumulator of the lane's next use, cleared
 };
 
+// A polynomial expansion is stored as 20 bytes per pixel and level: Ab = {A_xx, A_xy, A_yy, b_x} and
+// by = b_y (a float4 for A plus a float2 for b would be 24, a fifth of it padding, and the flow
+// updates re-read both frames' expansions once per update: at 1920x1080 that is most of the image
+// side's HBM traffic).
 struct ExpandBatch {
     const uint8_t* y8[kMaxBatch];
     float4* A[kMaxBatch];
-    float2* b[kMaxBatch];
+    float* b[kMaxBatch];
     const uint8_t* cls[kMaxBatch];                // for the hosted cross-tile hysteresis pass
     uint32_t* parent[kMaxBatch];
 };
@@ -115,14 +119,14 @@ struct PyrBatch {                                 // per-level path (more than t
     const uint8_t* y8[kMaxBatch];
     float* pyr[kMaxBatch];                        // all levels of the frame's pyramid, LevelGeom offsets
     float4* A[kMaxBatch];
-    float2* b[kMaxBatch];
+    float* b[kMaxBatch];
 };
 
 struct FlowBatch {                                // expansions at level 0; the launcher adds the level offset
     const float4* A1[kMaxBatch];
-    const float2* b1[kMaxBatch];
+    const float* b1[kMaxBatch];
     const float4* A2[kMaxBatch];
-    const float2* b2[kMaxBatch];
+    const float* b2[kMaxBatch];
     const float2* d_in[kMaxBatch];
     float2* d_out[kMaxBatch];
 };
