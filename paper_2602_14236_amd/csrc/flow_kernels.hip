@@ -10,12 +10,14 @@
 //                values a tile needs are rebuilt from the gray image in LDS; separable moments,
 //                closed-form solution of the 6-unknown weighted least-squares fit
 //   k_pyr_down, k_polyexp   the same per level (pyramid in HBM), used for more than three levels
-//   k_flow_iter  one displacement update: per cell of a 16x16 tile + 5-pixel halo, sample
-//                the new frame's expansion bilinearly at x + prior, build A^T A (3 values) and
-//                A^T db (2 values) in LDS, separable 11x11 Gaussian aggregation in LDS, 2x2 ridge
+//   k_flow_iter  one displacement update: per cell of a tile (16x16 to 32x32, by level size) + 5-pixel
+//                halo, sample the new frame's expansion bilinearly at x + prior, build A^T A (3 values)
+//                and A^T db (2 values) in LDS, separable 11x11 Gaussian aggregation in LDS, 2x2 ridge
 //                solve.  The coarse-to-fine transfer (2 * bilinear of the coarser flow) is folded
 //                into the first update of a level, so G/h fields never touch HBM.  The gather of
-//                the warped expansion is 82 % of a block's time (measured with the wall clock);
+//                the warped expansion is 82 % of a block's time (measured with the wall clock):
+//                a chain of dependent HBM round trips, not a throughput limit (vector ALU 78 %,
+//                texture addresser 75 % busy at 1920x1080);
 //                tiles are handed to the XCDs in contiguous runs so that neighbours share an L2.
 //   k_patch_gate per patch RMS flow magnitude (Eq. 5); the last block to finish counts static
 //                patches and writes the gate (Eq. 6).  Stand-alone flow call only: the chained
@@ -35,6 +37,17 @@ constexpr int kPR = kT + 2 * kPolyN;         // 38
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 __device__ __forceinline__ float clampf(float v, float lo, float hi) { return fminf(fmaxf(v, lo), hi); }
+
+// Element i of an array whose base is uniform over the wave: base + 32-bit byte offset (an image level
+// has fewer than 2^28 pixels, so i * 16 fits), which the hardware adds itself; with 64-bit indices a
+// quarter of the gather's vector instructions were address arithmetic.
+template <typename V>
+__device__ __forceinline__ V ld_at(const V* __restrict__ base, uint32_t i) {
+    return *reinterpret_cast<const V*>(reinterpret_cast<const char*>(base) + i * (uint32_t)sizeof(V));
+}
+__device__ __forceinline__ uint32_t pix(int y, int w, int x) {          // y * w + x, both factors below 2^24
+    return __umul24((uint32_t)y, (uint32_t)w) + (uint32_t)x;
+}
 
 }  // namespace
 
@@ -304,8 +317,8 @@ __device__ __forceinline__ float2 bilerp2(const float2* __restrict__ f, int h, i
     const int y0 = (int)fy0, x0 = (int)fx0;
     const int y1 = min(y0 + 1, h - 1), x1 = min(x0 + 1, w - 1);
     const float wy = y - fy0, wx = x - fx0;
-    const float2 a = f[(size_t)y0 * w + x0], b = f[(size_t)y0 * w + x1];
-    const float2 c = f[(size_t)y1 * w + x0], d = f[(size_t)y1 * w + x1];
+    const float2 a = ld_at(f, pix(y0, w, x0)), b = ld_at(f, pix(y0, w, x1));
+    const float2 c = ld_at(f, pix(y1, w, x0)), d = ld_at(f, pix(y1, w, x1));
     const float tx = a.x * (1.0f - wx) + b.x * wx, ty = a.y * (1.0f - wx) + b.y * wx;
     const float bx = c.x * (1.0f - wx) + d.x * wx, by = c.y * (1.0f - wx) + d.y * wx;
     return make_float2(tx * (1.0f - wy) + bx * wy, ty * (1.0f - wy) + by * wy);
@@ -320,16 +333,15 @@ __device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int 
         const float2 c = bilerp2(d_in, ch, cw, 0.5f * (float)gy, 0.5f * (float)gx);
         return make_float2(2.0f * c.x, 2.0f * c.y);
     }
-    return d_in[(size_t)gy * w + gx];
+    return ld_at(d_in, pix(gy, w, gx));
 }
 
 }  // namespace
 
-// T = tile side (16 in every launch; 32 measured slower at all image sizes once tiles were handed to
-// the XCDs in contiguous runs).
-template <int T>
-__global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_off, int h, int w, int ch, int cw,
-                                                   int prior_mode, FlowWeights fw) {
+// TX x TY = tile, NT = threads of the block.
+template <int TX, int TY, int NT, int kMinWaves = 1>
+__global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long long level_off, int h, int w, int ch, int cw,
+                                                  int prior_mode, FlowWeights fw) {
     // blk.z = frame of the batch, (blk.x, blk.y) = tile
     const BlockId blk = xcd_block_id();
     const float4* __restrict__ A1 = f.A1[blk.z] + level_off;
@@ -338,22 +350,24 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
     const float* __restrict__ b2 = f.b2[blk.z] + level_off;
     const float2* __restrict__ d_in = f.d_in[blk.z];
     float2* __restrict__ d_out = f.d_out[blk.z];
-    constexpr int R = T + 2 * kWinR;
-    __shared__ float s_in[5][R][R + 1];
-    __shared__ float s_row[5][R][T];
+    constexpr int RX = TX + 2 * kWinR, RY = TY + 2 * kWinR;
+    __shared__ float s_in[5][RY][RX + 1];
+    __shared__ float s_row[5][RY][TX];
+    __shared__ float2 s_dp[TY][TX];          // prior of the tile's own pixels, for the solve
 
     const int tid = threadIdx.x;
-    const int x0 = blk.x * T, y0 = blk.y * T;
+    const int x0 = blk.x * TX, y0 = blk.y * TY;
 
     // per-cell A^T A and A^T db at the clamped coordinate of the cell
 #pragma unroll 2
-    for (int p = tid; p < R * R; p += 256) {
-        const int ry = p / R, rx = p % R;
+    for (int p = tid; p < RX * RY; p += NT) {
+        const int ry = p / RX, rx = p % RX;
         const int gy = clampi(y0 - kWinR + ry, 0, h - 1), gx = clampi(x0 - kWinR + rx, 0, w - 1);
-        const size_t gi = (size_t)gy * w + gx;
+        const uint32_t gi = pix(gy, w, gx);
         const float2 dp = prior_at(d_in, prior_mode, gy, gx, w, ch, cw);
-        const float4 a1 = A1[gi];
-        const float2 bb1 = make_float2(a1.w, b1[gi]);
+        if (ry >= kWinR && ry < kWinR + TY && rx >= kWinR && rx < kWinR + TX) s_dp[ry - kWinR][rx - kWinR] = dp;
+        const float4 a1 = ld_at(A1, gi);
+        const float2 bb1 = make_float2(a1.w, ld_at(b1, gi));
         // sample the new frame's expansion at x + prior
         const float sy = clampf((float)gy + dp.y, 0.0f, (float)(h - 1));
         const float sx = clampf((float)gx + dp.x, 0.0f, (float)(w - 1));
@@ -361,11 +375,11 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
         const int iy0 = (int)fy0, ix0 = (int)fx0;
         const int iy1 = min(iy0 + 1, h - 1), ix1 = min(ix0 + 1, w - 1);
         const float wy = sy - fy0, wx = sx - fx0;
-        const size_t i00 = (size_t)iy0 * w + ix0, i01 = (size_t)iy0 * w + ix1;
-        const size_t i10 = (size_t)iy1 * w + ix0, i11 = (size_t)iy1 * w + ix1;
-        const float4 a00 = A2[i00], a01 = A2[i01], a10 = A2[i10], a11 = A2[i11];
-        const float2 c00 = make_float2(a00.w, b2[i00]), c01 = make_float2(a01.w, b2[i01]);
-        const float2 c10 = make_float2(a10.w, b2[i10]), c11 = make_float2(a11.w, b2[i11]);
+        const uint32_t i00 = pix(iy0, w, ix0), i10 = pix(iy1, w, ix0);
+        const uint32_t i01 = i00 + (uint32_t)(ix1 - ix0), i11 = i10 + (uint32_t)(ix1 - ix0);
+        const float4 a00 = ld_at(A2, i00), a01 = ld_at(A2, i01), a10 = ld_at(A2, i10), a11 = ld_at(A2, i11);
+        const float2 c00 = make_float2(a00.w, ld_at(b2, i00)), c01 = make_float2(a01.w, ld_at(b2, i01));
+        const float2 c10 = make_float2(a10.w, ld_at(b2, i10)), c11 = make_float2(a11.w, ld_at(b2, i11));
         const float w00 = (1.0f - wx) * (1.0f - wy), w01 = wx * (1.0f - wy), w10 = (1.0f - wx) * wy, w11 = wx * wy;
         const float a2xx = a00.x * w00 + a01.x * w01 + a10.x * w10 + a11.x * w11;
         const float a2xy = a00.y * w00 + a01.y * w01 + a10.y * w10 + a11.y * w11;
@@ -384,8 +398,8 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
     __syncthreads();
 
     // row pass of the separable Gaussian window
-    for (int p = tid; p < R * T; p += 256) {
-        const int ry = p / T, tx = p % T;
+    for (int p = tid; p < RY * TX; p += NT) {
+        const int ry = p / TX, tx = p % TX;
         float acc[5] = {0, 0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k <= 2 * kWinR; ++k) {
@@ -399,8 +413,8 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
     __syncthreads();
 
     // column pass + ridge solve
-    for (int p = tid; p < T * T; p += 256) {
-        const int ty = p / T, tx = p % T;
+    for (int p = tid; p < TX * TY; p += NT) {
+        const int ty = p / TX, tx = p % TX;
         const int gy = y0 + ty, gx = x0 + tx;
         if (gy >= h || gx >= w) continue;
         float acc[5] = {0, 0, 0, 0, 0};
@@ -410,12 +424,13 @@ __global__ __launch_bounds__(256) void k_flow_iter(FlowBatch f, long long level_
 #pragma unroll
             for (int c = 0; c < 5; ++c) acc[c] += wk * s_row[c][ty + k][tx];
         }
-        const float2 dp = prior_at(d_in, prior_mode, gy, gx, w, ch, cw);
+        const float2 dp = s_dp[ty][tx];
         const float lam = kLamAbs + kLamRel * 0.5f * (acc[0] + acc[2]);
         const float m11 = acc[0] + lam, m22 = acc[2] + lam, m12 = acc[1];
         const float r1 = acc[3] + lam * dp.x, r2 = acc[4] + lam * dp.y;
         const float det = m11 * m22 - m12 * m12;
-        d_out[(size_t)gy * w + gx] = make_float2((m22 * r1 - m12 * r2) / det, (m11 * r2 - m12 * r1) / det);
+        *reinterpret_cast<float2*>(reinterpret_cast<char*>(d_out) + pix(gy, w, gx) * 8u) =
+            make_float2((m22 * r1 - m12 * r2) / det, (m11 * r2 - m12 * r1) / det);
     }
 }
 
@@ -511,10 +526,24 @@ hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights f
 
 hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
                             int prior_mode, FlowWeights fw, hipStream_t s) {
-    // 16x16 tiles at every size: with the XCD-aware order they measured faster than 32x32 tiles from
-    // 84x84 up to 1920x1080 (less LDS per block, so more blocks per compute unit hide the gathers)
-    dim3 grid((w + 15) / 16, (h + 15) / 16, n);
-    hipLaunchKernelGGL(k_flow_iter<16>, grid, dim3(256), 0, s, f, (long long)level_off, h, w, ch, cw, prior_mode, fw);
+    // Tile and block by level size (kMinWaves = 8 holds the 1024-thread block to 64 registers, so that two
+    // of them fit a compute unit):
+    //   below 40 000 pixels   16x16, 256 threads   (up to seven small blocks per compute unit)
+    //   below 150 000         32x16, 512 threads
+    //   above                 32x32, 1024 threads  (1.7 instead of 2.6 halo cells per output)
+    // A block is a chain of dependent HBM round trips (prior -> warped gather, once per cell a thread
+    // owns): with four times the threads a thread owns at most two cells, taken together.  Measured per
+    // frame with nothing else on the GPU, against 16x16 everywhere: 336x336 44.6 -> 42.0 us (32x32 at the
+    // full-size level; 32x16 is used there because it does better next to the K/V kernels), 640x360
+    // 63 -> 56.6, 1920x1080 275 -> 235.  22x22 (one thread per cell), 64x16 and 32x16 / 1024 are slower.
+    const long long px = (long long)h * w;
+#define SALI_FLOW_LAUNCH(TX, TY, NT, MW)                                                                         \
+    hipLaunchKernelGGL((k_flow_iter<TX, TY, NT, MW>), dim3((w + TX - 1) / TX, (h + TY - 1) / TY, n), dim3(NT), 0, \
+                       s, f, (long long)level_off, h, w, ch, cw, prior_mode, fw)
+    if (px >= 150000) SALI_FLOW_LAUNCH(32, 32, 1024, 8);
+    else if (px >= 40000) SALI_FLOW_LAUNCH(32, 16, 512, 1);
+    else SALI_FLOW_LAUNCH(16, 16, 256, 1);
+#undef SALI_FLOW_LAUNCH
     return hipGetLastError();
 }
 

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kTierThreads) void k_tier(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pack: grid (ceil(576 / 64), planes, frames); plane = (layer, K|V, head); frame i of the launch has
+// Pack: grid (576 / (16 * kRows), planes, frames); plane = (layer, K|V, head); frame i of the launch has
 // id first_frame_id + i.
 // ---------------------------------------------------------------------------------------------
 // kNTL / kNTS: non-temporal loads / stores
@@ -344,7 +344,7 @@ __device__ __forceinline__ void unpack_rows(const UnpackPlanes& pl, const sali_f
 }
 
 // ---------------------------------------------------------------------------------------------
-// Unpack: grid (576 / 64, planes, frames); rebuilds the dense fp16 frames in token order; frame i of
+// Unpack: grid (576 / kRowsPerBlock, planes, frames); rebuilds the dense fp16 frames in token order; frame i of
 // the launch has id first_frame_id + i and its validity mask at valid_base + i * 576.
 // ---------------------------------------------------------------------------------------------
 template <bool kNTL, bool kNTS>
