@@ -379,7 +379,7 @@ def main():
         "algorithmic_bytes_per_launch": attn_b, "achieved_gbps": attn_b / pf_s / 1e9 if pf_s > 0 else 0.0,
         "hbm_frac": attn_b / pf_s / HBM_PEAK if pf_s > 0 else 0.0,
         "mfma_tflops_f16": pf_flops / pf_s / 1e12 if pf_s > 0 else 0.0,
-        "what": "32 queries per K/V head, one layer over all cached frames, v_mfma_f32_32x32x8_f16 on fp16 operands",
+        "what": "32 queries per K/V head, one layer over all cached frames, v_mfma_f32_32x32x16_f16 on fp16 operands",
     }
     del q32, out32, lse32
     if args.calibrate_copy:

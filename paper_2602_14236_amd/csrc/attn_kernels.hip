@@ -372,31 +372,38 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
 // ---------------------------------------------------------------------------------------------
 // Many queries per K/V head (16, 32 or 64: the tokens of a prompt attending to the cached video, or
 // large query groups): Q K^T and P V are real matrix products, so they run on the matrix cores
-// (v_mfma_f32_32x32x8_f16) and every compressed row is still read once for all queries.
+// (v_mfma_f32_32x32x16_f16) and every compressed row is still read once for all queries.
 //
 // One wave = one work item (a chunk of frames x a row split, as in the single-query kernel) x one
-// K/V head x one tile of 32 queries.  Per tile of 32 cached rows:
+// K/V head x one tile of 32 queries; the four waves of a block share the 32 queries (LDS).  Per tile
+// of 32 cached rows:
 //   S^T = K^ Q^T : A operand = K^ tile (lane = row n, registers = head-dim values), B operand = the
 //        queries (lane = query m); the result has lane = query, registers = rows, so the softmax
 //        over rows is a reduction over the lane's 16 registers and one exchange between the two
-//        lane halves, and P in that layout IS the B operand of the second product;
-//   out^T = V^^T P^T : A operand = V^^T (lane = head-dim value d, registers = 4 consecutive rows),
-//        read column-wise from the wave's own LDS copy of the V^ tile.
+//        lane halves, and P in that layout IS the B operand of the second product (the rows of the
+//        tile are contracted in the order the registers hold them);
+//   out^T = V^^T P^T : A operand = V^^T (lane = head-dim value d, registers = two runs of 4
+//        consecutive rows), read column-wise from the wave's LDS tile, which holds K^ first and V^ after.
 // The head-dim index of the contraction is permuted (lane half hh of a row holds values
-// [64 hh, 64 hh + 64), k-step t takes 4 of them from each half) so that a lane reads one contiguous
+// [64 hh, 64 hh + 64), k-step t takes 8 of them from each half) so that a lane reads one contiguous
 // piece of its row; Q uses the same permutation.  Here the dequantised values DO exist as fp16
 // (K^ = fp16(code * scale), fp16(code * scale + zero), the values dequantise-on-read produces) because
 // the matrix cores take fp16 operands; the softmax weights are rounded to fp16 for the second product
 // as well.  Both stay inside the tolerance of the floating-point results (largest error printed by
 // the tests).  Accumulation, softmax state and partials are fp32; partials have the layout of the
 // single-query kernel and are merged by the same k_attn_merge.
+// The kernel is bound by instruction issue (conversions of the codes, softmax, LDS traffic and the
+// matrix instructions of a tile share one SIMD): one, two or three resident waves per SIMD take the
+// same time, and so do 16 and 32 queries.
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 namespace {
 
 constexpr int kPfRows = 32;                       // cached rows per tile
-constexpr int kPfVStride = kHeadDim + 8;          // halves per LDS row of the V^ tile (skewed against bank conflicts)
+constexpr int kPfVStride = kHeadDim + 8;          // halves per LDS row of a tile (skewed against bank conflicts)
+constexpr int kPfWavesPerSimd = 2;                // resident waves the launch is sized for
 
 union Half8 {
     u32x4 u;
@@ -516,27 +523,37 @@ __device__ __forceinline__ void pf_lds_order() {
 // the tiles of one tier of one stored frame that fall to this wave
 template <int kTier>
 __device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size_t plane_v, int base, int count,
-                                        int split, int n_splits, int lane, const half4_t (&qb)[16],
-                                        float softmax_scale, float mult, _Float16 (*s_k)[kPfVStride],
-                                        _Float16 (*s_v)[kPfVStride], PfState& st) {
+                                        int split, int n_splits, int lane, const _Float16 (*s_q)[kPfVStride],
+                                        float softmax_scale, float mult, _Float16 (*s_t)[kPfVStride], PfState& st) {
     const int m = lane & 31, hh = lane >> 5;
     const size_t row0_k = pool_row0(pools, base, count, plane_k), row0_v = pool_row0(pools, base, count, plane_v);
-    for (int jb = split * kPfRows; jb < count; jb += n_splits * kPfRows) {
-        // all loads of the tile first: one memory latency per tile
-        PfRaw<kTier> rk, rv;
-        pf_load_tile(pools, row0_k, jb, count, lane, rk);
-        pf_load_tile(pools, row0_v, jb, count, lane, rv);
+    // Software pipeline: the loads of the next tile are in flight while this one is worked on (K^ rows
+    // are asked for as soon as this tile's K^ registers have gone to LDS, V^ rows likewise), and they are
+    // issued without a branch: past the end of the run every row index clamps to the run's last row, one
+    // cache line.  Without it the waves of the chip run in step, all waiting for memory and then all
+    // computing, and the kernel takes the sum of the two times instead of the larger.
+    const int step = n_splits * kPfRows;
+    int jb = split * kPfRows;
+    if (jb >= count) return;
+    PfRaw<kTier> rk, rv;
+    pf_load_tile(pools, row0_k, jb, count, lane, rk);
+    pf_load_tile(pools, row0_v, jb, count, lane, rv);
+    for (; jb < count; jb += step) {
         pf_lds_order();                                            // the previous tile's reads are done
-        pf_store_tile(rk, lane, s_k);
+        pf_store_tile(rk, lane, s_t);
         pf_lds_order();
-        // S^T = K^ Q^T: lane (row n = m, half hh), k-step t: values 64 hh + 4 t .. + 3 of the row
+        pf_load_tile(pools, row0_k, jb + step, count, lane, rk);
+        // S^T = K^ Q^T with v_mfma_f32_32x32x16_f16 (A[i][k]: lane = i + 32 (k / 8), element k % 8; B alike;
+        // D[i][j]: lane = j + 32 hh, register r holds i = 8 (r / 4) + 4 hh + r % 4).  Lane (row m, half hh),
+        // step t: values 64 hh + 8 t .. + 7 of the row; the queries use the same assignment
         float16_t s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.0f;
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const half4_t ka = *reinterpret_cast<const half4_t*>(&s_k[m][64 * hh + 4 * t]);
-            s = __builtin_amdgcn_mfma_f32_32x32x8f16(ka, qb[t], s, 0, 0, 0);
+        for (int t = 0; t < 8; ++t) {
+            const half8_t ka = *reinterpret_cast<const half8_t*>(&s_t[m][64 * hh + 8 * t]);
+            const half8_t qb = *reinterpret_cast<const half8_t*>(&s_q[m][64 * hh + 8 * t]);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka, qb, s, 0, 0, 0);
         }
         // s[r] = <K^ row jb + n(r), query m>, n(r) = 8 (r / 4) + 4 hh + r % 4
         float tmax = -INFINITY;
@@ -550,14 +567,16 @@ __device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size
         const float mnew = fmaxf(st.mx, tmax);
         const float corr = __expf(st.mx - mnew);
         float psum = 0.0f;
-        half4_t pb[4];
+        // the softmax weights in the order the second product wants them: step jj of two, element e of the
+        // lane's eight = row 16 jj + 8 (e / 4) + 4 hh + e % 4 of the tile, which is register 8 jj + e
+        half8_t pb[2];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
+        for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float p = mult * __expf(s[4 * jj + i] - mnew);
+            for (int e = 0; e < 8; ++e) {
+                const float p = mult * __expf(s[8 * jj + e] - mnew);
                 psum += p;
-                pb[jj][i] = (_Float16)p;
+                pb[jj][e] = (_Float16)p;
             }
         psum += __shfl_xor(psum, 32);
         st.lsum = st.lsum * corr + psum;
@@ -570,17 +589,19 @@ __device__ __forceinline__ void pf_tier(const Pools& pools, size_t plane_k, size
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st.acc[dt][r] *= corr;
         }
-        // out^T += V^^T P^T: A operand lane (value d = 32 dt + m, half hh): rows 8 jj + 4 hh + 0..3 of column d
-        pf_store_tile(rv, lane, s_v);
+        // out^T += V^^T P^T: A operand lane (value d = 32 dt + m, half hh): the same eight rows of column d
+        pf_lds_order();                                            // the K^ reads come first: same tile
+        pf_store_tile(rv, lane, s_t);
         pf_lds_order();
+        pf_load_tile(pools, row0_v, jb + step, count, lane, rv);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                half4_t va;
+            for (int jj = 0; jj < 2; ++jj) {
+                half8_t va;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) va[i] = s_v[8 * jj + 4 * hh + i][32 * dt + m];
-                st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x8f16(va, pb[jj], st.acc[dt], 0, 0, 0);
+                for (int e = 0; e < 8; ++e) va[e] = s_t[16 * jj + 8 * (e / 4) + 4 * hh + (e % 4)][32 * dt + m];
+                st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[jj], st.acc[dt], 0, 0, 0);
             }
     }
 }
@@ -592,32 +613,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                       int n_heads, const _Float16* __restrict__ q, int q_per_kv,
                                                       int frame_lo, int frame_hi, int frames_per_chunk, int n_splits,
                                                       int n_partials, float softmax_scale, float* __restrict__ partial) {
-    __shared__ __align__(16) _Float16 s_k_all[4][kPfRows][kPfVStride];
-    __shared__ __align__(16) _Float16 s_v_all[4][kPfRows][kPfVStride];
+    __shared__ __align__(16) _Float16 s_q[32][kPfVStride];               // the block's 32 queries (zeros past q_per_kv)
+    __shared__ __align__(16) _Float16 s_t_all[4][kPfRows][kPfVStride];   // one K^ / V^ tile per wave
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m = lane & 31, hh = lane >> 5;
+    const int h = blockIdx.y;
+    for (int idx = threadIdx.x; idx < 32 * 16; idx += 256) {
+        const int qrow = idx >> 4, piece = idx & 15;
+        const int qq = (int)blockIdx.z * 32 + qrow;
+        u32x4 v = (u32x4){0u, 0u, 0u, 0u};
+        if (qq < q_per_kv) v = reinterpret_cast<const u32x4*>(q + ((size_t)h * q_per_kv + qq) * kHeadDim)[piece];
+        *reinterpret_cast<u32x4*>(&s_q[qrow][8 * piece]) = v;
+    }
+    __syncthreads();
     const int item = (int)blockIdx.x * 4 + wave;
     if (item >= n_partials) return;
     const int chunk = item / n_splits, split = item % n_splits;
-    const int h = blockIdx.y;
     const int qi = (int)blockIdx.z * 32 + m;                 // this lane's query among the q_per_kv of the K/V head
     const bool q_valid = qi < q_per_kv;
     const size_t q_head = (size_t)h * q_per_kv + (q_valid ? qi : 0);
     const size_t plane_k = ((size_t)layer * 2 + 0) * n_heads + h;
     const size_t plane_v = ((size_t)layer * 2 + 1) * n_heads + h;
 
-    half4_t qb[16];
-    {
-        const u32x4* src = reinterpret_cast<const u32x4*>(q + q_head * kHeadDim + 64 * hh);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            Half8 c;
-            c.u = src[u];
-            if (!q_valid) c.u = (u32x4){0u, 0u, 0u, 0u};
-            qb[2 * u] = c.h4[0];
-            qb[2 * u + 1] = c.h4[1];
-        }
-    }
     PfState st;
     st.mx = -INFINITY;
     st.lsum = 0.0f;
@@ -644,12 +661,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             if (rows[t].src == src) ++n_uses;
         const float mult = (float)n_uses;
         const sali_frame_row row = rows[src];
-        pf_tier<SALI_TIER_FP16>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, lane, qb, softmax_scale, mult,
-                                s_k_all[wave], s_v_all[wave], st);
-        pf_tier<SALI_TIER_INT8>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, lane, qb, softmax_scale, mult,
-                                s_k_all[wave], s_v_all[wave], st);
-        pf_tier<SALI_TIER_INT4>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, lane, qb, softmax_scale, mult,
-                                s_k_all[wave], s_v_all[wave], st);
+        pf_tier<SALI_TIER_FP16>(pools, plane_k, plane_v, row.base16, row.n16, split, n_splits, lane, s_q, softmax_scale, mult,
+                                s_t_all[wave], st);
+        pf_tier<SALI_TIER_INT8>(pools, plane_k, plane_v, row.base8, row.n8, split, n_splits, lane, s_q, softmax_scale, mult,
+                                s_t_all[wave], st);
+        pf_tier<SALI_TIER_INT4>(pools, plane_k, plane_v, row.base4, row.n4, split, n_splits, lane, s_q, softmax_scale, mult,
+                                s_t_all[wave], st);
     }
     if (!q_valid) return;
     float* mine = partial + (q_head * (size_t)n_partials + item) * kPartialStride;
@@ -671,15 +688,28 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
     if (n_range > 0 && q_per_kv > kAttnMaxQPerKv) {
         // matrix-core path: 32 queries per wave; the scratch holds kAttnSlotsPerHead partials per K/V head,
         // shared out over the q_per_kv query heads
-        // and one resident round of waves (two per SIMD: 2048 on the chip) is the target, as for the streaming kernel
+        // and one resident round of waves (kPfWavesPerSimd per SIMD: 2048 on the chip) is the target, as for the streaming kernel
         int per_head = kAttnSlotsPerHead / q_per_kv;
-        const int round = (2 * 4 * 256) / (n_heads * ((q_per_kv + 31) / 32));
+        const int round = (kPfWavesPerSimd * 4 * 256) / (n_heads * ((q_per_kv + 31) / 32));
         per_head = per_head > round ? (round < 1 ? 1 : round) : per_head;
         per_head = per_head > kAttnPartials ? kAttnPartials : per_head;
-        const int fpc = (n_range + per_head - 1) / per_head;
-        const int n_chunks = (n_range + fpc - 1) / fpc;
-        int n_splits = per_head / n_chunks;
-        n_splits = n_splits < 1 ? 1 : (n_splits > kTokens / kPfRows ? kTokens / kPfRows : n_splits);
+        // work items = chunks of whole frames x row splits inside a frame; of the few ways to get close to
+        // per_head items take the one with the most items
+        int fpc = (n_range + per_head - 1) / per_head, n_chunks = 0, n_splits = 0;
+        for (int cand = fpc; cand <= fpc + 3; ++cand) {
+            const int chunks = (n_range + cand - 1) / cand;
+            int splits = per_head / chunks;
+            splits = splits < 1 ? 1 : (splits > kTokens / kPfRows ? kTokens / kPfRows : splits);
+            if (chunks * splits > n_chunks * n_splits && chunks * splits <= per_head) {
+                fpc = cand;
+                n_chunks = chunks;
+                n_splits = splits;
+            }
+        }
+        if (n_chunks == 0) {            // per_head below the number of chunks cannot happen (fpc covers the range)
+            n_chunks = (n_range + fpc - 1) / fpc;
+            n_splits = 1;
+        }
         n_partials = n_chunks * n_splits;
         if (ev_start != nullptr && hipEventRecord(ev_start, s) != hipSuccess) return hipErrorUnknown;
         const dim3 grid((n_partials + 3) / 4, n_heads, (q_per_kv + 31) / 32);
