@@ -498,10 +498,16 @@ __device__ __forceinline__ void pf_store_tile(const PfRaw<SALI_TIER_INT4>& r, in
 #pragma unroll
         for (int w = 0; w < 4; ++w) {                               // 8 values = one word of codes
             const uint32_t word = w == 0 ? r.c[u].x : (w == 1 ? r.c[u].y : (w == 2 ? r.c[u].z : r.c[u].w));
+            // nibbles to bytes first (even elements in one word, odd ones in another): a byte converts to
+            // fp32 in one instruction, a nibble needs a shift and a mask each
+            uint32_t ev = word & 0x0F0F0F0Fu, od = (word >> 4) & 0x0F0F0F0Fu;
+            asm volatile("" : "+v"(ev), "+v"(od));      // (keeps the compiler from folding the bytes back into nibbles)
             Half8 o;
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                o.h[i] = (_Float16)__builtin_fmaf((float)((word >> (4 * i)) & 0xFu), r.sc[u], r.zp[u]);
+            for (int i = 0; i < 4; ++i) {
+                o.h[2 * i] = (_Float16)__builtin_fmaf((float)((ev >> (8 * i)) & 0xFFu), r.sc[u], r.zp[u]);
+                o.h[2 * i + 1] = (_Float16)__builtin_fmaf((float)((od >> (8 * i)) & 0xFFu), r.sc[u], r.zp[u]);
+            }
             dst[w] = o.u;
         }
     }
