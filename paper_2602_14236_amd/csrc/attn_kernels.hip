@@ -115,8 +115,15 @@ __device__ __forceinline__ void row_values(const RawRow<SALI_TIER_INT8>& r, floa
     }
 }
 __device__ __forceinline__ void row_values(const RawRow<SALI_TIER_INT4>& r, float x[8]) {
+    // nibbles to bytes first (even elements in one word, odd ones in the other): a byte converts to fp32
+    // in one instruction; the empty asm keeps the compiler from folding the bytes back into nibbles
+    uint32_t ev = r.u & 0x0F0F0F0Fu, od = (r.u >> 4) & 0x0F0F0F0Fu;
+    asm volatile("" : "+v"(ev), "+v"(od));
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = (float)((r.u >> (4 * e)) & 0xF);
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = (float)((ev >> (8 * i)) & 0xFFu);
+        x[2 * i + 1] = (float)((od >> (8 * i)) & 0xFFu);
+    }
 }
 
 // <q, K^_row> of the lane from the sum over its raw values: K^ = code * scale (+ zero)
