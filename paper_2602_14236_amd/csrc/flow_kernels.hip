@@ -212,32 +212,49 @@ __device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, 
 
 }  // namespace
 
-// The first n_union blocks of every frame do something unrelated that has the same predecessor (the
+// n_union blocks per frame do something unrelated that has the same predecessor (the
 // saliency pre-pass) and nothing else to wait for: the cross-tile pass of the Canny hysteresis, one
 // 64 x 4 pixel strip per block.  Hosting it here saves a launch and its 10 us of latency-bound run
 // time on the critical path of a frame batch.
 __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int t1, int t2, int tx0, int tx1, int tx2,
                                                 FlowWeights fw, int n_union, int strips_x) {
-    if ((int)blockIdx.x < n_union) {
-        union_strip(f.cls[blockIdx.y], f.parent[blockIdx.y], g.h[0], g.w[0], (int)blockIdx.x % strips_x,
-                    (int)blockIdx.x / strips_x);
+    // Work order.  A level-2 tile costs about ten times a level-0 tile (97 x 97 gray pixels, two pyramid
+    // stages) and there are sixteen level-0 tiles for each: with the tiles of a frame in level order the
+    // heavy ones start last and the launch ends with a few of them on an idle chip (22 us per four
+    // 336x336 frames, 10 of them that tail).  So the linear block id is cut into runs, heaviest first,
+    // each run over all frames of the batch: level-2 tiles, the hysteresis strips (latency-bound, they
+    // ride along), level-1 tiles, level-0 tiles.
+    const int n_frames = (int)gridDim.y;
+    const int t3 = (int)gridDim.x - n_union;        // tiles of a frame over all levels
+    int idx = (int)blockIdx.x + (int)gridDim.x * (int)blockIdx.y;
+    int lvl, t, frame;
+    if (idx < n_frames * (t3 - t2)) {
+        lvl = 2;
+        frame = idx / (t3 - t2);
+        t = idx - frame * (t3 - t2);
+    } else if ((idx -= n_frames * (t3 - t2)) < n_frames * n_union) {
+        frame = idx / n_union;
+        idx -= frame * n_union;
+        union_strip(f.cls[frame], f.parent[frame], g.h[0], g.w[0], idx % strips_x, idx / strips_x);
         return;
+    } else if ((idx -= n_frames * n_union) < n_frames * (t2 - t1)) {
+        lvl = 1;
+        frame = idx / (t2 - t1);
+        t = idx - frame * (t2 - t1);
+    } else {
+        idx -= n_frames * (t2 - t1);
+        lvl = 0;
+        frame = idx / t1;
+        t = idx - frame * t1;
     }
-    // blockIdx.y = frame of the batch.  (Plain block order on purpose: the tiles of the three levels
-    // cost very different amounts, and the XCD-aware order puts all of a frame's expensive level-2
-    // tiles on one XCD; measured 6 % slower.)
-    const uint8_t* __restrict__ y8 = f.y8[blockIdx.y];
-    float4* __restrict__ A_out = f.A[blockIdx.y];
-    float* __restrict__ b_out = f.b[blockIdx.y];
+    const uint8_t* __restrict__ y8 = f.y8[frame];
+    float4* __restrict__ A_out = f.A[frame];
+    float* __restrict__ b_out = f.b[frame];
     __shared__ float s_q[kEQ * (kEQ + 1)];          // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
     __shared__ float s_p[kEP * (kEP + 1)];          // level-1 patch of a level-2 block
     __shared__ float s_f[kER][kER + 1];
     __shared__ float s_v[3][kET][kER + 1];
 
-    // block -> (level, tile)
-    const int b = (int)blockIdx.x - n_union;
-    const int lvl = b < t1 ? 0 : (b < t2 ? 1 : 2);
-    const int t = b - (lvl == 0 ? 0 : (lvl == 1 ? t1 : t2));
     const int tiles_x = lvl == 0 ? tx0 : (lvl == 1 ? tx1 : tx2);
     const int h = g.h[lvl], w = g.w[lvl];
     const int x0 = (t % tiles_x) * kET, y0 = (t / tiles_x) * kET;
