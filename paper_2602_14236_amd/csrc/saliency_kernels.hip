@@ -338,6 +338,9 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     // gate: n_static = #{dP_i < tau_t}, R = n_static / 576, redundant iff R > theta_R; a frame
     // without predecessor (no flow) is never redundant
     const bool have_flow = f.flow[b] != nullptr;
+    // the scores are asked for now, with the patch motions: one memory round trip instead of two on the
+    // critical path of the batch (a redundant frame does not use them)
+    const TierScores scores = tier_load_scores(f.scores[b]);
     int n = 0;
     if (have_flow) {
         for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
@@ -354,7 +357,7 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     TierCounts tc = {};
     tc.state = 1;
     if (!redundant)
-        tc = tier_rank(sh, f.scores[b], tl.tp, tl.tier + (size_t)b * kTokens, tl.slot + (size_t)b * kTokens,
+        tc = tier_rank(sh, scores, tl.tp, tl.tier + (size_t)b * kTokens, tl.slot + (size_t)b * kTokens,
                        tl.order + (size_t)b * kTokens);
     __syncthreads();
     if (threadIdx.x == 0) {

@@ -66,7 +66,22 @@ __device__ __forceinline__ int tier_count_above(const TierShared& sh, uint32_t m
 
 // Assigns tier, slot (rank inside the tier in token order) and the pool-order token list of one
 // non-redundant frame.  Returns the per-tier counts (every thread gets the same value).
-__device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const float* scores, const TierParams& tp,
+// The scores of the thread's tokens (0 past the end).  A step of its own so that a caller can ask for
+// them early, together with other loads it has to wait for anyway.
+struct TierScores {
+    float s[kTierSlots];
+};
+__device__ __forceinline__ TierScores tier_load_scores(const float* scores) {
+    TierScores v;
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = (int)threadIdx.x + k * kTierThreads;
+        v.s[k] = i < kTokens ? __hip_atomic_load(scores + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+    }
+    return v;
+}
+
+__device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const TierScores& loaded, const TierParams& tp,
                                                 uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
                                                 uint16_t* __restrict__ order_out) {
     const int tid = threadIdx.x;
@@ -83,7 +98,7 @@ __device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const float* sco
         s[k] = 0.0f;
         key[k] = 0u;
         if (i < kTokens) {
-            s[k] = __hip_atomic_load(scores + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s[k] = loaded.s[k];
             has_nan |= s[k] != s[k];
             // unsigned key with the same order as the float (and -0 == +0, as the float comparison has it)
             const uint32_t bits = (s[k] == 0.0f) ? 0u : __builtin_bit_cast(uint32_t, s[k]);
@@ -261,7 +276,7 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
                                           Cursors* cur, int cap16, int cap8, int cap4) {
     TierCounts tc = {};
     tc.state = 1;
-    if (!redundant) tc = tier_rank(sh, scores, tp, tier_out, slot_out, order_out);
+    if (!redundant) tc = tier_rank(sh, tier_load_scores(scores), tp, tier_out, slot_out, order_out);
     if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4);
 }
 
