@@ -157,6 +157,22 @@ def test_attend_full_shape_sampled_layers():
         assert np.all(np.abs(lse.cpu().numpy().astype(np.float64) - exp_lse) <= ATOL + RTOL * np.abs(exp_lse))
         worst = max(worst, float(err.max()))
     print(f"largest |out - oracle| = {worst:.3e}", flush=True)
+    # the same cache through the matrix-core path as bench.py times it: 32 queries on each of the 32 K/V heads
+    L, qpk = 17, 32
+    q = _q(90, wl.n_heads * qpk)
+    out = torch.empty((wl.n_heads * qpk, 128), dtype=torch.float32, device="cuda")
+    lse = torch.empty((wl.n_heads * qpk,), dtype=torch.float32, device="cuda")
+    for lo, hi in ((0, n), (2, 7)):
+        ctx.attend_decode_gqa(L, q, qpk, lo, hi, sm, out, lse)
+        torch.cuda.synchronize()
+        exp_out, exp_lse = attend_decode(orcs[L], 0, q.cpu().numpy(), lo, hi, sm, q_per_kv=qpk)
+        bound, lse_bound = _fp16_operand_bounds(orcs[L], q.cpu().numpy(), lo, hi, sm, qpk)
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exp_out)
+        assert np.all(err <= bound), f"32 queries per head, frames [{lo}, {hi}): max error {err.max():.3e}"
+        assert np.all(np.abs(lse.cpu().numpy() - exp_lse) <= lse_bound)
+        rms = math.sqrt(float((err ** 2).mean())) / math.sqrt(float((exp_out ** 2).mean()))
+        assert rms <= 1e-3, rms
+        print(f"32 queries per head, frames [{lo}, {hi}): largest error {err.max():.3e}, relative rms {rms:.2e}", flush=True)
     assert ctx.get_status() == 0
     ctx.close()
 
