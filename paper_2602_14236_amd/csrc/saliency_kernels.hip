@@ -367,7 +367,6 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
         gt.redundant = redundant ? 1 : 0;
         gt.reserved = 0;
         *f.gate[b] = gt;
-        *f.frame_done[b] = 0u;          // ready for the next launch
         int32_t* out = reinterpret_cast<int32_t*>(f.tcounts[b]);
         __hip_atomic_store(out + 0, tc.state, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
@@ -402,22 +401,18 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
 // Eq. 7 score of each patch and, in the chained step (do_tier), also its motion (Eq. 5) from the
 // flow field.  kWaves = 1: one wave per patch, four patches per block of 256 threads (small
 // patches); kWaves = 4: the whole block works on one patch (large frames).
-// kFusedTail: the last block of a FRAME to finish (atomic arrival counter, nobody waits) runs
-// pool_tail for it, so one launch replaces three, at the price of one device-scope fence per
-// block.  That pays for 144 blocks per frame; with 576 per frame (large frames) the fences and
-// arrivals cost 110 us per four-frame launch at 1920x1080 against 33 us of pooling, so there the
-// tail is a second small launch (k_pool_tail) and the blocks just end.
-template <int kWaves, bool kFusedTail>
+// The gate and the tiers (pool_tail) are a second, small launch.  Doing them in the last block of a
+// frame to finish (arrival counter) saves that launch but needs a device-scope fence per block, and
+// such a fence writes back and invalidates the issuing XCD's L2: with 144 blocks per frame it made the
+// K/V kernels running next to it 7 % slower (5 400 -> 5 700 frames/s without), and at 1920x1080 (576
+// blocks per frame) it cost the pooling kernel itself 110 us per four-frame launch against 33 us of work.
+template <int kWaves>
 __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w, uint8_t* __restrict__ salmap,
-                                                  int do_tier, float tau_t, float theta_r, TierLaunch tl,
-                                                  uint32_t* batch_done) {
+                                                  int do_tier) {
     static_assert(kTierThreads == 256, "four waves, one patch each");
     static_assert(kWaves == 1 || kWaves == 4, "");
-    __shared__ TierShared sh;
-    __shared__ int s_cnt[kTierThreads / 64];
     __shared__ uint32_t s_pq[kTierThreads / 64];
     __shared__ float s_pm[kTierThreads / 64];
-    __shared__ int s_last;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     {
         // blockIdx.y = frame of the batch
@@ -487,17 +482,6 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    if (!do_tier || !kFusedTail) return;
-    // Arrival counter, nobody waits: the last block of a frame goes on
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __threadfence();
-        s_last = (atomicAdd(f.frame_done[blockIdx.y], 1u) == gridDim.x - 1u) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    pool_tail(sh, s_cnt, f, (int)blockIdx.y, (int)gridDim.y, tau_t, theta_r, tl, batch_done);
 }
 
 // the tail as a launch of its own: one block per frame
@@ -534,18 +518,16 @@ hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salma
     TierLaunch t = {};
     if (tier_or_null != nullptr) t = *tier_or_null;
     const int do_tier = tier_or_null != nullptr ? 1 : 0;
-    // patches of up to 1024 pixels: one wave each, tail in the same launch
+    // patches of up to 1024 pixels: one wave each
     if ((long long)h * w <= 1024ll * kTokens) {
-        hipLaunchKernelGGL((k_pool<1, true>), dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null,
-                           do_tier, tau_t, theta_r, t, d_done_counter);
+        hipLaunchKernelGGL((k_pool<1>), dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null, do_tier);
     } else {
-        hipLaunchKernelGGL((k_pool<4, false>), dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null,
-                           do_tier, tau_t, theta_r, t, d_done_counter);
-        if (do_tier) {
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(k_pool_tail, dim3(n), dim3(kTierThreads), 0, s, f, tau_t, theta_r, t, d_done_counter);
-        }
+        hipLaunchKernelGGL((k_pool<4>), dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null, do_tier);
+    }
+    if (do_tier) {
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_pool_tail, dim3(n), dim3(kTierThreads), 0, s, f, tau_t, theta_r, t, d_done_counter);
     }
     return hipGetLastError();
 }
