@@ -43,7 +43,7 @@ struct TableLayout {
 
 struct LaneCounters {         // arrival counters, all self-resetting
     uint32_t patch_done;      // blocks of the stand-alone patch-motion kernel
-    uint32_t pool_done;       // blocks of the pooling kernel that work on the frame in this lane
+    uint32_t reserved;
     uint32_t batch_done;      // frames of a pooling launch whose first frame sits in this lane
 };
 
@@ -412,7 +412,6 @@ int enqueue_pool(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, uint
         f.flow[i] = flow != nullptr ? flow[i] : nullptr;
         f.dp[i] = lp.dp;
         f.gate[i] = lp.gate;
-        f.frame_done[i] = &lp.counters->pool_done;
         f.tcounts[i] = c->sc<TierCounts>(L.tcounts);
     }
     SALI_TRY(launch_pool(f, bp.n, c->cfg.src_h, c->cfg.src_w, d_salmap, tier, c->cfg.tau_t, c->cfg.theta_r,

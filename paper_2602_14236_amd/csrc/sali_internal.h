@@ -140,7 +140,6 @@ struct PoolBatch {
     const float2* flow[kMaxBatch];                // NULL: no predecessor (never redundant)
     float* dp[kMaxBatch];
     sali_gate* gate[kMaxBatch];
-    uint32_t* frame_done[kMaxBatch];              // arrival counter of the frame's blocks (self-resetting)
     struct TierCounts* tcounts[kMaxBatch];        // hand-over from the frame's ranking to the row writer
 };
 
@@ -209,7 +208,7 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
 hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool with_saliency, const uint16_t* d_lut, int lo2,
                        int hi2, hipStream_t s);
 hipError_t launch_union(const PrepBatch& f, int n, int h, int w, hipStream_t s);
-// d_salmap_or_null applies to frame 0 (stand-alone call); with `tier` the last block also evaluates
+// d_salmap_or_null applies to frame 0 (stand-alone call); with `tier` a second small launch evaluates
 // the gate and assigns tiers for the n frames in order
 hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salmap_or_null,
                        const TierLaunch* tier_or_null, float tau_t, float theta_r, uint32_t* d_done_counter,

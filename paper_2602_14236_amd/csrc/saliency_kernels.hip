@@ -17,9 +17,9 @@
 //   k_union  joins components across tile borders with global atomics (border pixels only).
 //   k_pool   per patch: E = edge pixel whose root is strong, C = V above the frame mean and
 //            above a floor; q = sum(E + C); score = floor(q * 2^15 / |P|) / 65536.  In the
-//            chained step it also reduces the flow field to the patch's motion (Eq. 5); the last
-//            block of a frame to finish evaluates the gate (Eq. 6) and ranks the frame's tokens,
-//            and the last of those in the launch writes the frame-table rows in video order.
+//            chained step it also reduces the flow field to the patch's motion (Eq. 5).
+//   k_pool_tail  one block per frame: the gate (Eq. 6) and the ranking of the frame's tokens; the
+//            last of them to finish writes the frame-table rows in video order.
 //
 // Every kernel takes the frame as a grid dimension (per-frame pointers in a by-value struct): one
 // small frame cannot fill 256 compute units.
