@@ -32,9 +32,9 @@ constexpr int kRowsPerBlock = 16 * kRowsPerLaneGroup;
 // Pack: two rows per lane group, 32 per block.  With four (all other things equal) the kernel is 3 %
 // faster when it has the GPU to itself (83 against 86 us per frame of the 7B shape), but it then
 // needs 52 registers instead of 34, and next to it the image-analysis kernels of other streams
-// (69 to 120 registers) hardly get onto a compute unit while it runs: analysis + store without
-// read-back reaches 8 450 frames/s with four rows and 9 400 (60 % of HBM peak) with two; with the
-// read-back in the step both give the same frames/s.  Three rows (43 registers) behave like four.
+// (61 to 120 registers) hardly get onto a compute unit while it runs: analysis + store without
+// read-back reaches 8 900 frames/s with four rows and 10 750 (69 % of HBM peak) with two; with the
+// read-back in the step 5 630 against 5 710.  Three rows (43 registers) behave like four.
 constexpr int kPackRows = 2;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
