@@ -156,7 +156,7 @@ def main():
     rgbs = [torch.from_numpy(video.frame(t)).to(dev) for t in range(n_src)]
     kvs = [synth.kv_frame(wl, t, device=dev, n_layers=n_layers, scale=scale) for t in range(n_src)]
     # frames per launch: 4 where the K/V side bounds the path (a batch of 8 costs more pipeline fill
-    # than it saves in a 64-step run), 8 where the image side does (configs 1 and 3: +16 % / +7 %)
+    # than it saves in a 64-step run), 8 where the image side does (configs 1 and 3: +30 % / +8 %)
     BATCH = int(os.environ.get("SALI_BENCH_BATCH", "8" if args.config in (1, 3) else "4"))
     outs = [torch.empty((n_layers, 2, wl.n_heads, 576, 128), dtype=torch.float16, device=dev)
             for _ in range(max(1, BATCH))]
