@@ -7,6 +7,21 @@ FLOW_RTOL = 1e-3
 FLOW_ATOL = 1e-4
 
 
+DRIFT_SHIFTS = (0.0, 0.3, 0.6, 0.9, 2.4)       # px; a slow pan of 0.3 px per frame, then a jump
+
+
+def drift_frame(shift, h=96, w=96):
+    """Band-limited texture evaluated analytically at x - shift (no interpolation), as uint8 RGB."""
+    rng = np.random.default_rng(11)
+    yy, xx = np.meshgrid(np.arange(h, dtype=np.float64), np.arange(w, dtype=np.float64), indexing="ij")
+    img = np.zeros((h, w))
+    for _ in range(10):
+        fx, fy = rng.uniform(-0.8, 0.8, 2)
+        img += rng.uniform(0.3, 1.0) * np.sin(fx * (xx - shift) + fy * yy + rng.uniform(0, 6.28))
+    g = np.clip(np.rint(128 + 35 * img), 0, 255).astype(np.uint8)
+    return np.stack([g, g, g], axis=-1)
+
+
 def params(src_h=336, src_w=336, **kw):
     p = dict(src_h=src_h, src_w=src_w, flow_levels=3, flow_iters=3, tau_t=0.5, theta_r=0.90, canny_lo=50,
              canny_hi=100, tier_mode=0, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0,

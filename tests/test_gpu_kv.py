@@ -163,6 +163,27 @@ def test_pool_overflow_and_faults_are_reported_not_fatal():
     ctx.close()
 
 
+def test_nonfinite_status_bit_equals_the_oracle_flag():
+    """inf / NaN in a kept token of each tier sets the bit, in a pruned token (never read) it does not."""
+    from paper_2602_14236_amd import binding
+    p = params(tier_mode=1, k_fp16=10, k_int8=10, k_int4=10, n_layers=1, n_heads=1, cap_fp16=100, cap_int8=100,
+               cap_int4=100, max_frames=2)
+    ctx = binding.SaliContext(lib_config(p))
+    scores = torch.linspace(1.0, 0.0, 576)
+    kv = _kv(21, 1, 1)
+    for tok, val in ((400, float("inf")), (3, float("inf")), (15, float("-inf")), (25, float("nan")), (None, 0.0)):
+        orc = SaliCacheOracle(oracle_config(p))
+        ctx.reset()
+        bad = kv.clone()
+        if tok is not None:
+            bad[0, 0, 0, tok, 100] = val
+        ctx.kv_compress(bad, scores.cuda(), 0)
+        orc.kv_compress(bad.cpu().numpy(), scores.numpy(), 0)
+        got = bool(ctx.get_status() & binding.FAULT_NONFINITE)
+        assert got == orc.nonfinite == (tok is not None and tok < 30), (tok, val, got, orc.nonfinite)
+    ctx.close()
+
+
 def test_argument_errors_are_synchronous():
     from paper_2602_14236_amd import binding
     p = params(max_frames=2)

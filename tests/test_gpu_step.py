@@ -86,6 +86,34 @@ def test_config1_whole():
     ctx.close()
 
 
+def test_slow_drift_reference_is_the_adjacent_frame():
+    """A pan of 0.3 px per frame (tau_t = 0.5): measured against the adjacent frame every drifting
+    frame is redundant and points at frame 0, measured against the last stored frame the third would
+    be stored (the CPU pin of the oracle shows both).  Same frames through sali_step."""
+    from paper_2602_14236_amd import binding
+    from _util import DRIFT_SHIFTS, drift_frame, params
+    p = params(96, 96, flow_levels=2, n_layers=1, n_heads=1, cap_fp16=4000, cap_int8=4000, cap_int4=4000, max_frames=8)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    g = torch.Generator().manual_seed(3)
+    for t, s in enumerate(DRIFT_SHIFTS):
+        rgb = drift_frame(s)
+        kv = torch.randn((1, 2, 1, 576, 128), generator=g).to(torch.float16)
+        ctx.step(torch.from_numpy(rgb).cuda(), kv.cuda(), t)
+        dp, gate, _ = ctx.read_last_step()
+        orc.step(rgb, kv.numpy(), t)
+        if t > 0:
+            n, r, red, margin = orc.last_gate
+            print(f"frame {t}: n_static {n} (device {gate.n_static}), gate margin {margin:.3e}", flush=True)
+            assert close(dp, orc.last_dp).all(), f"frame {t}: Delta P out of tolerance"
+            fragile = int(np.count_nonzero(np.abs(orc.last_dp - 0.5) <= FLOW_ATOL + FLOW_RTOL * 0.5))
+            assert abs(gate.n_static - n) <= fragile and gate.redundant == int(red)
+    assert [orc.rows[t].stored for t in range(5)] == [1, 0, 0, 0, 1]
+    assert [orc.rows[t].src for t in range(5)] == [0, 0, 0, 0, 4]
+    _compare_all(ctx, orc, range(5))
+    ctx.close()
+
+
 def test_tier_params_changed_between_frames():
     """sali_set_tier_params: thresholds -> top-k counts -> other thresholds while the video runs; the
     oracle's configuration is changed at the same frames.  Pool capacities are sized for any mix."""
