@@ -276,6 +276,24 @@ int sali_attend_decode(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32
 int sali_attend_decode_gqa(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t q_per_kv, int32_t frame_lo,
                            int32_t frame_hi, float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace for this call (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): sali_attend_decode with its
+ * partial softmax states kept in a device array that is part of the library image instead of the
+ * context's scratch buffer.  Arguments, results and tolerances are those of sali_attend_decode.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ *   - limit: the context's n_heads <= SALI_STATIC_ATTEND_MAX_HEADS, else SALI_ERR_SHAPE; the array is
+ *     SALI_STATIC_ATTEND_MAX_HEADS * 256 partials * 640 B = 10 MiB on every GPU the library is used on,
+ *     held until the process ends.
+ *   - the array's device address is looked up once per GPU in sali_create; SALI_ERR_STATE if the
+ *     current device is not the one the context was created on.
+ *   - all calls on one GPU share the array (whatever the context): calls that overlap on one GPU,
+ *     on different streams or contexts, race.  Nothing of a previous call's contents is read: every
+ *     partial the merge step reads is written by the same call first.
+ * It does not replace or share state with sali_attend_decode, which may run next to it. */
+#define SALI_STATIC_ATTEND_MAX_HEADS 64
+int sali_attend_decode_static(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
+                              float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
+
 /* One loop body of Algorithm 1 with look-ahead on caller-owned streams: analyses a later
  * frame `next_frame_id` (image d_rgb_next, may be NULL at the end of a sequence) on
  * `image_stream` and stores the K/V of the already analysed frame `frame_id` (d_kv, may be NULL

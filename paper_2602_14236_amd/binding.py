@@ -93,6 +93,8 @@ EXPORTS = {
                                      C.c_void_p, C.c_void_p]),
     "sali_attend_decode_gqa": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                          C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sali_attend_decode_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+                                            C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_step_pipelined": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p]),
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
@@ -245,6 +247,12 @@ class SaliContext:
         s = _stream() if stream is None else stream.cuda_stream
         _check(self.lib.sali_attend_decode(self.handle, layer, _ptr(q), frame_lo, frame_hi, softmax_scale, _ptr(out),
                                            _ptr(lse), s), "sali_attend_decode")
+
+    def attend_decode_static(self, layer: int, q, frame_lo: int, frame_hi: int, softmax_scale: float, out, lse=None,
+                             stream: Optional[torch.cuda.Stream] = None):
+        s = _stream() if stream is None else stream.cuda_stream
+        _check(self.lib.sali_attend_decode_static(self.handle, layer, _ptr(q), frame_lo, frame_hi, softmax_scale,
+                                                  _ptr(out), _ptr(lse), s), "sali_attend_decode_static")
 
     def attend_decode_gqa(self, layer: int, q, q_per_kv: int, frame_lo: int, frame_hi: int, softmax_scale: float, out,
                           lse=None, stream: Optional[torch.cuda.Stream] = None):

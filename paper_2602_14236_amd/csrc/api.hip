@@ -3,11 +3,18 @@
 // flow_kernels.hip; this file only validates, lays out the caller's buffers and enqueues.
 
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 
 #include "sali_internal.h"
 #include "tier_body.h"
+
+// Partial softmax states of sali_attend_decode_static: device memory that belongs to the library
+// image instead of the caller's scratch buffer, for callers that cannot allocate.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code this name is only a
+// stand-in for the symbol: the device address comes from hipGetSymbolAddress (static_scratch_for_device).
+static __device__ __align__(256) float scratch[SALI_STATIC_ATTEND_MAX_HEADS * sali::kAttnPartials * sali::kAttnPartialStride];
 
 namespace sali {
 
@@ -262,6 +269,8 @@ struct sali_ctx {
     unsigned lane_uses[kLanes];   // saliency passes run in each lane; the parity selects the frame-sum accumulator
     AnalysisRecord ring[kRing];
     hipEvent_t prof[3][2];    // [SALI_PROF_*][start, stop], armed for one launch
+    int device;               // the GPU that was current in sali_create (the buffers live there)
+    float* static_scratch;    // that GPU's copy of the library's own partial-result array
 
     template <typename T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
     template <typename T> T* tb(size_t off) const { return reinterpret_cast<T*>(tables + off); }
@@ -466,6 +475,28 @@ int wait_unless_same(hipStream_t s, hipStream_t recorded_on, hipEvent_t ev) {
     return SALI_OK;
 }
 
+// Device address of `scratch` on the current device, looked up once per device (with that device
+// current) and kept: each GPU has its own copy of the array at its own address.
+constexpr int kMaxDevices = 64;
+float* g_static_scratch[kMaxDevices] = {};
+std::mutex g_static_scratch_lock;
+
+int static_scratch_for_device(int* device_out, float** ptr_out) {
+    int dev = -1;
+    SALI_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return SALI_ERR_STATE;
+    std::lock_guard<std::mutex> hold(g_static_scratch_lock);
+    if (g_static_scratch[dev] == nullptr) {
+        void* p = nullptr;
+        SALI_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return SALI_ERR_HIP;
+        g_static_scratch[dev] = static_cast<float*>(p);
+    }
+    *device_out = dev;
+    *ptr_out = g_static_scratch[dev];
+    return SALI_OK;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
@@ -548,6 +579,13 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->n_analysed = 0;
     for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
     for (int i = 0; i < 3; ++i) c->prof[i][0] = c->prof[i][1] = nullptr;
+    {
+        const int src = static_scratch_for_device(&c->device, &c->static_scratch);
+        if (src != SALI_OK) {
+            delete c;
+            return src;
+        }
+    }
     for (int i = 0; i < kRing; ++i) {
         c->ring[i].frame_id = -1;
         c->ring[i].batch_last = i;
@@ -716,6 +754,25 @@ int sali_attend_decode(sali_ctx* c, int32_t layer, const void* d_q_fp16, int32_t
                        float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
     return sali_attend_decode_gqa(c, layer, d_q_fp16, 1, frame_lo, frame_hi, softmax_scale, d_out, d_lse_or_null,
                                   stream);
+}
+
+int sali_attend_decode_static(sali_ctx* c, int32_t layer, const void* d_q_fp16, int32_t frame_lo, int32_t frame_hi,
+                              float softmax_scale, float* d_out, float* d_lse_or_null, void* stream) {
+    if (c == nullptr || d_q_fp16 == nullptr || d_out == nullptr) return SALI_ERR_NULL;
+    if (c->cfg.n_heads > SALI_STATIC_ATTEND_MAX_HEADS) return SALI_ERR_SHAPE;      // the array holds no more
+    if (layer < 0 || layer >= c->cfg.n_layers) return SALI_ERR_SHAPE;
+    if (frame_lo < 0 || frame_hi < frame_lo || frame_hi > c->cfg.max_frames) return SALI_ERR_SHAPE;
+    if (!aligned16(d_q_fp16)) return SALI_ERR_ALIGN;
+    if (!(softmax_scale == softmax_scale)) return SALI_ERR_CONFIG;
+    int dev = -1;
+    SALI_TRY(hipGetDevice(&dev));
+    if (dev != c->device || c->static_scratch == nullptr) return SALI_ERR_STATE;
+    // every partial the merge kernel reads is written by the main kernel of the same call (one per
+    // block, empty blocks included), so nothing of the previous call's contents has to be cleared
+    const hipError_t e = launch_attend(c->rows(), c->pools, layer, c->cfg.n_heads, 1, d_q_fp16, frame_lo, frame_hi,
+                                       softmax_scale, c->static_scratch, d_out, d_lse_or_null, nullptr, nullptr,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SALI_OK : SALI_ERR_HIP;
 }
 
 int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t first_frame_id, int32_t n_frames,
