@@ -188,11 +188,15 @@ int sali_kv_decompress(sali_ctx* ctx, int32_t frame_id, void* d_kv_fp16_out,
                        uint8_t* d_valid576_or_null, void* stream);
 
 /* One loop body of Algorithm 1 for frame `frame_id` with image d_rgb_t and K/V d_kv_t:
- * flow against the frame of the previous sali_step call -> gate; a redundant frame becomes
- * a pointer row and nothing else happens; otherwise saliency -> tiers -> storage as in
+ * flow against the frame of the previous sali_step call (the adjacent frame, whether or not it
+ * was stored) -> gate; a redundant frame becomes a pointer row to the last stored frame: no
+ * ranking, no tiers, no K/V read or written; otherwise saliency -> tiers -> storage as in
  * sali_kv_compress.  The first call after create/reset has no previous frame and always
  * stores.  No host synchronisation: the gate lives in device memory and later kernels
- * test it. */
+ * test it.  Cost note: the edge / colour-variance pre-pass of the frame is launched together with
+ * its gray conversion, before the gate is known, so a redundant frame still pays for that pre-pass
+ * and its pooling (their results are dropped); what a redundant frame saves is the ranking and
+ * all K/V traffic. */
 int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id,
               void* stream);
 
@@ -250,9 +254,12 @@ int sali_step_batch(sali_ctx* ctx, const uint8_t* const* d_rgb_frames, const voi
  * head h:  s_j = softmax_scale * <q_h, K^_j>,  out_h = sum_j softmax(s)_j V^_j,
  * lse_h = log sum_j exp(s_j), over the logical token sequence of frames frame_lo .. frame_hi - 1:
  * every frame contributes the kept tokens of its cache entry, a redundant frame (pointer entry)
- * those of its source frame once more, pruned tokens and frames without data nothing.  K^, V^ are
- * exactly the values sali_kv_decompress returns.  With lse the caller can merge the result with
- * attention over other keys (text tokens).
+ * those of its source frame once more, pruned tokens and frames without data nothing.  "Fused" is
+ * taken literally: K^, V^ are the stored codes times their fp32 scales (plus the fp16 zero-point
+ * for INT4) as exact real numbers, evaluated in fp32 and never rounded to fp16 on the way; FP16 rows
+ * as stored.  (sali_kv_decompress rounds the same numbers to fp16, so attention over its output
+ * differs from this call by up to 2^-11 relative per K^ / V^ element.)  With lse the caller can merge
+ * the result with attention over other keys (text tokens).
  *   d_q_fp16   device, fp16 [n_heads][128], 16-byte aligned
  *   d_out      device, fp32 [n_heads][128]; zeros where the range holds no token
  *   d_lse_or_null  device, fp32 [n_heads]; -inf where the range holds no token
@@ -270,8 +277,9 @@ int sali_attend_decode(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32
  *                (K^, V^ never rounded to fp16).
  *   q_per_kv in 9 .. 64:      many queries against the cache (the tokens of a prompt, or of several
  *                query heads, laid out per K/V head); the two products run on the matrix cores,
- *                for which K^, V^ (the values sali_kv_decompress returns) and the softmax weights
- *                are fp16 operands; accumulation is fp32.
+ *                whose operands are fp16: here, and only here, K^, V^ are rounded to fp16 (the
+ *                values sali_kv_decompress returns) and so are the softmax weights; accumulation
+ *                is fp32.
  * SALI_ERR_SHAPE for another q_per_kv. */
 int sali_attend_decode_gqa(sali_ctx* ctx, int32_t layer, const void* d_q_fp16, int32_t q_per_kv, int32_t frame_lo,
                            int32_t frame_hi, float softmax_scale, float* d_out, float* d_lse_or_null, void* stream);
@@ -319,6 +327,14 @@ int sali_read_frame_tiers(sali_ctx* ctx, int32_t frame_id, uint8_t* h_tier576, u
  * of that analysis (or ordered after it). */
 int sali_read_last_step(sali_ctx* ctx, float* h_patch_motion576, sali_gate* h_gate,
                         float* h_scores576, void* stream);
+
+/* The same for any of the SALI_ANALYSIS_LANES most recently analysed frames (each analysis keeps
+ * its per-patch motion, gate and scores in its own scratch copy until that copy's next user, the
+ * analysis SALI_ANALYSIS_LANES frames later, is issued): Eq. 5 motion, Eq. 6 gate and Eq. 7 scores
+ * of frame `frame_id`.  Makes `stream` wait for that frame's analysis, then waits for `stream`.
+ * SALI_ERR_STATE if the frame is not among those frames. */
+int sali_read_analysis(sali_ctx* ctx, int32_t frame_id, float* h_patch_motion576, sali_gate* h_gate,
+                       float* h_scores576, void* stream);
 
 /* Measurement hook.  Arms one pair of caller-created HIP events (hipEvent_t, passed as void*):
  * the next launch of the chosen kernel records `start` just before and `stop` just after it on

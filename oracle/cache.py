@@ -70,6 +70,13 @@ class FrameRow:
                 self.n16, self.n8, self.n4, self.npr)
 
 
+def assign_tiers(c: OracleConfig, scores):
+    """Eq. 8 (mode 0) or the top-k counts (mode 1) of the configuration."""
+    if c.tier_mode == 0:
+        return oq.tiers_threshold(scores, c.tau_high, c.tau_med, c.tau_low)
+    return oq.tiers_topk(scores, c.k_fp16, c.k_int8, c.k_int4)
+
+
 class SaliCacheOracle:
     def __init__(self, cfg: OracleConfig):
         self.cfg = cfg
@@ -105,10 +112,7 @@ class SaliCacheOracle:
         return osal.saliency_pool(rgb, c.grid, c.canny_lo, c.canny_hi)
 
     def assign_tiers(self, scores):
-        c = self.cfg
-        if c.tier_mode == 0:
-            return oq.tiers_threshold(scores, c.tau_high, c.tau_med, c.tau_low)
-        return oq.tiers_topk(scores, c.k_fp16, c.k_int8, c.k_int4)
+        return assign_tiers(self.cfg, scores)
 
     def kv_compress(self, kv_fp16, scores, frame_id):
         """kv_fp16: [n_l, 2, n_h, N, D].  Stores the frame; returns its table row."""
@@ -193,3 +197,64 @@ class SaliCacheOracle:
         scores, _ = self.saliency_pool(rgb)
         self.last_scores = scores
         return self.kv_compress(kv_fp16, scores, frame_id)
+
+
+class ImageSideOracle:
+    """Algorithm 1 without the K/V tensors: everything the image decides.
+
+    Per frame: the temporal filter against the adjacent frame (Eq. 5, Eq. 6, R_frame > theta_R), and
+    for a non-redundant frame the saliency scores (Eq. 7), tiers (Eq. 8) and compaction indices;
+    then the frame-table row, whose pool bases advance by the tier counts exactly as in
+    SaliCacheOracle.kv_compress (same overflow rule).  The pools themselves are not kept, so whole
+    workloads at their stated K/V shapes can be walked; `analyze_pair` needs no history and may be
+    evaluated for many frames independently, `commit` is the sequential part.
+    """
+
+    def __init__(self, cfg: OracleConfig):
+        self.cfg = cfg
+        self.cursor = [0, 0, 0]
+        self.last_src = -1
+        self.rows: Dict[int, FrameRow] = {}
+        self.prev_rgb = None
+        self.overflow = False
+
+    def analyze_pair(self, prev_rgb, rgb, tau_t=None, theta_r=None):
+        """prev_rgb None = first frame (never redundant).  -> dict(redundant, dp, gate, scores, tier, slot, cnt)."""
+        c = self.cfg
+        tau_t = c.tau_t if tau_t is None else tau_t
+        theta_r = c.theta_r if theta_r is None else theta_r
+        out = dict(redundant=False, dp=None, gate=None, scores=None, tier=None, slot=None, cnt=None)
+        if prev_rgb is not None:
+            d = oflow.flow_from_gray(oflow.gray_float(prev_rgb), oflow.gray_float(rgb), c.flow_levels, c.flow_iters)
+            out["dp"] = oflow.patch_motion(d, c.grid)
+            out["gate"] = oflow.gate(out["dp"], tau_t, theta_r)
+            out["redundant"] = bool(out["gate"][2])
+        if out["redundant"]:
+            return out                      # Algorithm 1: pointer, then `continue`
+        out["scores"], _ = osal.saliency_pool(rgb, c.grid, c.canny_lo, c.canny_hi)
+        out["tier"] = assign_tiers(c, out["scores"])
+        out["slot"], out["cnt"] = oq.slots(out["tier"])
+        return out
+
+    def commit(self, frame_id, a) -> FrameRow:
+        c = self.cfg
+        if a["redundant"]:
+            row = FrameRow(frame_id, self.last_src, 0)
+        else:
+            cnt = a["cnt"]
+            if (self.cursor[0] + cnt[0] > c.cap_fp16 or self.cursor[1] + cnt[1] > c.cap_int8
+                    or self.cursor[2] + cnt[2] > c.cap_int4):
+                self.overflow = True
+                row = FrameRow(frame_id, -1, 0)
+            else:
+                b16, b8, b4 = self.cursor
+                row = FrameRow(frame_id, frame_id, 1, b16, b8, b4, int(cnt[0]), int(cnt[1]), int(cnt[2]), int(cnt[3]))
+                self.cursor = [b16 + int(cnt[0]), b8 + int(cnt[1]), b4 + int(cnt[2])]
+                self.last_src = frame_id
+        self.rows[frame_id] = row
+        return row
+
+    def step(self, rgb, frame_id, tau_t=None, theta_r=None):
+        a = self.analyze_pair(self.prev_rgb, rgb, tau_t, theta_r)
+        self.prev_rgb = rgb
+        return self.commit(frame_id, a), a

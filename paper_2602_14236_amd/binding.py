@@ -100,6 +100,7 @@ EXPORTS = {
     "sali_read_frame_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
     "sali_read_frame_tiers": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_read_last_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sali_read_analysis": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sali_set_profile_events": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
     "sali_get_status": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p]),
     "sali_error_string": (C.c_char_p, [C.c_int]),
@@ -305,6 +306,15 @@ class SaliContext:
         g = sali_gate()
         _check(self.lib.sali_read_last_step(self.handle, dp.ctypes.data_as(C.c_void_p), C.byref(g),
                                             sc.ctypes.data_as(C.c_void_p), _stream()), "sali_read_last_step")
+        return dp, g, sc
+
+    def read_analysis(self, frame_id: int):
+        """(Delta P [576], gate, scores [576]) of one of the most recently analysed frames."""
+        dp = np.empty(TOKENS, dtype=np.float32)
+        sc = np.empty(TOKENS, dtype=np.float32)
+        g = sali_gate()
+        _check(self.lib.sali_read_analysis(self.handle, frame_id, dp.ctypes.data_as(C.c_void_p), C.byref(g),
+                                           sc.ctypes.data_as(C.c_void_p), _stream()), "sali_read_analysis")
         return dp, g, sc
 
     def set_profile_events(self, which: int, start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]):

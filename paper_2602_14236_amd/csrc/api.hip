@@ -945,6 +945,32 @@ int sali_read_last_step(sali_ctx* c, float* h_patch_motion576, sali_gate* h_gate
     return SALI_OK;
 }
 
+int sali_read_analysis(sali_ctx* c, int32_t frame_id, float* h_patch_motion576, sali_gate* h_gate, float* h_scores576,
+                       void* stream) {
+    if (c == nullptr) return SALI_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int slot = -1;
+    for (int i = 0; i < kRing; ++i)
+        if (c->ring[i].frame_id == frame_id) slot = i;
+    if (slot < 0 || c->n_analysed == 0) return SALI_ERR_STATE;
+    // analysis number of that ring entry: the latest n < n_analysed with n % kRing == slot; its
+    // scratch copy has been handed to analysis n + kLanes if that one was issued already
+    const unsigned last = c->n_analysed - 1u;
+    const unsigned n = last - ((last + (unsigned)kRing - (unsigned)slot) % (unsigned)kRing);
+    if (c->n_analysed - n > (unsigned)kLanes) return SALI_ERR_STATE;
+    const AnalysisRecord& ev = c->ring[c->ring[slot].batch_last];
+    const int rc = wait_unless_same(s, ev.stream, ev.done);
+    if (rc != SALI_OK) return rc;
+    const LanePtrs lp = c->lane_ptrs((int)(n % kLanes));
+    if (h_patch_motion576 != nullptr)
+        SALI_TRY(hipMemcpyAsync(h_patch_motion576, lp.dp, kTokens * sizeof(float), hipMemcpyDeviceToHost, s));
+    if (h_gate != nullptr) SALI_TRY(hipMemcpyAsync(h_gate, lp.gate, sizeof(sali_gate), hipMemcpyDeviceToHost, s));
+    if (h_scores576 != nullptr)
+        SALI_TRY(hipMemcpyAsync(h_scores576, lp.scores, kTokens * sizeof(float), hipMemcpyDeviceToHost, s));
+    SALI_TRY(hipStreamSynchronize(s));
+    return SALI_OK;
+}
+
 int sali_set_profile_events(sali_ctx* c, int which, void* start_event, void* stop_event) {
     if (c == nullptr) return SALI_ERR_NULL;
     if (which != SALI_PROF_PACK && which != SALI_PROF_UNPACK && which != SALI_PROF_ATTEND) return SALI_ERR_SHAPE;

@@ -278,6 +278,17 @@ def _split_scene(wl: Workload) -> _Scene:
     return sc
 
 
+def gate_schedule(config: int) -> Dict[int, Tuple[float, float]]:
+    """Frames at which a workload changes the temporal thresholds: {frame: (tau_t, theta_R)}; the
+    values hold from that frame on until the next entry.  Config 5 evaluates its rational-boundary
+    frame (exactly 432 of 576 static patches) with theta_R = 0.75 and one duplicate frame with
+    tau_t = 0 (strict '<': no patch is below a zero threshold); everything else runs at the
+    defaults (0.5 px, 0.90)."""
+    if config == 5:
+        return {58: (0.5, 0.75), 59: (0.5, 0.90), 120: (0.0, 0.90), 121: (0.5, 0.90)}
+    return {}
+
+
 def video(config: int, n_frames: Optional[int] = None) -> Video:
     return Video(WORKLOADS[config], n_frames)
 

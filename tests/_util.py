@@ -22,6 +22,45 @@ def drift_frame(shift, h=96, w=96):
     return np.stack([g, g, g], axis=-1)
 
 
+def _render_range(args):
+    cfg_id, n, lo, hi = args
+    from paper_2602_14236_amd import synth
+    v = synth.video(cfg_id, n)
+    return lo, [v.frame(t) for t in range(lo, hi)]
+
+
+class FramePrefetcher:
+    """Renders the frames of a workload in worker processes (spawned: they import numpy only and never
+    touch the GPU), a chunk ahead of the consumer; frame(t) must be asked for in ascending order."""
+
+    def __init__(self, cfg_id, n, chunk=8, workers=8):
+        import multiprocessing as mp
+        from concurrent.futures import ProcessPoolExecutor
+        self.pool = ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn"))
+        self.chunks = [(cfg_id, n, lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+        self.depth = 2 * workers
+        self.futs = {}
+        self.next_submit = 0
+        self.cur = None
+        self._fill()
+
+    def _fill(self):
+        while self.next_submit < len(self.chunks) and len(self.futs) < self.depth:
+            c = self.chunks[self.next_submit]
+            self.futs[c[2]] = self.pool.submit(_render_range, c)
+            self.next_submit += 1
+
+    def frame(self, t):
+        if self.cur is None or not (self.cur[0] <= t < self.cur[0] + len(self.cur[1])):
+            lo = max(k for k in self.futs if k <= t)
+            self.cur = self.futs.pop(lo).result()
+            self._fill()
+        return self.cur[1][t - self.cur[0]]
+
+    def close(self):
+        self.pool.shutdown(wait=False, cancel_futures=True)
+
+
 def params(src_h=336, src_w=336, **kw):
     p = dict(src_h=src_h, src_w=src_w, flow_levels=3, flow_iters=3, tau_t=0.5, theta_r=0.90, canny_lo=50,
              canny_hi=100, tier_mode=0, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0,

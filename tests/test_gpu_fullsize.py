@@ -185,3 +185,189 @@ def test_config4_flow_field_1080p():
     g = gate.cpu().numpy()
     assert (int(g[0]), int(g[2])) == (n, int(red))
     ctx.close()
+
+
+# ---- whole workloads against the committed oracle records ---------------------------------------
+# tests/golden/image_side_cfg<N>.npz is written by tests/golden/make_image_golden.py, which calls only
+# the oracle: per frame the gate, Delta P, scores, tiers and frame-table row.  The library walks the
+# same frames at the workload's full K/V shape, in the benchmark's launch configuration, and every
+# frame is compared; the K/V contents are checked on sampled frames and planes against the oracle's
+# quantiser run here.
+import os
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _batches(n, schedule, batch=4):
+    """Consecutive frame ranges of at most `batch` frames that never straddle a threshold change."""
+    cuts = sorted(set([0, n] + [f for f in schedule if 0 < f < n]))
+    out = []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        for lo in range(a, b, batch):
+            out.append((lo, min(b, lo + batch)))
+    return out
+
+
+def _thresholds_at(schedule, t):
+    cur = (0.5, 0.90)
+    for f, v in sorted(schedule.items()):
+        if f <= t:
+            cur = v
+    return cur
+
+
+def _walk_workload(cfg_id, n_sample_planes, check_every, seed):
+    from paper_2602_14236_amd import binding
+    g = np.load(os.path.join(GOLDEN, f"image_side_cfg{cfg_id}.npz"))
+    wl = synth.WORKLOADS[cfg_id]
+    n = int(g["rows"].shape[0])
+    rows_exp = g["rows"]
+    stored = rows_exp[:, 2] == 1
+    totals = [int(rows_exp[stored, 6 + k].sum()) for k in range(3)]
+    p = workload_params(wl, frames=n, cap_fp16=max(1, totals[0]), cap_int8=max(1, totals[1]), cap_int4=max(1, totals[2]))
+    schedule = synth.gate_schedule(cfg_id)
+    from _util import FramePrefetcher
+    video = FramePrefetcher(cfg_id, n)
+    ctx = binding.SaliContext(lib_config(p))
+    scale = synth.kv_channel_scale(wl)
+    n_planes = wl.n_layers * 2 * wl.n_heads
+    rng = np.random.default_rng(seed)
+    planes = sorted(rng.choice(n_planes, n_sample_planes, replace=False).tolist())
+    plane_idx = torch.as_tensor(planes, device="cuda")
+    s_imgs = [torch.cuda.Stream(), torch.cuda.Stream()]
+    s_kv = torch.cuda.Stream()
+    batches = _batches(n, schedule)
+    print(f"{wl.name}: {n} frames in {len(batches)} launches, K/V {wl.n_layers} x 2 x {wl.n_heads} planes, "
+          f"{int((~stored).sum())} pointer frames in the record", flush=True)
+    rgbs = {}
+
+    def analyze(b):
+        if b < len(batches):
+            lo, hi = batches[b]
+            ctx.set_gate_thresholds(*_thresholds_at(schedule, lo))
+            for t in range(lo, hi):
+                rgbs[t] = torch.from_numpy(video.frame(t)).cuda()
+            ctx.analyze_batch([rgbs[t] for t in range(lo, hi)], lo, s_imgs[b % 2])
+
+    min_margin, fragile_frames, kv_checked = np.inf, 0, 0
+    stored_seen = 0
+    analyze(0)
+    for b, (lo, hi) in enumerate(batches):
+        analyze(b + 1)
+        kvs = [synth.kv_frame(wl, t, device="cuda", scale=scale) for t in range(lo, hi)]
+        outs = [torch.empty_like(k) for k in kvs]
+        torch.cuda.current_stream().synchronize()
+        ctx.store_batch(kvs, lo, s_kv)
+        ctx.kv_decompress_batch(lo, outs, None, s_kv)
+        s_kv.synchronize()
+        rows = ctx.read_frame_table(lo, hi - lo)
+        for i, t in enumerate(range(lo, hi)):
+            min_margin = min(min_margin, float(g["margin"][t]))
+            dp, gate, scores = ctx.read_analysis(t)
+            if g["n_static"][t] >= 0:
+                tau = float(g["tau_t"][t])
+                fragile = int(np.count_nonzero(np.abs(g["dp"][t].astype(np.float64) - tau) <= FLOW_ATOL + FLOW_RTOL * tau))
+                assert close(dp, g["dp"][t]).all(), f"frame {t}: Delta P out of tolerance"
+                assert abs(gate.n_static - int(g["n_static"][t])) <= fragile, f"frame {t}: n_static"
+                # the decision may differ only where the patches within tolerance of tau_t could change it
+                theta = np.float32(g["theta_r"][t])
+                n_exp = int(g["n_static"][t])
+                decisions = {bool(np.float32(k) / np.float32(576) > theta) for k in range(n_exp - fragile, n_exp + fragile + 1)}
+                if len(decisions) == 1:
+                    assert gate.redundant == int(g["redundant"][t]), f"frame {t}: gate"
+                fragile_frames += fragile > 0
+            if stored[t]:
+                assert_same(scores, g["scores"][t], f"scores of frame {t}")
+            assert rows[i].as_tuple() == tuple(int(v) for v in rows_exp[t]), \
+                f"row {t}: {rows[i].as_tuple()} vs {tuple(int(v) for v in rows_exp[t])}"
+            if not stored[t]:
+                if rows_exp[t, 1] >= 0:       # a pointer frame reads back its source frame
+                    assert bool((outs[i].view(n_planes, 576, 128)[plane_idx] == last_out_planes).all()), f"pointer frame {t}"
+                continue
+            tier, slot = ctx.read_frame_tiers(t)
+            exp_tier = g["tier"][t]
+            assert_same(tier, exp_tier, f"tier {t}")
+            exp_slot = np.zeros(576, np.int32)
+            for k in range(4):
+                idx = np.nonzero(exp_tier == k)[0]
+                exp_slot[idx] = np.arange(idx.size)
+            assert_same(slot.astype(np.int32), exp_slot, f"slot {t}")
+            last_out_planes = outs[i].view(n_planes, 576, 128)[plane_idx].clone()
+            stored_seen += 1
+            if stored_seen % check_every != 1 and check_every > 1 and t != n - 1:
+                continue
+            # K/V of this frame on the sampled planes: pool rows and read-back against the oracle's quantiser
+            kv_planes = kvs[i].view(n_planes, 576, 128)[plane_idx].cpu().numpy()
+            out_planes = last_out_planes.cpu().numpy()
+            P = n_planes
+            flat = ctx.pool_views_flat()
+
+            def pool_rows(name, base, cnt):
+                a = flat[name][base * P:(base + cnt) * P].view(P, cnt, -1)[plane_idx]
+                return a.cpu().numpy()
+
+            r = rows_exp[t]
+            i16, i8, i4, ip = (np.nonzero(exp_tier == k)[0] for k in range(4))
+            exp_out = np.zeros_like(kv_planes)
+            if i16.size:
+                assert_same(pool_rows("fp16", r[3], i16.size), kv_planes[:, i16], f"frame {t} fp16 pool rows")
+                exp_out[:, i16] = kv_planes[:, i16]
+            if i8.size:
+                q, s = oq.quant_int8(kv_planes[:, i8])
+                assert_same(pool_rows("codes8", r[4], i8.size), q, f"frame {t} int8 codes")
+                assert_same(pool_rows("scale8", r[4], i8.size), s, f"frame {t} int8 scales")
+                exp_out[:, i8] = oq.dequant_int8(q, s)
+            if i4.size:
+                q, s, z = oq.quant_int4(kv_planes[:, i4])
+                assert_same(pool_rows("codes4", r[5], i4.size), oq.pack_nibbles(q), f"frame {t} int4 codes")
+                assert_same(pool_rows("scale4", r[5], i4.size), s, f"frame {t} int4 scales")
+                assert_same(pool_rows("zero4", r[5], i4.size), z, f"frame {t} int4 zero-points")
+                exp_out[:, i4] = oq.dequant_int4(q, s, z)
+            assert_same(out_planes, exp_out, f"frame {t} dequantised planes")
+            kv_checked += 1
+        for t in range(lo, hi):
+            rgbs.pop(t, None)
+        if b % 16 == 0:
+            print(f"  frames {lo}..{hi - 1} ok", flush=True)
+    torch.cuda.synchronize()
+    assert ctx.get_status() == 0
+    video.close()
+    print(f"{wl.name}: {n} frames compared (rows, gate, Delta P, scores, tiers, slots of every frame in "
+          f"{len(batches)} launches; K/V of {kv_checked} frames on {n_sample_planes} planes); "
+          f"smallest gate margin in the record {min_margin:.3e}; frames with a patch within "
+          f"tolerance of tau_t: {fragile_frames}", flush=True)
+    ctx.close()
+    return g
+
+
+def test_config2_whole_workload():
+    g = _walk_workload(2, n_sample_planes=8, check_every=8, seed=11)
+    assert g["rows"].shape[0] == 64
+
+
+def test_config5_whole_workload():
+    """All 128 frames: scene cuts, duplicate runs, noise frames, the 432 / 576 boundary frame evaluated
+    with theta_R = 0.75 and the duplicate evaluated with tau_t = 0."""
+    g = _walk_workload(5, n_sample_planes=6, check_every=12, seed=12)
+    rows = g["rows"]
+    assert rows.shape[0] == 128
+    assert int(g["n_static"][58]) == 432 and rows[58, 2] == 1          # R == theta_R: not redundant
+    assert int(g["n_static"][120]) == 0 and rows[120, 2] == 1          # tau_t = 0 on a duplicate: stored
+    assert [int(v) for v in rows[5:9, 2]] == [0, 0, 0, 0]
+
+
+def test_config3_several_hundred_frames():
+    """The leading frames of the 1800-frame stream at its stated 4 x 32 K/V shape: moving runs and
+    near-static runs under fresh noise, many times round the analysis ring."""
+    g = _walk_workload(3, n_sample_planes=8, check_every=25, seed=13)
+    red = g["redundant"]
+    n = red.size
+    changes = int(np.count_nonzero(red[1:] != red[:-1]))
+    print(f"config 3: {n} frames covered, {int(red.sum())} redundant, {changes} run boundaries", flush=True)
+    assert n >= 300 and changes >= 4
+
+
+def test_config4_leading_frames():
+    g = _walk_workload(4, n_sample_planes=4, check_every=6, seed=14)
+    print(f"config 4: {g['rows'].shape[0]} frames covered", flush=True)
+    assert g["rows"].shape[0] >= 16
