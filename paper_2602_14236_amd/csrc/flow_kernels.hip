@@ -90,8 +90,11 @@ __global__ __launch_bounds__(256) void k_polyexp(PyrBatch f, LevelGeom g, FlowWe
     const float* __restrict__ pyr = f.pyr[blockIdx.y];
     float4* __restrict__ A_out = f.A[blockIdx.y];
     float* __restrict__ b_out = f.b[blockIdx.y];
-    __shared__ float s_f[kPR][kPR + 1];
-    __shared__ float s_v[3][kT][kPR + 1];
+    // unpadded rows: the passes that write and read these arrays column-wise address them linearly
+    // in the thread index (with a pad of one float, a group of 32 lanes that straddles two rows has
+    // two lanes on one bank: 23 % of the kernel's LDS cycles were bank conflicts)
+    __shared__ float s_f[kPR][kPR];
+    __shared__ float s_v[3][kT][kPR];
 
     int lvl = 0;
     while (lvl + 1 < g.levels && (int)blockIdx.x >= g.tile_start[lvl + 1]) ++lvl;
@@ -164,15 +167,39 @@ constexpr int kET = 16;                        // tile side
 constexpr int kER = kET + 2 * kPolyN;          // 22: region the expansion stencil reads
 constexpr int kEP = 2 * (kER - 1) + 5;         // 47: region one level below that feeds it
 constexpr int kEQ = 2 * (kEP - 1) + 5;         // 97: region two levels below
+// De-interleaved patches: even columns from float 48 of a row on; row strides chosen so that the stage
+// reading the patch sees addresses linear in its thread index (pyr_level_lds): a 47-wide patch is read
+// 22 cells per row (2 * 59 = 22 mod 32), a 97-wide one 47 cells per row by 48 lanes (2 * 104 = 48 mod 32).
+// The 97-wide patch puts its even columns at 48 = 16 (mod 32), so the two halves of a group of 32 lanes
+// that writes a row use disjoint banks; the 47-wide one at 24 (its writes, one per 25 reads, then see
+// two-way conflicts: 48 would need rows of 75 floats and cost the third resident block per compute unit).
+constexpr int kEvenP = 24, kEPS = 59;
+constexpr int kEvenQ = 48, kEQS = 104;
+static_assert(kEvenP + (kEP + 1) / 2 <= kEPS && kEvenQ + (kEQ + 1) / 2 <= kEQS, "a row holds both halves");
+static_assert(kEvenP >= kEP / 2 && kEvenQ >= kEQ / 2, "the odd half fits before the even half");
 
-// one level of the 5x5 binomial pyramid, LDS to LDS.  dst cell i (i < n_dst) stands for the
-// coordinate clamp(o_dst + i) of the upper level and reads src cells 2 * that + {-2..2} - o_src.
-template <int kSrcStride, int kDstStride>
+// LDS patches that feed a pyramid stage keep the odd columns of a row in its first part and the even
+// columns from kEven on (kEven = 0: plain layout): the stage reads columns 2 * cx + {-2..2}, a stride
+// of two over the lanes, which in the plain layout puts two lanes on every bank (measured: bank-conflict
+// cycles were 45 % of the kernel's LDS cycles); de-interleaved, every tap is a unit-stride read.
+template <int kEven>
+__device__ __forceinline__ int lds_col(int c) {
+    return kEven == 0 ? c : (c & 1 ? 0 : kEven) + (c >> 1);
+}
+
+// one level of the 5x5 binomial pyramid, LDS to LDS.  dst cell i (i < kN) stands for the
+// coordinate clamp(o_dst + i) of the upper level and reads src cells 2 * that + {-2..2} - o_src
+// (o_src is even, so the parity of a tap's column is the parity of the tap).  Threads take the cells in
+// row-major order, kLanesPerRow (>= kN) lanes per row; with 2 * kSrcStride = kLanesPerRow (mod 32) the
+// address of a tap is thread index + constant, i.e. free of bank conflicts.
+template <int kSrcStride, int kSrcEven, int kDstStride, int kDstEven, int kN, int kLanesPerRow>
 __device__ __forceinline__ void pyr_level_lds(const float* src, int o_src_y, int o_src_x, float* dst, int o_dst_y,
-                                              int o_dst_x, int n_dst, int dh, int dw) {
+                                              int o_dst_x, int dh, int dw) {
+    static_assert((2 * kSrcStride - kLanesPerRow) % 32 == 0, "tap addresses must be linear in the thread index");
     const float k[5] = {1.0f / 16, 4.0f / 16, 6.0f / 16, 4.0f / 16, 1.0f / 16};
-    for (int p = threadIdx.x; p < n_dst * n_dst; p += 256) {
-        const int ry = p / n_dst, rx = p % n_dst;
+    for (int p = threadIdx.x; p < kN * kLanesPerRow; p += 256) {
+        const int ry = p / kLanesPerRow, rx = p % kLanesPerRow;
+        if (rx >= kN) continue;
         const int cy = clampi(o_dst_y + ry, 0, dh - 1), cx = clampi(o_dst_x + rx, 0, dw - 1);
         const int sy = 2 * cy - o_src_y, sx = 2 * cx - o_src_x;
         float acc = 0.0f;
@@ -180,17 +207,18 @@ __device__ __forceinline__ void pyr_level_lds(const float* src, int o_src_y, int
         for (int a = -2; a <= 2; ++a) {
             float row = 0.0f;
 #pragma unroll
-            for (int b = -2; b <= 2; ++b) row += k[b + 2] * src[(sy + a) * kSrcStride + (sx + b)];
+            for (int b = -2; b <= 2; ++b) row += k[b + 2] * src[(sy + a) * kSrcStride + lds_col<kSrcEven>(sx + b)];
             acc += k[a + 2] * row;
         }
-        dst[ry * kDstStride + rx] = acc;
+        dst[ry * kDstStride + lds_col<kDstEven>(rx)] = acc;
     }
 }
 // Gray patch of kSide x kSide pixels with origin (qy, qx) (coordinates clamped to the image) into LDS
-// as gray / 255, row stride kStride.  All of a thread's loads are issued before the first one is
-// used: written as one loop the compiler waits for every byte in turn, up to 37 dependent round
-// trips, and next to a kernel that saturates the memory system each of them takes microseconds.
-template <int kSide, int kStride>
+// as gray / 255, row stride kStride, columns laid out by lds_col<kEven>.  All of a thread's loads are
+// issued before the first one is used: written as one loop the compiler waits for every byte in turn,
+// up to 37 dependent round trips, and next to a kernel that saturates the memory system each of them
+// takes microseconds.
+template <int kSide, int kStride, int kEven>
 __device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, int h0, int w0, int qy, int qx,
                                                 float* __restrict__ dst) {
     constexpr int kN = (kSide * kSide + 255) / 256;
@@ -206,7 +234,7 @@ __device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, 
 #pragma unroll
     for (int k = 0; k < kN; ++k) {
         const int p = (int)threadIdx.x + 256 * k;
-        if (p < kSide * kSide) dst[(p / kSide) * kStride + (p % kSide)] = (float)v[k] / 255.0f;
+        if (p < kSide * kSide) dst[(p / kSide) * kStride + lds_col<kEven>(p % kSide)] = (float)v[k] / 255.0f;
     }
 }
 
@@ -250,10 +278,15 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     const uint8_t* __restrict__ y8 = f.y8[frame];
     float4* __restrict__ A_out = f.A[frame];
     float* __restrict__ b_out = f.b[frame];
-    __shared__ float s_q[kEQ * (kEQ + 1)];          // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
-    __shared__ float s_p[kEP * (kEP + 1)];          // level-1 patch of a level-2 block
-    __shared__ float s_f[kER][kER + 1];
-    __shared__ float s_v[3][kET][kER + 1];
+    __shared__ float s_q[kEQ * kEQS];               // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
+    __shared__ float s_p[kEP * kEPS];               // level-1 patch of a level-2 block
+    // unpadded rows: both the pass that writes these arrays and the pass that reads them then see
+    // addresses linear in the thread index (the horizontal pass pairs rows eight apart, see below)
+    __shared__ float s_f[kER][kER];
+    // the vertical moments reuse the gray patch's memory: every path has a barrier between its last
+    // read of s_q and the pass that writes them (three blocks of 52 KB fit a compute unit, not of 57)
+    float (*s_v)[kET][kER] = reinterpret_cast<float (*)[kET][kER]>(s_q);
+    static_assert(3 * kET * kER <= kEQ * kEQS, "moments fit into the gray patch");
 
     const int tiles_x = lvl == 0 ? tx0 : (lvl == 1 ? tx1 : tx2);
     const int h = g.h[lvl], w = g.w[lvl];
@@ -263,21 +296,21 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     const int h0 = g.h[0], w0 = g.w[0];
 
     if (lvl == 0) {
-        load_gray_patch<kER, kER + 1>(y8, h, w, oy, ox, &s_f[0][0]);
+        load_gray_patch<kER, kER, 0>(y8, h, w, oy, ox, &s_f[0][0]);
     } else if (lvl == 1) {
         const int qy = 2 * oy - 2, qx = 2 * ox - 2;              // origin of the gray patch (47 x 47)
-        load_gray_patch<kEP, kEP + 1>(y8, h0, w0, qy, qx, s_q);
+        load_gray_patch<kEP, kEPS, kEvenP>(y8, h0, w0, qy, qx, s_q);
         __syncthreads();
-        pyr_level_lds<kEP + 1, kER + 1>(s_q, qy, qx, &s_f[0][0], oy, ox, kER, h, w);
+        pyr_level_lds<kEPS, kEvenP, kER, 0, kER, kER>(s_q, qy, qx, &s_f[0][0], oy, ox, h, w);
     } else {
         const int h1 = g.h[1], w1 = g.w[1];
         const int py = 2 * oy - 2, px = 2 * ox - 2;              // origin of the level-1 patch (47 x 47)
         const int qy = 2 * py - 2, qx = 2 * px - 2;              // origin of the gray patch (97 x 97)
-        load_gray_patch<kEQ, kEQ + 1>(y8, h0, w0, qy, qx, s_q);
+        load_gray_patch<kEQ, kEQS, kEvenQ>(y8, h0, w0, qy, qx, s_q);
         __syncthreads();
-        pyr_level_lds<kEQ + 1, kEP + 1>(s_q, qy, qx, s_p, py, px, kEP, h1, w1);
+        pyr_level_lds<kEQS, kEvenQ, kEPS, kEvenP, kEP, kEP + 1>(s_q, qy, qx, s_p, py, px, h1, w1);
         __syncthreads();
-        pyr_level_lds<kEP + 1, kER + 1>(s_p, py, px, &s_f[0][0], oy, ox, kER, h, w);
+        pyr_level_lds<kEPS, kEvenP, kER, 0, kER, kER>(s_p, py, px, &s_f[0][0], oy, ox, h, w);
     }
     __syncthreads();
 
@@ -298,7 +331,10 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     }
     __syncthreads();
     {
-        const int ty = tid / kET, tx = tid % kET;
+        // a group of 32 lanes takes the rows r and r + 8 (16 lanes each): 8 rows of 22 floats are 176 =
+        // 16 (mod 32) floats apart, so the two rows lie on disjoint banks
+        const int half = tid / kET, tx = tid % kET;
+        const int ty = (half >> 1) + 8 * (half & 1);
         const int gy = y0 + ty, gx = x0 + tx;
         if (gy < h && gx < w) {
             float s0 = 0, sx = 0, sxx = 0, sy = 0, sxy = 0, syy = 0;
@@ -368,7 +404,11 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
     const float2* __restrict__ d_in = f.d_in[blk.z];
     float2* __restrict__ d_out = f.d_out[blk.z];
     constexpr int RX = TX + 2 * kWinR, RY = TY + 2 * kWinR;
-    __shared__ float s_in[5][RY][RX + 1];
+    // row stride of the per-cell terms: a group of 32 lanes of the row pass reads one row of a 32-wide
+    // tile but two rows (16 lanes each) of a 16-wide one, which must not share banks: 16 mod 32
+    // (with RX + 1 = 27 the 16x16 kernel spent 37 % of its LDS cycles on bank conflicts)
+    constexpr int RXS = TX == 16 ? 48 : RX + 1;
+    __shared__ float s_in[5][RY][RXS];
     __shared__ float s_row[5][RY][TX];
     __shared__ float2 s_dp[TY][TX];          // prior of the tile's own pixels, for the solve
 
