@@ -83,8 +83,24 @@ typedef struct sali_config {
     int64_t cap_fp16, cap_int8, cap_int4;    /* pool capacities in tokens (rows per layer/K|V/head),
                                                 each below 2^24                                          */
     int32_t max_frames;              /* frame ids are 0 .. max_frames-1                                */
-    int32_t reserved;
+    int32_t budget_tokens;           /* memory budget in cached patches (Experimental Setup: 784); 0 = none,
+                                        else >= 576.  See "Memory budget" below.                        */
 } sali_config;
+
+/* Memory budget (Experimental Setup: the methods are compared under a strict budget of 784 patches; the
+ * paper states no eviction rule for its own cache, this is the library's).  With budget_tokens > 0 the
+ * cache holds at most that many patches (tokens kept at any precision; pruned tokens and pointer entries
+ * hold nothing).  When a frame is about to be stored, the oldest stored frames are evicted whole, oldest
+ * first, until the new frame's kept tokens fit the budget and its rows fit the pools, which are rings in
+ * this mode: a frame's rows of one pool stay one run [base, base + n), placed at the pool's cursor if the
+ * run ends inside the pool, else at row 0, and never on rows of a frame still held.  An evicted frame and
+ * every pointer entry that referred to it hold no data afterwards: their rows read src = -1, stored = 0,
+ * sali_kv_decompress returns zeros and sets SALI_FAULT_NO_DATA, attention skips them.  A frame that an
+ * empty cache cannot hold (a pool smaller than its rows) is recorded as not stored (SALI_FAULT_OVERFLOW).
+ * Frame ids must increase from call to call (SALI_ERR_STATE otherwise).  Eviction happens when a frame is
+ * analysed (sali_analyze*, sali_step*, sali_kv_compress), so reads of a frame issued after a later
+ * frame's analysis may already find it evicted; within one batch the frames are taken in order, and a
+ * frame evicted by a later frame of its own batch is never written. */
 
 /* Result of the temporal filter for one frame pair (Eq. 6 and the reuse rule). */
 typedef struct sali_gate {

@@ -8,6 +8,18 @@ the previous entry and nothing else happens; otherwise compute the saliency
 map, pool it per patch, assign Q(s_i) and store (K_i, V_i) at that precision.
 Just-In-Time Dequantization: entries are expanded again when read.
 
+Memory budget (Experimental Setup: the methods are compared under a strict budget of 784
+patches; the paper gives no eviction rule for its own method).  Reading taken, `budget_tokens`
+> 0: the cache may hold at most that many patches (tokens kept at any precision; pruned tokens
+and pointer entries hold nothing).  Before a frame is stored, the oldest stored frames are
+evicted whole, oldest first (the order of the sliding-window baseline, at the granularity of a
+cache entry because pointer entries share a stored frame's rows), until the new frame's kept
+tokens fit the budget and its rows fit the pools.  An evicted frame and every pointer entry that
+referred to it hold no data afterwards (src = -1).  The pools are then rings: a frame's rows of a
+pool are one run [base, base + n); the run goes at the pool's cursor if it ends inside the pool,
+else at row 0, and a place is free if it touches no row of a frame still held; the cursor
+follows the newest run.  Frame ids must increase from call to call in this mode.
+
 Storage reading (the paper describes none): three pools indexed
 [layer][K|V][head][slot][...], slots handed out in token order per tier; a
 frame-table row (frame_id, src, stored, base16, base8, base4, n16, n8, n4, np)
@@ -50,6 +62,7 @@ class OracleConfig:
     cap_int8: int = 0
     cap_int4: int = 0
     max_frames: int = 0
+    budget_tokens: int = 0          # 0 = no budget (append only)
 
 
 @dataclasses.dataclass
@@ -70,6 +83,80 @@ class FrameRow:
                 self.n16, self.n8, self.n4, self.npr)
 
 
+class _FrameTable:
+    """Frame-table rows, pool cursors and (with a budget) the set of frames still held.  Shared by the
+    full oracle and the image-only walk so that both hand out the same rows."""
+
+    def __init__(self, cfg: OracleConfig):
+        self.cfg = cfg
+        self.cursor = [0, 0, 0]
+        self.last_src = -1
+        self.rows: Dict[int, FrameRow] = {}
+        self.held = []                  # stored frames still in the cache, oldest first (budget mode)
+        self.overflow = False
+
+    def _place(self, pool, n, cap):
+        """Base of a run of n rows in `pool`, or None if no candidate place is free."""
+        if n == 0:
+            return self.cursor[pool]
+        candidates = ([self.cursor[pool]] if self.cursor[pool] + n <= cap else []) + ([0] if n <= cap else [])
+        for b in candidates:
+            free = True
+            for f in self.held:
+                r = self.rows[f]
+                fb, fn = (r.base16, r.base8, r.base4)[pool], (r.n16, r.n8, r.n4)[pool]
+                if fn > 0 and b < fb + fn and fb < b + n:
+                    free = False
+            if free:
+                return b
+        return None
+
+    def _evict_oldest(self):
+        g = self.held.pop(0)
+        self.rows[g] = FrameRow(g, -1, 0)
+        for f, r in self.rows.items():
+            if r.stored == 0 and r.src == g:
+                self.rows[f] = FrameRow(f, -1, 0)
+
+    def pointer(self, frame_id) -> FrameRow:
+        row = FrameRow(frame_id, self.last_src, 0)
+        self.rows[frame_id] = row
+        return row
+
+    def store(self, frame_id, cnt) -> FrameRow:
+        """Row of a frame with cnt = (n16, n8, n4, n_pruned) tokens per tier; stored = 0 if it cannot be held."""
+        c = self.cfg
+        caps = (c.cap_fp16, c.cap_int8, c.cap_int4)
+        n = [int(cnt[0]), int(cnt[1]), int(cnt[2])]
+        if c.budget_tokens > 0:
+            assert frame_id > max(self.rows, default=-1), "frame ids must increase in budget mode"
+            while True:
+                bases = [self._place(p, n[p], caps[p]) for p in range(3)]
+                held_tokens = sum(self.rows[f].n16 + self.rows[f].n8 + self.rows[f].n4 for f in self.held)
+                if held_tokens + sum(n) <= c.budget_tokens and None not in bases:
+                    break
+                if not self.held:
+                    bases = None
+                    break
+                self._evict_oldest()
+        else:
+            bases = list(self.cursor) if all(self.cursor[p] + n[p] <= caps[p] for p in range(3)) else None
+        if bases is None:
+            self.overflow = True
+            row = FrameRow(frame_id, -1, 0)
+            self.rows[frame_id] = row
+            return row
+        row = FrameRow(frame_id, frame_id, 1, bases[0], bases[1], bases[2], n[0], n[1], n[2], int(cnt[3]))
+        for p in range(3):
+            if n[p] > 0:
+                self.cursor[p] = bases[p] + n[p]
+        self.last_src = frame_id
+        self.rows[frame_id] = row
+        if c.budget_tokens > 0:
+            self.held.append(frame_id)
+        return row
+
+
 def assign_tiers(c: OracleConfig, scores):
     """Eq. 8 (mode 0) or the top-k counts (mode 1) of the configuration."""
     if c.tier_mode == 0:
@@ -88,17 +175,20 @@ class SaliCacheOracle:
         self.codes4 = np.zeros((nl, 2, nh, cfg.cap_int4, d // 2), dtype=np.uint8)
         self.scale4 = np.zeros((nl, 2, nh, cfg.cap_int4, g), dtype=np.float32)
         self.zero4 = np.zeros((nl, 2, nh, cfg.cap_int4, g), dtype=np.float16)
-        self.cursor = [0, 0, 0]
-        self.last_src = -1
-        self.rows: Dict[int, FrameRow] = {}
+        self.table = _FrameTable(cfg)
         self.tier: Dict[int, np.ndarray] = {}
         self.slot: Dict[int, np.ndarray] = {}
         self.prev_gray: Optional[np.ndarray] = None
-        self.overflow = False
         self.nonfinite = False
         self.last_gate = None
         self.last_dp = None
         self.last_scores = None
+
+    # rows, cursors and the overflow flag live in the frame table
+    rows = property(lambda self: self.table.rows)
+    cursor = property(lambda self: self.table.cursor)
+    last_src = property(lambda self: self.table.last_src)
+    overflow = property(lambda self: self.table.overflow)
 
     # ---- the stand-alone calls ------------------------------------------------
     def flow_score(self, prev_rgb, cur_rgb):
@@ -121,14 +211,10 @@ class SaliCacheOracle:
         c = self.cfg
         if oq.has_nonfinite(kv_fp16[:, :, :, tier != oq.T_PRUNE, :]):
             self.nonfinite = True
-        if (self.cursor[0] + cnt[0] > c.cap_fp16 or self.cursor[1] + cnt[1] > c.cap_int8
-                or self.cursor[2] + cnt[2] > c.cap_int4):
-            self.overflow = True
-            row = FrameRow(frame_id, -1, 0)
-            self.rows[frame_id] = row
+        row = self.table.store(frame_id, cnt)
+        if not row.stored:
             return row
-        b16, b8, b4 = self.cursor
-        row = FrameRow(frame_id, frame_id, 1, b16, b8, b4, int(cnt[0]), int(cnt[1]), int(cnt[2]), int(cnt[3]))
+        b16, b8, b4 = row.base16, row.base8, row.base4
         i16 = np.nonzero(tier == oq.T_FP16)[0]
         i8 = np.nonzero(tier == oq.T_INT8)[0]
         i4 = np.nonzero(tier == oq.T_INT4)[0]
@@ -143,9 +229,6 @@ class SaliCacheOracle:
             self.codes4[:, :, :, b4 + slot[i4], :] = oq.pack_nibbles(q)
             self.scale4[:, :, :, b4 + slot[i4], :] = s
             self.zero4[:, :, :, b4 + slot[i4], :] = z
-        self.cursor = [b16 + int(cnt[0]), b8 + int(cnt[1]), b4 + int(cnt[2])]
-        self.last_src = frame_id
-        self.rows[frame_id] = row
         self.tier[frame_id] = tier
         self.slot[frame_id] = slot
         return row
@@ -191,9 +274,7 @@ class SaliCacheOracle:
             redundant = self.last_gate[2]
         self.prev_gray = gray
         if redundant:
-            row = FrameRow(frame_id, self.last_src, 0)
-            self.rows[frame_id] = row
-            return row
+            return self.table.pointer(frame_id)
         scores, _ = self.saliency_pool(rgb)
         self.last_scores = scores
         return self.kv_compress(kv_fp16, scores, frame_id)
@@ -212,11 +293,13 @@ class ImageSideOracle:
 
     def __init__(self, cfg: OracleConfig):
         self.cfg = cfg
-        self.cursor = [0, 0, 0]
-        self.last_src = -1
-        self.rows: Dict[int, FrameRow] = {}
+        self.table = _FrameTable(cfg)
         self.prev_rgb = None
-        self.overflow = False
+
+    rows = property(lambda self: self.table.rows)
+    cursor = property(lambda self: self.table.cursor)
+    last_src = property(lambda self: self.table.last_src)
+    overflow = property(lambda self: self.table.overflow)
 
     def analyze_pair(self, prev_rgb, rgb, tau_t=None, theta_r=None):
         """prev_rgb None = first frame (never redundant).  -> dict(redundant, dp, gate, scores, tier, slot, cnt)."""
@@ -237,22 +320,9 @@ class ImageSideOracle:
         return out
 
     def commit(self, frame_id, a) -> FrameRow:
-        c = self.cfg
         if a["redundant"]:
-            row = FrameRow(frame_id, self.last_src, 0)
-        else:
-            cnt = a["cnt"]
-            if (self.cursor[0] + cnt[0] > c.cap_fp16 or self.cursor[1] + cnt[1] > c.cap_int8
-                    or self.cursor[2] + cnt[2] > c.cap_int4):
-                self.overflow = True
-                row = FrameRow(frame_id, -1, 0)
-            else:
-                b16, b8, b4 = self.cursor
-                row = FrameRow(frame_id, frame_id, 1, b16, b8, b4, int(cnt[0]), int(cnt[1]), int(cnt[2]), int(cnt[3]))
-                self.cursor = [b16 + int(cnt[0]), b8 + int(cnt[1]), b4 + int(cnt[2])]
-                self.last_src = frame_id
-        self.rows[frame_id] = row
-        return row
+            return self.table.pointer(frame_id)
+        return self.table.store(frame_id, a["cnt"])
 
     def step(self, rgb, frame_id, tau_t=None, theta_r=None):
         a = self.analyze_pair(self.prev_rgb, rgb, tau_t, theta_r)

@@ -75,6 +75,8 @@ int check_config(const sali_config* c) {
     // a frame's rows of one plane stay far below 4 GiB: the kernels address inside them with 32 bits
     if (c->cap_fp16 >= (1ll << 24) || c->cap_int8 >= (1ll << 24) || c->cap_int4 >= (1ll << 24)) return SALI_ERR_CONFIG;
     if (c->max_frames < 1 || c->max_frames > (1 << 24)) return SALI_ERR_CONFIG;
+    // a budget holds at least one whole frame, so the newest frame can always stay
+    if (c->budget_tokens != 0 && c->budget_tokens < kTokens) return SALI_ERR_CONFIG;
     // the smallest pyramid level must still be an image
     int h = c->src_h, w = c->src_w;
     for (int l = 1; l < c->flow_levels; ++l) {
@@ -236,6 +238,7 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, Lane
     if (i == 0) {
         Cursors c = {};
         c.last_src = -1;
+        c.ring.oldest = -1;
         *cur = c;
     }
 }
@@ -265,6 +268,7 @@ struct sali_ctx {
     uint8_t* tables;
     Pools pools;
     int n_planes;
+    int last_frame_id;        // highest frame id handed to an analysis or to sali_kv_compress (budget mode: ids increase)
     unsigned n_analysed;      // analyses since create / reset; analysis n uses lane n % kLanes
     unsigned lane_uses[kLanes];   // saliency passes run in each lane; the parity selects the frame-sum accumulator
     AnalysisRecord ring[kRing];
@@ -452,6 +456,7 @@ TierLaunch tier_launch(sali_ctx* c, int frame_id) {
     t.cap16 = c->pools.cap16;
     t.cap8 = c->pools.cap8;
     t.cap4 = c->pools.cap4;
+    t.budget = c->cfg.budget_tokens;
     return t;
 }
 
@@ -577,6 +582,7 @@ int sali_create(const sali_config* cfg, void* d_scratch, void* d_pools, void* d_
     c->n_planes = cfg->n_layers * 2 * cfg->n_heads;
     c->pools.n_planes = c->n_planes;
     c->n_analysed = 0;
+    c->last_frame_id = -1;
     for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
     for (int i = 0; i < 3; ++i) c->prof[i][0] = c->prof[i][1] = nullptr;
     {
@@ -628,6 +634,7 @@ int sali_reset(sali_ctx* c, void* stream) {
                        lanes);
     SALI_TRY(hipGetLastError());
     c->n_analysed = 0;
+    c->last_frame_id = -1;
     for (int l = 0; l < kLanes; ++l) c->lane_uses[l] = 0;
     for (int i = 0; i < kRing; ++i) c->ring[i].frame_id = -1;
     return SALI_OK;
@@ -699,9 +706,11 @@ int sali_kv_compress(sali_ctx* c, const void* d_kv_fp16, const float* d_scores57
     if (c == nullptr || d_kv_fp16 == nullptr || d_scores576 == nullptr) return SALI_ERR_NULL;
     if (frame_id < 0 || frame_id >= c->cfg.max_frames) return SALI_ERR_SHAPE;
     if (!aligned16(d_kv_fp16)) return SALI_ERR_ALIGN;
+    if (c->cfg.budget_tokens > 0 && frame_id <= c->last_frame_id) return SALI_ERR_STATE;
+    if (frame_id > c->last_frame_id) c->last_frame_id = frame_id;
     hipStream_t s = static_cast<hipStream_t>(stream);
     SALI_TRY(launch_tier(d_scores576, nullptr, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
-                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, s));
+                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, c->cfg.budget_tokens, s));
     return enqueue_pack(c, &d_kv_fp16, frame_id, 1, s);
 }
 
@@ -782,6 +791,8 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
     if (first_frame_id < 0 || (long long)first_frame_id + n_frames > c->cfg.max_frames) return SALI_ERR_SHAPE;
     for (int i = 0; i < n_frames; ++i)
         if (d_rgb_frames[i] == nullptr) return SALI_ERR_NULL;
+    if (c->cfg.budget_tokens > 0 && first_frame_id <= c->last_frame_id) return SALI_ERR_STATE;
+    if (first_frame_id + n_frames - 1 > c->last_frame_id) c->last_frame_id = first_frame_id + n_frames - 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned n0 = c->n_analysed;                  // analysis number of the batch's first frame
     const unsigned n_last = n0 + (unsigned)n_frames - 1u;

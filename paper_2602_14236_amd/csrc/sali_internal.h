@@ -35,11 +35,23 @@ constexpr float kLamRel = 1e-2f;
 constexpr uint32_t kVMin = 10000u;          // floor of the colour-variance mask
 
 // Device-resident bookkeeping (lives in the caller's table buffer).
+// Memory-budget mode: the frames still held form a queue (oldest first) and each pool is a ring.
+// The rows of the held frames of a pool are the cyclic window tail .. head (head = the pool's cursor);
+// `wrapped` says that the window passes the end of the pool, in which case the rows before the wrap
+// end at `end` (the cursor's value when a frame did not fit behind it and went to row 0).
+struct RingState {
+    int32_t oldest;             // oldest stored frame still held, -1 = none
+    int32_t live_tokens;        // kept tokens of the held frames
+    int32_t tail[3], end[3], live_rows[3], wrapped[3];
+};
+
 struct Cursors {
     int32_t c16, c8, c4;        // next free row of each pool
     int32_t last_src;           // frame id of the last stored frame, -1 = none
     uint32_t status;            // sticky SALI_FAULT_* bits
     uint32_t pad[3];
+    RingState ring;             // used with a memory budget only
+    uint32_t pad2[2];
 };
 
 // The six pool arrays.  Layout of each: frame-major.  A stored frame with first row `base` and
@@ -81,6 +93,7 @@ struct TierLaunch {
     uint16_t* order;
     Cursors* cur;
     int32_t cap16, cap8, cap4;
+    int32_t budget;             // most tokens the cache may hold, 0 = no budget
 };
 
 struct LevelGeom {
@@ -186,7 +199,7 @@ __device__ __forceinline__ BlockId xcd_block_id() {
 // kv_kernels.hip
 hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,
                        sali_frame_row* d_rows, uint8_t* d_tier, uint16_t* d_slot, uint16_t* d_order,
-                       Cursors* d_cur, Pools pools, hipStream_t s);
+                       Cursors* d_cur, Pools pools, int budget, hipStream_t s);
 // frame i of a batched launch has id first_frame_id + i; f.kv[i] is its dense fp16 K/V (source of
 // the pack, destination of the unpack)
 hipError_t launch_pack(const KvBatch& f, int n, const sali_frame_row* d_rows, int first_frame_id,

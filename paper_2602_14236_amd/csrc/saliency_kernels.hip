@@ -392,7 +392,7 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
             CursorRegs cr = cursor_load(tl.cur);
 #pragma unroll
             for (int i = 0; i < kMaxBatch; ++i)
-                if (i < n_frames) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4);
+                if (i < n_frames) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget);
             cursor_store(tl.cur, cr);
         }
     }

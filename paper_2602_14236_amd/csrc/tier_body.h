@@ -209,10 +209,98 @@ struct CursorRegs {
     uint32_t faults;
 };
 
+// ---- memory budget (Experimental Setup: a strict budget of 784 patches; the eviction rule is this
+// library's reading: whole frames leave oldest first until the new frame's kept tokens fit the budget
+// and its rows fit the ring-shaped pools) -----------------------------------------------------------
+// First row of a run of n rows in a ring pool, -1 if neither candidate place (the cursor, then row 0)
+// is free.  The rows of held frames are the window tail .. head, so the test needs no look at the frames.
+__device__ __forceinline__ int ring_place(int head, int n, int cap, int tail, int live_rows, int wrapped) {
+    if (n == 0) return head;
+    if (live_rows == 0) return head + n <= cap ? head : (n <= cap ? 0 : -1);
+    if (!wrapped) return head + n <= cap ? head : (n <= tail ? 0 : -1);
+    return head + n <= tail ? head : -1;
+}
+
+// Budget mode, ONE thread: evicts until the frame fits, then places it.  Returns false if the frame
+// cannot be held even by an empty cache.  The ring state is read from and written back to *cur.
+__device__ __noinline__ bool tier_place_with_budget(const TierCounts& tc, int frame_id, sali_frame_row* rows,
+                                                    CursorRegs& cr, Cursors* cur, int cap16, int cap8, int cap4,
+                                                    int budget, int* base_out) {
+    RingState rs = cur->ring;
+    int head[3] = {cr.c16, cr.c8, cr.c4};
+    const int cap[3] = {cap16, cap8, cap4};
+    const int n[3] = {tc.cnt[0], tc.cnt[1], tc.cnt[2]};
+    const int need = n[0] + n[1] + n[2];
+    bool ok;
+    for (;;) {
+        ok = rs.live_tokens + need <= budget;
+        for (int p = 0; p < 3; ++p) {
+            base_out[p] = ring_place(head[p], n[p], cap[p], rs.tail[p], rs.live_rows[p], rs.wrapped[p]);
+            ok = ok && base_out[p] >= 0;
+        }
+        if (ok || rs.oldest < 0) break;
+        // the oldest held frame leaves
+        const int g = rs.oldest;
+        const sali_frame_row rg = rows[g];
+        const int gb[3] = {rg.base16, rg.base8, rg.base4}, gn[3] = {rg.n16, rg.n8, rg.n4};
+        rs.live_tokens -= gn[0] + gn[1] + gn[2];
+        for (int p = 0; p < 3; ++p) {
+            if (gn[p] == 0) continue;
+            rs.live_rows[p] -= gn[p];
+            if (rs.live_rows[p] == 0) {
+                rs.wrapped[p] = 0;
+            } else {
+                rs.tail[p] = gb[p] + gn[p];
+                if (rs.wrapped[p] && rs.tail[p] == rs.end[p]) {      // the rows before the wrap are all gone
+                    rs.tail[p] = 0;
+                    rs.wrapped[p] = 0;
+                }
+            }
+        }
+        sali_frame_row dead = {};
+        dead.frame_id = g;
+        dead.src = -1;
+        rows[g] = dead;
+        // pointer entries behind it hold no data any more; the next stored frame becomes the oldest
+        rs.oldest = -1;
+        for (int f = g + 1; f < frame_id; ++f) {
+            const sali_frame_row r = rows[f];
+            if (r.frame_id != f) continue;              // a row that was never written
+            if (r.stored) {
+                rs.oldest = f;
+                break;
+            }
+            if (r.src == g) rows[f].src = -1;
+        }
+    }
+    if (ok) {
+        for (int p = 0; p < 3; ++p) {
+            if (n[p] == 0) continue;
+            if (rs.live_rows[p] == 0) {
+                rs.tail[p] = base_out[p];
+                rs.wrapped[p] = 0;
+            } else if (!rs.wrapped[p] && base_out[p] == 0) {         // did not fit behind the cursor: wrap
+                rs.end[p] = head[p];
+                rs.wrapped[p] = 1;
+            }
+            head[p] = base_out[p] + n[p];
+            rs.live_rows[p] += n[p];
+        }
+        rs.live_tokens += need;
+        if (rs.oldest < 0) rs.oldest = frame_id;
+        cr.c16 = head[0];
+        cr.c8 = head[1];
+        cr.c4 = head[2];
+    }
+    cur->ring = rs;
+    return ok;
+}
+
 // Frame-table row of one frame from its counts and the running cursors; ONE thread, frames in
 // video order.
 __device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_id, sali_frame_row* rows,
-                                                CursorRegs& cr, int cap16, int cap8, int cap4) {
+                                                CursorRegs& cr, int cap16, int cap8, int cap4, Cursors* cur = nullptr,
+                                                int budget = 0) {
     sali_frame_row r = {};
     r.frame_id = frame_id;
     if (tc.state == 1) {
@@ -222,6 +310,23 @@ __device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_
     } else if (tc.state == 2) {
         cr.faults |= SALI_FAULT_NAN_SCORE;
         r.src = -1;
+    } else if (budget > 0) {
+        int base[3];
+        if (tier_place_with_budget(tc, frame_id, rows, cr, cur, cap16, cap8, cap4, budget, base)) {
+            r.src = frame_id;
+            r.stored = 1;
+            r.base16 = base[0];
+            r.base8 = base[1];
+            r.base4 = base[2];
+            r.n16 = tc.cnt[0];
+            r.n8 = tc.cnt[1];
+            r.n4 = tc.cnt[2];
+            r.n_pruned = tc.cnt[3];
+            cr.last_src = frame_id;
+        } else {
+            cr.faults |= SALI_FAULT_OVERFLOW;
+            r.src = -1;
+        }
     } else if ((long long)cr.c16 + tc.cnt[0] > cap16 || (long long)cr.c8 + tc.cnt[1] > cap8 ||
                (long long)cr.c4 + tc.cnt[2] > cap4) {
         cr.faults |= SALI_FAULT_OVERFLOW;
@@ -263,9 +368,9 @@ __device__ __forceinline__ void cursor_store(Cursors* cur, const CursorRegs& cr)
 }
 
 __device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, sali_frame_row* rows, Cursors* cur,
-                                            int cap16, int cap8, int cap4) {
+                                            int cap16, int cap8, int cap4, int budget) {
     CursorRegs cr = cursor_load(cur);
-    tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4);
+    tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4, cur, budget);
     cursor_store(cur, cr);
 }
 
@@ -273,11 +378,11 @@ __device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, 
 __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, bool redundant, const TierParams& tp,
                                           int frame_id, sali_frame_row* rows, uint8_t* __restrict__ tier_out,
                                           uint16_t* __restrict__ slot_out, uint16_t* __restrict__ order_out,
-                                          Cursors* cur, int cap16, int cap8, int cap4) {
+                                          Cursors* cur, int cap16, int cap8, int cap4, int budget) {
     TierCounts tc = {};
     tc.state = 1;
     if (!redundant) tc = tier_rank(sh, tier_load_scores(scores), tp, tier_out, slot_out, order_out);
-    if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4);
+    if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4, budget);
 }
 
 }  // namespace sali
