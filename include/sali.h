@@ -85,6 +85,9 @@ typedef struct sali_config {
     int32_t max_frames;              /* frame ids are 0 .. max_frames-1                                */
     int32_t budget_tokens;           /* memory budget in cached patches (Experimental Setup: 784); 0 = none,
                                         else >= 576.  See "Memory budget" below.                        */
+    int32_t tiles_per_frame;         /* images of 576 patches that make up one video frame, 1..8; 0 reads as 1.
+                                        See "Dynamic-resolution frames" below.                          */
+    int32_t reserved;
 } sali_config;
 
 /* Memory budget (Experimental Setup: the methods are compared under a strict budget of 784 patches; the
@@ -101,6 +104,21 @@ typedef struct sali_config {
  * analysed (sali_analyze*, sali_step*, sali_kv_compress), so reads of a frame issued after a later
  * frame's analysis may already find it evicted; within one batch the frames are taken in order, and a
  * frame evicted by a later frame of its own batch is never written. */
+
+/* Dynamic-resolution frames (Background, Adapter Projection: the vision encoder of the model the paper
+ * uses cuts a high-resolution frame into several images of 576 patches each, so a frame has a multiple of
+ * 576 visual tokens).  With tiles_per_frame = T > 1 a video frame is T images ("tiles") of src_h x src_w
+ * pixels; its N_p = 576 T patches are the patches of all of them.  Every tile is a cache entry of its own:
+ * entry id e = t T + j for tile j of frame t, and wherever this header says "frame id", "frame-table row"
+ * or "frames" of a batch, entries are meant (max_frames counts entries; the K/V of an entry is
+ * [n_layers][2][n_heads][576][head_dim]).  The analysis calls take whole video frames: first id and count
+ * multiples of T (SALI_ERR_SHAPE otherwise; so sali_step / sali_analyze need T = 1, tiled frames go through
+ * the batched calls, up to SALI_MAX_BATCH / T frames per call).  The flow of a tile is taken against the
+ * same tile of the adjacent frame; Eq. 6 counts the static patches of all T tiles, and the reuse rule takes
+ * one decision for the frame (sali_gate then holds the frame's n_static out of 576 T in every entry); the
+ * entries of a redundant frame point at the last stored entry of their own tile; otherwise each tile gets
+ * its saliency scores and tiers (Eq. 8 per patch; the top-k counts apply per tile) and is stored.
+ * Not combined with a memory budget (SALI_ERR_CONFIG). */
 
 /* Result of the temporal filter for one frame pair (Eq. 6 and the reuse rule). */
 typedef struct sali_gate {

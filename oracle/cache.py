@@ -20,6 +20,15 @@ pool are one run [base, base + n); the run goes at the pool's cursor if it ends 
 else at row 0, and a place is free if it touches no row of a frame still held; the cursor
 follows the newest run.  Frame ids must increase from call to call in this mode.
 
+Dynamic-resolution encoding (Background, Adapter Projection: the vision encoder of the model the
+paper uses cuts a high-resolution frame into several images of 576 patches each).  Reading taken,
+`tiles_per_frame` = T > 1: a video frame is T images ("tiles"), its N_p = 576 T patches are the
+patches of all of them; cache entry e = t T + j holds tile j of frame t.  The flow is taken per
+tile against the same tile of the adjacent frame; Eq. 6 counts the static patches of all tiles
+and the reuse rule takes ONE decision for the frame; a redundant frame's entries point at the last
+stored entry of their own tile; otherwise every tile gets its saliency scores and its tiers
+(Eq. 8 per patch; top-k counts per tile) and is stored as an entry of its own.
+
 Storage reading (the paper describes none): three pools indexed
 [layer][K|V][head][slot][...], slots handed out in token order per tier; a
 frame-table row (frame_id, src, stored, base16, base8, base4, n16, n8, n4, np)
@@ -63,6 +72,7 @@ class OracleConfig:
     cap_int4: int = 0
     max_frames: int = 0
     budget_tokens: int = 0          # 0 = no budget (append only)
+    tiles_per_frame: int = 1        # images (of grid x grid patches each) that make up one video frame
 
 
 @dataclasses.dataclass
@@ -94,6 +104,8 @@ class _FrameTable:
         self.rows: Dict[int, FrameRow] = {}
         self.held = []                  # stored frames still in the cache, oldest first (budget mode)
         self.overflow = False
+        self.last_src_tile = {}         # tile index -> last stored entry of that tile (tiles_per_frame > 1)
+        assert cfg.tiles_per_frame == 1 or cfg.budget_tokens == 0, "a budget evicts entries, not tiled frames"
 
     def _place(self, pool, n, cap):
         """Base of a run of n rows in `pool`, or None if no candidate place is free."""
@@ -119,7 +131,8 @@ class _FrameTable:
                 self.rows[f] = FrameRow(f, -1, 0)
 
     def pointer(self, frame_id) -> FrameRow:
-        row = FrameRow(frame_id, self.last_src, 0)
+        T = self.cfg.tiles_per_frame
+        row = FrameRow(frame_id, self.last_src if T == 1 else self.last_src_tile.get(frame_id % T, -1), 0)
         self.rows[frame_id] = row
         return row
 
@@ -151,6 +164,7 @@ class _FrameTable:
             if n[p] > 0:
                 self.cursor[p] = bases[p] + n[p]
         self.last_src = frame_id
+        self.last_src_tile[frame_id % c.tiles_per_frame] = frame_id
         self.rows[frame_id] = row
         if c.budget_tokens > 0:
             self.held.append(frame_id)
@@ -179,6 +193,7 @@ class SaliCacheOracle:
         self.tier: Dict[int, np.ndarray] = {}
         self.slot: Dict[int, np.ndarray] = {}
         self.prev_gray: Optional[np.ndarray] = None
+        self.prev_tile_grays = None
         self.nonfinite = False
         self.last_gate = None
         self.last_dp = None
@@ -278,6 +293,35 @@ class SaliCacheOracle:
         scores, _ = self.saliency_pool(rgb)
         self.last_scores = scores
         return self.kv_compress(kv_fp16, scores, frame_id)
+
+
+def step_tiles(orc: SaliCacheOracle, rgbs, kvs, frame_t):
+    """Algorithm 1 for a video frame of T = tiles_per_frame images: one gate over the patches of all
+    tiles, then per tile either a pointer entry or saliency -> tiers -> storage.  Entry ids t T + j.
+    -> (rows of the T entries, gate or None)."""
+    c = orc.cfg
+    T = c.tiles_per_frame
+    assert len(rgbs) == T and len(kvs) == T
+    grays = [oflow.gray_float(r) for r in rgbs]
+    redundant, gate = False, None
+    orc.last_dp = None
+    if orc.prev_tile_grays is not None:
+        dps = [oflow.patch_motion(oflow.flow_from_gray(pg, g, c.flow_levels, c.flow_iters), c.grid)
+               for pg, g in zip(orc.prev_tile_grays, grays)]
+        orc.last_dp = dps
+        gate = oflow.gate(np.concatenate(dps), c.tau_t, c.theta_r)          # Eq. 6 over all T * 576 patches
+        redundant = gate[2]
+    orc.prev_tile_grays = grays
+    orc.last_gate = gate
+    rows = []
+    for j in range(T):
+        e = frame_t * T + j
+        if redundant:
+            rows.append(orc.table.pointer(e))
+        else:
+            scores, _ = orc.saliency_pool(rgbs[j])
+            rows.append(orc.kv_compress(kvs[j], scores, e))
+    return rows, gate
 
 
 class ImageSideOracle:

@@ -77,6 +77,9 @@ int check_config(const sali_config* c) {
     if (c->max_frames < 1 || c->max_frames > (1 << 24)) return SALI_ERR_CONFIG;
     // a budget holds at least one whole frame, so the newest frame can always stay
     if (c->budget_tokens != 0 && c->budget_tokens < kTokens) return SALI_ERR_CONFIG;
+    if (c->tiles_per_frame < 0 || c->tiles_per_frame > kMaxTiles) return SALI_ERR_CONFIG;
+    // eviction works on cache entries, a tiled frame is several: the two are not combined
+    if (c->budget_tokens != 0 && c->tiles_per_frame > 1) return SALI_ERR_CONFIG;
     // the smallest pyramid level must still be an image
     int h = c->src_h, w = c->src_w;
     for (int l = 1; l < c->flow_levels; ++l) {
@@ -239,6 +242,7 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, Lane
         Cursors c = {};
         c.last_src = -1;
         c.ring.oldest = -1;
+        for (int j = 0; j < kMaxBatch; ++j) c.last_src_tile[j] = -1;
         *cur = c;
     }
 }
@@ -457,6 +461,7 @@ TierLaunch tier_launch(sali_ctx* c, int frame_id) {
     t.cap8 = c->pools.cap8;
     t.cap4 = c->pools.cap4;
     t.budget = c->cfg.budget_tokens;
+    t.tiles = c->cfg.tiles_per_frame > 1 ? c->cfg.tiles_per_frame : 1;
     return t;
 }
 
@@ -710,7 +715,8 @@ int sali_kv_compress(sali_ctx* c, const void* d_kv_fp16, const float* d_scores57
     if (frame_id > c->last_frame_id) c->last_frame_id = frame_id;
     hipStream_t s = static_cast<hipStream_t>(stream);
     SALI_TRY(launch_tier(d_scores576, nullptr, tier_params(c->cfg), frame_id, c->rows(), c->tier(frame_id),
-                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, c->cfg.budget_tokens, s));
+                         c->slot(frame_id), c->order(frame_id), c->cursors(), c->pools, c->cfg.budget_tokens,
+                         c->cfg.tiles_per_frame > 1 ? c->cfg.tiles_per_frame : 1, s));
     return enqueue_pack(c, &d_kv_fp16, frame_id, 1, s);
 }
 
@@ -792,6 +798,10 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
     for (int i = 0; i < n_frames; ++i)
         if (d_rgb_frames[i] == nullptr) return SALI_ERR_NULL;
     if (c->cfg.budget_tokens > 0 && first_frame_id <= c->last_frame_id) return SALI_ERR_STATE;
+    // tiled frames come whole: entries t T .. t T + T - 1 in one call, and analysis number = entry number
+    // modulo T, so that an entry's predecessor (the same tile of the frame before) is T analyses back
+    const int tiles = c->cfg.tiles_per_frame > 1 ? c->cfg.tiles_per_frame : 1;
+    if (first_frame_id % tiles != 0 || n_frames % tiles != 0) return SALI_ERR_SHAPE;
     if (first_frame_id + n_frames - 1 > c->last_frame_id) c->last_frame_id = first_frame_id + n_frames - 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned n0 = c->n_analysed;                  // analysis number of the batch's first frame
@@ -802,7 +812,7 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
         const unsigned n = n0 + (unsigned)i;
         bp.lane[i] = (int)(n % kLanes);
         bp.slot[i] = (int)(n % kStepSlots);
-        bp.prev_slot[i] = n >= 1 ? (int)((n - 1) % kStepSlots) : -1;
+        bp.prev_slot[i] = n >= (unsigned)tiles ? (int)((n - (unsigned)tiles) % kStepSlots) : -1;
         bp.parity[i] = c->lane_uses[bp.lane[i]]++ & 1u;      // alternates per saliency pass in the lane
     }
     const AnalysisRecord* prev = n0 >= 1 ? &c->ring[c->ring[(n0 - 1) % kRing].batch_last] : nullptr;

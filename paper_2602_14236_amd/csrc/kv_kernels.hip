@@ -100,10 +100,11 @@ __global__ __launch_bounds__(kTierThreads) void k_tier(const float* __restrict__
                                                   TierParams tp, int frame_id, sali_frame_row* rows,
                                                   uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
                                                   uint16_t* __restrict__ order_out, Cursors* cur, int cap16,
-                                                  int cap8, int cap4, int budget) {
+                                                  int cap8, int cap4, int budget, int tiles) {
     __shared__ TierShared sh;
     const bool redundant = gate != nullptr && gate->redundant != 0;
-    tier_body(sh, scores, redundant, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4, budget);
+    tier_body(sh, scores, redundant, tp, frame_id, rows, tier_out, slot_out, order_out, cur, cap16, cap8, cap4, budget,
+              tiles);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -402,9 +403,9 @@ __global__ __launch_bounds__(256) void k_unpack(const sali_frame_row* __restrict
 // ---------------------------------------------------------------------------------------------
 hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,
                        sali_frame_row* d_rows, uint8_t* d_tier, uint16_t* d_slot, uint16_t* d_order,
-                       Cursors* d_cur, Pools pools, int budget, hipStream_t s) {
+                       Cursors* d_cur, Pools pools, int budget, int tiles, hipStream_t s) {
     hipLaunchKernelGGL(k_tier, dim3(1), dim3(kTierThreads), 0, s, d_scores, d_gate_or_null, tp, frame_id, d_rows,
-                       d_tier, d_slot, d_order, d_cur, pools.cap16, pools.cap8, pools.cap4, budget);
+                       d_tier, d_slot, d_order, d_cur, pools.cap16, pools.cap8, pools.cap4, budget, tiles);
     return hipGetLastError();
 }
 

@@ -22,6 +22,7 @@ constexpr int kAttnMaxQPerKv = 8;           // query heads that may share one K/
 constexpr int kAttnSlotsPerHead = 4096;     // partial-result slots of the scratch per K/V head (shared out over its queries)
 constexpr int kAttnPartialStride = 160;     // floats per partial: max, sum, 128 values; 640 B = five whole 128-byte lines
 constexpr int kMaxBatch = SALI_MAX_BATCH;   // frames analysed by one set of launches (blockIdx.z / .y)
+constexpr int kMaxTiles = SALI_MAX_BATCH;   // images per video frame (a frame's tiles are analysed in one batch)
 
 // flow constants (polynomial expansion 7x7 sigma 1.5; aggregation window 11x11 sigma 2.5;
 // prior-centred ridge term lambda = kLamAbs + kLamRel * trace(G) / 2)
@@ -51,6 +52,7 @@ struct Cursors {
     uint32_t status;            // sticky SALI_FAULT_* bits
     uint32_t pad[3];
     RingState ring;             // used with a memory budget only
+    int32_t last_src_tile[kMaxBatch];   // tiled frames: last stored entry of each tile, -1 = none
     uint32_t pad2[2];
 };
 
@@ -94,6 +96,7 @@ struct TierLaunch {
     Cursors* cur;
     int32_t cap16, cap8, cap4;
     int32_t budget;             // most tokens the cache may hold, 0 = no budget
+    int32_t tiles;              // images per video frame (entries per frame), >= 1
 };
 
 struct LevelGeom {
@@ -199,7 +202,7 @@ __device__ __forceinline__ BlockId xcd_block_id() {
 // kv_kernels.hip
 hipError_t launch_tier(const float* d_scores, const sali_gate* d_gate_or_null, TierParams tp, int frame_id,
                        sali_frame_row* d_rows, uint8_t* d_tier, uint16_t* d_slot, uint16_t* d_order,
-                       Cursors* d_cur, Pools pools, int budget, hipStream_t s);
+                       Cursors* d_cur, Pools pools, int budget, int tiles, hipStream_t s);
 // frame i of a batched launch has id first_frame_id + i; f.kv[i] is its dense fp16 K/V (source of
 // the pack, destination of the unpack)
 hipError_t launch_pack(const KvBatch& f, int n, const sali_frame_row* d_rows, int first_frame_id,

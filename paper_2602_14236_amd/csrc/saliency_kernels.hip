@@ -341,18 +341,23 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     // the scores are asked for now, with the patch motions: one memory round trip instead of two on the
     // critical path of the batch (a redundant frame does not use them)
     const TierScores scores = tier_load_scores(f.scores[b]);
+    // a tiled frame's patches are those of all its tiles (entries b0 .. b0 + tiles - 1 of the launch): the
+    // block of every tile counts them all and so reaches the frame's one decision on its own
+    const int tiles = tl.tiles;
+    const int b0 = b - b % tiles;
     int n = 0;
     if (have_flow) {
-        for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
-            const float v = __hip_atomic_load(f.dp[b] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            n += (v < tau_t) ? 1 : 0;
-        }
+        for (int j = 0; j < tiles; ++j)
+            for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
+                const float v = __hip_atomic_load(f.dp[b0 + j] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                n += (v < tau_t) ? 1 : 0;
+            }
     }
     for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
     if (lane == 0) s_cnt[wave] = n;
     __syncthreads();
     const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-    const float r = (float)n_static / (float)kTokens;
+    const float r = (float)n_static / (float)(kTokens * tiles);
     const bool redundant = have_flow && r > theta_r;
     TierCounts tc = {};
     tc.state = 1;
@@ -392,7 +397,7 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
             CursorRegs cr = cursor_load(tl.cur);
 #pragma unroll
             for (int i = 0; i < kMaxBatch; ++i)
-                if (i < n_frames) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget);
+                if (i < n_frames) tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget, tl.tiles);
             cursor_store(tl.cur, cr);
         }
     }

@@ -300,12 +300,13 @@ __device__ __noinline__ bool tier_place_with_budget(const TierCounts& tc, int fr
 // video order.
 __device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_id, sali_frame_row* rows,
                                                 CursorRegs& cr, int cap16, int cap8, int cap4, Cursors* cur = nullptr,
-                                                int budget = 0) {
+                                                int budget = 0, int tiles = 1) {
     sali_frame_row r = {};
     r.frame_id = frame_id;
     if (tc.state == 1) {
-        // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame.
-        r.src = cr.last_src;
+        // Algorithm 1: C[t] <- Pointer(C[t-1]); chains resolve to the last stored frame (of a tiled
+        // frame: to the last stored entry of the same tile).
+        r.src = tiles > 1 ? cur->last_src_tile[frame_id % tiles] : cr.last_src;
         r.stored = 0;
     } else if (tc.state == 2) {
         cr.faults |= SALI_FAULT_NAN_SCORE;
@@ -346,6 +347,7 @@ __device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_
         cr.c4 += tc.cnt[2];
         cr.last_src = frame_id;
     }
+    if (tiles > 1 && r.stored) cur->last_src_tile[frame_id % tiles] = frame_id;
     rows[frame_id] = r;
 }
 
@@ -368,9 +370,9 @@ __device__ __forceinline__ void cursor_store(Cursors* cur, const CursorRegs& cr)
 }
 
 __device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, sali_frame_row* rows, Cursors* cur,
-                                            int cap16, int cap8, int cap4, int budget) {
+                                            int cap16, int cap8, int cap4, int budget, int tiles) {
     CursorRegs cr = cursor_load(cur);
-    tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4, cur, budget);
+    tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4, cur, budget, tiles);
     cursor_store(cur, cr);
 }
 
@@ -378,11 +380,11 @@ __device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, 
 __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, bool redundant, const TierParams& tp,
                                           int frame_id, sali_frame_row* rows, uint8_t* __restrict__ tier_out,
                                           uint16_t* __restrict__ slot_out, uint16_t* __restrict__ order_out,
-                                          Cursors* cur, int cap16, int cap8, int cap4, int budget) {
+                                          Cursors* cur, int cap16, int cap8, int cap4, int budget, int tiles) {
     TierCounts tc = {};
     tc.state = 1;
     if (!redundant) tc = tier_rank(sh, tier_load_scores(scores), tp, tier_out, slot_out, order_out);
-    if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4, budget);
+    if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4, budget, tiles);
 }
 
 }  // namespace sali

@@ -53,5 +53,5 @@ def test_struct_sizes_match_header():
     from paper_2602_14236_amd import binding
     assert ctypes.sizeof(binding.sali_frame_row) == 48
     assert ctypes.sizeof(binding.sali_gate) == 16
-    assert ctypes.sizeof(binding.sali_config) == 112
+    assert ctypes.sizeof(binding.sali_config) == 120
     assert ctypes.sizeof(binding.sali_pool_layout) == 56
