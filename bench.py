@@ -155,8 +155,8 @@ class Runner:
         self.rgbs = [torch.from_numpy(video.frame(t)).to(dev) for t in range(n_src)]
         self.kvs = [synth.kv_frame(wl, t, device=dev, n_layers=self.n_layers, scale=scale) for t in range(n_src)]
         # frames per launch: 4 where the K/V side bounds the path (a batch of 8 costs more pipeline fill
-        # than it saves in a 64-step run), 8 where the image side does (workloads 1 and 3)
-        self.batch = batch if batch is not None else int(os.environ.get("SALI_BENCH_BATCH", "8" if config in (1, 3) else "4"))
+        # than it saves in a 64-step run), 8 where the image side does (workloads 1, 3 and 5)
+        self.batch = batch if batch is not None else int(os.environ.get("SALI_BENCH_BATCH", "8" if config in (1, 3, 5) else "4"))
         self.outs = [torch.empty((self.n_layers, 2, wl.n_heads, 576, 128), dtype=torch.float16, device=dev)
                      for _ in range(max(1, self.batch))]
         self.lookahead = int(os.environ.get("SALI_BENCH_LOOKAHEAD", "2"))
@@ -397,8 +397,8 @@ def recorded_traffic(wl_name):
     return None, None
 
 
-# short runs of the other workloads: (steps, what the run covers)
-OTHER_CONFIGS = {1: 8, 3: 64, 4: 24, 5: 32}
+# runs of the other workloads: leading frames (workload 1 and 5: all of them)
+OTHER_CONFIGS = {1: 8, 3: 128, 4: 32, 5: 128}
 
 
 def main():
@@ -513,7 +513,7 @@ def main():
                     "fps", "ms_per_step", "step_with_readback_hbm_frac", "sali_step_only", "k_pack", "k_unpack")
             others[f"cfg{cid}"] = {k: o[k] for k in keep}
         result["configs"] = others
-        result["configs_note"] = ("short runs (leading frames of each workload, same calls, same timing protocol); "
+        result["configs_note"] = ("the leading frames of each workload (1 and 5: the whole workload), same calls, same timing protocol; "
                                   "workloads 1 and 3 move a few MB per step and are bound by the latency of the image "
                                   "side's launch chain, not by HBM")
     if not args.no_cpu:

@@ -315,6 +315,17 @@ struct BatchPlan {
     unsigned parity[kMaxBatch];     // which frame-sum accumulator of the lane this pass uses
 };
 
+// Pyramid and polynomial expansion in one launch (k_expand: every tile rebuilds the pyramid values it
+// needs from the gray image in LDS) or level by level (k_pyr_down per level, then k_polyexp).  The fused
+// launch saves two dependent launches and hosts the hysteresis strips, but does several times the work per
+// pixel (a 16x16 tile of level 2 reads a 97x97 gray patch), so it is the choice only while the launch
+// chain, not the work, bounds a batch: up to three levels and small frames.  Measured in the pipeline,
+// eight frames per launch: 336x336 the same either way (a single frame per launch: fused 7 % faster),
+// 640x360 level by level 25 100 -> 27 500 frames/s.
+bool fused_expansion(const sali_ctx* c, int /*n_frames*/) {
+    return c->geom.levels <= 3 && (long long)c->cfg.src_h * c->cfg.src_w < 160000;
+}
+
 // gray (+ saliency pre-pass) of the batch's frames; the other frame-sum accumulator of each lane is
 // cleared for the lane's next use
 int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool with_saliency,
@@ -336,7 +347,7 @@ int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, 
                          cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
     // cross-tile hysteresis after a kernel boundary (the cheapest device-wide ordering there is): a
     // launch of its own, unless the expansion launch that follows will carry it
-    if (with_saliency && !(union_with_expansion && c->geom.levels <= 3))
+    if (with_saliency && !(union_with_expansion && fused_expansion(c, bp.n)))
         SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
     return SALI_OK;
 }
@@ -345,7 +356,7 @@ int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, 
 // the frames' saliency pre-pass has run and its cross-tile hysteresis pass is still due
 int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, bool with_union, hipStream_t s) {
     const LevelGeom& g = c->geom;
-    if (g.levels <= 3) {
+    if (fused_expansion(c, bp.n)) {
         ExpandBatch f = {};
         for (int i = 0; i < bp.n; ++i) {
             const LaneLayout& L = c->sl.lane[bp.lane[i]];
