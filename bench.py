@@ -397,8 +397,8 @@ def recorded_traffic(wl_name):
     return None, None
 
 
-# runs of the other workloads: leading frames (workload 1 and 5: all of them)
-OTHER_CONFIGS = {1: 8, 3: 128, 4: 32, 5: 128}
+# runs of the other workloads: leading frames (workload 5: all of them; workload 1: its 8 frames cycled 8 times)
+OTHER_CONFIGS = {1: 64, 3: 128, 4: 32, 5: 128}
 
 
 def main():
@@ -513,7 +513,7 @@ def main():
                     "fps", "ms_per_step", "step_with_readback_hbm_frac", "sali_step_only", "k_pack", "k_unpack")
             others[f"cfg{cid}"] = {k: o[k] for k in keep}
         result["configs"] = others
-        result["configs_note"] = ("the leading frames of each workload (1 and 5: the whole workload), same calls, same timing protocol; "
+        result["configs_note"] = ("the leading frames of each workload (5: the whole workload; 1: its 8 frames cycled 8 times), same calls, same timing protocol; "
                                   "workloads 1 and 3 move a few MB per step and are bound by the latency of the image "
                                   "side's launch chain, not by HBM")
     if not args.no_cpu:
