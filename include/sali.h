@@ -74,9 +74,11 @@ typedef struct sali_config {
     float   tau_t;                   /* Eq. 5/6: patch i is static iff Delta P_i < tau_t (pixels)      */
     float   theta_r;                 /* frame is redundant iff R_frame > theta_r                       */
     int32_t canny_lo, canny_hi;      /* Sobel-magnitude thresholds, 1 <= lo <= hi <= 1442              */
-    int32_t tier_mode;               /* 0: thresholds of Eq. 8; 1: top-k counts                        */
+    int32_t tier_mode;               /* 0: thresholds of Eq. 8; 1: top-k counts; 2: Eq. 8 with adaptive
+                                        thresholds (see "Adaptive thresholds" below)                   */
     float   tau_high, tau_med, tau_low;      /* mode 0, tau_low <= tau_med <= tau_high                 */
-    int32_t k_fp16, k_int8, k_int4;  /* mode 1: tokens per tier by descending score; rest pruned       */
+    int32_t k_fp16, k_int8, k_int4;  /* mode 1: tokens per tier by descending score; rest pruned;
+                                        mode 2: the target counts the thresholds are steered to        */
     int32_t n_layers, n_heads;       /* K/V shape [n_layers][2][n_heads][576][head_dim]                */
     int32_t head_dim;                /* must be 128                                                    */
     int32_t group;                   /* quantisation group along head_dim; must be 32                  */
@@ -87,7 +89,7 @@ typedef struct sali_config {
                                         else >= 576.  See "Memory budget" below.                        */
     int32_t tiles_per_frame;         /* images of 576 patches that make up one video frame, 1..8; 0 reads as 1.
                                         See "Dynamic-resolution frames" below.                          */
-    int32_t reserved;
+    int32_t adapt_rate_q8;           /* mode 2: step of the threshold update in 1/256, 0..256          */
 } sali_config;
 
 /* Memory budget (Experimental Setup: the methods are compared under a strict budget of 784 patches; the
@@ -104,6 +106,18 @@ typedef struct sali_config {
  * analysed (sali_analyze*, sali_step*, sali_kv_compress), so reads of a frame issued after a later
  * frame's analysis may already find it evicted; within one batch the frames are taken in order, and a
  * frame evicted by a later frame of its own batch is never written. */
+
+/* Adaptive thresholds (the Discussion says the thresholds need tuning per video domain, the Conclusion
+ * names adaptive thresholds as future work; the paper gives no rule, this is the library's).  With
+ * tier_mode = 2 every stored frame is tiered by Eq. 8 with the thresholds in force, and afterwards each
+ * threshold moves adapt_rate_q8 / 256 of the way to the score quantile that would have given its tier the
+ * target count in that frame: q_high = the score of rank k_fp16 in (score descending, token index
+ * ascending) order, q_med at rank k_fp16 + k_int8, q_low at rank k_fp16 + k_int8 + k_int4 (0 if there is no
+ * such rank).  Thresholds and quantiles are integers in units of 2^-16 (floor; the scores of
+ * sali_saliency_pool are exact multiples): tau <- tau + floor((q - tau) * adapt_rate_q8 / 256).  The state
+ * lives in device memory, starts at sali_create / sali_reset from tau_high, tau_med, tau_low, is carried from
+ * stored frame to stored frame in video order (pointer frames and frames that could not be stored leave it
+ * alone) and is what sali_kv_compress uses too.  adapt_rate_q8 = 0 is Eq. 8 with fixed thresholds. */
 
 /* Dynamic-resolution frames (Background, Adapter Projection: the vision encoder of the model the paper
  * uses cuts a high-resolution frame into several images of 576 patches each, so a frame has a multiple of
@@ -176,10 +190,10 @@ int sali_reset(sali_ctx* ctx, void* stream);
  * video domain).  Applies to calls issued afterwards. */
 int sali_set_gate_thresholds(sali_ctx* ctx, float tau_t, float theta_r);
 
-/* Change the spatial thresholds or the top-k counts that turn scores into tiers (Eq. 8; the
- * Discussion and the Conclusion name adaptive threshold tuning as the next step: the policy that
- * picks the values is the caller's, this call only installs them).  tier_mode, thresholds and
- * counts as in sali_config, same consistency rules (SALI_ERR_CONFIG otherwise, nothing changes).
+/* Change the spatial thresholds or the top-k counts that turn scores into tiers (Eq. 8), for callers
+ * that steer them themselves (tier_mode 2 is the built-in policy).  tier_mode, thresholds and
+ * counts as in sali_config, same consistency rules (SALI_ERR_CONFIG otherwise, nothing changes); in
+ * mode 2 the thresholds in force are not touched (they restart from the configuration at sali_reset).
  * Applies to frames analysed or compressed by calls issued afterwards; frames already in the
  * cache keep their tiers. */
 int sali_set_tier_params(sali_ctx* ctx, int32_t tier_mode, float tau_high, float tau_med, float tau_low,

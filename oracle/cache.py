@@ -29,6 +29,18 @@ and the reuse rule takes ONE decision for the frame; a redundant frame's entries
 stored entry of their own tile; otherwise every tile gets its saliency scores and its tiers
 (Eq. 8 per patch; top-k counts per tile) and is stored as an entry of its own.
 
+Adaptive thresholds (Discussion: the thresholds need tuning per video domain; Conclusion: adaptive
+thresholds are future work; the paper gives no rule).  Reading taken, `tier_mode` = 2: Eq. 8 is
+applied to every frame with the thresholds in force, and after a frame has been stored each
+threshold moves a fraction alpha = adapt_rate_q8 / 256 of the way to the score quantile that would
+have given the target share of its tier in that frame (targets k_fp16, k_int8, k_int4 tokens:
+q_high = the score of rank k_fp16 in (score descending, index ascending) order, i.e. the largest
+score outside the top k_fp16; q_med, q_low at ranks k_fp16 + k_int8 and k_fp16 + k_int8 + k_int4;
+0 if that rank does not exist).  Thresholds and quantiles live on the score lattice (integers in
+units of 2^-16, floor): tau <- tau + floor((q - tau) * adapt_rate_q8 / 256), so both sides of a
+parity test do integer arithmetic.  The state starts from the configured tau_high / tau_med /
+tau_low and is carried from stored frame to stored frame (pointer frames leave it alone).
+
 Storage reading (the paper describes none): three pools indexed
 [layer][K|V][head][slot][...], slots handed out in token order per tier; a
 frame-table row (frame_id, src, stored, base16, base8, base4, n16, n8, n4, np)
@@ -73,6 +85,7 @@ class OracleConfig:
     max_frames: int = 0
     budget_tokens: int = 0          # 0 = no budget (append only)
     tiles_per_frame: int = 1        # images (of grid x grid patches each) that make up one video frame
+    adapt_rate_q8: int = 0          # tier_mode 2: step of the threshold update in 1/256
 
 
 @dataclasses.dataclass
@@ -105,6 +118,7 @@ class _FrameTable:
         self.held = []                  # stored frames still in the cache, oldest first (budget mode)
         self.overflow = False
         self.last_src_tile = {}         # tile index -> last stored entry of that tile (tiles_per_frame > 1)
+        self.adapt_tau = [to_lattice(cfg.tau_high), to_lattice(cfg.tau_med), to_lattice(cfg.tau_low)]
         assert cfg.tiles_per_frame == 1 or cfg.budget_tokens == 0, "a budget evicts entries, not tiled frames"
 
     def _place(self, pool, n, cap):
@@ -171,11 +185,31 @@ class _FrameTable:
         return row
 
 
-def assign_tiers(c: OracleConfig, scores):
-    """Eq. 8 (mode 0) or the top-k counts (mode 1) of the configuration."""
+def to_lattice(x):
+    """floor(clamp(x, 0, 1) * 2^16): a score or threshold in units of 2^-16."""
+    return int(np.floor(min(max(float(np.float32(x)), 0.0), 1.0) * 65536.0))
+
+
+def assign_tiers(c: OracleConfig, scores, adapt_tau=None):
+    """Eq. 8 (mode 0), the top-k counts (mode 1), or Eq. 8 with the adaptive thresholds in force
+    (mode 2; adapt_tau = the three thresholds in units of 2^-16)."""
     if c.tier_mode == 0:
         return oq.tiers_threshold(scores, c.tau_high, c.tau_med, c.tau_low)
+    if c.tier_mode == 2:
+        return oq.tiers_threshold(scores, *(np.float32(t) / np.float32(65536.0) for t in adapt_tau))
     return oq.tiers_topk(scores, c.k_fp16, c.k_int8, c.k_int4)
+
+
+def adapted_thresholds(c: OracleConfig, adapt_tau, scores):
+    """The thresholds after a stored frame with these scores (tier_mode 2)."""
+    s = np.asarray(scores, dtype=np.float32)
+    order = sorted(range(s.size), key=lambda i: (-float(s[i]), i))
+    ranks = (c.k_fp16, c.k_fp16 + c.k_int8, c.k_fp16 + c.k_int8 + c.k_int4)
+    out = []
+    for tau, r in zip(adapt_tau, ranks):
+        q = to_lattice(s[order[r]]) if r < s.size else 0
+        out.append(tau + ((q - tau) * c.adapt_rate_q8) // 256)          # floor division
+    return out
 
 
 class SaliCacheOracle:
@@ -217,7 +251,7 @@ class SaliCacheOracle:
         return osal.saliency_pool(rgb, c.grid, c.canny_lo, c.canny_hi)
 
     def assign_tiers(self, scores):
-        return assign_tiers(self.cfg, scores)
+        return assign_tiers(self.cfg, scores, self.table.adapt_tau)
 
     def kv_compress(self, kv_fp16, scores, frame_id):
         """kv_fp16: [n_l, 2, n_h, N, D].  Stores the frame; returns its table row."""
@@ -229,6 +263,8 @@ class SaliCacheOracle:
         row = self.table.store(frame_id, cnt)
         if not row.stored:
             return row
+        if c.tier_mode == 2:
+            self.table.adapt_tau = adapted_thresholds(c, self.table.adapt_tau, scores)
         b16, b8, b4 = row.base16, row.base8, row.base4
         i16 = np.nonzero(tier == oq.T_FP16)[0]
         i8 = np.nonzero(tier == oq.T_INT8)[0]
@@ -359,14 +395,19 @@ class ImageSideOracle:
         if out["redundant"]:
             return out                      # Algorithm 1: pointer, then `continue`
         out["scores"], _ = osal.saliency_pool(rgb, c.grid, c.canny_lo, c.canny_hi)
-        out["tier"] = assign_tiers(c, out["scores"])
+        out["tier"] = assign_tiers(c, out["scores"], self.table.adapt_tau)
         out["slot"], out["cnt"] = oq.slots(out["tier"])
         return out
 
     def commit(self, frame_id, a) -> FrameRow:
         if a["redundant"]:
             return self.table.pointer(frame_id)
-        return self.table.store(frame_id, a["cnt"])
+        row = self.table.store(frame_id, a["cnt"])
+        if row.stored and self.cfg.tier_mode == 2:
+            # (an image-only walk with adaptive thresholds must go frame by frame: analyze_pair of frame t
+            # needs the thresholds that frame t - 1 left)
+            self.table.adapt_tau = adapted_thresholds(self.cfg, self.table.adapt_tau, a["scores"])
+        return row
 
     def step(self, rgb, frame_id, tau_t=None, theta_r=None):
         a = self.analyze_pair(self.prev_rgb, rgb, tau_t, theta_r)

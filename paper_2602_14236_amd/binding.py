@@ -40,7 +40,7 @@ class sali_config(C.Structure):
         ("k_fp16", C.c_int32), ("k_int8", C.c_int32), ("k_int4", C.c_int32),
         ("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("group", C.c_int32),
         ("cap_fp16", C.c_int64), ("cap_int8", C.c_int64), ("cap_int4", C.c_int64),
-        ("max_frames", C.c_int32), ("budget_tokens", C.c_int32), ("tiles_per_frame", C.c_int32), ("reserved", C.c_int32),
+        ("max_frames", C.c_int32), ("budget_tokens", C.c_int32), ("tiles_per_frame", C.c_int32), ("adapt_rate_q8", C.c_int32),
     ]
 
 
@@ -152,10 +152,10 @@ def _ptr(t: Optional[torch.Tensor]):
 def make_config(src_h, src_w, *, flow_levels=3, flow_iters=3, tau_t=0.5, theta_r=0.90, canny_lo=50, canny_hi=100,
                 tier_mode=0, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0,
                 n_layers=1, n_heads=32, cap_fp16=0, cap_int8=0, cap_int4=0, max_frames=1,
-                budget_tokens=0, tiles_per_frame=1) -> sali_config:
+                budget_tokens=0, tiles_per_frame=1, adapt_rate_q8=0) -> sali_config:
     return sali_config(src_h, src_w, 24, flow_levels, flow_iters, tau_t, theta_r, canny_lo, canny_hi, tier_mode,
                        tau_high, tau_med, tau_low, k_fp16, k_int8, k_int4, n_layers, n_heads, 128, 32,
-                       cap_fp16, cap_int8, cap_int4, max_frames, budget_tokens, tiles_per_frame, 0)
+                       cap_fp16, cap_int8, cap_int4, max_frames, budget_tokens, tiles_per_frame, adapt_rate_q8)
 
 
 def workspace_bytes(cfg: sali_config):

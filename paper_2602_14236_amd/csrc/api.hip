@@ -62,10 +62,12 @@ int check_config(const sali_config* c) {
         return SALI_ERR_CONFIG;
     if (!(c->tau_t >= 0.0f) || !(c->theta_r >= 0.0f)) return SALI_ERR_CONFIG;
     if (c->canny_lo < 1 || c->canny_hi < c->canny_lo || c->canny_hi > 1442) return SALI_ERR_CONFIG;
-    if (c->tier_mode != 0 && c->tier_mode != 1) return SALI_ERR_CONFIG;
-    if (c->tier_mode == 0) {
+    if (c->tier_mode < 0 || c->tier_mode > 2) return SALI_ERR_CONFIG;
+    if (c->adapt_rate_q8 < 0 || c->adapt_rate_q8 > 256) return SALI_ERR_CONFIG;
+    if (c->tier_mode != 1) {
         if (!(c->tau_low <= c->tau_med) || !(c->tau_med <= c->tau_high)) return SALI_ERR_CONFIG;
-    } else {
+    }
+    if (c->tier_mode != 0) {
         if (c->k_fp16 < 0 || c->k_int8 < 0 || c->k_int4 < 0 ||
             (long long)c->k_fp16 + c->k_int8 + c->k_int4 > kTokens)
             return SALI_ERR_CONFIG;
@@ -216,7 +218,8 @@ struct LanePtrArray {
     LanePtrs lane[kLanes];
 };
 
-__global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, LanePtrArray lanes) {
+__global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, LanePtrArray lanes, int tau0, int tau1,
+                        int tau2) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < max_frames) {
         sali_frame_row r = {};
@@ -243,6 +246,9 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, Lane
         c.last_src = -1;
         c.ring.oldest = -1;
         for (int j = 0; j < kMaxBatch; ++j) c.last_src_tile[j] = -1;
+        c.adapt_tau[0] = tau0;
+        c.adapt_tau[1] = tau1;
+        c.adapt_tau[2] = tau2;
         *cur = c;
     }
 }
@@ -456,6 +462,7 @@ TierParams tier_params(const sali_config& cfg) {
     tp.k16 = cfg.k_fp16;
     tp.k8 = cfg.k_int8;
     tp.k4 = cfg.k_int4;
+    tp.adapt_q8 = cfg.adapt_rate_q8;
     return tp;
 }
 
@@ -646,8 +653,10 @@ int sali_reset(sali_ctx* c, void* stream) {
     const int n = c->cfg.max_frames > kTokens ? c->cfg.max_frames : kTokens;
     LanePtrArray lanes;
     for (int l = 0; l < kLanes; ++l) lanes.lane[l] = c->lane_ptrs(l);
+    // the adaptive thresholds start from the configured ones, on the 2^-16 lattice
+    auto lattice = [](float x) { return (int)floorf(fminf(fmaxf(x, 0.0f), 1.0f) * 65536.0f); };
     hipLaunchKernelGGL(k_reset, dim3((n + 255) / 256), dim3(256), 0, s, c->cursors(), c->rows(), c->cfg.max_frames,
-                       lanes);
+                       lanes, lattice(c->cfg.tau_high), lattice(c->cfg.tau_med), lattice(c->cfg.tau_low));
     SALI_TRY(hipGetLastError());
     c->n_analysed = 0;
     c->last_frame_id = -1;

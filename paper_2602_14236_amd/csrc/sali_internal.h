@@ -53,7 +53,8 @@ struct Cursors {
     uint32_t pad[3];
     RingState ring;             // used with a memory budget only
     int32_t last_src_tile[kMaxBatch];   // tiled frames: last stored entry of each tile, -1 = none
-    uint32_t pad2[2];
+    int32_t adapt_tau[3];       // adaptive thresholds in force (tier_mode 2), units of 2^-16
+    uint32_t pad2[3];
 };
 
 // The six pool arrays.  Layout of each: frame-major.  A stored frame with first row `base` and
@@ -79,9 +80,10 @@ __host__ __device__ inline size_t pool_row0(const Pools& p, int base, int n, siz
 }
 
 struct TierParams {
-    int32_t mode;
+    int32_t mode;               // 0: Eq. 8 thresholds, 1: top-k counts, 2: adaptive thresholds (k = target counts)
     float tau_high, tau_med, tau_low;
     int32_t k16, k8, k4;
+    int32_t adapt_q8;           // mode 2: step of the threshold update in 1/256
 };
 
 // everything the tier / compaction step needs when it is fused into another kernel; in a batched

@@ -20,8 +20,10 @@ constexpr int kTierGroups = kTokens / 64;                                    // 
 
 // what tier_rank hands to tier_commit
 struct TierCounts {
-    int32_t state;          // 0 = tiers assigned, 1 = redundant frame, 2 = a score was NaN
+    int32_t state;          // 0 = tiers assigned, 1 = redundant frame, 2 = a score was NaN,
+                            // 3 = ranked only (adaptive thresholds: tiers are assigned in frame order)
     int32_t cnt[4];         // tokens per tier
+    int32_t q[3];           // state 3: the frame's score quantiles at the target ranks, units of 2^-16
 };
 
 struct TierShared {
@@ -29,7 +31,15 @@ struct TierShared {
     int group_cnt[kTierGroups][4];
     int part_rank[4][64];           // partial ranks of tokens 512..575, one row per wave
     int nan_flag;
+    int q[3];                       // adaptive thresholds: quantiles found by the ranking
+    int tau[3];                     // adaptive thresholds in force, units of 2^-16
 };
+
+// floor(clamp(x, 0, 1) * 2^16): scores and thresholds of the adaptive mode live on this lattice, so
+// that the update rule is integer arithmetic
+__device__ __forceinline__ int to_lattice(float x) {
+    return (int)floorf(fminf(fmaxf(x, 0.0f), 1.0f) * 65536.0f);
+}
 
 // Number of tokens j in key blocks [j4_lo, j4_hi) (four keys per block) that precede token i in
 // (key descending, index ascending) order; `me` = key of token i.  Blocks before the token's own
@@ -81,81 +91,27 @@ __device__ __forceinline__ TierScores tier_load_scores(const float* scores) {
     return v;
 }
 
-__device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const TierScores& loaded, const TierParams& tp,
-                                                uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
-                                                uint16_t* __restrict__ order_out) {
+// Eq. 8 for the thread's tokens, inequalities as printed
+__device__ __forceinline__ void tier_by_thresholds(const float* s, float tau_high, float tau_med, float tau_low, int* tier) {
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = (int)threadIdx.x + k * kTierThreads;
+        tier[k] = SALI_TIER_PRUNE;
+        if (i >= kTokens) continue;
+        if (s[k] > tau_low) tier[k] = SALI_TIER_INT4;
+        if (s[k] > tau_med) tier[k] = SALI_TIER_INT8;
+        if (s[k] > tau_high) tier[k] = SALI_TIER_FP16;
+    }
+}
+
+// Compaction indices from the tiers of the thread's tokens; writes tier, slot and the pool-order token
+// list and returns the per-tier counts (every thread gets the same value).  Whole block.
+__device__ __forceinline__ TierCounts tier_finish(TierShared& sh, const int* tier, uint8_t* __restrict__ tier_out,
+                                                  uint16_t* __restrict__ slot_out, uint16_t* __restrict__ order_out) {
+    // slot = number of earlier tokens in the same tier: ballot inside the group + prefix over groups
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     TierCounts res = {};
-
-    if (tid == 0) sh.nan_flag = 0;
-    float s[kTierSlots];
-    uint32_t key[kTierSlots];
-    bool has_nan = false;
-#pragma unroll
-    for (int k = 0; k < kTierSlots; ++k) {
-        const int i = tid + k * kTierThreads;
-        s[k] = 0.0f;
-        key[k] = 0u;
-        if (i < kTokens) {
-            s[k] = loaded.s[k];
-            has_nan |= s[k] != s[k];
-            // unsigned key with the same order as the float (and -0 == +0, as the float comparison has it)
-            const uint32_t bits = (s[k] == 0.0f) ? 0u : __builtin_bit_cast(uint32_t, s[k]);
-            key[k] = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-            reinterpret_cast<uint32_t*>(sh.key4)[i] = key[k];
-        }
-    }
-    __syncthreads();
-    if (has_nan) sh.nan_flag = 1;
-    __syncthreads();
-    if (sh.nan_flag) {
-        res.state = 2;
-        return res;
-    }
-
-    int tier[kTierSlots];
-    if (tp.mode == 0) {
-#pragma unroll
-        for (int k = 0; k < kTierSlots; ++k) {
-            const int i = tid + k * kTierThreads;
-            tier[k] = SALI_TIER_PRUNE;
-            if (i >= kTokens) continue;
-            // Eq. 8, inequalities as printed
-            if (s[k] > tp.tau_low) tier[k] = SALI_TIER_INT4;
-            if (s[k] > tp.tau_med) tier[k] = SALI_TIER_INT8;
-            if (s[k] > tp.tau_high) tier[k] = SALI_TIER_FP16;
-        }
-    } else {
-        // rank by (score descending, token index ascending) = number of tokens j with a larger key,
-        // or an equal key and j < i.  Work is dealt evenly: tokens 0..511 are two per thread against
-        // all 576 keys; the last 64 tokens are taken by all four waves, a quarter of the keys each
-        // (partial counts meet in LDS).  All lanes of a wave share the 64-token group of their
-        // token, so the comparison regime of a key block is uniform in the wave.
-        int rank[kTierSlots];
-#pragma unroll
-        for (int k = 0; k < 2; ++k) rank[k] = tier_count_above(sh, key[k], tid + k * kTierThreads, 0, kTokens / 4);
-        {
-            const int wave = tid >> 6;
-            const int i = 2 * kTierThreads + lane;                      // 512 + lane, every wave
-            const uint32_t me = reinterpret_cast<const uint32_t*>(sh.key4)[i];
-            const int part = tier_count_above(sh, me, i, wave * (kTokens / 16), (wave + 1) * (kTokens / 16));
-            sh.part_rank[wave][lane] = part;
-        }
-        __syncthreads();
-        rank[2] = sh.part_rank[0][lane] + sh.part_rank[1][lane] + sh.part_rank[2][lane] + sh.part_rank[3][lane];
-#pragma unroll
-        for (int k = 0; k < kTierSlots; ++k) {
-            const int i = tid + k * kTierThreads;
-            tier[k] = SALI_TIER_PRUNE;
-            if (i >= kTokens) continue;
-            if (rank[k] < tp.k16 + tp.k8 + tp.k4) tier[k] = SALI_TIER_INT4;
-            if (rank[k] < tp.k16 + tp.k8) tier[k] = SALI_TIER_INT8;
-            if (rank[k] < tp.k16) tier[k] = SALI_TIER_FP16;
-        }
-    }
-
-    // slot = number of earlier tokens in the same tier: ballot inside the group + prefix over groups
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     int in_group[kTierSlots];
 #pragma unroll
@@ -201,6 +157,91 @@ __device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const TierScores
 #pragma unroll
     for (int t = 0; t < 4; ++t) res.cnt[t] = cnt[t];
     return res;
+}
+
+__device__ __forceinline__ TierCounts tier_rank(TierShared& sh, const TierScores& loaded, const TierParams& tp,
+                                                uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
+                                                uint16_t* __restrict__ order_out) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    TierCounts res = {};
+
+    if (tid == 0) sh.nan_flag = 0;
+    float s[kTierSlots];
+    uint32_t key[kTierSlots];
+    bool has_nan = false;
+#pragma unroll
+    for (int k = 0; k < kTierSlots; ++k) {
+        const int i = tid + k * kTierThreads;
+        s[k] = 0.0f;
+        key[k] = 0u;
+        if (i < kTokens) {
+            s[k] = loaded.s[k];
+            has_nan |= s[k] != s[k];
+            // unsigned key with the same order as the float (and -0 == +0, as the float comparison has it)
+            const uint32_t bits = (s[k] == 0.0f) ? 0u : __builtin_bit_cast(uint32_t, s[k]);
+            key[k] = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+            reinterpret_cast<uint32_t*>(sh.key4)[i] = key[k];
+        }
+    }
+    __syncthreads();
+    if (has_nan) sh.nan_flag = 1;
+    __syncthreads();
+    if (sh.nan_flag) {
+        res.state = 2;
+        return res;
+    }
+
+    int tier[kTierSlots];
+    if (tp.mode == 0) {
+        tier_by_thresholds(s, tp.tau_high, tp.tau_med, tp.tau_low, tier);
+    } else {
+        // rank by (score descending, token index ascending) = number of tokens j with a larger key,
+        // or an equal key and j < i.  Work is dealt evenly: tokens 0..511 are two per thread against
+        // all 576 keys; the last 64 tokens are taken by all four waves, a quarter of the keys each
+        // (partial counts meet in LDS).  All lanes of a wave share the 64-token group of their
+        // token, so the comparison regime of a key block is uniform in the wave.
+        int rank[kTierSlots];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) rank[k] = tier_count_above(sh, key[k], tid + k * kTierThreads, 0, kTokens / 4);
+        {
+            const int wave = tid >> 6;
+            const int i = 2 * kTierThreads + lane;                      // 512 + lane, every wave
+            const uint32_t me = reinterpret_cast<const uint32_t*>(sh.key4)[i];
+            const int part = tier_count_above(sh, me, i, wave * (kTokens / 16), (wave + 1) * (kTokens / 16));
+            sh.part_rank[wave][lane] = part;
+        }
+        if (tid < 3) sh.q[tid] = 0;
+        __syncthreads();
+        rank[2] = sh.part_rank[0][lane] + sh.part_rank[1][lane] + sh.part_rank[2][lane] + sh.part_rank[3][lane];
+        if (tp.mode == 2) {
+            // adaptive thresholds: only the quantiles at the target ranks are taken from the ranking
+            // (every rank belongs to exactly one token; a rank past the last token leaves 0)
+#pragma unroll
+            for (int k = 0; k < kTierSlots; ++k) {
+                const int i = tid + k * kTierThreads;
+                if (i >= kTokens) continue;
+                if (rank[k] == tp.k16) sh.q[0] = to_lattice(s[k]);
+                if (rank[k] == tp.k16 + tp.k8) sh.q[1] = to_lattice(s[k]);
+                if (rank[k] == tp.k16 + tp.k8 + tp.k4) sh.q[2] = to_lattice(s[k]);
+            }
+            __syncthreads();
+            res.state = 3;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) res.q[j] = sh.q[j];
+            return res;
+        }
+#pragma unroll
+        for (int k = 0; k < kTierSlots; ++k) {
+            const int i = tid + k * kTierThreads;
+            tier[k] = SALI_TIER_PRUNE;
+            if (i >= kTokens) continue;
+            if (rank[k] < tp.k16 + tp.k8 + tp.k4) tier[k] = SALI_TIER_INT4;
+            if (rank[k] < tp.k16 + tp.k8) tier[k] = SALI_TIER_INT8;
+            if (rank[k] < tp.k16) tier[k] = SALI_TIER_FP16;
+        }
+    }
+    return tier_finish(sh, tier, tier_out, slot_out, order_out);
 }
 
 // Cursor state carried in registers through the frames of one commit pass.
@@ -298,7 +339,7 @@ __device__ __noinline__ bool tier_place_with_budget(const TierCounts& tc, int fr
 
 // Frame-table row of one frame from its counts and the running cursors; ONE thread, frames in
 // video order.
-__device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_id, sali_frame_row* rows,
+__device__ __forceinline__ bool tier_commit_one(const TierCounts& tc, int frame_id, sali_frame_row* rows,
                                                 CursorRegs& cr, int cap16, int cap8, int cap4, Cursors* cur = nullptr,
                                                 int budget = 0, int tiles = 1) {
     sali_frame_row r = {};
@@ -349,6 +390,28 @@ __device__ __forceinline__ void tier_commit_one(const TierCounts& tc, int frame_
     }
     if (tiles > 1 && r.stored) cur->last_src_tile[frame_id % tiles] = frame_id;
     rows[frame_id] = r;
+    return r.stored != 0;
+}
+
+// Adaptive thresholds (tier_mode 2; the Discussion says the thresholds need tuning per video domain, the
+// Conclusion names adaptive thresholds as future work; the rule is this library's reading): Eq. 8 with the
+// thresholds in force; after a stored frame each threshold moves adapt_q8 / 256 of the way to the frame's
+// score quantile at its target rank.  Integer arithmetic on the 2^-16 lattice, floor.
+// Tiers of one ranked frame (state 3) from the thresholds sh.tau; whole block.
+__device__ __forceinline__ TierCounts tier_assign_adaptive(TierShared& sh, const TierScores& loaded,
+                                                           uint8_t* __restrict__ tier_out, uint16_t* __restrict__ slot_out,
+                                                           uint16_t* __restrict__ order_out) {
+    int tier[kTierSlots];
+    const float th = (float)sh.tau[0] * (1.0f / 65536.0f), tm = (float)sh.tau[1] * (1.0f / 65536.0f),
+                tl = (float)sh.tau[2] * (1.0f / 65536.0f);          // exact: at most 17 significant bits
+    tier_by_thresholds(loaded.s, th, tm, tl, tier);
+    return tier_finish(sh, tier, tier_out, slot_out, order_out);
+}
+
+// ONE thread, after the frame's row is written
+__device__ __forceinline__ void tier_adapt_update(TierShared& sh, const int* q, int adapt_q8) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) sh.tau[j] += ((q[j] - sh.tau[j]) * adapt_q8) >> 8;      // arithmetic shift = floor
 }
 
 __device__ __forceinline__ CursorRegs cursor_load(const Cursors* cur) {
@@ -369,13 +432,6 @@ __device__ __forceinline__ void cursor_store(Cursors* cur, const CursorRegs& cr)
     if (cr.faults != 0u) atomicOr(&cur->status, cr.faults);
 }
 
-__device__ __forceinline__ void tier_commit(const TierCounts& tc, int frame_id, sali_frame_row* rows, Cursors* cur,
-                                            int cap16, int cap8, int cap4, int budget, int tiles) {
-    CursorRegs cr = cursor_load(cur);
-    tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4, cur, budget, tiles);
-    cursor_store(cur, cr);
-}
-
 // both parts for one frame (whole block)
 __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, bool redundant, const TierParams& tp,
                                           int frame_id, sali_frame_row* rows, uint8_t* __restrict__ tier_out,
@@ -383,8 +439,25 @@ __device__ __forceinline__ void tier_body(TierShared& sh, const float* scores, b
                                           Cursors* cur, int cap16, int cap8, int cap4, int budget, int tiles) {
     TierCounts tc = {};
     tc.state = 1;
-    if (!redundant) tc = tier_rank(sh, tier_load_scores(scores), tp, tier_out, slot_out, order_out);
-    if (threadIdx.x == 0) tier_commit(tc, frame_id, rows, cur, cap16, cap8, cap4, budget, tiles);
+    const TierScores loaded = tier_load_scores(scores);
+    if (!redundant) tc = tier_rank(sh, loaded, tp, tier_out, slot_out, order_out);
+    int q[3] = {tc.q[0], tc.q[1], tc.q[2]};
+    const bool adaptive = tc.state == 3;
+    if (adaptive) {
+        if (threadIdx.x < 3) sh.tau[threadIdx.x] = cur->adapt_tau[threadIdx.x];
+        __syncthreads();
+        tc = tier_assign_adaptive(sh, loaded, tier_out, slot_out, order_out);
+    }
+    if (threadIdx.x == 0) {
+        CursorRegs cr = cursor_load(cur);
+        const bool stored = tier_commit_one(tc, frame_id, rows, cr, cap16, cap8, cap4, cur, budget, tiles);
+        cursor_store(cur, cr);
+        if (adaptive && stored) {
+            tier_adapt_update(sh, q, tp.adapt_q8);
+#pragma unroll
+            for (int j = 0; j < 3; ++j) cur->adapt_tau[j] = sh.tau[j];
+        }
+    }
 }
 
 }  // namespace sali

@@ -64,7 +64,7 @@ class FramePrefetcher:
 def params(src_h=336, src_w=336, **kw):
     p = dict(src_h=src_h, src_w=src_w, flow_levels=3, flow_iters=3, tau_t=0.5, theta_r=0.90, canny_lo=50,
              canny_hi=100, tier_mode=0, tau_high=0.30, tau_med=0.15, tau_low=0.03, k_fp16=0, k_int8=0, k_int4=0,
-             n_layers=1, n_heads=2, cap_fp16=1200, cap_int8=1200, cap_int4=1200, max_frames=8, budget_tokens=0, tiles_per_frame=1)
+             n_layers=1, n_heads=2, cap_fp16=1200, cap_int8=1200, cap_int4=1200, max_frames=8, budget_tokens=0, tiles_per_frame=1, adapt_rate_q8=0)
     p.update(kw)
     return p
 

@@ -36,7 +36,7 @@ def test_host_only_calls():
     assert lay.off_scale8 - lay.off_codes8 >= planes * 403 * 64 * 128
     assert pools == lay.total_bytes >= planes * 64 * (173 * 256 + 403 * 144)
     assert scratch > 336 * 336 * 4 * 24 and tables > 64 * 576 * 5
-    for bad in (dict(src_h=10), dict(flow_levels=0), dict(canny_lo=0), dict(tier_mode=2), dict(n_heads=0),
+    for bad in (dict(src_h=10), dict(flow_levels=0), dict(canny_lo=0), dict(tier_mode=3), dict(adapt_rate_q8=257), dict(tiles_per_frame=9), dict(n_heads=0),
                 dict(max_frames=0), dict(tau_low=0.5), dict(flow_levels=6, src_h=24, src_w=24),
                 dict(cap_fp16=1 << 24), dict(cap_int4=(1 << 24) + 5)):       # a pool plane stays under 4 GiB
         kw = dict(src_h=336, src_w=336)
