@@ -154,9 +154,9 @@ class Runner:
         scale = synth.kv_channel_scale(wl, self.n_layers)
         self.rgbs = [torch.from_numpy(video.frame(t)).to(dev) for t in range(n_src)]
         self.kvs = [synth.kv_frame(wl, t, device=dev, n_layers=self.n_layers, scale=scale) for t in range(n_src)]
-        # frames per launch: 4 where the K/V side bounds the path (a batch of 8 costs more pipeline fill
-        # than it saves in a 64-step run), 8 where the image side does (workloads 1, 3 and 5)
-        self.batch = batch if batch is not None else int(os.environ.get("SALI_BENCH_BATCH", "8" if config in (1, 3, 5) else "4"))
+        # frames per launch: 4 where the K/V side bounds the path (a larger batch costs more pipeline fill
+        # than it saves in a 64-step run), 16 where the image side does (workloads 1, 3 and 5)
+        self.batch = batch if batch is not None else int(os.environ.get("SALI_BENCH_BATCH", "16" if config in (1, 3, 5) else "4"))
         self.outs = [torch.empty((self.n_layers, 2, wl.n_heads, 576, 128), dtype=torch.float16, device=dev)
                      for _ in range(max(1, self.batch))]
         self.lookahead = int(os.environ.get("SALI_BENCH_LOOKAHEAD", "2"))

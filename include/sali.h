@@ -61,8 +61,8 @@ extern "C" {
 #define SALI_TIER_PRUNE 3
 
 #define SALI_TOKENS_MAX 576     /* grid * grid; grid is 24 (576 visual tokens per frame)     */
-#define SALI_MAX_BATCH 8        /* frames that one sali_analyze_batch call may take               */
-#define SALI_ANALYSIS_LANES 16  /* frames whose image-side analysis may be in flight at once      */
+#define SALI_MAX_BATCH 16       /* frames that one sali_analyze_batch call may take               */
+#define SALI_ANALYSIS_LANES 32  /* frames whose image-side analysis may be in flight at once      */
 
 typedef struct sali_ctx sali_ctx;   /* opaque host object; owns no device memory */
 

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsali.so
 _lib = None
 
 TOKENS = 576
-MAX_BATCH = 8           # SALI_MAX_BATCH
+MAX_BATCH = 16          # SALI_MAX_BATCH
 TIER_FP16, TIER_INT8, TIER_INT4, TIER_PRUNE = 0, 1, 2, 3
 FAULT_OVERFLOW, FAULT_NONFINITE, FAULT_NAN_SCORE, FAULT_NO_DATA = 1, 2, 4, 8
 

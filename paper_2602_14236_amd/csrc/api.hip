@@ -245,7 +245,7 @@ __global__ void k_reset(Cursors* cur, sali_frame_row* rows, int max_frames, Lane
         Cursors c = {};
         c.last_src = -1;
         c.ring.oldest = -1;
-        for (int j = 0; j < kMaxBatch; ++j) c.last_src_tile[j] = -1;
+        for (int j = 0; j < kMaxTiles; ++j) c.last_src_tile[j] = -1;
         c.adapt_tau[0] = tau0;
         c.adapt_tau[1] = tau1;
         c.adapt_tau[2] = tau2;

@@ -22,7 +22,7 @@ constexpr int kAttnMaxQPerKv = 8;           // query heads that may share one K/
 constexpr int kAttnSlotsPerHead = 4096;     // partial-result slots of the scratch per K/V head (shared out over its queries)
 constexpr int kAttnPartialStride = 160;     // floats per partial: max, sum, 128 values; 640 B = five whole 128-byte lines
 constexpr int kMaxBatch = SALI_MAX_BATCH;   // frames analysed by one set of launches (blockIdx.z / .y)
-constexpr int kMaxTiles = SALI_MAX_BATCH;   // images per video frame (a frame's tiles are analysed in one batch)
+constexpr int kMaxTiles = 8;                // images per video frame (a frame's tiles are analysed in one batch)
 
 // flow constants (polynomial expansion 7x7 sigma 1.5; aggregation window 11x11 sigma 2.5;
 // prior-centred ridge term lambda = kLamAbs + kLamRel * trace(G) / 2)
@@ -52,7 +52,7 @@ struct Cursors {
     uint32_t status;            // sticky SALI_FAULT_* bits
     uint32_t pad[3];
     RingState ring;             // used with a memory budget only
-    int32_t last_src_tile[kMaxBatch];   // tiled frames: last stored entry of each tile, -1 = none
+    int32_t last_src_tile[kMaxTiles];   // tiled frames: last stored entry of each tile, -1 = none
     int32_t adapt_tau[3];       // adaptive thresholds in force (tier_mode 2), units of 2^-16
     uint32_t pad2[3];
 };

@@ -180,6 +180,31 @@ def test_config5_adversarial_prefix():
     ctx.close()
 
 
+def test_read_analysis_of_recent_frames_only():
+    """sali_read_analysis returns a frame's own Delta P / gate / scores while its scratch copy is still its
+    own (the 32 most recent analyses) and refuses older or unknown frames."""
+    from paper_2602_14236_amd import binding
+    from _util import params
+    p = params(96, 96, flow_levels=2, n_layers=1, n_heads=1, max_frames=48, cap_fp16=576 * 48, cap_int8=576 * 48,
+               cap_int4=576 * 48)
+    ctx = binding.SaliContext(lib_config(p))
+    rng = np.random.default_rng(0)
+    frames = [torch.from_numpy(rng.integers(0, 256, (96, 96, 3), dtype=np.uint8)).cuda() for _ in range(4)]
+    seen = {}
+    for t in range(40):
+        ctx.analyze(frames[t % 4], t)
+        seen[t] = ctx.read_analysis(t)
+    for t in range(8, 40):                      # still in their scratch copies: identical to what was read at the time
+        dp, gate, sc = ctx.read_analysis(t)
+        assert np.array_equal(dp, seen[t][0]) and np.array_equal(sc, seen[t][2]) and gate.n_static == seen[t][1].n_static
+    assert not np.array_equal(seen[5][2], seen[6][2])
+    for bad in (0, 7, 45):
+        with pytest.raises(binding.SaliError) as e:
+            ctx.read_analysis(bad)
+        assert e.value.code == -5
+    ctx.close()
+
+
 def test_reset_forgets_history():
     from paper_2602_14236_amd import binding
     wl = synth.WORKLOADS[1]
@@ -252,8 +277,8 @@ def test_batched_analysis_matches_oracle():
     for t in range(n):
         orc.step(v.frame(t), kvs[t].cpu().numpy(), t)
     print("oracle done", flush=True)
-    assert binding.MAX_BATCH == 8
-    sizes = [8, 8, 4, 3, 1, 8, 4]
+    assert binding.MAX_BATCH == 16
+    sizes = [16, 8, 4, 3, 1, 4]
     assert sum(sizes) == n
     ctx = binding.SaliContext(lib_config(p))
     s_imgs = [torch.cuda.Stream(), torch.cuda.Stream()]
@@ -283,7 +308,7 @@ def test_batched_analysis_matches_oracle():
         assert_same(valid[576 * i:576 * (i + 1)].cpu().numpy(), exp_valid, f"batched valid mask {2 + i}")
     # argument checks
     with pytest.raises(binding.SaliError) as e:
-        ctx.analyze_batch(rgbs[:9], 0, s_imgs[0])
+        ctx.analyze_batch(rgbs[:17], 0, s_imgs[0])
     assert e.value.code == -2
     with pytest.raises(binding.SaliError) as e:
         ctx.analyze_batch(rgbs[:4], n - 2, s_imgs[0])

@@ -35,7 +35,7 @@ def test_image_side_walk_equals_the_full_oracle():
     assert img.overflow                      # the second configuration runs out of fp16 rows at the third stored frame
 
 
-@pytest.mark.parametrize("cfg_id,frames", [(2, (0, 17)), (5, (8, 9, 58, 120)), (3, (40,))])
+@pytest.mark.parametrize("cfg_id,frames", [(2, (0, 17)), (5, (8, 9, 58, 120)), (3, (40, 1234))])
 def test_committed_records_are_what_the_oracle_computes(cfg_id, frames):
     path = os.path.join(GOLDEN, f"image_side_cfg{cfg_id}.npz")
     g = np.load(path)
