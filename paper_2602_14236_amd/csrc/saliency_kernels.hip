@@ -390,32 +390,28 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     }
     __syncthreads();
     if (s_cnt[0] == 0) return;
-    // all counts first (independent loads), then the rows with the cursors in registers
-    TierCounts all[kMaxBatch];
-#pragma unroll
-    for (int i = 0; i < kMaxBatch; ++i) {
-        all[i] = {};
-        if (i < n_frames) {
-            const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
-            all[i].state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                all[i].cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int j = 0; j < 3; ++j)
-                all[i].q[j] = __hip_atomic_load(in + 5 + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
     if (tl.tp.mode != 2) {
-        if (threadIdx.x == 0) {
-            CursorRegs cr = cursor_load(tl.cur);
+        if (threadIdx.x != 0) return;
+        // all counts first (independent loads), then the rows with the cursors in registers
+        TierCounts all[kMaxBatch];
 #pragma unroll
-            for (int i = 0; i < kMaxBatch; ++i)
-                if (i < n_frames)
-                    tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget,
-                                    tl.tiles);
-            cursor_store(tl.cur, cr);
+        for (int i = 0; i < kMaxBatch; ++i) {
+            all[i] = {};
+            if (i < n_frames) {
+                const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
+                all[i].state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    all[i].cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
+        CursorRegs cr = cursor_load(tl.cur);
+#pragma unroll
+        for (int i = 0; i < kMaxBatch; ++i)
+            if (i < n_frames)
+                tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget,
+                                tl.tiles);
+        cursor_store(tl.cur, cr);
         return;
     }
     // Adaptive thresholds: the ranking above gave each frame's quantiles; its tiers depend on the
@@ -426,15 +422,22 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     if (threadIdx.x < 3) sh.tau[threadIdx.x] = tl.cur->adapt_tau[threadIdx.x];
     __syncthreads();
     for (int i = 0; i < n_frames; ++i) {
-        TierCounts tci = all[i];
-        if (all[i].state == 3)
+        // the frame's hand-over record, the same words for every thread
+        const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
+        TierCounts tci = {};
+        tci.state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int q[3];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) q[j] = __hip_atomic_load(in + 5 + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool ranked = tci.state == 3;
+        if (ranked)
             tci = tier_assign_adaptive(sh, tier_load_scores(f.scores[i]), tl.tier + (size_t)i * kTokens,
                                        tl.slot + (size_t)i * kTokens, tl.order + (size_t)i * kTokens);
         __syncthreads();
         if (threadIdx.x == 0) {
             const bool stored = tier_commit_one(tci, tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur,
                                                 tl.budget, tl.tiles);
-            if (all[i].state == 3 && stored) tier_adapt_update(sh, all[i].q, tl.tp.adapt_q8);
+            if (ranked && stored) tier_adapt_update(sh, q, tl.tp.adapt_q8);
         }
         __syncthreads();
     }
