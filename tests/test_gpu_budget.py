@@ -92,6 +92,29 @@ def test_budget_kv_compress_random_sequence():
     ctx.close()
 
 
+def test_budget_with_adaptive_thresholds():
+    """The two optional modes together: thresholds that follow the score quantiles decide how many tokens a
+    frame keeps, the budget decides how many frames stay."""
+    from paper_2602_14236_amd import binding
+    n = 24
+    p = params(n_layers=1, n_heads=1, cap_fp16=600, cap_int8=600, cap_int4=600, max_frames=n, budget_tokens=900,
+               tier_mode=2, k_fp16=60, k_int8=90, k_int4=120, adapt_rate_q8=160)
+    ctx = binding.SaliContext(lib_config(p))
+    orc = SaliCacheOracle(oracle_config(p))
+    rng = np.random.default_rng(17)
+    g = torch.Generator(device="cuda").manual_seed(4)
+    for f in range(n):
+        scores = (rng.integers(0, 65537, 576) / 65536.0 * rng.uniform(0.2, 1.0)).astype(np.float32)
+        kv = torch.randn((1, 2, 1, 576, 128), generator=g, device="cuda").to(torch.float16)
+        ctx.kv_compress(kv, torch.from_numpy(scores).cuda(), f)
+        orc.kv_compress(kv.cpu().numpy(), scores, f)
+        _check_rows(ctx, orc, f + 1)
+    print(f"held {orc.table.held}, thresholds {orc.table.adapt_tau}", flush=True)
+    assert 1 <= len(orc.table.held) < n
+    _check_contents(ctx, orc, n)
+    ctx.close()
+
+
 def test_budget_wrap_and_oversized_frame():
     """Frames that keep 200 fp16 tokens in a pool of 500 rows: two fit, every further one evicts the oldest
     and goes to row 0 or behind the cursor in turn; then a frame whose rows no empty pool can hold."""
