@@ -241,10 +241,9 @@ int sali_kv_decompress(sali_ctx* ctx, int32_t frame_id, void* d_kv_fp16_out,
  * ranking, no tiers, no K/V read or written; otherwise saliency -> tiers -> storage as in
  * sali_kv_compress.  The first call after create/reset has no previous frame and always
  * stores.  No host synchronisation: the gate lives in device memory and later kernels
- * test it.  Cost note: the edge / colour-variance pre-pass of the frame is launched together with
- * its gray conversion, before the gate is known, so a redundant frame still pays for that pre-pass
- * and its pooling (their results are dropped); what a redundant frame saves is the ranking and
- * all K/V traffic. */
+ * test it: the temporal filter runs first (gray, pyramid, expansion, flow, per-patch motion), and every
+ * kernel of the spatial filter evaluates the reuse rule from the motions and leaves at once for a
+ * redundant frame, so such a frame costs its flow and nothing else (Algorithm 1). */
 int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id,
               void* stream);
 
@@ -370,8 +369,8 @@ int sali_read_frame_tiers(sali_ctx* ctx, int32_t frame_id, uint8_t* h_tier576, u
 
 /* Results that the most recently analysed frame (the last one of a batch) left in device
  * memory, copied to host: per-patch motion (fp32[576]), the gate, and the saliency scores
- * (fp32[576], computed for redundant frames too); any pointer may be NULL.  Motion and gate
- * are zeros if the frame had no predecessor.  Waits for `stream`, which must be the stream
+ * (fp32[576]; not computed for a redundant frame, whose 576 values are then unspecified); any
+ * pointer may be NULL.  Motion and gate are zeros if the frame had no predecessor.  Waits for `stream`, which must be the stream
  * of that analysis (or ordered after it). */
 int sali_read_last_step(sali_ctx* ctx, float* h_patch_motion576, sali_gate* h_gate,
                         float* h_scores576, void* stream);

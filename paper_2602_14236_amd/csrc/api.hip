@@ -50,7 +50,7 @@ struct TableLayout {
 
 struct LaneCounters {         // arrival counters, all self-resetting
     uint32_t patch_done;      // blocks of the stand-alone patch-motion kernel
-    uint32_t reserved;
+    uint32_t skip;            // the saliency pre-pass found the lane's frame redundant (not a counter: a flag)
     uint32_t batch_done;      // frames of a pooling launch whose first frame sits in this lane
 };
 
@@ -323,7 +323,7 @@ struct BatchPlan {
 
 // Pyramid and polynomial expansion in one launch (k_expand: every tile rebuilds the pyramid values it
 // needs from the gray image in LDS) or level by level (k_pyr_down per level, then k_polyexp).  The fused
-// launch saves two dependent launches and hosts the hysteresis strips, but does several times the work per
+// launch saves two dependent launches, but does several times the work per
 // pixel (a 16x16 tile of level 2 reads a 97x97 gray patch), so it is the choice only while the launch
 // chain, not the work, bounds a batch: up to three levels and small frames.  Measured in the pipeline,
 // eight frames per launch: 336x336 the same either way (a single frame per launch: fused 7 % faster),
@@ -332,11 +332,16 @@ bool fused_expansion(const sali_ctx* c, int /*n_frames*/) {
     return c->geom.levels <= 3 && (long long)c->cfg.src_h * c->cfg.src_w < 160000;
 }
 
-// gray (+ saliency pre-pass) of the batch's frames; the other frame-sum accumulator of each lane is
-// cleared for the lane's next use
-int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool with_saliency,
-                 bool union_with_expansion, hipStream_t s) {
-    const sali_config& cfg = c->cfg;
+GateParams gate_params(const sali_ctx* c) {
+    GateParams gp;
+    gp.tau_t = c->cfg.tau_t;
+    gp.theta_r = c->cfg.theta_r;
+    gp.tiles = c->cfg.tiles_per_frame > 1 ? c->cfg.tiles_per_frame : 1;
+    return gp;
+}
+
+PrepBatch prep_batch(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool with_saliency,
+                     const float2* const* flow_or_null) {
     PrepBatch f = {};
     for (int i = 0; i < bp.n; ++i) {
         const LaneLayout& L = c->sl.lane[bp.lane[i]];
@@ -348,19 +353,38 @@ int enqueue_prep(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, 
         f.parent[i] = c->sc<uint32_t>(L.parent);
         f.msum_acc[i] = with_saliency ? msum + (bp.parity[i] & 1u) : nullptr;
         f.msum_clear[i] = with_saliency ? msum + ((bp.parity[i] + 1u) & 1u) : nullptr;
+        // a frame with a predecessor has per-patch motions by the time the pre-pass runs: the reuse rule applies
+        f.dp[i] = (flow_or_null != nullptr && flow_or_null[i] != nullptr) ? c->lane_ptrs(bp.lane[i]).dp : nullptr;
+        f.skip[i] = &c->lane_ptrs(bp.lane[i]).counters->skip;
     }
-    SALI_TRY(launch_prep(f, bp.n, cfg.src_h, cfg.src_w, with_saliency, c->tb<uint16_t>(c->tl.lut),
-                         cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
-    // cross-tile hysteresis after a kernel boundary (the cheapest device-wide ordering there is): a
-    // launch of its own, unless the expansion launch that follows will carry it
-    if (with_saliency && !(union_with_expansion && fused_expansion(c, bp.n)))
-        SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
+    return f;
+}
+
+// gray image of the batch's frames (what the flow needs)
+int enqueue_gray(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, hipStream_t s) {
+    const PrepBatch f = prep_batch(c, d_rgb, bp, false, nullptr);
+    SALI_TRY(launch_gray(f, bp.n, c->cfg.src_h, c->cfg.src_w, s));
     return SALI_OK;
 }
 
-// pyramid and polynomial expansion of each frame's gray image into its expansion slot; with_union:
-// the frames' saliency pre-pass has run and its cross-tile hysteresis pass is still due
-int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, bool with_union, hipStream_t s) {
+// Saliency pre-pass (edges, colour variance, tile-local hysteresis) and the cross-tile hysteresis pass
+// after a kernel boundary (the cheapest device-wide ordering there is).  flow_or_null: the chained step,
+// after the flow and the per-patch motions: frames that the reuse rule finds redundant are skipped
+// (Algorithm 1).  write_gray: the stand-alone call, which has no gray image yet.  The other frame-sum
+// accumulator of each lane is cleared for the lane's next use.
+int enqueue_saliency(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool write_gray,
+                     const float2* const* flow_or_null, hipStream_t s) {
+    const sali_config& cfg = c->cfg;
+    const PrepBatch f = prep_batch(c, d_rgb, bp, true, flow_or_null);
+    const GateParams gp = gate_params(c);
+    SALI_TRY(launch_prep(f, bp.n, cfg.src_h, cfg.src_w, write_gray, gp, c->tb<uint16_t>(c->tl.lut),
+                         cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
+    SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
+    return SALI_OK;
+}
+
+// pyramid and polynomial expansion of each frame's gray image into its expansion slot
+int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, hipStream_t s) {
     const LevelGeom& g = c->geom;
     if (fused_expansion(c, bp.n)) {
         ExpandBatch f = {};
@@ -369,10 +393,8 @@ int enqueue_expansion(sali_ctx* c, const BatchPlan& bp, bool with_union, hipStre
             f.y8[i] = c->sc<uint8_t>(L.y8);
             f.A[i] = c->sc<float4>(c->sl.expA[bp.slot[i]]);
             f.b[i] = c->sc<float>(c->sl.expB[bp.slot[i]]);
-            f.cls[i] = c->sc<uint8_t>(L.cls);
-            f.parent[i] = c->sc<uint32_t>(L.parent);
         }
-        SALI_TRY(launch_expand(f, bp.n, g, c->fw, with_union, s));
+        SALI_TRY(launch_expand(f, bp.n, g, c->fw, s));
         return SALI_OK;
     }
     PyrBatch f = {};
@@ -428,12 +450,7 @@ int enqueue_flow(sali_ctx* c, const BatchPlan& bp, const float2** flow, hipStrea
     return SALI_OK;
 }
 
-// pooling of the batch's saliency pre-pass.  With `tier` (the chained step) the kernel also reduces
-// each frame's flow (NULL: no predecessor) to per-patch motion, evaluates the gates and writes the
-// frame-table rows with tiers and compaction indices, in frame order.  d_scores_or_null / d_salmap
-// redirect the outputs of a stand-alone single-frame call.
-int enqueue_pool(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, uint8_t* d_salmap,
-                 const TierLaunch* tier, const float2* const* flow, hipStream_t s) {
+PoolBatch pool_batch(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, const float2* const* flow) {
     PoolBatch f = {};
     for (int i = 0; i < bp.n; ++i) {
         const LaneLayout& L = c->sl.lane[bp.lane[i]];
@@ -444,11 +461,30 @@ int enqueue_pool(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, uint
         f.msum[i] = lp.msum + (bp.parity[i] & 1u);
         f.scores[i] = d_scores_or_null != nullptr ? d_scores_or_null : lp.scores;
         f.flow[i] = flow != nullptr ? flow[i] : nullptr;
-        f.dp[i] = lp.dp;
+        f.dp_out[i] = lp.dp;
+        f.dp[i] = f.flow[i] != nullptr ? lp.dp : nullptr;
+        f.skip[i] = &lp.counters->skip;
         f.gate[i] = lp.gate;
         f.tcounts[i] = c->sc<TierCounts>(L.tcounts);
     }
-    SALI_TRY(launch_pool(f, bp.n, c->cfg.src_h, c->cfg.src_w, d_salmap, tier, c->cfg.tau_t, c->cfg.theta_r,
+    return f;
+}
+
+// Eq. 5: each frame's flow (NULL: no predecessor) reduced to per-patch motion
+int enqueue_motion(sali_ctx* c, const BatchPlan& bp, const float2* const* flow, hipStream_t s) {
+    const PoolBatch f = pool_batch(c, bp, nullptr, flow);
+    SALI_TRY(launch_motion(f, bp.n, c->cfg.src_h, c->cfg.src_w, s));
+    return SALI_OK;
+}
+
+// Pooling of the batch's saliency pre-pass (Eq. 7).  With `tier` (the chained step) a second launch
+// evaluates the gates and writes the frame-table rows with tiers and compaction indices, in frame
+// order; redundant frames get no scores.  d_scores_or_null / d_salmap redirect the outputs of a
+// stand-alone single-frame call.
+int enqueue_pool(sali_ctx* c, const BatchPlan& bp, float* d_scores_or_null, uint8_t* d_salmap,
+                 const TierLaunch* tier, const float2* const* flow, hipStream_t s) {
+    const PoolBatch f = pool_batch(c, bp, d_scores_or_null, flow);
+    SALI_TRY(launch_pool(f, bp.n, c->cfg.src_h, c->cfg.src_w, d_salmap, tier, gate_params(c),
                          &c->lane_ptrs(bp.lane[0]).counters->batch_done, s));
     return SALI_OK;
 }
@@ -702,10 +738,10 @@ int sali_flow_score(sali_ctx* c, const uint8_t* d_prev_rgb, const uint8_t* d_cur
     pa.prev_slot[0] = -1;
     pb.slot[0] = kStepSlots + 1;
     pb.prev_slot[0] = kStepSlots;
-    int rc = enqueue_prep(c, &d_prev_rgb, pa, false, false, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, pa, false, s);
-    if (rc == SALI_OK) rc = enqueue_prep(c, &d_cur_rgb, pb, false, false, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, pb, false, s);
+    int rc = enqueue_gray(c, &d_prev_rgb, pa, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, pa, s);
+    if (rc == SALI_OK) rc = enqueue_gray(c, &d_cur_rgb, pb, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, pb, s);
     if (rc != SALI_OK) return rc;
     const float2* flow = nullptr;
     rc = enqueue_flow(c, pb, &flow, s);
@@ -722,7 +758,7 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
     BatchPlan bp = {};
     bp.n = 1;
     bp.parity[0] = c->lane_uses[0]++ & 1u;
-    int rc = enqueue_prep(c, &d_rgb, bp, true, false, s);
+    int rc = enqueue_saliency(c, &d_rgb, bp, true, nullptr, s);
     if (rc == SALI_OK) rc = enqueue_pool(c, bp, d_scores576, d_salmap_or_null, nullptr, nullptr, s);
     return rc;
 }
@@ -845,8 +881,9 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
         rc = wait_unless_same(s, old.stream, old.done);
         if (rc != SALI_OK) return rc;
     }
-    rc = enqueue_prep(c, d_rgb_frames, bp, true, true, s);
-    if (rc == SALI_OK) rc = enqueue_expansion(c, bp, true, s);
+    // the temporal filter first: gray, pyramid + expansion, flow, per-patch motion
+    rc = enqueue_gray(c, d_rgb_frames, bp, s);
+    if (rc == SALI_OK) rc = enqueue_expansion(c, bp, s);
     if (rc != SALI_OK) return rc;
     // the batch's events live in the ring entry of its last frame
     AnalysisRecord& rec = c->ring[n_last % kRing];
@@ -857,13 +894,17 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
         if (rc != SALI_OK) return rc;
     }
     rc = enqueue_flow(c, bp, flow, s);
+    if (rc == SALI_OK) rc = enqueue_motion(c, bp, flow, s);
+    // then the spatial filter, for the frames the reuse rule does not find redundant (Algorithm 1: a
+    // redundant frame bypasses it): every kernel from here on evaluates the rule from the motions
+    if (rc == SALI_OK) rc = enqueue_saliency(c, d_rgb_frames, bp, false, flow, s);
     if (rc != SALI_OK) return rc;
     if (prev != nullptr) {
         // tiers are handed out in frame order: the cursors must have seen the previous frame
         rc = wait_unless_same(s, prev->stream, prev->done);
         if (rc != SALI_OK) return rc;
     }
-    // per-patch motion, gate, pooling, tiers: one launch
+    // pooling, then gate and tiers
     const TierLaunch tl = tier_launch(c, first_frame_id);
     rc = enqueue_pool(c, bp, nullptr, nullptr, &tl, flow, s);
     if (rc != SALI_OK) return rc;

@@ -26,7 +26,6 @@
 // The batched kernels take the frame as a grid dimension.  All stencils replicate the border.
 
 #include "sali_internal.h"
-#include "hysteresis.h"
 
 namespace sali {
 
@@ -240,32 +239,22 @@ __device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, 
 
 }  // namespace
 
-// n_union blocks per frame do something unrelated that has the same predecessor (the
-// saliency pre-pass) and nothing else to wait for: the cross-tile pass of the Canny hysteresis, one
-// 64 x 4 pixel strip per block.  Hosting it here saves a launch and its 10 us of latency-bound run
-// time on the critical path of a frame batch.
 __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int t1, int t2, int tx0, int tx1, int tx2,
-                                                FlowWeights fw, int n_union, int strips_x) {
+                                                FlowWeights fw) {
     // Work order.  A level-2 tile costs about ten times a level-0 tile (97 x 97 gray pixels, two pyramid
     // stages) and there are sixteen level-0 tiles for each: with the tiles of a frame in level order the
     // heavy ones start last and the launch ends with a few of them on an idle chip (22 us per four
     // 336x336 frames, 10 of them that tail).  So the linear block id is cut into runs, heaviest first,
-    // each run over all frames of the batch: level-2 tiles, the hysteresis strips (latency-bound, they
-    // ride along), level-1 tiles, level-0 tiles.
+    // each run over all frames of the batch: level-2 tiles, level-1 tiles, level-0 tiles.
     const int n_frames = (int)gridDim.y;
-    const int t3 = (int)gridDim.x - n_union;        // tiles of a frame over all levels
+    const int t3 = (int)gridDim.x;                  // tiles of a frame over all levels
     int idx = (int)blockIdx.x + (int)gridDim.x * (int)blockIdx.y;
     int lvl, t, frame;
     if (idx < n_frames * (t3 - t2)) {
         lvl = 2;
         frame = idx / (t3 - t2);
         t = idx - frame * (t3 - t2);
-    } else if ((idx -= n_frames * (t3 - t2)) < n_frames * n_union) {
-        frame = idx / n_union;
-        idx -= frame * n_union;
-        union_strip(f.cls[frame], f.parent[frame], g.h[0], g.w[0], idx % strips_x, idx / strips_x);
-        return;
-    } else if ((idx -= n_frames * n_union) < n_frames * (t2 - t1)) {
+    } else if ((idx -= n_frames * (t3 - t2)) < n_frames * (t2 - t1)) {
         lvl = 1;
         frame = idx / (t2 - t1);
         t = idx - frame * (t2 - t1);
@@ -563,7 +552,7 @@ hipError_t launch_polyexp(const PyrBatch& f, int n, LevelGeom g, FlowWeights fw,
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, bool with_union, hipStream_t s) {
+hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s) {
     // up to three levels, 16x16 tiles, one launch
     int tx[3] = {1, 1, 1}, start[4] = {0, 0, 0, 0};
     for (int l = 0; l < 3; ++l) {
@@ -574,10 +563,7 @@ hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights f
         }
         start[l + 1] = start[l] + tiles;
     }
-    const int strips_x = (g.w[0] + 63) / 64;
-    const int n_union = with_union ? strips_x * ((g.h[0] + 3) / 4) : 0;
-    hipLaunchKernelGGL(k_expand, dim3(n_union + start[3], n), dim3(256), 0, s, f, g, start[1], start[2], tx[0], tx[1],
-                       tx[2], fw, n_union, strips_x);
+    hipLaunchKernelGGL(k_expand, dim3(start[3], n), dim3(256), 0, s, f, g, start[1], start[2], tx[0], tx[1], tx[2], fw);
     return hipGetLastError();
 }
 

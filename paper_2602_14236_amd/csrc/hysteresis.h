@@ -1,5 +1,5 @@
-// Hysteresis of the Canny stage as a lock-free union-find, shared by the saliency kernels and by the
-// expansion kernel that hosts the cross-tile pass (Implementation Details: Canny edge detection).
+// Hysteresis of the Canny stage as a lock-free union-find, shared by the saliency kernels
+// (Implementation Details: Canny edge detection).
 // A pixel's key is its index with bit 31 set for weak pixels; links always point to the smaller
 // key, so the root of a component is a strong pixel iff the component has one.
 #pragma once

@@ -119,6 +119,15 @@ struct PrepBatch {
     uint32_t* parent[kMaxBatch];
     unsigned long long* msum_acc[kMaxBatch];      // frame sum of the colour variance, accumulated
     unsigned long long* msum_clear[kMaxBatch];    // the accumulator of the lane's next use, cleared
+    const float* dp[kMaxBatch];                   // the frame's per-patch motions, for the reuse rule; NULL: never redundant
+    uint32_t* skip[kMaxBatch];                    // the pre-pass leaves the rule's answer here (1: redundant, no saliency)
+};
+
+// The reuse rule (Eq. 6, R_frame > theta_R) as the kernels that come after the flow evaluate it for
+// themselves: tiles = images per video frame (their patches count together).
+struct GateParams {
+    float tau_t, theta_r;
+    int32_t tiles;
 };
 
 // A polynomial expansion is stored as 20 bytes per pixel and level: Ab = {A_xx, A_xy, A_yy, b_x} and
@@ -129,8 +138,6 @@ struct ExpandBatch {
     const uint8_t* y8[kMaxBatch];
     float4* A[kMaxBatch];
     float* b[kMaxBatch];
-    const uint8_t* cls[kMaxBatch];                // for the hosted cross-tile hysteresis pass
-    uint32_t* parent[kMaxBatch];
 };
 
 struct PyrBatch {                                 // per-level path (more than three levels)
@@ -156,7 +163,9 @@ struct PoolBatch {
     const unsigned long long* msum[kMaxBatch];
     float* scores[kMaxBatch];
     const float2* flow[kMaxBatch];                // NULL: no predecessor (never redundant)
-    float* dp[kMaxBatch];
+    float* dp_out[kMaxBatch];                     // per-patch motion, written by the motion launch
+    const float* dp[kMaxBatch];                   // the same for the reuse rule; NULL: never redundant
+    const uint32_t* skip[kMaxBatch];              // what the pre-pass found (1: redundant, no scores)
     sali_gate* gate[kMaxBatch];
     struct TierCounts* tcounts[kMaxBatch];        // hand-over from the frame's ranking to the row writer
 };
@@ -222,21 +231,26 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
                          float* d_out, float* d_lse_or_null, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s);
 
 // saliency_kernels.hip
-// n = frames in the batch (1..kMaxBatch); with_saliency = false converts to gray only (n must be 1)
-hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool with_saliency, const uint16_t* d_lut, int lo2,
-                       int hi2, hipStream_t s);
+// n = frames in the batch (1..kMaxBatch).  launch_gray: RGB -> gray only.  launch_prep: the edge / colour
+// variance pre-pass (write_gray: also the gray image); frames that the reuse rule finds redundant from
+// f.dp are skipped (Algorithm 1: their saliency is not computed) and marked in f.skip, which launch_union
+// and launch_pool go by.
+hipError_t launch_gray(const PrepBatch& f, int n, int h, int w, hipStream_t s);
+hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool write_gray, GateParams gp, const uint16_t* d_lut,
+                       int lo2, int hi2, hipStream_t s);
 hipError_t launch_union(const PrepBatch& f, int n, int h, int w, hipStream_t s);
+// launch_motion: Eq. 5, per-patch motion of every frame of the batch from its flow (0 without flow).
+// launch_pool: Eq. 7 scores (none for frames marked in f.skip);
 // d_salmap_or_null applies to frame 0 (stand-alone call); with `tier` a second small launch evaluates
 // the gate and assigns tiers for the n frames in order
+hipError_t launch_motion(const PoolBatch& f, int n, int h, int w, hipStream_t s);
 hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salmap_or_null,
-                       const TierLaunch* tier_or_null, float tau_t, float theta_r, uint32_t* d_done_counter,
-                       hipStream_t s);
+                       const TierLaunch* tier_or_null, GateParams gp, uint32_t* d_done_counter, hipStream_t s);
 
 // flow_kernels.hip
 hipError_t launch_pyr_down(const PyrBatch& f, int n, const LevelGeom& g, int lvl, hipStream_t s);
 hipError_t launch_polyexp(const PyrBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
-// with_union: the launch also carries the blocks of the cross-tile hysteresis pass (f.cls / f.parent)
-hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, bool with_union, hipStream_t s);
+hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights fw, hipStream_t s);
 hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
                             int prior_mode, FlowWeights fw, hipStream_t s);
 hipError_t launch_patch_gate(const float2* d_flow, int h, int w, float tau_t, float theta_r, float* d_dp,

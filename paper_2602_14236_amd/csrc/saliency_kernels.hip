@@ -45,12 +45,61 @@ __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? l
 
 }  // namespace
 
-// gray only (the stand-alone flow call needs no saliency)
-__global__ __launch_bounds__(256) void k_gray(const uint8_t* __restrict__ rgb, int n, uint8_t* __restrict__ y8_out) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const uint8_t* px = rgb + (size_t)i * 3;
-    y8_out[i] = (uint8_t)((77 * px[0] + 150 * px[1] + 29 * px[2] + 128) >> 8);
+// gray only, blockIdx.y = frame of the batch: what the flow needs of a frame.  The rest of the spatial
+// filter waits until the reuse rule has spoken.  Sixteen pixels per thread (48 bytes in, 16 out) where
+// the caller's image is 16-byte aligned, else pixel by pixel.
+__device__ __forceinline__ uint32_t gray_of(uint32_t r, uint32_t g, uint32_t b) {
+    return (77u * r + 150u * g + 29u * b + 128u) >> 8;
+}
+
+__global__ __launch_bounds__(256) void k_gray(PrepBatch f, int n) {
+    const uint8_t* __restrict__ rgb = f.rgb[blockIdx.y];
+    uint8_t* __restrict__ y8 = f.y8[blockIdx.y];
+    const int i0 = (blockIdx.x * 256 + threadIdx.x) * 16;
+    if (i0 >= n) return;
+    if (i0 + 16 <= n && (reinterpret_cast<uintptr_t>(rgb) & 15u) == 0) {
+        const uint4* src = reinterpret_cast<const uint4*>(rgb + (size_t)i0 * 3);
+        const uint4 a = src[0], b = src[1], c = src[2];
+        const uint32_t in[12] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w, c.x, c.y, c.z, c.w};
+        uint32_t out[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {           // four pixels = three words: RGBR GBRG BRGB
+            const uint32_t w0 = in[3 * q], w1 = in[3 * q + 1], w2 = in[3 * q + 2];
+            const uint32_t g0 = gray_of(w0 & 0xFF, (w0 >> 8) & 0xFF, (w0 >> 16) & 0xFF);
+            const uint32_t g1 = gray_of(w0 >> 24, w1 & 0xFF, (w1 >> 8) & 0xFF);
+            const uint32_t g2 = gray_of((w1 >> 16) & 0xFF, w1 >> 24, w2 & 0xFF);
+            const uint32_t g3 = gray_of((w2 >> 8) & 0xFF, (w2 >> 16) & 0xFF, w2 >> 24);
+            out[q] = g0 | (g1 << 8) | (g2 << 16) | (g3 << 24);
+        }
+        *reinterpret_cast<uint4*>(y8 + i0) = make_uint4(out[0], out[1], out[2], out[3]);   // lane scratch: 256-byte aligned
+        return;
+    }
+    for (int i = i0; i < n && i < i0 + 16; ++i) {
+        const uint8_t* px = rgb + (size_t)i * 3;
+        y8[i] = (uint8_t)gray_of(px[0], px[1], px[2]);
+    }
+}
+
+// Eq. 6 and the reuse rule for frame b of a launch, evaluated by a whole block of 256 threads from the
+// per-patch motions that an earlier kernel left (dp[b] NULL: no predecessor, never redundant): the
+// kernels of the spatial filter ask this first and leave at once for a redundant frame (Algorithm 1
+// skips its saliency).  Same counts and the same fp32 quotient as the tail kernel that writes the gate,
+// so all of them take the same decision.  s_cnt: four ints of LDS.
+__device__ __forceinline__ bool frame_redundant(const float* const* dp, int b, const GateParams& gp, int* s_cnt) {
+    const int b0 = b - b % gp.tiles;
+    if (dp[b0] == nullptr) return false;
+    int n = 0;
+    for (int j = 0; j < gp.tiles; ++j)
+        for (int i = threadIdx.x; i < kTokens; i += 256) {
+            const float v = __hip_atomic_load(dp[b0 + j] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            n += (v < gp.tau_t) ? 1 : 0;
+        }
+    for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = n;
+    __syncthreads();
+    const int n_static = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    __syncthreads();
+    return (float)n_static / (float)(kTokens * gp.tiles) > gp.theta_r;
 }
 
 // 256 threads per 32x32 tile, four output pixels per thread (pixel p = tid + 256 q sits in tile
@@ -60,7 +109,7 @@ constexpr int kPrepThreads = 256;
 constexpr int kPrepPx = kTile * kTile / kPrepThreads;                          // 4
 constexpr int kPrepCells = (kReg * kReg + kPrepThreads - 1) / kPrepThreads;   // 7
 
-__global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w,
+__global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w, int write_gray, GateParams gp,
                                                        const uint32_t* __restrict__ lut_words, int lo2, int hi2) {
     // blockIdx.z = frame of the batch
     const uint8_t* __restrict__ rgb = f.rgb[blockIdx.z];
@@ -86,8 +135,8 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
 
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0 && msum_clear != nullptr) *msum_clear = 0ull;
 
-    // stage 1a: colour tables -> LDS; RGB of the 40x40 region (clamped coordinates) -> gray
-    for (int i = tid; i < (256 + 4096) / 2; i += kPrepThreads) s_lut[i] = lut_words[i];
+    // stage 1a: RGB of the 40x40 region (clamped coordinates).  The loads are issued before the reuse
+    // rule is looked at, so that its memory round trip and theirs overlap: most frames are not redundant.
     uint32_t crgb[kPrepCells];
 #pragma unroll
     for (int k = 0; k < kPrepCells; ++k) {
@@ -99,7 +148,24 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
             const uint8_t* px = rgb + ((size_t)gy * w + gx) * 3;
             const uint32_t r = px[0], g = px[1], b = px[2];
             crgb[k] = r | (g << 8) | (b << 16);
-            s_y[ry][rx] = (uint8_t)((77 * r + 150 * g + 29 * b + 128) >> 8);
+        }
+    }
+    {
+        // no saliency for a redundant frame; the frame's first block leaves the decision for the kernels
+        // after this one, whose blocks are too small to count 576 patches each
+        __shared__ int s_gate[4];
+        const bool skip = frame_redundant(f.dp, blockIdx.z, gp, s_gate);
+        if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *f.skip[blockIdx.z] = skip ? 1u : 0u;
+        if (skip) return;
+    }
+    // colour tables -> LDS, gray of the region
+    for (int i = tid; i < (256 + 4096) / 2; i += kPrepThreads) s_lut[i] = lut_words[i];
+#pragma unroll
+    for (int k = 0; k < kPrepCells; ++k) {
+        const int p = tid + k * kPrepThreads;
+        if (p < kReg * kReg) {
+            const uint32_t r = crgb[k] & 0xFF, g = (crgb[k] >> 8) & 0xFF, b = crgb[k] >> 16;
+            s_y[p / kReg][p % kReg] = (uint8_t)((77 * r + 150 * g + 29 * b + 128) >> 8);
         }
     }
     __syncthreads();
@@ -121,13 +187,15 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
         s_lab[2][ry - 2][rx - 2] = (uint8_t)clampi((200 * (fy - fz) + 4194304 + 16384) >> 15, 0, 255);
     }
 
-    // gray image for the flow pyramid
+    // gray image for the flow pyramid (the chained step has written it already, before the flow)
     const int tx = tid % kTile;
     const int gx = x0 + tx;
+    if (write_gray) {
 #pragma unroll
-    for (int q = 0; q < kPrepPx; ++q) {
-        const int ty = (tid + q * kPrepThreads) / kTile;
-        if (y0 + ty < h && gx < w) y8_out[(size_t)(y0 + ty) * w + gx] = s_y[ty + kHalo][tx + kHalo];
+        for (int q = 0; q < kPrepPx; ++q) {
+            const int ty = (tid + q * kPrepThreads) / kTile;
+            if (y0 + ty < h && gx < w) y8_out[(size_t)(y0 + ty) * w + gx] = s_y[ty + kHalo][tx + kHalo];
+        }
     }
 
     // Region arrays are indexed by (image coordinate - region origin).  A stage evaluates its
@@ -321,9 +389,9 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
     }
 }
 
-// hysteresis, cross-tile part as a kernel of its own (the stand-alone saliency call and the
-// per-level expansion path; the chained step runs it inside k_expand's launch)
+// hysteresis, cross-tile part
 __global__ __launch_bounds__(256) void k_union(PrepBatch f, int h, int w) {
+    if (*f.skip[blockIdx.z] != 0u) return;          // redundant frame, says the pre-pass
     union_strip(f.cls[blockIdx.z], f.parent[blockIdx.z], h, w, blockIdx.x, blockIdx.y);
 }
 
@@ -448,22 +516,23 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     }
 }
 
-// Eq. 7 score of each patch and, in the chained step (do_tier), also its motion (Eq. 5) from the
-// flow field.  kWaves = 1: one wave per patch, four patches per block of 256 threads (small
-// patches); kWaves = 4: the whole block works on one patch (large frames).
-// The gate and the tiers (pool_tail) are a second, small launch.  Doing them in the last block of a
+// Eq. 5 motion (kMotion) or Eq. 7 score (!kMotion) of each patch.  kWaves = 1: one wave per patch, four
+// patches per block of 256 threads (small patches); kWaves = 4: the whole block works on one patch (large
+// frames).  The chained step launches the motion variant after the flow and the score variant after the
+// saliency pre-pass; a frame that the reuse rule finds redundant gets no scores (Algorithm 1).
+// The gate and the tiers (pool_tail) are a further, small launch.  Doing them in the last block of a
 // frame to finish (arrival counter) saves that launch but needs a device-scope fence per block, and
 // such a fence writes back and invalidates the issuing XCD's L2: with 144 blocks per frame it made the
 // K/V kernels running next to it 7 % slower (5 400 -> 5 700 frames/s without), and at 1920x1080 (576
 // blocks per frame) it cost the pooling kernel itself 110 us per four-frame launch against 33 us of work.
-template <int kWaves>
-__global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w, uint8_t* __restrict__ salmap,
-                                                  int do_tier) {
+template <int kWaves, bool kMotion>
+__global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w, uint8_t* __restrict__ salmap) {
     static_assert(kTierThreads == 256, "four waves, one patch each");
     static_assert(kWaves == 1 || kWaves == 4, "");
     __shared__ uint32_t s_pq[kTierThreads / 64];
     __shared__ float s_pm[kTierThreads / 64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (!kMotion && *f.skip[blockIdx.y] != 0u) return;      // redundant frame, says the pre-pass
     {
         // blockIdx.y = frame of the batch
         const uint8_t* __restrict__ cls = f.cls[blockIdx.y];
@@ -475,7 +544,13 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
         const int ya = (pr * h) / kGrid, yb = ((pr + 1) * h) / kGrid;
         const int xa = (pc * w) / kGrid, xb = ((pc + 1) * w) / kGrid;
         const int pw = xb - xa, area = pw * (yb - ya);
-        const unsigned long long m = *f.msum[blockIdx.y];
+        if (kMotion && flow == nullptr) {           // no predecessor: no motion
+            if (lane == 0 && (kWaves == 1 || wave == 0))
+                __hip_atomic_store(f.dp_out[blockIdx.y] + token, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        unsigned long long m = 0ull;
+        if (!kMotion) m = *f.msum[blockIdx.y];
         const unsigned long long hw = (unsigned long long)h * (unsigned long long)w;
         uint32_t q = 0;
         float mag = 0.0f;
@@ -494,25 +569,31 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
                 ok[u] = p < area;
                 const int pp = ok[u] ? p : 0;
                 gi[u] = (size_t)(ya + pp / pw) * w + (xa + pp % pw);
-                c[u] = cls[gi[u]];
-                v[u] = var[gi[u]];
-                d[u] = flow != nullptr ? flow[gi[u]] : make_float2(0.0f, 0.0f);
+                if (kMotion) {
+                    d[u] = flow[gi[u]];
+                } else {
+                    c[u] = cls[gi[u]];
+                    v[u] = var[gi[u]];
+                }
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 if (!ok[u]) continue;
-                uint32_t e = 0;
-                if (c[u] == 2) e = 1;
-                else if (c[u] == 1) e = (uf_find_settled(parent, (uint32_t)gi[u] | kWeakBit) & kWeakBit) ? 0u : 1u;
-                const uint32_t cm = ((unsigned long long)v[u] * hw > m && v[u] >= kVMin) ? 1u : 0u;
-                q += e + cm;
-                if (salmap != nullptr) salmap[gi[u]] = (uint8_t)(e + cm);
-                mag += d[u].x * d[u].x + d[u].y * d[u].y;
+                if (kMotion) {
+                    mag += d[u].x * d[u].x + d[u].y * d[u].y;
+                } else {
+                    uint32_t e = 0;
+                    if (c[u] == 2) e = 1;
+                    else if (c[u] == 1) e = (uf_find_settled(parent, (uint32_t)gi[u] | kWeakBit) & kWeakBit) ? 0u : 1u;
+                    const uint32_t cm = ((unsigned long long)v[u] * hw > m && v[u] >= kVMin) ? 1u : 0u;
+                    q += e + cm;
+                    if (salmap != nullptr) salmap[gi[u]] = (uint8_t)(e + cm);
+                }
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
-            q += __shfl_down(q, off);
-            mag += __shfl_down(mag, off);
+            if (kMotion) mag += __shfl_down(mag, off);
+            else q += __shfl_down(q, off);
         }
         if (kWaves == 4) {
             if (lane == 0) {
@@ -524,12 +605,14 @@ __global__ __launch_bounds__(kTierThreads) void k_pool(PoolBatch f, int h, int w
             mag = (s_pm[0] + s_pm[1]) + (s_pm[2] + s_pm[3]);
         }
         if (lane == 0 && (kWaves == 1 || wave == 0)) {
-            const uint32_t s_fix = (uint32_t)(((unsigned long long)q << 15) / (unsigned long long)area);
-            const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
-            __hip_atomic_store(f.scores[blockIdx.y] + token, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (do_tier)
-                __hip_atomic_store(f.dp[blockIdx.y] + token, flow != nullptr ? sqrtf(mag / (float)area) : 0.0f,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (kMotion) {
+                __hip_atomic_store(f.dp_out[blockIdx.y] + token, sqrtf(mag / (float)area), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                const uint32_t s_fix = (uint32_t)(((unsigned long long)q << 15) / (unsigned long long)area);
+                const float score = (float)s_fix * (1.0f / 65536.0f);      // exact: s_fix <= 2^16
+                __hip_atomic_store(f.scores[blockIdx.y] + token, score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
@@ -543,16 +626,17 @@ __global__ __launch_bounds__(kTierThreads) void k_pool_tail(PoolBatch f, float t
 }
 
 // ---------------------------------------------------------------------------------------------
-hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool with_saliency, const uint16_t* d_lut, int lo2,
-                       int hi2, hipStream_t s) {
-    if (!with_saliency) {
-        const int px = h * w;
-        hipLaunchKernelGGL(k_gray, dim3((px + 255) / 256), dim3(256), 0, s, f.rgb[0], px, f.y8[0]);
-        return hipGetLastError();
-    }
+hipError_t launch_gray(const PrepBatch& f, int n, int h, int w, hipStream_t s) {
+    const int px = h * w;
+    hipLaunchKernelGGL(k_gray, dim3((px + 4095) / 4096, n), dim3(256), 0, s, f, px);
+    return hipGetLastError();
+}
+
+hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool write_gray, GateParams gp, const uint16_t* d_lut,
+                       int lo2, int hi2, hipStream_t s) {
     dim3 grid((w + kTile - 1) / kTile, (h + kTile - 1) / kTile, n);
-    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, f, h, w, reinterpret_cast<const uint32_t*>(d_lut), lo2,
-                       hi2);
+    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, f, h, w, write_gray ? 1 : 0, gp,
+                       reinterpret_cast<const uint32_t*>(d_lut), lo2, hi2);
     return hipGetLastError();
 }
 
@@ -562,22 +646,29 @@ hipError_t launch_union(const PrepBatch& f, int n, int h, int w, hipStream_t s) 
     return hipGetLastError();
 }
 
-hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salmap_or_null,
-                       const TierLaunch* tier_or_null, float tau_t, float theta_r, uint32_t* d_done_counter,
-                       hipStream_t s) {
-    TierLaunch t = {};
-    if (tier_or_null != nullptr) t = *tier_or_null;
-    const int do_tier = tier_or_null != nullptr ? 1 : 0;
+hipError_t launch_motion(const PoolBatch& f, int n, int h, int w, hipStream_t s) {
     // patches of up to 1024 pixels: one wave each
     if ((long long)h * w <= 1024ll * kTokens) {
-        hipLaunchKernelGGL((k_pool<1>), dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null, do_tier);
+        hipLaunchKernelGGL((k_pool<1, true>), dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, nullptr);
     } else {
-        hipLaunchKernelGGL((k_pool<4>), dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null, do_tier);
+        hipLaunchKernelGGL((k_pool<4, true>), dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, nullptr);
     }
-    if (do_tier) {
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(const PoolBatch& f, int n, int h, int w, uint8_t* d_salmap_or_null,
+                       const TierLaunch* tier_or_null, GateParams gp, uint32_t* d_done_counter, hipStream_t s) {
+    TierLaunch t = {};
+    if (tier_or_null != nullptr) t = *tier_or_null;
+    if ((long long)h * w <= 1024ll * kTokens) {
+        hipLaunchKernelGGL((k_pool<1, false>), dim3(kTokens / 4, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null);
+    } else {
+        hipLaunchKernelGGL((k_pool<4, false>), dim3(kTokens, n), dim3(kTierThreads), 0, s, f, h, w, d_salmap_or_null);
+    }
+    if (tier_or_null != nullptr) {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k_pool_tail, dim3(n), dim3(kTierThreads), 0, s, f, tau_t, theta_r, t, d_done_counter);
+        hipLaunchKernelGGL(k_pool_tail, dim3(n), dim3(kTierThreads), 0, s, f, gp.tau_t, gp.theta_r, t, d_done_counter);
     }
     return hipGetLastError();
 }
