@@ -80,6 +80,18 @@ __global__ __launch_bounds__(256) void k_gray(PrepBatch f, int n) {
     }
 }
 
+// #{dP_i < tau_t} over the thread's share of one image's 576 patch motions (block of 256 threads); the
+// loads are independent and issued together
+__device__ __forceinline__ int count_static(const float* dp, float tau_t) {
+    float v[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const int i = (int)threadIdx.x + 256 * k;
+        v[k] = i < kTokens ? __hip_atomic_load(dp + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : tau_t;
+    }
+    return (v[0] < tau_t ? 1 : 0) + (v[1] < tau_t ? 1 : 0) + (v[2] < tau_t ? 1 : 0);
+}
+
 // Eq. 6 and the reuse rule for frame b of a launch, evaluated by a whole block of 256 threads from the
 // per-patch motions that an earlier kernel left (dp[b] NULL: no predecessor, never redundant): the
 // kernels of the spatial filter ask this first and leave at once for a redundant frame (Algorithm 1
@@ -89,11 +101,7 @@ __device__ __forceinline__ bool frame_redundant(const float* const* dp, int b, c
     const int b0 = b - b % gp.tiles;
     if (dp[b0] == nullptr) return false;
     int n = 0;
-    for (int j = 0; j < gp.tiles; ++j)
-        for (int i = threadIdx.x; i < kTokens; i += 256) {
-            const float v = __hip_atomic_load(dp[b0 + j] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            n += (v < gp.tau_t) ? 1 : 0;
-        }
+    for (int j = 0; j < gp.tiles; ++j) n += count_static(dp[b0 + j], gp.tau_t);
     for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
     if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = n;
     __syncthreads();
@@ -414,13 +422,8 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     const int tiles = tl.tiles;
     const int b0 = b - b % tiles;
     int n = 0;
-    if (have_flow) {
-        for (int j = 0; j < tiles; ++j)
-            for (int i = threadIdx.x; i < kTokens; i += kTierThreads) {
-                const float v = __hip_atomic_load(f.dp[b0 + j] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                n += (v < tau_t) ? 1 : 0;
-            }
-    }
+    if (have_flow)
+        for (int j = 0; j < tiles; ++j) n += count_static(f.dp[b0 + j], tau_t);
     for (int off = 32; off > 0; off >>= 1) n += __shfl_down(n, off);
     if (lane == 0) s_cnt[wave] = n;
     __syncthreads();
@@ -459,26 +462,27 @@ __device__ __forceinline__ void pool_tail(TierShared& sh, int* s_cnt, const Pool
     __syncthreads();
     if (s_cnt[0] == 0) return;
     if (tl.tp.mode != 2) {
-        if (threadIdx.x != 0) return;
-        // all counts first (independent loads), then the rows with the cursors in registers
-        TierCounts all[kMaxBatch];
+        // every hand-over record by a thread of its own (one round trip), then the rows by one thread with
+        // the cursors in registers; the loop is kept rolled: sixteen copies of the commit step are more
+        // code than this one wave should have to fetch
+        TierCounts* all = reinterpret_cast<TierCounts*>(&sh);
+        static_assert(sizeof(TierCounts) * kMaxBatch <= sizeof(TierShared), "records fit the ranking's memory");
+        if ((int)threadIdx.x < n_frames) {
+            const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[threadIdx.x]);
+            TierCounts rec = {};
+            rec.state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-        for (int i = 0; i < kMaxBatch; ++i) {
-            all[i] = {};
-            if (i < n_frames) {
-                const int32_t* in = reinterpret_cast<const int32_t*>(f.tcounts[i]);
-                all[i].state = __hip_atomic_load(in + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    all[i].cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            for (int t = 0; t < 4; ++t) rec.cnt[t] = __hip_atomic_load(in + 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            all[threadIdx.x] = rec;
         }
-        CursorRegs cr = cursor_load(tl.cur);
-#pragma unroll
-        for (int i = 0; i < kMaxBatch; ++i)
-            if (i < n_frames)
-                tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget,
-                                tl.tiles);
+        CursorRegs cr = {};
+        if (threadIdx.x == 0) cr = cursor_load(tl.cur);
+        __syncthreads();
+        if (threadIdx.x != 0) return;
+#pragma unroll 1
+        for (int i = 0; i < n_frames; ++i)
+            tier_commit_one(all[i], tl.frame_id + i, tl.rows, cr, tl.cap16, tl.cap8, tl.cap4, tl.cur, tl.budget,
+                            tl.tiles);
         cursor_store(tl.cur, cr);
         return;
     }
