@@ -241,9 +241,9 @@ int sali_kv_decompress(sali_ctx* ctx, int32_t frame_id, void* d_kv_fp16_out,
  * ranking, no tiers, no K/V read or written; otherwise saliency -> tiers -> storage as in
  * sali_kv_compress.  The first call after create/reset has no previous frame and always
  * stores.  No host synchronisation: the gate lives in device memory and later kernels
- * test it: the temporal filter runs first (gray, pyramid, expansion, flow, per-patch motion), and every
- * kernel of the spatial filter evaluates the reuse rule from the motions and leaves at once for a
- * redundant frame, so such a frame costs its flow and nothing else (Algorithm 1). */
+ * test it: the temporal filter runs first (gray, pyramid, expansion, flow, per-patch motion), and the
+ * kernels of the spatial filter go by the reuse rule evaluated from the motions and leave at once for
+ * a redundant frame, so such a frame costs its temporal filter and nothing else (Algorithm 1). */
 int sali_step(sali_ctx* ctx, const uint8_t* d_rgb_t, const void* d_kv_t, int32_t frame_id,
               void* stream);
 
