@@ -107,3 +107,31 @@ def test_gate_rational_boundary_on_device():
     _, _, gate = _run(ctx, prev, cur)
     assert gate[2] == 1
     ctx.close()
+
+
+@pytest.mark.parametrize("h,w", [(97, 131), (336, 336)])
+def test_image_address_does_not_matter(h, w):
+    """The gray conversion takes 16 pixels per thread from a 16-byte aligned image and single pixels
+    otherwise (and for the last pixels of a frame whose size is no multiple of 16): both give the same bits."""
+    from paper_2602_14236_amd import binding
+    ctx = binding.SaliContext(lib_config(params(h, w)))
+    rng = np.random.default_rng(7)
+    prev = rng.integers(0, 256, (h, w, 3), dtype=np.uint8)
+    cur = np.roll(prev, (1, 2), axis=(0, 1))
+    cur[..., 0] = np.clip(cur[..., 0].astype(np.int64) + rng.integers(-3, 4, (h, w)), 0, 255).astype(np.uint8)
+    ref = _run(ctx, prev, cur)
+    n = h * w * 3
+    for off in (1, 3, 8):
+        buf = torch.zeros(2 * n + 64, dtype=torch.uint8, device="cuda")
+        d_prev = buf[off:off + n].view(h, w, 3)
+        d_cur = buf[n + 32 + off:n + 32 + off + n].view(h, w, 3)
+        assert d_prev.data_ptr() % 16 == off
+        d_prev.copy_(torch.from_numpy(prev))
+        d_cur.copy_(torch.from_numpy(cur))
+        uv = torch.full((2, h, w), 99.0, dtype=torch.float32, device="cuda")
+        dp = torch.full((576,), -1.0, dtype=torch.float32, device="cuda")
+        gate = torch.zeros(4, dtype=torch.int32, device="cuda")
+        ctx.flow_score(d_prev, d_cur, uv, dp, gate)
+        torch.cuda.synchronize()
+        assert np.array_equal(uv.cpu().numpy(), ref[0]) and np.array_equal(dp.cpu().numpy(), ref[1]), off
+    ctx.close()
