@@ -54,13 +54,16 @@ def _check_gate(ctx, orc, T, t):
         f"frame {t}: gate {(gate.n_static, gate.r_frame, gate.redundant)} vs {(n, float(r), int(red))}"
 
 
-def test_two_tiles_joint_decision_drift_sequence():
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_two_tiles_joint_decision_drift_sequence(adaptive):
     """The sequence of the oracle's pin: frame 1 has a static and a moving tile (stored whole), frames 2 and
-    3 are redundant (pointer entries per tile), frame 4 is stored again.  One video frame per call."""
+    3 are redundant (pointer entries per tile), frame 4 is stored again.  One video frame per call.
+    adaptive: with thresholds that follow the score quantiles, moved after every stored entry (tile)."""
     from paper_2602_14236_amd import binding
     T = 2
+    extra = dict(tier_mode=2, k_fp16=100, k_int8=150, k_int4=200, adapt_rate_q8=96) if adaptive else {}
     p = params(96, 96, flow_levels=2, n_layers=1, n_heads=1, cap_fp16=6000, cap_int8=6000, cap_int4=6000, max_frames=16,
-               tiles_per_frame=T)
+               tiles_per_frame=T, **extra)
     ctx = binding.SaliContext(lib_config(p))
     orc = SaliCacheOracle(oracle_config(p))
     seq = [(0.0, 5.0), (0.0, 7.0), (0.0, 7.0), (0.3, 7.3), (3.0, 7.3)]
@@ -72,6 +75,9 @@ def test_two_tiles_joint_decision_drift_sequence():
         step_tiles(orc, rgbs, [k.numpy() for k in kvs], t)
         _check_gate(ctx, orc, T, t)
     assert [orc.rows[e].stored for e in range(10)] == [1, 1, 1, 1, 0, 0, 0, 0, 1, 1]
+    if adaptive:
+        print("thresholds at the end:", orc.table.adapt_tau, [orc.rows[e].as_tuple()[6:10] for e in (0, 1, 8, 9)], flush=True)
+        assert orc.rows[0].as_tuple()[6:10] != orc.rows[9].as_tuple()[6:10]      # the thresholds did move
     assert [orc.rows[e].src for e in range(10)] == [0, 1, 2, 3, 2, 3, 2, 3, 8, 9]
     _compare(ctx, orc, 10)
     # whole frames only
