@@ -370,14 +370,13 @@ int enqueue_gray(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, 
 // Saliency pre-pass (edges, colour variance, tile-local hysteresis) and the cross-tile hysteresis pass
 // after a kernel boundary (the cheapest device-wide ordering there is).  flow_or_null: the chained step,
 // after the flow and the per-patch motions: frames that the reuse rule finds redundant are skipped
-// (Algorithm 1).  write_gray: the stand-alone call, which has no gray image yet.  The other frame-sum
-// accumulator of each lane is cleared for the lane's next use.
-int enqueue_saliency(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp, bool write_gray,
+// (Algorithm 1).  The other frame-sum accumulator of each lane is cleared for the lane's next use.
+int enqueue_saliency(sali_ctx* c, const uint8_t* const* d_rgb, const BatchPlan& bp,
                      const float2* const* flow_or_null, hipStream_t s) {
     const sali_config& cfg = c->cfg;
     const PrepBatch f = prep_batch(c, d_rgb, bp, true, flow_or_null);
     const GateParams gp = gate_params(c);
-    SALI_TRY(launch_prep(f, bp.n, cfg.src_h, cfg.src_w, write_gray, gp, c->tb<uint16_t>(c->tl.lut),
+    SALI_TRY(launch_prep(f, bp.n, cfg.src_h, cfg.src_w, gp, c->tb<uint16_t>(c->tl.lut),
                          cfg.canny_lo * cfg.canny_lo, cfg.canny_hi * cfg.canny_hi, s));
     SALI_TRY(launch_union(f, bp.n, cfg.src_h, cfg.src_w, s));
     return SALI_OK;
@@ -758,7 +757,7 @@ int sali_saliency_pool(sali_ctx* c, const uint8_t* d_rgb, uint8_t* d_salmap_or_n
     BatchPlan bp = {};
     bp.n = 1;
     bp.parity[0] = c->lane_uses[0]++ & 1u;
-    int rc = enqueue_saliency(c, &d_rgb, bp, true, nullptr, s);
+    int rc = enqueue_saliency(c, &d_rgb, bp, nullptr, s);
     if (rc == SALI_OK) rc = enqueue_pool(c, bp, d_scores576, d_salmap_or_null, nullptr, nullptr, s);
     return rc;
 }
@@ -897,7 +896,7 @@ int sali_analyze_batch(sali_ctx* c, const uint8_t* const* d_rgb_frames, int32_t 
     if (rc == SALI_OK) rc = enqueue_motion(c, bp, flow, s);
     // then the spatial filter, for the frames the reuse rule does not find redundant (Algorithm 1: a
     // redundant frame bypasses it): every kernel from here on evaluates the rule from the motions
-    if (rc == SALI_OK) rc = enqueue_saliency(c, d_rgb_frames, bp, false, flow, s);
+    if (rc == SALI_OK) rc = enqueue_saliency(c, d_rgb_frames, bp, flow, s);
     if (rc != SALI_OK) return rc;
     if (prev != nullptr) {
         // tiers are handed out in frame order: the cursors must have seen the previous frame

@@ -232,11 +232,11 @@ hipError_t launch_attend(const sali_frame_row* d_rows, Pools pools, int layer, i
 
 // saliency_kernels.hip
 // n = frames in the batch (1..kMaxBatch).  launch_gray: RGB -> gray only.  launch_prep: the edge / colour
-// variance pre-pass (write_gray: also the gray image); frames that the reuse rule finds redundant from
+// variance pre-pass; frames that the reuse rule finds redundant from
 // f.dp are skipped (Algorithm 1: their saliency is not computed) and marked in f.skip, which launch_union
 // and launch_pool go by.
 hipError_t launch_gray(const PrepBatch& f, int n, int h, int w, hipStream_t s);
-hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool write_gray, GateParams gp, const uint16_t* d_lut,
+hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, GateParams gp, const uint16_t* d_lut,
                        int lo2, int hi2, hipStream_t s);
 hipError_t launch_union(const PrepBatch& f, int n, int h, int w, hipStream_t s);
 // launch_motion: Eq. 5, per-patch motion of every frame of the batch from its flow (0 without flow).

@@ -117,11 +117,10 @@ constexpr int kPrepThreads = 256;
 constexpr int kPrepPx = kTile * kTile / kPrepThreads;                          // 4
 constexpr int kPrepCells = (kReg * kReg + kPrepThreads - 1) / kPrepThreads;   // 7
 
-__global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w, int write_gray, GateParams gp,
+__global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w, GateParams gp,
                                                        const uint32_t* __restrict__ lut_words, int lo2, int hi2) {
     // blockIdx.z = frame of the batch
     const uint8_t* __restrict__ rgb = f.rgb[blockIdx.z];
-    uint8_t* __restrict__ y8_out = f.y8[blockIdx.z];
     uint8_t* __restrict__ cls_out = f.cls[blockIdx.z];
     uint32_t* __restrict__ var_out = f.var[blockIdx.z];
     uint32_t* __restrict__ parent_out = f.parent[blockIdx.z];
@@ -195,16 +194,8 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(PrepBatch f, int h, int w
         s_lab[2][ry - 2][rx - 2] = (uint8_t)clampi((200 * (fy - fz) + 4194304 + 16384) >> 15, 0, 255);
     }
 
-    // gray image for the flow pyramid (the chained step has written it already, before the flow)
     const int tx = tid % kTile;
     const int gx = x0 + tx;
-    if (write_gray) {
-#pragma unroll
-        for (int q = 0; q < kPrepPx; ++q) {
-            const int ty = (tid + q * kPrepThreads) / kTile;
-            if (y0 + ty < h && gx < w) y8_out[(size_t)(y0 + ty) * w + gx] = s_y[ty + kHalo][tx + kHalo];
-        }
-    }
 
     // Region arrays are indexed by (image coordinate - region origin).  A stage evaluates its
     // stencil at the CLAMPED image coordinate c of each region cell and reads its input at
@@ -636,10 +627,10 @@ hipError_t launch_gray(const PrepBatch& f, int n, int h, int w, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, bool write_gray, GateParams gp, const uint16_t* d_lut,
+hipError_t launch_prep(const PrepBatch& f, int n, int h, int w, GateParams gp, const uint16_t* d_lut,
                        int lo2, int hi2, hipStream_t s) {
     dim3 grid((w + kTile - 1) / kTile, (h + kTile - 1) / kTile, n);
-    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, f, h, w, write_gray ? 1 : 0, gp,
+    hipLaunchKernelGGL(k_prep, grid, dim3(kPrepThreads), 0, s, f, h, w, gp,
                        reinterpret_cast<const uint32_t*>(d_lut), lo2, hi2);
     return hipGetLastError();
 }
