@@ -398,7 +398,6 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
     // (with RX + 1 = 27 the 16x16 kernel spent 37 % of its LDS cycles on bank conflicts)
     constexpr int RXS = TX == 16 ? 48 : RX + 1;
     __shared__ float s_in[5][RY][RXS];
-    __shared__ float s_row[5][RY][TX];
     __shared__ float2 s_dp[TY][TX];          // prior of the tile's own pixels, for the solve
 
     const int tid = threadIdx.x;
@@ -443,20 +442,58 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
     }
     __syncthreads();
 
-    // row pass of the separable Gaussian window
-    for (int p = tid; p < RY * TX; p += NT) {
-        const int ry = p / TX, tx = p % TX;
-        float acc[5] = {0, 0, 0, 0, 0};
+    // The 1024-thread kernel already fills a compute unit's wave slots with two blocks and has no
+    // registers to spare for the in-place row pass below: it keeps a second array for the row sums.
+    constexpr bool kInPlace = NT < 1024;
+    __shared__ float s_row[kInPlace ? 1 : 5][kInPlace ? 1 : RY][TX];
+    if constexpr (kInPlace) {
+        // Row pass of the separable Gaussian window, in place: every thread keeps the sums of its (at most
+        // kRowItems) outputs in registers until all taps of all threads are read, then writes them over the
+        // terms at [ry][tx].  A second array for the row sums would cost 17 KB (32x16 tile): with it three
+        // blocks fit a compute unit, without it four, and next to the K/V kernels, where a block spends its
+        // time waiting for memory, the blocks in flight are what sets the kernel's speed.
+        constexpr int kRowItems = (RY * TX + NT - 1) / NT;
+        float racc[kRowItems][5];
 #pragma unroll
-        for (int k = 0; k <= 2 * kWinR; ++k) {
-            const float wk = fw.win_g[k];
+        for (int q = 0; q < kRowItems; ++q) {
+            const int p = tid + q * NT;
+            const int ry = p / TX, tx = p % TX;
 #pragma unroll
-            for (int c = 0; c < 5; ++c) acc[c] += wk * s_in[c][ry][tx + k];
+            for (int c = 0; c < 5; ++c) racc[q][c] = 0.0f;
+            if (p < RY * TX) {
+#pragma unroll
+                for (int k = 0; k <= 2 * kWinR; ++k) {
+                    const float wk = fw.win_g[k];
+#pragma unroll
+                    for (int c = 0; c < 5; ++c) racc[q][c] += wk * s_in[c][ry][tx + k];
+                }
+            }
         }
+        __syncthreads();
 #pragma unroll
-        for (int c = 0; c < 5; ++c) s_row[c][ry][tx] = acc[c];
+        for (int q = 0; q < kRowItems; ++q) {
+            const int p = tid + q * NT;
+            if (p < RY * TX) {
+#pragma unroll
+                for (int c = 0; c < 5; ++c) s_in[c][p / TX][p % TX] = racc[q][c];
+            }
+        }
+        __syncthreads();
+    } else {
+        for (int p = tid; p < RY * TX; p += NT) {
+            const int ry = p / TX, tx = p % TX;
+            float acc[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+            for (int k = 0; k <= 2 * kWinR; ++k) {
+                const float wk = fw.win_g[k];
+#pragma unroll
+                for (int c = 0; c < 5; ++c) acc[c] += wk * s_in[c][ry][tx + k];
+            }
+#pragma unroll
+            for (int c = 0; c < 5; ++c) s_row[c][ry][tx] = acc[c];
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // column pass + ridge solve
     for (int p = tid; p < TX * TY; p += NT) {
@@ -468,7 +505,7 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
         for (int k = 0; k <= 2 * kWinR; ++k) {
             const float wk = fw.win_g[k];
 #pragma unroll
-            for (int c = 0; c < 5; ++c) acc[c] += wk * s_row[c][ty + k][tx];
+            for (int c = 0; c < 5; ++c) acc[c] += wk * (kInPlace ? s_in[c][ty + k][tx] : s_row[c][ty + k][tx]);
         }
         const float2 dp = s_dp[ty][tx];
         const float lam = kLamAbs + kLamRel * 0.5f * (acc[0] + acc[2]);
