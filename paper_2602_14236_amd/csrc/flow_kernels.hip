@@ -378,6 +378,22 @@ __device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int 
     return ld_at(d_in, pix(gy, w, gx));
 }
 
+// Row and column of item p of a window pass over n_rows rows of TX outputs.  TX = 32: row-major.
+// TX = 16: the 32 lanes of a group take rows r and r + 4 (blocks of eight rows: groups 0..3 take rows
+// (0,4) (1,5) (2,6) (3,7), and so on); what is left of n_rows after whole blocks is taken row by row.
+template <int TX>
+__device__ __forceinline__ void window_item(int p, int n_rows, int& row, int& col) {
+    if constexpr (TX == 16) {
+        const int g = p >> 5, half = (p >> 4) & 1;
+        col = p & 15;
+        const int paired = (n_rows / 8) * 8;             // rows covered by whole blocks of eight
+        row = g < paired / 2 ? (g >> 2) * 8 + (g & 3) + 4 * half : paired + 2 * (g - paired / 2) + half;
+    } else {
+        row = p / TX;
+        col = p % TX;
+    }
+}
+
 }  // namespace
 
 // TX x TY = tile, NT = threads of the block.
@@ -393,10 +409,14 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
     const float2* __restrict__ d_in = f.d_in[blk.z];
     float2* __restrict__ d_out = f.d_out[blk.z];
     constexpr int RX = TX + 2 * kWinR, RY = TY + 2 * kWinR;
-    // row stride of the per-cell terms: a group of 32 lanes of the row pass reads one row of a 32-wide
-    // tile but two rows (16 lanes each) of a 16-wide one, which must not share banks: 16 mod 32
-    // (with RX + 1 = 27 the 16x16 kernel spent 37 % of its LDS cycles on bank conflicts)
-    constexpr int RXS = TX == 16 ? 48 : RX + 1;
+    // Row stride of the per-cell terms.  A group of 32 lanes of a window pass reads one row of a 32-wide
+    // tile but two rows (16 lanes each) of a 16-wide one, which must not share banks: their distance has
+    // to be 16 mod 32 floats.  With adjacent rows that takes a stride of 48 floats for 26 cells (25 KB a
+    // block, five blocks per compute unit; RX + 1 = 27 spent 37 % of the LDS cycles on bank conflicts);
+    // instead the two rows of a group are four apart (window_row below) and the stride is 28: 4 * 28 =
+    // 16 mod 32, 17 KB a block, eight blocks = every wave slot of a compute unit.
+    constexpr int RXS = TX == 16 ? 28 : RX + 1;
+    static_assert(TX != 16 || ((4 * RXS) % 32 == 16 && TY % 8 == 0), "rows four apart sit 16 banks apart");
     __shared__ float s_in[5][RY][RXS];
     __shared__ float2 s_dp[TY][TX];          // prior of the tile's own pixels, for the solve
 
@@ -457,7 +477,8 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
 #pragma unroll
         for (int q = 0; q < kRowItems; ++q) {
             const int p = tid + q * NT;
-            const int ry = p / TX, tx = p % TX;
+            int ry, tx;
+            window_item<TX>(p, RY, ry, tx);
 #pragma unroll
             for (int c = 0; c < 5; ++c) racc[q][c] = 0.0f;
             if (p < RY * TX) {
@@ -474,8 +495,10 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
         for (int q = 0; q < kRowItems; ++q) {
             const int p = tid + q * NT;
             if (p < RY * TX) {
+                int ry, tx;
+                window_item<TX>(p, RY, ry, tx);
 #pragma unroll
-                for (int c = 0; c < 5; ++c) s_in[c][p / TX][p % TX] = racc[q][c];
+                for (int c = 0; c < 5; ++c) s_in[c][ry][tx] = racc[q][c];
             }
         }
         __syncthreads();
@@ -497,7 +520,8 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
 
     // column pass + ridge solve
     for (int p = tid; p < TX * TY; p += NT) {
-        const int ty = p / TX, tx = p % TX;
+        int ty, tx;
+        window_item<TX>(p, TY, ty, tx);
         const int gy = y0 + ty, gx = x0 + tx;
         if (gy >= h || gx >= w) continue;
         float acc[5] = {0, 0, 0, 0, 0};
