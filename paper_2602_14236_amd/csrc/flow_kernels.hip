@@ -166,16 +166,17 @@ constexpr int kET = 16;                        // tile side
 constexpr int kER = kET + 2 * kPolyN;          // 22: region the expansion stencil reads
 constexpr int kEP = 2 * (kER - 1) + 5;         // 47: region one level below that feeds it
 constexpr int kEQ = 2 * (kEP - 1) + 5;         // 97: region two levels below
-// De-interleaved patches: even columns from float 48 of a row on; row strides chosen so that the stage
-// reading the patch sees addresses linear in its thread index (pyr_level_lds): a 47-wide patch is read
-// 22 cells per row (2 * 59 = 22 mod 32), a 97-wide one 47 cells per row by 48 lanes (2 * 104 = 48 mod 32).
-// The 97-wide patch puts its even columns at 48 = 16 (mod 32), so the two halves of a group of 32 lanes
-// that writes a row use disjoint banks; the 47-wide one at 24 (its writes, one per 25 reads, then see
-// two-way conflicts: 48 would need rows of 75 floats and cost the third resident block per compute unit).
+// The 47-wide float patch is de-interleaved: even columns from float 24 of a row on, row stride 59, so
+// that the stage reading it (22 cells per row) sees addresses linear in its thread index (pyr_level_lds:
+// 2 * 59 = 22 mod 32); its writes, one per 25 reads, then see two-way conflicts (even columns at 48 would
+// need rows of 75 floats).  The 97-wide gray patch of a level-2 tile stays in bytes, plain layout, rows of
+// 112 bytes: the stage that reads it takes 47 cells per row by 48 lanes at a stride of two bytes, so a
+// group of 32 lanes reads 16 words (two lanes a word: a broadcast), and the second half of a wave,
+// which straddles two cell rows = 2 * 28 words = 24 banks apart, still hits every bank at most once.
 constexpr int kEvenP = 24, kEPS = 59;
-constexpr int kEvenQ = 48, kEQS = 104;
-static_assert(kEvenP + (kEP + 1) / 2 <= kEPS && kEvenQ + (kEQ + 1) / 2 <= kEQS, "a row holds both halves");
-static_assert(kEvenP >= kEP / 2 && kEvenQ >= kEQ / 2, "the odd half fits before the even half");
+constexpr int kEQB = 112;
+static_assert(kEvenP + (kEP + 1) / 2 <= kEPS && kEvenP >= kEP / 2, "a row holds both halves");
+static_assert(kEQB % 4 == 0 && kEQB >= (kEQ + 3) / 4 * 4 && (2 * (kEQB / 4)) % 32 == 24, "byte rows");
 
 // LDS patches that feed a pyramid stage keep the odd columns of a row in its first part and the even
 // columns from kEven on (kEven = 0: plain layout): the stage reads columns 2 * cx + {-2..2}, a stride
@@ -237,6 +238,59 @@ __device__ __forceinline__ void load_gray_patch(const uint8_t* __restrict__ y8, 
     }
 }
 
+// The 97 x 97 gray patch of a level-2 tile, origin (qy, qx), coordinates clamped to the image, as bytes:
+// a thread takes four columns at a time (one 32-bit LDS write; one 32-bit load where the four lie inside the
+// image, the compiler is told nothing about its alignment) and has all its loads in flight before the
+// first is used.  As floats the patch took 40 KB and the block 52: three blocks per compute unit, also for
+// the level-0 and level-1 tiles of the same launch, which need none of it; in bytes the block takes 24 KB.
+__device__ __forceinline__ void load_gray_patch_bytes(const uint8_t* __restrict__ y8, int h0, int w0, int qy, int qx,
+                                                      uint32_t* __restrict__ dst) {
+    constexpr int kQuads = (kEQ + 3) / 4, kItems = kEQ * kQuads, kN = (kItems + 255) / 256;
+    uint32_t v[kN];
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        const int p = (int)threadIdx.x + 256 * k;
+        const int pp = p < kItems ? p : 0;
+        const int ry = pp / kQuads, x = qx + 4 * (pp % kQuads);
+        const uint8_t* row = y8 + (size_t)clampi(qy + ry, 0, h0 - 1) * w0;
+        if (x >= 0 && x + 3 < w0) {
+            __builtin_memcpy(&v[k], row + x, 4);
+        } else {
+            v[k] = (uint32_t)row[clampi(x, 0, w0 - 1)] | ((uint32_t)row[clampi(x + 1, 0, w0 - 1)] << 8) |
+                   ((uint32_t)row[clampi(x + 2, 0, w0 - 1)] << 16) | ((uint32_t)row[clampi(x + 3, 0, w0 - 1)] << 24);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        const int p = (int)threadIdx.x + 256 * k;
+        if (p < kItems) dst[(p / kQuads) * (kEQB / 4) + p % kQuads] = v[k];
+    }
+}
+
+// First pyramid level of a level-2 tile from the byte patch: the 5x5 binomial sum in integers (weights
+// 1 4 6 4 1 squared: at most 256 * 255, exact) and one division by 256 * 255, i.e. the level-1 value of
+// gray / 255 rounded once.  Cells and lanes as in pyr_level_lds.
+template <int kDstStride, int kDstEven, int kN, int kLanesPerRow>
+__device__ __forceinline__ void pyr_level_from_bytes(const uint8_t* src, int o_src_y, int o_src_x, float* dst,
+                                                     int o_dst_y, int o_dst_x, int dh, int dw) {
+    const uint32_t k[5] = {1u, 4u, 6u, 4u, 1u};
+    for (int p = threadIdx.x; p < kN * kLanesPerRow; p += 256) {
+        const int ry = p / kLanesPerRow, rx = p % kLanesPerRow;
+        if (rx >= kN) continue;
+        const int cy = clampi(o_dst_y + ry, 0, dh - 1), cx = clampi(o_dst_x + rx, 0, dw - 1);
+        const int sy = 2 * cy - o_src_y, sx = 2 * cx - o_src_x;
+        uint32_t acc = 0u;
+#pragma unroll
+        for (int a = -2; a <= 2; ++a) {
+            uint32_t row = 0u;
+#pragma unroll
+            for (int b = -2; b <= 2; ++b) row += k[b + 2] * (uint32_t)src[(sy + a) * kEQB + sx + b];
+            acc += k[a + 2] * row;
+        }
+        dst[ry * kDstStride + lds_col<kDstEven>(rx)] = (float)acc / 65280.0f;
+    }
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int t1, int t2, int tx0, int tx1, int tx2,
@@ -267,15 +321,15 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
     const uint8_t* __restrict__ y8 = f.y8[frame];
     float4* __restrict__ A_out = f.A[frame];
     float* __restrict__ b_out = f.b[frame];
-    __shared__ float s_q[kEQ * kEQS];               // gray patch (level-2 blocks: 97 wide; level-1 blocks: 47 wide)
-    __shared__ float s_p[kEP * kEPS];               // level-1 patch of a level-2 block
+    __shared__ uint32_t s_qb[kEQ * (kEQB / 4)];     // gray patch of a level-2 block, bytes
+    __shared__ float s_p[kEP * kEPS];               // level-1 patch of a level-2 block; gray patch of a level-1 block
     // unpadded rows: both the pass that writes these arrays and the pass that reads them then see
     // addresses linear in the thread index (the horizontal pass pairs rows eight apart, see below)
     __shared__ float s_f[kER][kER];
-    // the vertical moments reuse the gray patch's memory: every path has a barrier between its last
-    // read of s_q and the pass that writes them (three blocks of 52 KB fit a compute unit, not of 57)
-    float (*s_v)[kET][kER] = reinterpret_cast<float (*)[kET][kER]>(s_q);
-    static_assert(3 * kET * kER <= kEQ * kEQS, "moments fit into the gray patch");
+    // the vertical moments reuse the 47-wide patch's memory: every path has a barrier between its last
+    // read of s_p and the pass that writes them
+    float (*s_v)[kET][kER] = reinterpret_cast<float (*)[kET][kER]>(s_p);
+    static_assert(3 * kET * kER <= kEP * kEPS, "moments fit into the 47-wide patch");
 
     const int tiles_x = lvl == 0 ? tx0 : (lvl == 1 ? tx1 : tx2);
     const int h = g.h[lvl], w = g.w[lvl];
@@ -288,16 +342,17 @@ __global__ __launch_bounds__(256) void k_expand(ExpandBatch f, LevelGeom g, int 
         load_gray_patch<kER, kER, 0>(y8, h, w, oy, ox, &s_f[0][0]);
     } else if (lvl == 1) {
         const int qy = 2 * oy - 2, qx = 2 * ox - 2;              // origin of the gray patch (47 x 47)
-        load_gray_patch<kEP, kEPS, kEvenP>(y8, h0, w0, qy, qx, s_q);
+        load_gray_patch<kEP, kEPS, kEvenP>(y8, h0, w0, qy, qx, s_p);
         __syncthreads();
-        pyr_level_lds<kEPS, kEvenP, kER, 0, kER, kER>(s_q, qy, qx, &s_f[0][0], oy, ox, h, w);
+        pyr_level_lds<kEPS, kEvenP, kER, 0, kER, kER>(s_p, qy, qx, &s_f[0][0], oy, ox, h, w);
     } else {
         const int h1 = g.h[1], w1 = g.w[1];
         const int py = 2 * oy - 2, px = 2 * ox - 2;              // origin of the level-1 patch (47 x 47)
         const int qy = 2 * py - 2, qx = 2 * px - 2;              // origin of the gray patch (97 x 97)
-        load_gray_patch<kEQ, kEQS, kEvenQ>(y8, h0, w0, qy, qx, s_q);
+        load_gray_patch_bytes(y8, h0, w0, qy, qx, s_qb);
         __syncthreads();
-        pyr_level_lds<kEQS, kEvenQ, kEPS, kEvenP, kEP, kEP + 1>(s_q, qy, qx, s_p, py, px, h1, w1);
+        pyr_level_from_bytes<kEPS, kEvenP, kEP, kEP + 1>(reinterpret_cast<const uint8_t*>(s_qb), qy, qx, s_p, py, px, h1,
+                                                         w1);
         __syncthreads();
         pyr_level_lds<kEPS, kEvenP, kER, 0, kER, kER>(s_p, py, px, &s_f[0][0], oy, ox, h, w);
     }
