@@ -433,20 +433,39 @@ __device__ __forceinline__ float2 prior_at(const float2* __restrict__ d_in, int 
     return ld_at(d_in, pix(gy, w, gx));
 }
 
-// Row and column of item p of a window pass over n_rows rows of TX outputs.  TX = 32: row-major.
-// TX = 16: the 32 lanes of a group take rows r and r + 4 (blocks of eight rows: groups 0..3 take rows
-// (0,4) (1,5) (2,6) (3,7), and so on); what is left of n_rows after whole blocks is taken row by row.
+// Row and column of item p of a window pass over n_rows rows of TX outputs; false = an idle lane.
+// TX = 32: row-major.  TX = 16: the 32 lanes of a group take rows r and r + 8 (first the whole blocks of 16
+// rows: groups 0..7 take rows (0,8) .. (7,15); of the rest, n_rows - 16 k <= 15 rows, those that have a
+// partner eight further on are paired, the others get a group of their own with its upper half idle).
 template <int TX>
-__device__ __forceinline__ void window_item(int p, int n_rows, int& row, int& col) {
+__device__ __forceinline__ bool window_item(int p, int n_rows, int& row, int& col) {
     if constexpr (TX == 16) {
         const int g = p >> 5, half = (p >> 4) & 1;
         col = p & 15;
-        const int paired = (n_rows / 8) * 8;             // rows covered by whole blocks of eight
-        row = g < paired / 2 ? (g >> 2) * 8 + (g & 3) + 4 * half : paired + 2 * (g - paired / 2) + half;
+        const int full = n_rows / 16, base = 16 * full;
+        if (g < 8 * full) {
+            row = (g >> 3) * 16 + (g & 7) + 8 * half;
+            return true;
+        }
+        const int rest = n_rows - base, gg = g - 8 * full, npair = rest > 8 ? rest - 8 : 0;
+        if (gg < npair) {
+            row = base + gg + 8 * half;
+            return true;
+        }
+        row = base + npair + (gg - npair);
+        return half == 0 && row < base + (rest > 8 ? 8 : rest);
     } else {
         row = p / TX;
         col = p % TX;
+        return row < n_rows;
     }
+}
+// items (lanes, idle ones included) of such a pass
+template <int TX>
+constexpr int window_items(int n_rows) {
+    if (TX != 16) return n_rows * TX;
+    const int rest = n_rows % 16, npair = rest > 8 ? rest - 8 : 0;
+    return 32 * (8 * (n_rows / 16) + npair + ((rest > 8 ? 8 : rest) - npair));
 }
 
 }  // namespace
@@ -467,11 +486,12 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
     // Row stride of the per-cell terms.  A group of 32 lanes of a window pass reads one row of a 32-wide
     // tile but two rows (16 lanes each) of a 16-wide one, which must not share banks: their distance has
     // to be 16 mod 32 floats.  With adjacent rows that takes a stride of 48 floats for 26 cells (25 KB a
-    // block, five blocks per compute unit; RX + 1 = 27 spent 37 % of the LDS cycles on bank conflicts);
-    // instead the two rows of a group are four apart (window_row below) and the stride is 28: 4 * 28 =
-    // 16 mod 32, 17 KB a block, eight blocks = every wave slot of a compute unit.
-    constexpr int RXS = TX == 16 ? 28 : RX + 1;
-    static_assert(TX != 16 || ((4 * RXS) % 32 == 16 && TY % 8 == 0), "rows four apart sit 16 banks apart");
+    // block, five blocks per compute unit; RX + 1 = 27 spent 37 % of the LDS cycles on bank conflicts).
+    // Instead the two rows of a group are eight apart (window_item) and the rows are unpadded: 8 * 26 = 16
+    // mod 32; the pass that writes the terms then sees addresses linear in the thread index, and a block
+    // takes 16 KB, so that eight blocks fill every wave slot of a compute unit.
+    constexpr int RXS = TX == 16 ? RX : RX + 1;
+    static_assert(TX != 16 || (8 * RXS) % 32 == 16, "rows eight apart sit 16 banks apart");
     __shared__ float s_in[5][RY][RXS];
     __shared__ float2 s_dp[TY][TX];          // prior of the tile's own pixels, for the solve
 
@@ -527,16 +547,16 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
         // terms at [ry][tx].  A second array for the row sums would cost 17 KB (32x16 tile): with it three
         // blocks fit a compute unit, without it four, and next to the K/V kernels, where a block spends its
         // time waiting for memory, the blocks in flight are what sets the kernel's speed.
-        constexpr int kRowItems = (RY * TX + NT - 1) / NT;
+        constexpr int kRowItems = (window_items<TX>(RY) + NT - 1) / NT;
         float racc[kRowItems][5];
 #pragma unroll
         for (int q = 0; q < kRowItems; ++q) {
             const int p = tid + q * NT;
             int ry, tx;
-            window_item<TX>(p, RY, ry, tx);
+            const bool mine = window_item<TX>(p, RY, ry, tx);
 #pragma unroll
             for (int c = 0; c < 5; ++c) racc[q][c] = 0.0f;
-            if (p < RY * TX) {
+            if (mine) {
 #pragma unroll
                 for (int k = 0; k <= 2 * kWinR; ++k) {
                     const float wk = fw.win_g[k];
@@ -549,9 +569,8 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
 #pragma unroll
         for (int q = 0; q < kRowItems; ++q) {
             const int p = tid + q * NT;
-            if (p < RY * TX) {
-                int ry, tx;
-                window_item<TX>(p, RY, ry, tx);
+            int ry, tx;
+            if (window_item<TX>(p, RY, ry, tx)) {
 #pragma unroll
                 for (int c = 0; c < 5; ++c) s_in[c][ry][tx] = racc[q][c];
             }
