@@ -10,7 +10,7 @@
 //                values a tile needs are rebuilt from the gray image in LDS; separable moments,
 //                closed-form solution of the 6-unknown weighted least-squares fit
 //   k_pyr_down, k_polyexp   the same per level (pyramid in HBM), used for more than three levels
-//   k_flow_iter  one displacement update: per cell of a tile (16x16 to 32x32, by level size) + 5-pixel
+//   k_flow_iter  one displacement update: per cell of a tile (16x16 or 32x16, by level size) + 5-pixel
 //                halo, sample the new frame's expansion bilinearly at x + prior, build A^T A (3 values)
 //                and A^T db (2 values) in LDS, separable 11x11 Gaussian aggregation in LDS, 2x2 ridge
 //                solve.  The coarse-to-fine transfer (2 * bilinear of the coarser flow) is folded
@@ -471,8 +471,8 @@ constexpr int window_items(int n_rows) {
 }  // namespace
 
 // TX x TY = tile, NT = threads of the block.
-template <int TX, int TY, int NT, int kMinWaves = 1>
-__global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long long level_off, int h, int w, int ch, int cw,
+template <int TX, int TY, int NT>
+__global__ __launch_bounds__(NT) void k_flow_iter(FlowBatch f, long long level_off, int h, int w, int ch, int cw,
                                                   int prior_mode, FlowWeights fw) {
     // blk.z = frame of the batch, (blk.x, blk.y) = tile
     const BlockId blk = xcd_block_id();
@@ -537,11 +537,7 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
     }
     __syncthreads();
 
-    // The 1024-thread kernel already fills a compute unit's wave slots with two blocks and has no
-    // registers to spare for the in-place row pass below: it keeps a second array for the row sums.
-    constexpr bool kInPlace = NT < 1024;
-    __shared__ float s_row[kInPlace ? 1 : 5][kInPlace ? 1 : RY][TX];
-    if constexpr (kInPlace) {
+    {
         // Row pass of the separable Gaussian window, in place: every thread keeps the sums of its (at most
         // kRowItems) outputs in registers until all taps of all threads are read, then writes them over the
         // terms at [ry][tx].  A second array for the row sums would cost 17 KB (32x16 tile): with it three
@@ -576,20 +572,6 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
             }
         }
         __syncthreads();
-    } else {
-        for (int p = tid; p < RY * TX; p += NT) {
-            const int ry = p / TX, tx = p % TX;
-            float acc[5] = {0, 0, 0, 0, 0};
-#pragma unroll
-            for (int k = 0; k <= 2 * kWinR; ++k) {
-                const float wk = fw.win_g[k];
-#pragma unroll
-                for (int c = 0; c < 5; ++c) acc[c] += wk * s_in[c][ry][tx + k];
-            }
-#pragma unroll
-            for (int c = 0; c < 5; ++c) s_row[c][ry][tx] = acc[c];
-        }
-        __syncthreads();
     }
 
     // column pass + ridge solve
@@ -603,7 +585,7 @@ __global__ __launch_bounds__(NT, kMinWaves) void k_flow_iter(FlowBatch f, long l
         for (int k = 0; k <= 2 * kWinR; ++k) {
             const float wk = fw.win_g[k];
 #pragma unroll
-            for (int c = 0; c < 5; ++c) acc[c] += wk * (kInPlace ? s_in[c][ty + k][tx] : s_row[c][ty + k][tx]);
+            for (int c = 0; c < 5; ++c) acc[c] += wk * s_in[c][ty + k][tx];
         }
         const float2 dp = s_dp[ty][tx];
         const float lam = kLamAbs + kLamRel * 0.5f * (acc[0] + acc[2]);
@@ -704,23 +686,24 @@ hipError_t launch_expand(const ExpandBatch& f, int n, LevelGeom g, FlowWeights f
 
 hipError_t launch_flow_iter(const FlowBatch& f, int n, int64_t level_off, int h, int w, int ch, int cw,
                             int prior_mode, FlowWeights fw, hipStream_t s) {
-    // Tile and block by level size (kMinWaves = 8 holds the 1024-thread block to 64 registers, so that two
-    // of them fit a compute unit):
-    //   below 40 000 pixels   16x16, 256 threads   (up to seven small blocks per compute unit)
-    //   below 150 000         32x16, 512 threads
-    //   above                 32x32, 1024 threads  (1.7 instead of 2.6 halo cells per output)
+    // Tile and block by level size:
+    //   below 40 000 pixels   16x16, 256 threads   (16 KB of LDS: eight blocks per compute unit)
+    //   above                 32x16, 512 threads   (26 KB: four blocks; 2.1 instead of 2.6 halo cells per output)
     // A block is a chain of dependent HBM round trips (prior -> warped gather, once per cell a thread
-    // owns): with four times the threads a thread owns at most two cells, taken together.  Measured per
-    // frame with nothing else on the GPU, against 16x16 everywhere: 336x336 44.6 -> 42.0 us (32x32 at the
-    // full-size level; 32x16 is used there because it does better next to the K/V kernels), 640x360
-    // 63 -> 56.6, 1920x1080 275 -> 235.  22x22 (one thread per cell), 64x16 and 32x16 / 1024 are slower.
+    // owns); with twice the threads a thread owns about two cells, taken together.  Both shapes fill every
+    // wave slot of a compute unit, which is what counts next to the K/V kernels, where a block mostly waits
+    // for memory.  A 32x32 tile on 1024 threads (1.7 halo cells per output, two blocks per compute unit,
+    // 64 registers) was used from 150 000 pixels up until the row pass went in place: alone on the GPU it
+    // is 1.5 % faster at 1920x1080 (235 against 239 us per frame), inside the pipeline 2 - 3 % slower
+    // (1080p 3 090 -> 3 160 frames/s, 640x360 32 150 -> 33 100): a block of 1024 threads needs sixteen free
+    // wave slots on one compute unit at once.  The same tile on 512 threads (84 registers, three blocks) is
+    // slower everywhere; 22x22 (one thread per cell), 64x16 and 32x16 on 1024 threads are slower as well.
     const long long px = (long long)h * w;
-#define SALI_FLOW_LAUNCH(TX, TY, NT, MW)                                                                         \
-    hipLaunchKernelGGL((k_flow_iter<TX, TY, NT, MW>), dim3((w + TX - 1) / TX, (h + TY - 1) / TY, n), dim3(NT), 0, \
+#define SALI_FLOW_LAUNCH(TX, TY, NT)                                                                         \
+    hipLaunchKernelGGL((k_flow_iter<TX, TY, NT>), dim3((w + TX - 1) / TX, (h + TY - 1) / TY, n), dim3(NT), 0, \
                        s, f, (long long)level_off, h, w, ch, cw, prior_mode, fw)
-    if (px >= 150000) SALI_FLOW_LAUNCH(32, 32, 1024, 8);
-    else if (px >= 40000) SALI_FLOW_LAUNCH(32, 16, 512, 1);
-    else SALI_FLOW_LAUNCH(16, 16, 256, 1);
+    if (px >= 40000) SALI_FLOW_LAUNCH(32, 16, 512);
+    else SALI_FLOW_LAUNCH(16, 16, 256);
 #undef SALI_FLOW_LAUNCH
     return hipGetLastError();
 }

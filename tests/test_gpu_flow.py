@@ -68,9 +68,8 @@ def test_identical_frames_are_exactly_static():
     ctx.close()
 
 
-# the flow update picks its tile by level size (32x32 from 150 000 pixels, 32x16 from 40 000, else 16x16):
-# 360x640 has one level of each class and 200x264 a ragged 32x16 level; 200x200 and 300x500 sit exactly on
-# the two size limits
+# the flow update picks its tile by level size (32x16 from 40 000 pixels, else 16x16): 360x640 has levels of
+# both classes and 200x264 a ragged 32x16 level; 200x200 sits exactly on the size limit
 @pytest.mark.parametrize("h,w,levels", [(24, 24, 1), (50, 77, 2), (97, 131, 3), (360, 640, 3), (200, 264, 5),
                                         (200, 200, 2), (300, 500, 3)])
 def test_ragged_sizes_and_level_counts(h, w, levels):
